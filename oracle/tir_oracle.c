@@ -1,0 +1,258 @@
+/*
+ * CPU oracle for the tensor-contraction operators (test infrastructure, NOT the product).
+ *
+ * This file is the plain definition of the three operators the GPU library computes, written
+ * as direct loops in fp64 (floating inputs) or int64 (int8 inputs).  It exists only so that
+ * tests, the smoke check and the benchmark's cpu_baseline leg have something slow and obviously
+ * correct to compare the HIP kernels with.  It shares no code, header, table or helper with
+ * the GPU path and must never be called from it.
+ *
+ * What is computed (TensorIR paper, section 4.2):
+ *   GEMM   C[x,y]     = sum_k A[x,k] * B[k,y]                      (Eq. 1, reduction init 0, sec. 3.1)
+ *   BMM    C[b,i,j]   = sum_r A[b,i,r] * B[b,r,j]                  (sec. 4.2, b stays data-parallel)
+ *   Conv2D C[n,h,w,co] = sum_{rh,rw,rc} A[n, h*s_h + rh*d_h - pad_h, w*s_w + rw*d_w - pad_w, g*Cg + rc]
+ *                                        * W[co, rh, rw, rc]       (sec. 4.2 formula, NHWC)
+ *     with the readings the paper leaves open: zero padding (taps outside the input add 0),
+ *     cross-correlation (no filter flip), filter stored [K][R][S][C/groups], group of an output
+ *     channel g = co / (K/groups), output extent floor((H + 2*pad - d*(R-1) - 1)/s) + 1.
+ *
+ * Inputs are the raw bits the GPU receives (IEEE binary16, bfloat16, or two's-complement int8);
+ * each is decoded exactly to double / int64 here.  A product of two binary16 or two bfloat16
+ * values is exact in double, so the only rounding is the fp64 summation (relative error
+ * <= K * 2^-53 of sum|a*b|), far below the GPU tolerance.  For every output element the
+ * side output S = sum |a*b| is produced as well; the parity bound is expressed in it.
+ *
+ * Every per-element sum runs over k in ascending order.  Loops over k sit outside the loop over
+ * the output column only so that the innermost loop walks memory contiguously; each C[i,j] still
+ * receives exactly the terms k = 0, 1, ..., K-1 in that order.
+ *
+ * Parity pins (tests/test_oracle_*.py): all 65536 binary16 / bfloat16 patterns against numpy's
+ * own decode; brute-force per-element gathers on tiny shapes; identity matrices; conv ==
+ * explicit im2col + matmul; 1x1 conv == GEMM; linearity; delta and all-ones closed forms; groups
+ * == independent convs; fp64 library convolution (torch CPU) on strided/dilated/padded/grouped
+ * cases; closed forms C = K and C = K*i*j.  No function in this file is "parity unpinned".
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+enum { ORACLE_F16 = 0, ORACLE_BF16 = 1, ORACLE_I8 = 2 };
+enum { ORACLE_OK = 0, ORACLE_BAD_ARG = 1, ORACLE_NO_MEMORY = 2 };
+
+static int g_threads = 0; /* 0 = OpenMP default */
+
+void oracle_set_threads(int n) { g_threads = n > 0 ? n : 0; }
+
+int oracle_get_threads(void) {
+#ifdef _OPENMP
+    return g_threads > 0 ? g_threads : omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* IEEE 754 binary16 -> double, exact (1 sign, 5 exponent bits with bias 15, 10 fraction bits). */
+static double f16_bits_to_double(uint16_t h) {
+    int sign = (h >> 15) & 1;
+    int e = (h >> 10) & 0x1f;
+    int f = h & 0x3ff;
+    double v;
+    if (e == 0) {
+        v = ldexp((double)f, -24); /* zero or subnormal: f * 2^-10 * 2^-14 */
+    } else if (e == 31) {
+        v = f ? NAN : INFINITY;
+    } else {
+        v = ldexp((double)(1024 + f), e - 25); /* (1 + f/1024) * 2^(e-15) */
+    }
+    return sign ? -v : v;
+}
+
+/* bfloat16 is the upper half of an IEEE binary32. */
+static double bf16_bits_to_double(uint16_t h) {
+    uint32_t u = (uint32_t)h << 16;
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return (double)f;
+}
+
+static double load_float(int dtype, const void* p, int64_t idx) {
+    uint16_t bits = ((const uint16_t*)p)[idx];
+    return dtype == ORACLE_F16 ? f16_bits_to_double(bits) : bf16_bits_to_double(bits);
+}
+
+/* Exposed so a test can pin the decoders against an independent decode of every bit pattern. */
+int oracle_decode(int dtype, const void* bits, int64_t n, double* out) {
+    if (n < 0 || (n > 0 && (!bits || !out))) return ORACLE_BAD_ARG;
+    for (int64_t i = 0; i < n; ++i) {
+        if (dtype == ORACLE_I8) out[i] = (double)((const int8_t*)bits)[i];
+        else if (dtype == ORACLE_F16 || dtype == ORACLE_BF16) out[i] = load_float(dtype, bits, i);
+        else return ORACLE_BAD_ARG;
+    }
+    return ORACLE_OK;
+}
+
+/* Gather a strided [rows, cols] operand into a dense row-major array of doubles / int64. */
+static double* gather_f(int dtype, const void* p, int64_t rows, int64_t cols, int64_t rs, int64_t cs) {
+    double* d = (double*)malloc(sizeof(double) * (size_t)(rows * cols > 0 ? rows * cols : 1));
+    if (!d) return NULL;
+    for (int64_t r = 0; r < rows; ++r)
+        for (int64_t c = 0; c < cols; ++c) d[r * cols + c] = load_float(dtype, p, r * rs + c * cs);
+    return d;
+}
+
+static int64_t* gather_i(const void* p, int64_t rows, int64_t cols, int64_t rs, int64_t cs) {
+    int64_t* d = (int64_t*)malloc(sizeof(int64_t) * (size_t)(rows * cols > 0 ? rows * cols : 1));
+    if (!d) return NULL;
+    for (int64_t r = 0; r < rows; ++r)
+        for (int64_t c = 0; c < cols; ++c) d[r * cols + c] = ((const int8_t*)p)[r * rs + c * cs];
+    return d;
+}
+
+/*
+ * GEMM, Eq. 1: C[i,j] = sum_k A[i,k] * B[k,j].  Element (i,k) of A sits at A[i*a_rs + k*a_cs],
+ * element (k,j) of B at B[k*b_rs + j*b_cs] (strides in elements, non-negative).
+ * C is dense row-major [M,N]: double for f16/bf16, int64 for int8.  S (double [M,N], may be NULL,
+ * ignored for int8) receives sum_k |A[i,k] * B[k,j]|.  K = 0 gives C = 0.
+ */
+int oracle_gemm(int dtype, const void* A, const void* B, int64_t M, int64_t N, int64_t K,
+                int64_t a_rs, int64_t a_cs, int64_t b_rs, int64_t b_cs, void* C, double* S) {
+    if (M < 0 || N < 0 || K < 0) return ORACLE_BAD_ARG;
+    if (dtype != ORACLE_F16 && dtype != ORACLE_BF16 && dtype != ORACLE_I8) return ORACLE_BAD_ARG;
+    if (M == 0 || N == 0) return ORACLE_OK;
+    if (!C || (K > 0 && (!A || !B))) return ORACLE_BAD_ARG;
+    int nt = oracle_get_threads();
+    (void)nt;
+    if (dtype == ORACLE_I8) {
+        int64_t* a = gather_i(A, M, K, a_rs, a_cs);
+        int64_t* b = gather_i(B, K, N, b_rs, b_cs);
+        if (!a || !b) { free(a); free(b); return ORACLE_NO_MEMORY; }
+        int64_t* c = (int64_t*)C;
+#pragma omp parallel for schedule(static) num_threads(nt)
+        for (int64_t i = 0; i < M; ++i) {
+            for (int64_t j = 0; j < N; ++j) c[i * N + j] = 0; /* reduction init */
+            for (int64_t k = 0; k < K; ++k) {
+                int64_t aik = a[i * K + k];
+                for (int64_t j = 0; j < N; ++j) c[i * N + j] += aik * b[k * N + j];
+            }
+        }
+        free(a); free(b);
+        return ORACLE_OK;
+    }
+    double* a = gather_f(dtype, A, M, K, a_rs, a_cs);
+    double* b = gather_f(dtype, B, K, N, b_rs, b_cs);
+    if (!a || !b) { free(a); free(b); return ORACLE_NO_MEMORY; }
+    double* c = (double*)C;
+#pragma omp parallel for schedule(static) num_threads(nt)
+    for (int64_t i = 0; i < M; ++i) {
+        for (int64_t j = 0; j < N; ++j) { c[i * N + j] = 0.0; if (S) S[i * N + j] = 0.0; }
+        for (int64_t k = 0; k < K; ++k) {
+            double aik = a[i * K + k];
+            for (int64_t j = 0; j < N; ++j) {
+                double t = aik * b[k * N + j];
+                c[i * N + j] += t;
+                if (S) S[i * N + j] += fabs(t);
+            }
+        }
+    }
+    free(a); free(b);
+    return ORACLE_OK;
+}
+
+/*
+ * Batched matmul: C[b,i,j] = sum_r A[b,i,r] * B[b,r,j]; the batch iterator maps to nothing in the
+ * intrinsic and is a plain outer loop.  a_bs / b_bs are batch strides in elements (0 = the same
+ * matrix for every batch).  C (and S) are dense [batch, M, N].
+ */
+int oracle_batch_matmul(int dtype, const void* A, const void* B, int64_t batch, int64_t M, int64_t N,
+                        int64_t K, int64_t a_bs, int64_t a_rs, int64_t a_cs, int64_t b_bs, int64_t b_rs,
+                        int64_t b_cs, void* C, double* S) {
+    if (batch < 0) return ORACLE_BAD_ARG;
+    size_t in_size = dtype == ORACLE_I8 ? 1 : 2;
+    size_t out_size = 8;
+    for (int64_t bi = 0; bi < batch; ++bi) {
+        const char* a = A ? (const char*)A + (size_t)(bi * a_bs) * in_size : NULL;
+        const char* b = B ? (const char*)B + (size_t)(bi * b_bs) * in_size : NULL;
+        char* c = C ? (char*)C + (size_t)(bi * M * N) * out_size : NULL;
+        double* s = S ? S + bi * M * N : NULL;
+        int rc = oracle_gemm(dtype, a, b, M, N, K, a_rs, a_cs, b_rs, b_cs, c, s);
+        if (rc != ORACLE_OK) return rc;
+    }
+    return ORACLE_OK;
+}
+
+/* Output extent of one spatial axis; <= 0 means the filter does not fit. */
+int64_t oracle_conv_out_extent(int64_t in, int64_t filt, int64_t stride, int64_t pad, int64_t dil) {
+    int64_t span = in + 2 * pad - dil * (filt - 1) - 1;
+    if (span < 0) return 0;
+    return span / stride + 1;
+}
+
+/*
+ * Conv2D, direct loops.  x: [N,H,W,C] (NHWC), w: [K,R,S,C/groups], y (and Sabs): dense [N,P,Q,K].
+ * y is double (f16/bf16) or int64 (int8).
+ */
+int oracle_conv2d(int dtype, const void* x, const void* w, int64_t N, int64_t H, int64_t W, int64_t C,
+                  int64_t K, int64_t R, int64_t S, int64_t stride_h, int64_t stride_w, int64_t pad_h,
+                  int64_t pad_w, int64_t dil_h, int64_t dil_w, int64_t groups, void* y, double* Sabs) {
+    if (N < 0 || H <= 0 || W <= 0 || C <= 0 || K <= 0 || R <= 0 || S <= 0) return ORACLE_BAD_ARG;
+    if (stride_h <= 0 || stride_w <= 0 || dil_h <= 0 || dil_w <= 0 || pad_h < 0 || pad_w < 0) return ORACLE_BAD_ARG;
+    if (groups <= 0 || C % groups || K % groups) return ORACLE_BAD_ARG;
+    if (dtype != ORACLE_F16 && dtype != ORACLE_BF16 && dtype != ORACLE_I8) return ORACLE_BAD_ARG;
+    int64_t P = oracle_conv_out_extent(H, R, stride_h, pad_h, dil_h);
+    int64_t Q = oracle_conv_out_extent(W, S, stride_w, pad_w, dil_w);
+    if (P <= 0 || Q <= 0) return ORACLE_BAD_ARG;
+    if (N == 0) return ORACLE_OK;
+    if (!x || !w || !y) return ORACLE_BAD_ARG;
+    int64_t Cg = C / groups, Kg = K / groups;
+    int nt = oracle_get_threads();
+    (void)nt;
+    int is_int = dtype == ORACLE_I8;
+    /* decode once; the loops below then read doubles / int64 */
+    double* xf = NULL; double* wf = NULL; int64_t* xi = NULL; int64_t* wi = NULL;
+    if (is_int) {
+        xi = gather_i(x, 1, N * H * W * C, 0, 1);
+        wi = gather_i(w, 1, K * R * S * Cg, 0, 1);
+        if (!xi || !wi) { free(xi); free(wi); return ORACLE_NO_MEMORY; }
+    } else {
+        xf = gather_f(dtype, x, 1, N * H * W * C, 0, 1);
+        wf = gather_f(dtype, w, 1, K * R * S * Cg, 0, 1);
+        if (!xf || !wf) { free(xf); free(wf); return ORACLE_NO_MEMORY; }
+    }
+#pragma omp parallel for collapse(2) schedule(static) num_threads(nt)
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t p = 0; p < P; ++p)
+            for (int64_t q = 0; q < Q; ++q)
+                for (int64_t k = 0; k < K; ++k) {
+                    int64_t g = k / Kg;
+                    double accf = 0.0, accs = 0.0;
+                    int64_t acci = 0;
+                    for (int64_t r = 0; r < R; ++r) {
+                        int64_t ih = p * stride_h - pad_h + r * dil_h;
+                        if (ih < 0 || ih >= H) continue; /* zero padding */
+                        for (int64_t s = 0; s < S; ++s) {
+                            int64_t iw = q * stride_w - pad_w + s * dil_w;
+                            if (iw < 0 || iw >= W) continue;
+                            int64_t xo = ((n * H + ih) * W + iw) * C + g * Cg;
+                            int64_t wo = ((k * R + r) * S + s) * Cg;
+                            for (int64_t c = 0; c < Cg; ++c) {
+                                if (is_int) {
+                                    acci += xi[xo + c] * wi[wo + c];
+                                } else {
+                                    double t = xf[xo + c] * wf[wo + c];
+                                    accf += t;
+                                    accs += fabs(t);
+                                }
+                            }
+                        }
+                    }
+                    int64_t o = ((n * P + p) * Q + q) * K + k;
+                    if (is_int) ((int64_t*)y)[o] = acci;
+                    else { ((double*)y)[o] = accf; if (Sabs) Sabs[o] = accs; }
+                }
+    free(xf); free(wf); free(xi); free(wi);
+    return ORACLE_OK;
+}

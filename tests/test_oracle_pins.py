@@ -1,0 +1,370 @@
+"""Pins for the CPU oracle: each checks it against something other than itself.
+
+The paper prints no numeric worked example for these operators, so the pins are bit-pattern
+decodes by numpy, per-element brute force with differently structured code, algebraic identities,
+closed forms, the conv == im2col-GEMM rewrite of section 4.2, and torch's fp64 CPU convolution as
+an independent library routine.
+"""
+import itertools
+
+import numpy as np
+import pytest
+
+from paper_2207_04296_amd import inputs as I
+
+
+# ----------------------------------------------------------------------------- decoders
+def test_decode_every_f16_pattern(oracle):
+    bits = np.arange(65536, dtype=np.uint16)
+    got = oracle.decode("f16", bits)
+    want = bits.view(np.float16).astype(np.float64)
+    assert np.array_equal(np.isnan(got), np.isnan(want))
+    m = ~np.isnan(want)
+    assert np.array_equal(got[m], want[m])
+    assert np.array_equal(np.signbit(got[m]), np.signbit(want[m]))
+
+
+def test_decode_every_bf16_pattern(oracle):
+    bits = np.arange(65536, dtype=np.uint16)
+    got = oracle.decode("bf16", bits)
+    with np.errstate(invalid="ignore"):
+        want = (bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    m = ~np.isnan(want)
+    assert np.array_equal(np.isnan(got), np.isnan(want))
+    assert np.array_equal(got[m], want[m])
+
+
+def test_decode_int8(oracle):
+    bits = np.arange(-128, 128, dtype=np.int8)
+    assert np.array_equal(oracle.decode("i8", bits), np.arange(-128, 128, dtype=np.float64))
+
+
+def test_known_f16_values(oracle):
+    # values fixed by IEEE 754 binary16: 1.0, -2.0, 65504 (max), 2^-24 (min subnormal), 2^-14 (min normal)
+    bits = np.array([0x3C00, 0xC000, 0x7BFF, 0x0001, 0x0400, 0x3555], dtype=np.uint16)
+    want = [1.0, -2.0, 65504.0, 2.0 ** -24, 2.0 ** -14, 0.333251953125]
+    assert oracle.decode("f16", bits).tolist() == want
+
+
+# ----------------------------------------------------------------------------- helpers
+def _vals(dtype, bits):
+    """Independent decode through numpy (not through the oracle)."""
+    if dtype == "i8":
+        return bits.astype(np.int64)
+    if dtype == "f16":
+        return bits.view(np.float16).astype(np.float64)
+    return (bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+def _brute_gemm(a, b):
+    """Per-element gather: one Python-level dot product per output element."""
+    M, K = a.shape
+    N = b.shape[1]
+    out = np.zeros((M, N), dtype=a.dtype)
+    for i, j in itertools.product(range(M), range(N)):
+        out[i, j] = sum(a[i, k] * b[k, j] for k in range(K))
+    return out
+
+
+def _brute_conv(x, w, stride, pad, dil, groups):
+    """Scatter formulation (loops over input pixels and taps, adds into the outputs they touch):
+    structurally different from the oracle's gather loops."""
+    N, H, W, C = x.shape
+    K, R, S, Cg = w.shape
+    P = (H + 2 * pad[0] - dil[0] * (R - 1) - 1) // stride[0] + 1
+    Q = (W + 2 * pad[1] - dil[1] * (S - 1) - 1) // stride[1] + 1
+    Kg = K // groups
+    y = np.zeros((N, P, Q, K), dtype=x.dtype)
+    for n, ih, iw, r, s in itertools.product(range(N), range(H), range(W), range(R), range(S)):
+        ph = ih + pad[0] - r * dil[0]
+        qw = iw + pad[1] - s * dil[1]
+        if ph < 0 or qw < 0 or ph % stride[0] or qw % stride[1]:
+            continue
+        p, q = ph // stride[0], qw // stride[1]
+        if p >= P or q >= Q:
+            continue
+        for k in range(K):
+            g = k // Kg
+            y[n, p, q, k] += np.dot(x[n, ih, iw, g * Cg:(g + 1) * Cg], w[k, r, s, :])
+    return y
+
+
+# ----------------------------------------------------------------------------- GEMM pins
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "i8"])
+@pytest.mark.parametrize("M,N,K", [(1, 1, 1), (2, 3, 4), (5, 4, 3), (3, 5, 5), (4, 1, 5)])
+def test_gemm_brute_force_tiny(oracle, dtype, M, N, K):
+    A = I.make_tensor(dtype, "u", 11 + M, (M, K))
+    B = I.make_tensor(dtype, "u", 12 + N, (K, N))
+    C, S = oracle.gemm(dtype, A, B, M, N, K, K, 1, N, 1)
+    a, b = _vals(dtype, A), _vals(dtype, B)
+    want = _brute_gemm(a, b)
+    if dtype == "i8":
+        assert np.array_equal(C, want)
+    else:
+        np.testing.assert_allclose(C, want, rtol=0, atol=1e-13)
+        np.testing.assert_allclose(S, _brute_gemm(np.abs(a), np.abs(b)), rtol=0, atol=1e-13)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "i8"])
+def test_gemm_strides_transposed_operands(oracle, dtype):
+    # A stored as [K,M] and B stored as [N,K], addressed through strides; non-square so a
+    # transposed-operand mistake changes the answer (or the shape).
+    M, N, K = 4, 5, 3
+    At = I.make_tensor(dtype, "u", 21, (K, M))
+    Bt = I.make_tensor(dtype, "u", 22, (N, K))
+    C, _ = oracle.gemm(dtype, At, Bt, M, N, K, 1, M, 1, K)
+    want = _brute_gemm(_vals(dtype, At).T.copy(), _vals(dtype, Bt).T.copy())
+    if dtype == "i8":
+        assert np.array_equal(C, want)
+    else:
+        np.testing.assert_allclose(C, want, rtol=0, atol=1e-13)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "i8"])
+def test_gemm_identity(oracle, dtype):
+    n = 17
+    A = I.make_tensor(dtype, "u", 31, (n, n))
+    one = {"f16": 0x3C00, "bf16": 0x3F80}.get(dtype, 1)
+    eye = np.zeros((n, n), dtype=A.dtype)
+    eye[np.arange(n), np.arange(n)] = one
+    C1, _ = oracle.gemm(dtype, A, eye, n, n, n, n, 1, n, 1)
+    C2, _ = oracle.gemm(dtype, eye, A, n, n, n, n, 1, n, 1)
+    assert np.array_equal(C1, _vals(dtype, A))
+    assert np.array_equal(C2, _vals(dtype, A))
+
+
+def test_gemm_closed_forms(oracle):
+    # A = 1, B = 1  =>  C = K ; A[i,k] = i, B[k,j] = j  =>  C = K*i*j  (all exactly representable)
+    M, N, K = 33, 20, 47
+    ones_a = np.full((M, K), 0x3C00, dtype=np.uint16)
+    ones_b = np.full((K, N), 0x3C00, dtype=np.uint16)
+    C, S = oracle.gemm("f16", ones_a, ones_b, M, N, K, K, 1, N, 1)
+    assert np.all(C == K) and np.all(S == K)
+    a = np.repeat(np.arange(M, dtype=np.float64)[:, None], K, axis=1)
+    b = np.repeat(np.arange(N, dtype=np.float64)[None, :], K, axis=0)
+    C, _ = oracle.gemm("f16", I.to_f16_bits(a), I.to_f16_bits(b), M, N, K, K, 1, N, 1)
+    assert np.array_equal(C, K * np.outer(np.arange(M), np.arange(N)))
+    # int8 at the largest magnitude the workloads reach: 2048 * 127 * 127 fits in int32
+    a8 = np.full((2, 2048), 127, dtype=np.int8)
+    b8 = np.full((2048, 3), -127, dtype=np.int8)
+    C, _ = oracle.gemm("i8", a8, b8, 2, 3, 2048, 2048, 1, 3, 1)
+    assert np.all(C == -2048 * 127 * 127) and abs(int(C[0, 0])) < 2 ** 31
+
+
+def test_gemm_k_zero_is_reduction_init(oracle):
+    C, S = oracle.gemm("f16", np.zeros(0, np.uint16), np.zeros(0, np.uint16), 3, 4, 0, 0, 1, 4, 1)
+    assert np.all(C == 0) and np.all(S == 0)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "i8"])
+def test_gemm_linearity_in_each_input(oracle, dtype):
+    # small-integer-valued operands: every intermediate is exact, so linearity must hold exactly
+    M, N, K = 9, 7, 13
+    rng = np.random.default_rng(5)
+
+    def enc(v):
+        return v.astype(np.int8) if dtype == "i8" else I.to_f16_bits(v.astype(np.float64))
+
+    A1, A2 = rng.integers(-7, 8, (M, K)), rng.integers(-7, 8, (M, K))
+    B1, B2 = rng.integers(-7, 8, (K, N)), rng.integers(-7, 8, (K, N))
+    f = lambda a, b: oracle.gemm(dtype, enc(a), enc(b), M, N, K, K, 1, N, 1)[0]
+    assert np.array_equal(f(3 * A1 + A2, B1), 3 * f(A1, B1) + f(A2, B1))
+    assert np.array_equal(f(A1, 3 * B1 + B2), 3 * f(A1, B1) + f(A1, B2))
+
+
+def test_gemm_matches_numpy_matmul_medium(oracle):
+    # library routine as the second opinion at a size spanning many rows / columns
+    M, N, K = 70, 50, 90
+    A = I.make_tensor("f16", "u", 41, (M, K))
+    B = I.make_tensor("f16", "u", 42, (K, N))
+    C, S = oracle.gemm("f16", A, B, M, N, K, K, 1, N, 1)
+    a, b = _vals("f16", A), _vals("f16", B)
+    np.testing.assert_allclose(C, a @ b, rtol=0, atol=1e-12)
+    np.testing.assert_allclose(S, np.abs(a) @ np.abs(b), rtol=1e-14, atol=0)
+
+
+# ----------------------------------------------------------------------------- BMM pins
+@pytest.mark.parametrize("dtype", ["f16", "i8"])
+def test_bmm_is_loop_of_gemms_and_broadcast(oracle, dtype):
+    Bn, M, N, K = 3, 4, 5, 6
+    A = I.make_tensor(dtype, "u", 51, (Bn, M, K))
+    B = I.make_tensor(dtype, "u", 52, (Bn, N, K))       # stored transposed, like K in Q.K^T
+    C, S = oracle.batch_matmul(dtype, A, B, Bn, M, N, K, M * K, K, 1, N * K, 1, K)
+    a, b = _vals(dtype, A), _vals(dtype, B)
+    want = np.einsum("bik,bjk->bij", a, b)
+    if dtype == "i8":
+        assert np.array_equal(C, want)
+    else:
+        np.testing.assert_allclose(C, want, rtol=0, atol=1e-13)
+        np.testing.assert_allclose(S, np.einsum("bik,bjk->bij", np.abs(a), np.abs(b)), rtol=0, atol=1e-13)
+    # batch stride 0 on B: every batch multiplies by the first matrix
+    C0, _ = oracle.batch_matmul(dtype, A, B, Bn, M, N, K, M * K, K, 1, 0, 1, K)
+    want0 = np.einsum("bik,jk->bij", a, b[0])
+    if dtype == "i8":
+        assert np.array_equal(C0, want0)
+    else:
+        np.testing.assert_allclose(C0, want0, rtol=0, atol=1e-13)
+
+
+# ----------------------------------------------------------------------------- conv pins
+_CONV_CASES = [
+    # N,H,W,C,K,R,S, stride, pad, dil, groups
+    (1, 5, 5, 2, 2, 3, 3, (1, 1), (0, 0), (1, 1), 1),
+    (2, 5, 4, 4, 4, 3, 2, (2, 1), (1, 2), (1, 1), 2),
+    (1, 5, 5, 4, 4, 2, 2, (1, 2), (2, 0), (2, 2), 4),     # depth-wise, dilated
+    (2, 4, 5, 3, 2, 3, 3, (2, 2), (1, 1), (1, 2), 1),
+    (1, 3, 3, 2, 4, 1, 1, (1, 1), (0, 0), (1, 1), 2),
+    (1, 5, 5, 2, 2, 3, 3, (1, 1), (2, 2), (2, 2), 1),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "i8"])
+@pytest.mark.parametrize("case", _CONV_CASES)
+def test_conv_brute_force_scatter(oracle, dtype, case):
+    N, H, W, C, K, R, S, stride, pad, dil, groups = case
+    x = I.make_tensor(dtype, "u", 61, (N, H, W, C))
+    w = I.make_tensor(dtype, "u", 62, (K, R, S, C // groups))
+    y, Sabs = oracle.conv2d(dtype, x, w, stride, pad, dil, groups)
+    xv, wv = _vals(dtype, x), _vals(dtype, w)
+    want = _brute_conv(xv, wv, stride, pad, dil, groups)
+    assert y.shape == want.shape
+    if dtype == "i8":
+        assert np.array_equal(y, want)
+    else:
+        np.testing.assert_allclose(y, want, rtol=0, atol=1e-13)
+        np.testing.assert_allclose(Sabs, _brute_conv(np.abs(xv), np.abs(wv), stride, pad, dil, groups),
+                                   rtol=0, atol=1e-13)
+
+
+def _im2col(xv, R, S, stride, pad, dil):
+    """A_t[fuse(n,h,w), fuse(rh,rw,rc)] of section 4.2, materialised (zero rows for padding)."""
+    N, H, W, C = xv.shape
+    P = (H + 2 * pad[0] - dil[0] * (R - 1) - 1) // stride[0] + 1
+    Q = (W + 2 * pad[1] - dil[1] * (S - 1) - 1) // stride[1] + 1
+    xp = np.zeros((N, H + 2 * pad[0], W + 2 * pad[1], C), dtype=xv.dtype)
+    xp[:, pad[0]:pad[0] + H, pad[1]:pad[1] + W, :] = xv
+    cols = np.zeros((N, P, Q, R, S, C), dtype=xv.dtype)
+    for r in range(R):
+        for s in range(S):
+            cols[:, :, :, r, s, :] = xp[:, r * dil[0]: r * dil[0] + (P - 1) * stride[0] + 1: stride[0],
+                                        s * dil[1]: s * dil[1] + (Q - 1) * stride[1] + 1: stride[1], :]
+    return cols.reshape(N * P * Q, R * S * C), (N, P, Q)
+
+
+@pytest.mark.parametrize("stride,pad,dil", [((1, 1), (1, 1), (1, 1)), ((2, 2), (1, 1), (1, 1)),
+                                            ((1, 1), (2, 2), (2, 2)), ((2, 1), (0, 3), (1, 2))])
+def test_conv_equals_im2col_gemm_exact_int(oracle, stride, pad, dil):
+    # Section 4.2: C_t[fuse(n,h,w), co] += A_t[fuse(n,h,w), fuse(rh,rw,rc)] * B_t[fuse(rh,rw,rc), co].
+    # The GEMM side also goes through the oracle's GEMM, so the two operators pin each other and
+    # both are pinned to numpy by the integer matmul below.
+    N, H, W, C, K, R, S = 2, 9, 8, 6, 5, 3, 3
+    x = I.make_tensor("i8", "i", 71, (N, H, W, C))
+    w = I.make_tensor("i8", "i", 72, (K, R, S, C))
+    y, _ = oracle.conv2d("i8", x, w, stride, pad, dil, 1)
+    At, (n, p, q) = _im2col(x.astype(np.int64), R, S, stride, pad, dil)
+    Bt = w.astype(np.int64).reshape(K, R * S * C).T            # [fuse(rh,rw,rc), co]
+    assert np.array_equal(y.reshape(n * p * q, K), At @ Bt)
+    Kd = R * S * C
+    Cg, _ = oracle.gemm("i8", At.astype(np.int8), w.reshape(K, Kd), n * p * q, K, Kd, Kd, 1, 1, Kd)
+    assert np.array_equal(y.reshape(n * p * q, K), Cg)
+
+
+def test_conv_1x1_is_gemm(oracle):
+    N, H, W, C, K = 2, 4, 3, 8, 5
+    x = I.make_tensor("f16", "u", 81, (N, H, W, C))
+    w = I.make_tensor("f16", "u", 82, (K, 1, 1, C))
+    y, S1 = oracle.conv2d("f16", x, w)
+    Cg, S2 = oracle.gemm("f16", x, w, N * H * W, K, C, C, 1, 1, C)
+    assert np.array_equal(y.reshape(-1, K), Cg)
+    assert np.array_equal(S1.reshape(-1, K), S2)
+    np.testing.assert_allclose(Cg, _vals("f16", x).reshape(-1, C) @ _vals("f16", w).reshape(K, C).T, atol=1e-13)
+
+
+def test_conv_delta_input_shows_filter_footprint(oracle):
+    # a single 1 at (ih, iw, c0): y[p,q,k] = w[k,r,s,c0] where p*s_h - pad + r*d_h = ih etc.
+    H = W = 9
+    C, K, R, S = 3, 2, 3, 3
+    stride, pad, dil = (2, 1), (2, 2), (2, 1)
+    ih, iw, c0 = 4, 5, 1
+    x = np.zeros((1, H, W, C), dtype=np.int8)
+    x[0, ih, iw, c0] = 1
+    w = I.make_tensor("i8", "i", 91, (K, R, S, C))
+    y, _ = oracle.conv2d("i8", x, w, stride, pad, dil, 1)
+    want = np.zeros_like(y)
+    P, Q = y.shape[1:3]
+    for r in range(R):
+        for s in range(S):
+            ph, qw = ih + pad[0] - r * dil[0], iw + pad[1] - s * dil[1]
+            if ph >= 0 and qw >= 0 and ph % stride[0] == 0 and qw % stride[1] == 0:
+                p, q = ph // stride[0], qw // stride[1]
+                if p < P and q < Q:
+                    want[0, p, q, :] += w[:, r, s, c0]
+    assert np.array_equal(y, want) and np.count_nonzero(want) > 0
+
+
+def test_conv_all_ones_counts_valid_taps(oracle):
+    # x = 1, w = 1: y = (C/G) * (#taps whose input coordinate is inside the image), a closed form
+    # that separates rows and columns.
+    N, H, W, C, K, R, S, groups = 1, 7, 6, 4, 4, 3, 3, 2
+    stride, pad, dil = (1, 2), (2, 1), (2, 1)
+    x = np.ones((N, H, W, C), dtype=np.int8)
+    w = np.ones((K, R, S, C // groups), dtype=np.int8)
+    y, _ = oracle.conv2d("i8", x, w, stride, pad, dil, groups)
+    P, Q = y.shape[1:3]
+    rows = np.array([sum(0 <= p * stride[0] - pad[0] + r * dil[0] < H for r in range(R)) for p in range(P)])
+    cols = np.array([sum(0 <= q * stride[1] - pad[1] + s * dil[1] < W for s in range(S)) for q in range(Q)])
+    want = (C // groups) * np.outer(rows, cols)
+    for k in range(K):
+        assert np.array_equal(y[0, :, :, k], want)
+    assert want.max() == R * S * (C // groups) and want.min() < want.max()
+
+
+def test_conv_groups_are_independent_convs(oracle):
+    N, H, W, C, K, R, S, G = 2, 6, 6, 8, 6, 3, 3, 2
+    x = I.make_tensor("f16", "u", 101, (N, H, W, C))
+    w = I.make_tensor("f16", "u", 102, (K, R, S, C // G))
+    y, _ = oracle.conv2d("f16", x, w, (1, 1), (1, 1), (1, 1), G)
+    Cg, Kg = C // G, K // G
+    for g in range(G):
+        yg, _ = oracle.conv2d("f16", np.ascontiguousarray(x[..., g * Cg:(g + 1) * Cg]),
+                              np.ascontiguousarray(w[g * Kg:(g + 1) * Kg]), (1, 1), (1, 1), (1, 1), 1)
+        assert np.array_equal(y[..., g * Kg:(g + 1) * Kg], yg)
+
+
+@pytest.mark.parametrize("case", [
+    (2, 12, 11, 8, 6, 3, 3, (1, 1), (1, 1), (1, 1), 1),
+    (2, 12, 11, 8, 6, 3, 3, (2, 2), (1, 1), (1, 1), 1),
+    (1, 13, 12, 8, 8, 3, 3, (1, 1), (2, 2), (2, 2), 4),
+    (1, 10, 9, 6, 6, 5, 3, (2, 1), (2, 1), (1, 2), 6),
+    (3, 7, 7, 4, 10, 1, 1, (1, 1), (0, 0), (1, 1), 2),
+])
+def test_conv_matches_torch_fp64_library(oracle, case):
+    torch = pytest.importorskip("torch")
+    N, H, W, C, K, R, S, stride, pad, dil, groups = case
+    x = I.make_tensor("f16", "n0.1", 111, (N, H, W, C))
+    w = I.make_tensor("f16", "n0.1", 112, (K, R, S, C // groups))
+    y, _ = oracle.conv2d("f16", x, w, stride, pad, dil, groups)
+    xt = torch.from_numpy(_vals("f16", x)).permute(0, 3, 1, 2)              # NCHW
+    wt = torch.from_numpy(_vals("f16", w)).permute(0, 3, 1, 2)              # K,C/g,R,S
+    ref = torch.nn.functional.conv2d(xt, wt, None, stride, pad, dil, groups).permute(0, 2, 3, 1).numpy()
+    assert y.shape == ref.shape
+    np.testing.assert_allclose(y, ref, rtol=0, atol=1e-12)
+
+
+def test_conv_out_extent_rule(oracle):
+    assert oracle.conv_out_extent(56, 3, 1, 1, 1) == 56
+    assert oracle.conv_out_extent(28, 3, 2, 1, 1) == 14
+    assert oracle.conv_out_extent(28, 3, 1, 2, 2) == 28
+    assert oracle.conv_out_extent(2, 3, 1, 0, 1) == 0          # filter does not fit
+    assert oracle.conv_out_extent(7, 3, 2, 0, 1) == 3
+
+
+def test_conv_linearity_in_each_input(oracle):
+    rng = np.random.default_rng(9)
+    shape_x, shape_w = (1, 6, 6, 4), (4, 3, 3, 2)
+    X1, X2 = rng.integers(-5, 6, shape_x), rng.integers(-5, 6, shape_x)
+    W1, W2 = rng.integers(-5, 6, shape_w), rng.integers(-5, 6, shape_w)
+    enc = lambda v: I.to_f16_bits(v.astype(np.float64))
+    f = lambda x, w: oracle.conv2d("f16", enc(x), enc(w), (1, 1), (1, 1), (2, 2), 2)[0]
+    assert np.array_equal(f(2 * X1 + X2, W1), 2 * f(X1, W1) + f(X2, W1))
+    assert np.array_equal(f(X1, 2 * W1 + W2), 2 * f(X1, W1) + f(X1, W2))
