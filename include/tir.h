@@ -1,0 +1,117 @@
+/*
+ * tir.h — C ABI of the MI355X (gfx950) tensor-contraction library.
+ *
+ * Three operators, each computed by decomposing its loop nest into blocks that map onto one
+ * MFMA tile (the hardware tensor intrinsic C[x,y] += A[x,k] * B[k,y], TensorIR paper Eq. 1):
+ *
+ *   tir_gemm          C[x,y]       = sum_k A[x,k] * B[k,y]                     (Eq. 1)
+ *   tir_batch_matmul  C[b,i,j]     = sum_r A[b,i,r] * B[b,r,j]                 (sec. 4.2; x,y,k -> i,j,r,
+ *                                                                               b stays a data-parallel loop)
+ *   tir_conv2d        C[n,h,w,co]  = sum A[n, h*s_h + rh*d_h - pad_h, w*s_w + rw*d_w - pad_w, rc]
+ *                                        * W[co, rh, rw, rc]                   (sec. 4.2 Conv2D formula;
+ *                       mapped onto Eq. 1 by ReIndex + fuse: x = fuse(n,h,w), y = co, k = fuse(rh,rw,rc))
+ *
+ * Common conventions
+ *   - Every pointer is a DEVICE pointer owned by the caller.  The library never allocates, frees,
+ *     copies to the host or synchronises; each call enqueues kernels on `stream` and returns.
+ *   - The output is fully overwritten (reduction init is 0; there is no alpha / beta), and must not
+ *     overlap an input.
+ *   - Inputs F16 / BF16 accumulate in fp32; input I8 accumulates in int32 (wrap-around on overflow,
+ *     which inputs in [-127,127] with K <= 133000 cannot reach).
+ *   - Allowed (in, out) pairs: (F16, F32) (F16, F16) (BF16, F32) (BF16, BF16) (I8, I32).
+ *     16-bit outputs are rounded to nearest even from the fp32 accumulator.
+ *   - Strides are in ELEMENTS and must be >= 0.  Any strides are accepted; the fast kernels need the
+ *     reduction axis or the other axis of each input contiguous (stride 1), 16-byte aligned base
+ *     pointers and leading strides that are multiples of 16 bytes, and a unit column stride on C.
+ *     Everything else runs on a slower general kernel with the same results.
+ *   - Return value: TIR_OK or an error code; on error nothing was launched and tir_last_error()
+ *     describes the problem.  No C++ exception crosses this boundary.
+ *   - Zero-sized M, N, batch (or conv batch N) is a successful no-op.  K == 0 zero-fills C.
+ */
+#ifndef TIR_H_
+#define TIR_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    TIR_OK = 0,
+    TIR_ERR_INVALID_ARG = 1,  /* null pointer, negative size or stride, bad dtype code, groups not dividing */
+    TIR_ERR_UNSUPPORTED = 2,  /* a (in, out) dtype pair outside the list above, or sizes beyond 2^31-1 */
+    TIR_ERR_ALIGNMENT = 3,    /* pointer not aligned to its element size */
+    TIR_ERR_LAUNCH = 4        /* the HIP runtime refused the launch; message holds hipGetErrorString */
+} tir_status;
+
+typedef enum { TIR_F16 = 0, TIR_BF16 = 1, TIR_I8 = 2, TIR_F32 = 3, TIR_I32 = 4 } tir_dtype;
+
+/* Opaque stream handle: pass a hipStream_t (NULL = the default stream). */
+typedef void* tir_stream;
+
+/*
+ * GEMM, Eq. 1.  Element (i,k) of A is A[i*a_rs + k*a_cs], (k,j) of B is B[k*b_rs + j*b_cs],
+ * (i,j) of C is C[i*c_rs + j*c_cs].  Row-major operands: a_rs=K,a_cs=1, b_rs=N,b_cs=1, c_rs=N,c_cs=1;
+ * a transposed operand is expressed by swapping its strides.
+ */
+tir_status tir_gemm(const void* A, const void* B, void* C, int64_t M, int64_t N, int64_t K,
+                    int64_t a_rs, int64_t a_cs, int64_t b_rs, int64_t b_cs, int64_t c_rs, int64_t c_cs,
+                    tir_dtype in, tir_dtype out, tir_stream stream);
+
+/*
+ * Batched matmul (sec. 4.2): C[b] = A[b] * B[b] for b < batch.  *_bs are batch strides in
+ * elements; a_bs or b_bs may be 0 (the same matrix for every batch), c_bs must make the C
+ * matrices disjoint.
+ */
+tir_status tir_batch_matmul(const void* A, const void* B, void* C, int64_t batch, int64_t M, int64_t N,
+                            int64_t K, int64_t a_bs, int64_t a_rs, int64_t a_cs, int64_t b_bs, int64_t b_rs,
+                            int64_t b_cs, int64_t c_bs, int64_t c_rs, int64_t c_cs, tir_dtype in,
+                            tir_dtype out, tir_stream stream);
+
+/*
+ * 2-D convolution (sec. 4.2), cross-correlation with zero padding.
+ *   x: [N,H,W,C] NHWC, dense.   w: [K,R,S,C/groups], dense (filter of output channel k, tap (r,s)).
+ *   y: [N,P,Q,K] NHWC, dense, P = floor((H + 2*pad_h - dil_h*(R-1) - 1)/stride_h) + 1, Q likewise.
+ *   Output channel k belongs to group k / (K/groups) and reads input channels
+ *   [g*C/groups, (g+1)*C/groups).  groups must divide C and K; P and Q must be >= 1.
+ * The im2col matrix is never materialised: input coordinates are recomputed from the fused
+ * iterators inside the kernel.
+ */
+tir_status tir_conv2d(const void* x, const void* w, void* y, int64_t N, int64_t H, int64_t W, int64_t C,
+                      int64_t K, int64_t R, int64_t S, int stride_h, int stride_w, int pad_h, int pad_w,
+                      int dil_h, int dil_w, int groups, tir_dtype in, tir_dtype out, tir_stream stream);
+
+/* Message for the calling thread's last failed call ("" if none).  Never NULL; valid until the
+ * thread's next failing call. */
+const char* tir_last_error(void);
+
+/*
+ * Name of the kernel variant the next identical call would launch (for profiling harnesses), e.g.
+ * "f16_f32_t256x256x64_akm_bnm".  Arguments as for tir_batch_matmul / tir_conv2d without pointers
+ * being dereferenced; returns "" on invalid arguments.  The string is static.
+ */
+const char* tir_gemm_variant(int64_t batch, int64_t M, int64_t N, int64_t K, int64_t a_rs, int64_t a_cs,
+                             int64_t b_rs, int64_t b_cs, int64_t c_rs, int64_t c_cs, tir_dtype in,
+                             tir_dtype out);
+const char* tir_conv2d_variant(int64_t N, int64_t H, int64_t W, int64_t C, int64_t K, int64_t R, int64_t S,
+                               int stride_h, int stride_w, int pad_h, int pad_w, int dil_h, int dil_w,
+                               int groups, tir_dtype in, tir_dtype out);
+
+/*
+ * Testing / tuning hooks (process-wide, not thread-safe).
+ * tir_debug_force_tile: make later calls use the bm x bn workgroup tile when the chosen copy mode
+ * has such a variant (0,0 restores the automatic choice).
+ * tir_debug_tile_of_block: host copy of the kernels' workgroup-id -> output-tile map (a bijection
+ * of [0, tiles_m*tiles_n) that keeps the tiles of one L2 domain adjacent).
+ */
+void tir_debug_force_tile(int bm, int bn);
+void tir_debug_tile_of_block(int bid, int tiles_m, int tiles_n, int* tm, int* tn);
+
+/* Library version as "major.minor". */
+const char* tir_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TIR_H_ */

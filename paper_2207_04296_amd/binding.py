@@ -1,0 +1,191 @@
+"""ctypes binding of libtir.so: same names as the C ABI, argument marshalling only.
+
+Every operator call ends in one of the ``extern "C"`` entry points declared in ``include/tir.h``;
+there is no Python or PyTorch fallback.  If the library has not been built, loading fails loudly.
+PyTorch is used for device memory and streams only.
+"""
+from __future__ import annotations
+
+import ctypes
+from pathlib import Path
+
+_PKG = Path(__file__).resolve().parent
+_LIBPATH = _PKG / "libtir.so"
+
+TIR_OK, TIR_ERR_INVALID_ARG, TIR_ERR_UNSUPPORTED, TIR_ERR_ALIGNMENT, TIR_ERR_LAUNCH = range(5)
+TIR_F16, TIR_BF16, TIR_I8, TIR_F32, TIR_I32 = range(5)
+DTYPE_CODES = {"f16": TIR_F16, "bf16": TIR_BF16, "i8": TIR_I8, "f32": TIR_F32, "i32": TIR_I32}
+
+EXPORTS = ["tir_gemm", "tir_batch_matmul", "tir_conv2d", "tir_last_error", "tir_gemm_variant",
+           "tir_conv2d_variant", "tir_debug_force_tile", "tir_debug_tile_of_block", "tir_version"]
+
+
+class TirError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"tir status {status}: {message}")
+        self.status = status
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load libtir.so (built by ``python -m paper_2207_04296_amd.buildlib``)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not _LIBPATH.exists():
+        raise RuntimeError(f"{_LIBPATH} is missing: build it with `python -m paper_2207_04296_amd.buildlib` "
+                           "(there is no fallback path)")
+    L = ctypes.CDLL(str(_LIBPATH))
+    i64, vp, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
+    L.tir_gemm.argtypes = [vp, vp, vp] + [i64] * 9 + [ci, ci, vp]
+    L.tir_gemm.restype = ci
+    L.tir_batch_matmul.argtypes = [vp, vp, vp] + [i64] * 13 + [ci, ci, vp]
+    L.tir_batch_matmul.restype = ci
+    L.tir_conv2d.argtypes = [vp, vp, vp] + [i64] * 7 + [ci] * 7 + [ci, ci, vp]
+    L.tir_conv2d.restype = ci
+    L.tir_last_error.restype = ctypes.c_char_p
+    L.tir_gemm_variant.argtypes = [i64] * 10 + [ci, ci]
+    L.tir_gemm_variant.restype = ctypes.c_char_p
+    L.tir_conv2d_variant.argtypes = [i64] * 7 + [ci] * 7 + [ci, ci]
+    L.tir_conv2d_variant.restype = ctypes.c_char_p
+    L.tir_debug_force_tile.argtypes = [ci, ci]
+    L.tir_debug_force_tile.restype = None
+    L.tir_debug_tile_of_block.argtypes = [ci, ci, ci, ctypes.POINTER(ci), ctypes.POINTER(ci)]
+    L.tir_debug_tile_of_block.restype = None
+    L.tir_version.restype = ctypes.c_char_p
+    _lib = L
+    return L
+
+
+def _ptr(t) -> int:
+    """Device pointer of a torch tensor, or an int passed through."""
+    if t is None:
+        return 0
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def _code(d) -> int:
+    return DTYPE_CODES[d] if isinstance(d, str) else int(d)
+
+
+def _check(status: int) -> None:
+    if status != TIR_OK:
+        raise TirError(status, lib().tir_last_error().decode())
+
+
+def last_error() -> str:
+    return lib().tir_last_error().decode()
+
+
+def tir_gemm_status(A, B, C, M, N, K, a_rs, a_cs, b_rs, b_cs, c_rs, c_cs, in_dtype, out_dtype, stream=0) -> int:
+    """Raw call returning the status code (used by the error-path tests; needs no GPU to fail)."""
+    return lib().tir_gemm(_ptr(A), _ptr(B), _ptr(C), M, N, K, a_rs, a_cs, b_rs, b_cs, c_rs, c_cs,
+                          _code(in_dtype), _code(out_dtype), stream)
+
+
+def tir_batch_matmul_status(A, B, C, batch, M, N, K, a_bs, a_rs, a_cs, b_bs, b_rs, b_cs, c_bs, c_rs, c_cs,
+                            in_dtype, out_dtype, stream=0) -> int:
+    return lib().tir_batch_matmul(_ptr(A), _ptr(B), _ptr(C), batch, M, N, K, a_bs, a_rs, a_cs, b_bs, b_rs, b_cs,
+                                  c_bs, c_rs, c_cs, _code(in_dtype), _code(out_dtype), stream)
+
+
+def tir_conv2d_status(x, w, y, N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, groups,
+                      in_dtype, out_dtype, stream=0) -> int:
+    return lib().tir_conv2d(_ptr(x), _ptr(w), _ptr(y), N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w,
+                            dil_h, dil_w, groups, _code(in_dtype), _code(out_dtype), stream)
+
+
+def tir_gemm(A, B, C, M, N, K, a_rs, a_cs, b_rs, b_cs, c_rs, c_cs, in_dtype, out_dtype, stream=None) -> None:
+    _check(tir_gemm_status(A, B, C, M, N, K, a_rs, a_cs, b_rs, b_cs, c_rs, c_cs, in_dtype, out_dtype,
+                           _stream(stream)))
+
+
+def tir_batch_matmul(A, B, C, batch, M, N, K, a_bs, a_rs, a_cs, b_bs, b_rs, b_cs, c_bs, c_rs, c_cs,
+                     in_dtype, out_dtype, stream=None) -> None:
+    _check(tir_batch_matmul_status(A, B, C, batch, M, N, K, a_bs, a_rs, a_cs, b_bs, b_rs, b_cs, c_bs, c_rs, c_cs,
+                                   in_dtype, out_dtype, _stream(stream)))
+
+
+def tir_conv2d(x, w, y, N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, groups,
+               in_dtype, out_dtype, stream=None) -> None:
+    _check(tir_conv2d_status(x, w, y, N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, groups,
+                             in_dtype, out_dtype, _stream(stream)))
+
+
+def tir_gemm_variant(batch, M, N, K, a_rs, a_cs, b_rs, b_cs, c_rs, c_cs, in_dtype, out_dtype) -> str:
+    return lib().tir_gemm_variant(batch, M, N, K, a_rs, a_cs, b_rs, b_cs, c_rs, c_cs, _code(in_dtype),
+                                  _code(out_dtype)).decode()
+
+
+def tir_conv2d_variant(N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, groups, in_dtype,
+                       out_dtype) -> str:
+    return lib().tir_conv2d_variant(N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, groups,
+                                    _code(in_dtype), _code(out_dtype)).decode()
+
+
+def tir_debug_force_tile(bm: int, bn: int) -> None:
+    lib().tir_debug_force_tile(bm, bn)
+
+
+def tir_debug_tile_of_block(bid: int, tiles_m: int, tiles_n: int):
+    tm, tn = ctypes.c_int(), ctypes.c_int()
+    lib().tir_debug_tile_of_block(bid, tiles_m, tiles_n, ctypes.byref(tm), ctypes.byref(tn))
+    return tm.value, tn.value
+
+
+def tir_version() -> str:
+    return lib().tir_version().decode()
+
+
+# ------------------------------------------------------------------------------------------------
+# device-memory plumbing for harnesses (bits <-> torch tensors); no arithmetic
+# ------------------------------------------------------------------------------------------------
+def to_device(bits, dtype: str, device="cuda:0"):
+    """numpy raw bits (uint16 / int8) -> torch device tensor of the matching dtype."""
+    import numpy as np
+    import torch
+    if dtype == "i8":
+        return torch.from_numpy(np.ascontiguousarray(bits)).to(device)
+    t = torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(device)
+    return t.view(torch.float16 if dtype == "f16" else torch.bfloat16)
+
+
+def empty_out(shape, out_dtype: str, device="cuda:0"):
+    import torch
+    dt = {"f32": torch.float32, "i32": torch.int32, "f16": torch.float16, "bf16": torch.bfloat16}[out_dtype]
+    return torch.empty(shape, dtype=dt, device=device)
+
+
+def run_workload(wl, a_dev, b_dev, c_dev, stream=None) -> None:
+    """Launch one paper_2207_04296_amd.inputs.Workload on resident operands."""
+    if wl.kind == "conv2d":
+        tir_conv2d(a_dev, b_dev, c_dev, wl.n, wl.h, wl.w, wl.c, wl.k, wl.r, wl.s, wl.stride[0], wl.stride[1],
+                   wl.pad[0], wl.pad[1], wl.dil[0], wl.dil[1], wl.groups, wl.dtype, wl.out, stream)
+        return
+    M, N, K = wl.M, wl.N, wl.K
+    b_rs, b_cs = (1, K) if wl.trans_b else (N, 1)
+    if wl.kind == "gemm":
+        tir_gemm(a_dev, b_dev, c_dev, M, N, K, K, 1, b_rs, b_cs, N, 1, wl.dtype, wl.out, stream)
+    else:
+        tir_batch_matmul(a_dev, b_dev, c_dev, wl.batch, M, N, K, M * K, K, 1, K * N, b_rs, b_cs, M * N, N, 1,
+                         wl.dtype, wl.out, stream)
+
+
+def out_shape(wl):
+    if wl.kind == "conv2d":
+        p, q = wl.out_hw()
+        return (wl.n, p, q, wl.k)
+    return (wl.batch, wl.M, wl.N) if wl.kind == "bmm" else (wl.M, wl.N)

@@ -1,0 +1,68 @@
+"""Build libtir.so (HIP kernels + C ABI) for gfx950 with hipcc, in-tree.
+
+``python -m paper_2207_04296_amd.buildlib`` compiles every translation unit (in parallel) and
+links ``paper_2207_04296_amd/libtir.so``.  Nothing is compiled at import time or inside tests.
+"""
+from __future__ import annotations
+
+import os
+import subprocess
+import sys
+from concurrent.futures import ThreadPoolExecutor
+from pathlib import Path
+
+PKG = Path(__file__).resolve().parent
+CSRC = PKG / "csrc"
+INCLUDE = PKG.parent / "include"
+OBJ = PKG / "_build"
+LIB = PKG / "libtir.so"
+N_UNITS = 5
+
+HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-but-set-variable",
+         "-Wno-unused-variable", "-Wno-unused-local-typedef",
+         # packed fp32 instructions are kept off for every kernel of this library
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         f"-I{INCLUDE}", f"-I{CSRC}"]
+
+
+def _compile(args):
+    src, obj, extra = args
+    cmd = [HIPCC, *FLAGS, *extra, "-c", str(src), "-o", str(obj)]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
+    if r.returncode != 0:
+        raise RuntimeError(f"hipcc failed: {' '.join(cmd)}\n{err}")
+    return err
+
+
+def sources():
+    return sorted(CSRC.glob("*.hip")) + sorted(CSRC.glob("*.h")) + sorted(CSRC.glob("*.def")) + [INCLUDE / "tir.h"]
+
+
+def is_stale() -> bool:
+    if not LIB.exists():
+        return True
+    t = LIB.stat().st_mtime
+    return any(s.stat().st_mtime > t for s in sources())
+
+
+def build(verbose: bool = True, jobs: int | None = None) -> Path:
+    OBJ.mkdir(exist_ok=True)
+    jobs_list = [(CSRC / "tir_api.hip", OBJ / "tir_api.o", [])]
+    for u in range(N_UNITS):
+        jobs_list.append((CSRC / "tir_inst.hip", OBJ / f"tir_inst{u}.o", [f"-DTIR_UNIT={u}"]))
+    with ThreadPoolExecutor(max_workers=jobs or min(8, os.cpu_count() or 1)) as ex:
+        for warn in ex.map(_compile, jobs_list):
+            if verbose and warn.strip():
+                print(warn, file=sys.stderr)
+    objs = [str(j[1]) for j in jobs_list]
+    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", str(LIB), *objs]
+    subprocess.run(cmd, check=True)
+    if verbose:
+        print(f"built {LIB}")
+    return LIB
+
+
+if __name__ == "__main__":
+    build()

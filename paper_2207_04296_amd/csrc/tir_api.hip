@@ -1,0 +1,256 @@
+// C-ABI entry points: argument validation, choice of kernel variant, launch.
+// Everything a caller can get wrong is caught here, before any HIP call, so that a bad call
+// never reaches a kernel.  See include/tir.h for the contract.
+#include <hip/hip_runtime.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "tir.h"
+#include "tir_launch.h"
+
+namespace tir {
+
+// ------------------------------------------------------------------------------- variant table
+#define TIR_ROW(name, DT, OUT, BM, BN, WM, WN, AM, BMO) \
+    {name, DT, OUT, BM, BN, WM * WN * 64, AM, BMO, &launch_cfg<Cfg<DT, OUT, BM, BN, WM, WN, AM, BMO>>},
+#define V0 TIR_ROW
+#define V1 TIR_ROW
+#define V2 TIR_ROW
+#define V3 TIR_ROW
+#define V4 TIR_ROW
+static const Variant kVariants[] = {
+#include "tir_variants.def"
+};
+static const int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
+
+static thread_local char g_err[512] = "";
+static int g_force_bm = 0, g_force_bn = 0;
+
+static tir_status fail(tir_status st, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+static const int64_t kMaxExtent = 2147483647LL;
+static const int kTargetTiles = 256;  // one workgroup per CU
+
+static bool dtype_pair_ok(int in, int out) {
+    return (in == TIR_F16 && (out == TIR_F32 || out == TIR_F16)) ||
+           (in == TIR_BF16 && (out == TIR_F32 || out == TIR_BF16)) || (in == TIR_I8 && out == TIR_I32);
+}
+
+static bool aligned(const void* p, uintptr_t a) { return ((uintptr_t)p % a) == 0; }
+
+// Pick a tile for (dt, out, amode, bmode): the largest listed tile that still yields at least
+// one workgroup per CU, else the tile giving the most workgroups (the smallest).
+static const Variant* pick(int dt, int out, int amode, int bmode, int64_t batch, int64_t M, int64_t N) {
+    const Variant* best = nullptr;
+    const Variant* smallest = nullptr;
+    for (int i = 0; i < kNumVariants; ++i) {
+        const Variant* v = &kVariants[i];
+        if (v->dt != dt || v->out != out || v->amode != amode || v->bmode != bmode) continue;
+        if (g_force_bm && v->bm == g_force_bm && v->bn == g_force_bn) return v;  // testing / tuning override
+        int64_t tiles = ((M + v->bm - 1) / v->bm) * ((N + v->bn - 1) / v->bn) * batch;
+        if (!smallest || v->bm * v->bn < smallest->bm * smallest->bn) smallest = v;
+        if (tiles >= kTargetTiles && (!best || v->bm * v->bn > best->bm * best->bn)) best = v;
+    }
+    return best ? best : smallest;
+}
+
+struct Plan {
+    const Variant* v;
+    Params p;
+};
+
+static tir_status check_common(const void* A, const void* B, const void* C, int in, int out) {
+    if (in < 0 || in > TIR_I32 || out < 0 || out > TIR_I32) return fail(TIR_ERR_INVALID_ARG, "unknown dtype code (in=%d out=%d)", in, out);
+    if (!dtype_pair_ok(in, out)) return fail(TIR_ERR_UNSUPPORTED, "unsupported (in, out) dtype pair (%d, %d)", in, out);
+    const int es = elem_size(in), os = elem_size(out);
+    if (!aligned(A, es) || !aligned(B, es)) return fail(TIR_ERR_ALIGNMENT, "input pointer not aligned to its element size");
+    if (!aligned(C, os)) return fail(TIR_ERR_ALIGNMENT, "output pointer not aligned to its element size");
+    return TIR_OK;
+}
+
+// Build the launch plan of a (batched) GEMM.  Pointers may be null only for planning (variant query).
+static tir_status plan_gemm(bool need_ptrs, const void* A, const void* B, void* C, int64_t batch, int64_t M, int64_t N,
+                            int64_t K, int64_t a_bs, int64_t a_rs, int64_t a_cs, int64_t b_bs, int64_t b_rs,
+                            int64_t b_cs, int64_t c_bs, int64_t c_rs, int64_t c_cs, int in, int out, Plan* plan) {
+    plan->v = nullptr;
+    tir_status st = check_common(A, B, C, in, out);
+    if (st != TIR_OK) return st;
+    if (batch < 0 || M < 0 || N < 0 || K < 0) return fail(TIR_ERR_INVALID_ARG, "negative extent (batch=%lld M=%lld N=%lld K=%lld)", (long long)batch, (long long)M, (long long)N, (long long)K);
+    if (a_bs < 0 || a_rs < 0 || a_cs < 0 || b_bs < 0 || b_rs < 0 || b_cs < 0 || c_bs < 0 || c_rs < 0 || c_cs < 0)
+        return fail(TIR_ERR_INVALID_ARG, "negative stride");
+    if (M > kMaxExtent || N > kMaxExtent || K > kMaxExtent || batch > kMaxExtent)
+        return fail(TIR_ERR_UNSUPPORTED, "extent beyond 2^31-1");
+    if (batch == 0 || M == 0 || N == 0) return TIR_OK;  // nothing to do, plan->v stays null
+    if (need_ptrs) {
+        if (!C) return fail(TIR_ERR_INVALID_ARG, "C is null");
+        if (K > 0 && (!A || !B)) return fail(TIR_ERR_INVALID_ARG, "A or B is null");
+    }
+    if (M > 1 && N > 1 && c_rs == 0 && c_cs == 0) return fail(TIR_ERR_INVALID_ARG, "C strides are both zero");
+    if (batch > 1 && c_bs == 0) return fail(TIR_ERR_INVALID_ARG, "c_bs is zero: the C matrices of different batches overlap");
+
+    const int es = elem_size(in);
+    const int vec = 16 / es;
+    const bool k_vec = K % vec == 0;
+    int amode = A_GENERIC, bmode = B_GENERIC;
+    // fast copy modes need 16-byte vectors along the contiguous axis
+    if (a_cs == 1 && k_vec && a_rs % vec == 0 && a_bs % vec == 0 && aligned(A, 16) && a_rs * es * 256 < kMaxExtent) amode = A_KMAJOR;
+    if (b_rs == 1 && k_vec && b_cs % vec == 0 && b_bs % vec == 0 && aligned(B, 16) && b_cs * es * 256 < kMaxExtent) bmode = B_KMAJOR;
+    else if (b_cs == 1 && N % vec == 0 && b_rs % vec == 0 && b_bs % vec == 0 && aligned(B, 16)) bmode = B_NMAJOR;
+    if (amode == A_GENERIC || bmode == B_GENERIC) { amode = A_GENERIC; bmode = B_GENERIC; }
+
+    const Variant* v = pick(in, out, amode, bmode, batch, M, N);
+    if (!v) return fail(TIR_ERR_UNSUPPORTED, "no kernel variant for this dtype / layout / forced tile");
+    Params& p = plan->p;
+    memset(&p, 0, sizeof p);
+    p.A = A; p.B = B; p.C = C;
+    p.M = (int)M; p.N = (int)N; p.K = (int)K;
+    p.batch = (int)batch;
+    p.tiles_m = (int)((M + v->bm - 1) / v->bm);
+    p.tiles_n = (int)((N + v->bn - 1) / v->bn);
+    if ((int64_t)p.tiles_m * p.tiles_n > kMaxExtent) return fail(TIR_ERR_UNSUPPORTED, "too many output tiles");
+    p.a_bs = a_bs; p.b_bs = b_bs; p.c_bs = c_bs;
+    p.a_rs = a_rs; p.a_cs = a_cs; p.b_rs = b_rs; p.b_cs = b_cs; p.c_rs = c_rs; p.c_cs = c_cs;
+    plan->v = v;
+    return TIR_OK;
+}
+
+static int64_t conv_extent(int64_t in, int64_t filt, int64_t stride, int64_t pad, int64_t dil) {
+    int64_t span = in + 2 * pad - dil * (filt - 1) - 1;
+    return span < 0 ? 0 : span / stride + 1;
+}
+
+static tir_status plan_conv(bool need_ptrs, const void* x, const void* w, void* y, int64_t N, int64_t H, int64_t W,
+                            int64_t C, int64_t K, int64_t R, int64_t S, int stride_h, int stride_w, int pad_h,
+                            int pad_w, int dil_h, int dil_w, int groups, int in, int out, Plan* plan) {
+    plan->v = nullptr;
+    tir_status st = check_common(x, w, y, in, out);
+    if (st != TIR_OK) return st;
+    if (N < 0 || H <= 0 || W <= 0 || C <= 0 || K <= 0 || R <= 0 || S <= 0)
+        return fail(TIR_ERR_INVALID_ARG, "non-positive extent (N=%lld H=%lld W=%lld C=%lld K=%lld R=%lld S=%lld)", (long long)N, (long long)H, (long long)W, (long long)C, (long long)K, (long long)R, (long long)S);
+    if (stride_h <= 0 || stride_w <= 0 || dil_h <= 0 || dil_w <= 0 || pad_h < 0 || pad_w < 0)
+        return fail(TIR_ERR_INVALID_ARG, "stride and dilation must be positive, padding non-negative");
+    if (groups <= 0 || C % groups != 0 || K % groups != 0)
+        return fail(TIR_ERR_INVALID_ARG, "groups=%d must divide C=%lld and K=%lld", groups, (long long)C, (long long)K);
+    const int64_t P = conv_extent(H, R, stride_h, pad_h, dil_h), Q = conv_extent(W, S, stride_w, pad_w, dil_w);
+    if (P <= 0 || Q <= 0) return fail(TIR_ERR_INVALID_ARG, "empty output: the dilated filter does not fit the padded input");
+    // the kernels keep input coordinates in 16 bits and element offsets in 32 bits
+    if (H > 16383 || W > 16383 || pad_h > 8191 || pad_w > 8191 || (R - 1) * dil_h > 8191 || (S - 1) * dil_w > 8191)
+        return fail(TIR_ERR_UNSUPPORTED, "spatial extent, padding or dilated filter span too large");
+    const int64_t Cg = C / groups, Kg = K / groups;
+    const int64_t Mg = N * P * Q, Kd = R * S * Cg;
+    if (N * H * W * C > kMaxExtent || Mg > kMaxExtent || Kd > kMaxExtent || N * P * Q * K > (int64_t)1 << 40)
+        return fail(TIR_ERR_UNSUPPORTED, "tensor too large for 32-bit element offsets");
+    if (N == 0) return TIR_OK;
+    if (need_ptrs && (!x || !w || !y)) return fail(TIR_ERR_INVALID_ARG, "x, w or y is null");
+
+    const int es = elem_size(in);
+    const int vec = 16 / es;
+    int amode = A_CONV_GENERIC, bmode = B_GENERIC;
+    if (Cg % vec == 0 && aligned(x, 16) && aligned(w, 16)) { amode = A_CONV; bmode = B_KMAJOR; }
+    const Variant* v = pick(in, out, amode, bmode, groups, Mg, Kg);
+    if (!v) return fail(TIR_ERR_UNSUPPORTED, "no kernel variant for this dtype / forced tile");
+    Params& p = plan->p;
+    memset(&p, 0, sizeof p);
+    p.A = x; p.B = w; p.C = y;
+    p.M = (int)Mg; p.N = (int)Kg; p.K = (int)Kd;
+    p.batch = groups;
+    p.tiles_m = (int)((Mg + v->bm - 1) / v->bm);
+    p.tiles_n = (int)((Kg + v->bn - 1) / v->bn);
+    p.a_bs = Cg;            // a group starts Cg channels further
+    p.b_bs = Kg * Kd;       // filters of one group are contiguous
+    p.c_bs = Kg;
+    p.a_rs = 0; p.a_cs = 1;
+    p.b_rs = 1; p.b_cs = Kd;          // B[k][y] = w[y][k]: the KRSC filter is B stored K-major
+    p.c_rs = K; p.c_cs = 1;           // NHWC output is C_t[fuse(n,h,w)][co]
+    p.H = (int)H; p.W = (int)W; p.Cin = (int)C; p.Cg = (int)Cg; p.P = (int)P; p.Q = (int)Q; p.R = (int)R; p.S = (int)S;
+    p.stride_h = stride_h; p.stride_w = stride_w; p.pad_h = pad_h; p.pad_w = pad_w; p.dil_h = dil_h; p.dil_w = dil_w;
+    plan->v = v;
+    return TIR_OK;
+}
+
+static tir_status run(const Plan& plan, hipStream_t stream) {
+    if (!plan.v) return TIR_OK;
+    // grid.y is limited to 65535: launch the batch in slices
+    const int es = elem_size(plan.v->dt), os = elem_size(plan.v->out);
+    const int total = plan.p.batch;
+    for (int b0 = 0; b0 < total; b0 += 65535) {
+        Params p = plan.p;
+        p.batch = total - b0 < 65535 ? total - b0 : 65535;
+        p.A = (const char*)plan.p.A + (long long)b0 * p.a_bs * es;
+        p.B = (const char*)plan.p.B + (long long)b0 * p.b_bs * es;
+        p.C = (char*)plan.p.C + (long long)b0 * p.c_bs * os;
+        hipError_t e = plan.v->fn(p, stream);
+        if (e != hipSuccess) return fail(TIR_ERR_LAUNCH, "launch of %s failed: %s", plan.v->name, hipGetErrorString(e));
+    }
+    return TIR_OK;
+}
+
+}  // namespace tir
+
+using namespace tir;
+
+extern "C" {
+
+tir_status tir_gemm(const void* A, const void* B, void* C, int64_t M, int64_t N, int64_t K, int64_t a_rs,
+                    int64_t a_cs, int64_t b_rs, int64_t b_cs, int64_t c_rs, int64_t c_cs, tir_dtype in,
+                    tir_dtype out, tir_stream stream) {
+    Plan plan;
+    tir_status st = plan_gemm(true, A, B, C, 1, M, N, K, 0, a_rs, a_cs, 0, b_rs, b_cs, 0, c_rs, c_cs, (int)in, (int)out, &plan);
+    if (st != TIR_OK) return st;
+    return run(plan, (hipStream_t)stream);
+}
+
+tir_status tir_batch_matmul(const void* A, const void* B, void* C, int64_t batch, int64_t M, int64_t N, int64_t K,
+                            int64_t a_bs, int64_t a_rs, int64_t a_cs, int64_t b_bs, int64_t b_rs, int64_t b_cs,
+                            int64_t c_bs, int64_t c_rs, int64_t c_cs, tir_dtype in, tir_dtype out,
+                            tir_stream stream) {
+    Plan plan;
+    tir_status st = plan_gemm(true, A, B, C, batch, M, N, K, a_bs, a_rs, a_cs, b_bs, b_rs, b_cs, c_bs, c_rs, c_cs, (int)in, (int)out, &plan);
+    if (st != TIR_OK) return st;
+    return run(plan, (hipStream_t)stream);
+}
+
+tir_status tir_conv2d(const void* x, const void* w, void* y, int64_t N, int64_t H, int64_t W, int64_t C, int64_t K,
+                      int64_t R, int64_t S, int stride_h, int stride_w, int pad_h, int pad_w, int dil_h, int dil_w,
+                      int groups, tir_dtype in, tir_dtype out, tir_stream stream) {
+    Plan plan;
+    tir_status st = plan_conv(true, x, w, y, N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, groups, (int)in, (int)out, &plan);
+    if (st != TIR_OK) return st;
+    return run(plan, (hipStream_t)stream);
+}
+
+const char* tir_last_error(void) { return g_err; }
+
+const char* tir_gemm_variant(int64_t batch, int64_t M, int64_t N, int64_t K, int64_t a_rs, int64_t a_cs, int64_t b_rs,
+                             int64_t b_cs, int64_t c_rs, int64_t c_cs, tir_dtype in, tir_dtype out) {
+    Plan plan;
+    // batch strides of dense operands, only their divisibility matters for the choice
+    tir_status st = plan_gemm(false, nullptr, nullptr, nullptr, batch, M, N, K, M * K, a_rs, a_cs, K * N, b_rs, b_cs, M * N, c_rs, c_cs, (int)in, (int)out, &plan);
+    return (st == TIR_OK && plan.v) ? plan.v->name : "";
+}
+
+const char* tir_conv2d_variant(int64_t N, int64_t H, int64_t W, int64_t C, int64_t K, int64_t R, int64_t S,
+                               int stride_h, int stride_w, int pad_h, int pad_w, int dil_h, int dil_w, int groups,
+                               tir_dtype in, tir_dtype out) {
+    Plan plan;
+    tir_status st = plan_conv(false, nullptr, nullptr, nullptr, N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, groups, (int)in, (int)out, &plan);
+    return (st == TIR_OK && plan.v) ? plan.v->name : "";
+}
+
+void tir_debug_force_tile(int bm, int bn) {
+    g_force_bm = bm;
+    g_force_bn = bn;
+}
+
+void tir_debug_tile_of_block(int bid, int tiles_m, int tiles_n, int* tm, int* tn) { tile_of_block(bid, tiles_m, tiles_n, tm, tn); }
+
+const char* tir_version(void) { return "0.1"; }
+
+}  // extern "C"

@@ -1,0 +1,91 @@
+// Kernel parameter block and small host/device helpers shared by the host dispatcher and the
+// gfx950 kernels.  Nothing here is visible across the C ABI.
+#pragma once
+#include <stdint.h>
+
+namespace tir {
+
+enum : int { DT_F16 = 0, DT_BF16 = 1, DT_I8 = 2, DT_F32 = 3, DT_I32 = 4 };
+
+// How the A (x,k) tile and the B (k,y) tile are fetched from global memory.
+enum : int {
+    A_KMAJOR = 0,   // A[x][k], k contiguous, 16-byte vectors
+    A_CONV = 1,     // implicit im2col of an NHWC tensor, channel vectors of 16 bytes
+    A_GENERIC = 2,  // any strides, element-wise loads
+    A_CONV_GENERIC = 3  // implicit im2col, element-wise (C/groups not a multiple of the vector)
+};
+enum : int {
+    B_KMAJOR = 0,   // B stored [y][k], k contiguous (a "transposed" B, or a KRSC filter)
+    B_NMAJOR = 1,   // B stored [k][y], y contiguous (row-major B); transposed on the LDS read
+    B_GENERIC = 2   // any strides, element-wise loads
+};
+
+struct Params {
+    const void* A;
+    const void* B;
+    void* C;
+    int M, N, K;      // extents of one contraction (per batch / per group)
+    int batch;        // number of independent contractions (grid.y)
+    int tiles_m, tiles_n;
+    long long a_bs, b_bs, c_bs;                 // per-batch offsets, in elements
+    long long a_rs, a_cs, b_rs, b_cs, c_rs, c_cs;  // element strides; for conv: a_* unused
+    // convolution geometry (A_CONV*): x is [n][H][W][Cin], one group reads Cg channels
+    int H, W, Cin, Cg, P, Q, R, S;
+    int stride_h, stride_w, pad_h, pad_w, dil_h, dil_w;
+};
+
+// Number of XCDs (L2 domains) workgroups are dealt to round-robin by the dispatcher.
+constexpr int kXcds = 8;
+// Tile rows walked together before moving to the next tile column (L2 reuse of the B tile).
+constexpr int kGroupM = 4;
+
+// Map a linear workgroup id to an output tile.  Consecutive hardware ids land on different XCDs,
+// so ids are first regrouped such that each XCD owns a contiguous run of logical tiles (its L2
+// then sees few distinct A/B panels), and logical tiles walk kGroupM tile-rows at a time.
+// The map is a bijection from [0, tiles_m*tiles_n) onto the tile grid.
+__host__ __device__ inline void tile_of_block(int bid, int tiles_m, int tiles_n, int* tm, int* tn) {
+    int nb = tiles_m * tiles_n;
+    int nb8 = nb - nb % kXcds;
+    int logical = bid;
+    if (bid < nb8) logical = (bid % kXcds) * (nb8 / kXcds) + bid / kXcds;
+    int width = kGroupM * tiles_n;
+    int group = logical / width;
+    int first_m = group * kGroupM;
+    int gsz = tiles_m - first_m < kGroupM ? tiles_m - first_m : kGroupM;
+    int in_group = logical - group * width;
+    *tm = first_m + in_group % gsz;
+    *tn = in_group / gsz;
+}
+
+constexpr int elem_size(int dt) { return dt == DT_I8 ? 1 : (dt == DT_F16 || dt == DT_BF16) ? 2 : 4; }
+
+// Compile-time shape of one kernel variant: BM x BN workgroup tile, WM x WN waves.
+template <int DT_, int OUT_, int BM_, int BN_, int WM_, int WN_, int AMODE_, int BMODE_>
+struct Cfg {
+    static constexpr int DT = DT_, OUT = OUT_, BM = BM_, BN = BN_, WM = WM_, WN = WN_;
+    static constexpr int AMODE = AMODE_, BMODE = BMODE_;
+    static constexpr int THREADS = WM * WN * 64;
+    static constexpr int ES = elem_size(DT);
+    static constexpr int VEC = 16 / ES;        // elements per 16-byte vector
+    static constexpr int BK = 128 / ES;        // elements of k per slab
+    static constexpr int TM = BM / WM, TN = BN / WN;
+    static constexpr int MI = TM / 32, NI = TN / 32;
+    static constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128;
+    static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
+    static constexpr int LDS_BYTES = 2 * STAGE_BYTES;
+    static constexpr int A_IT = BM * 8 / THREADS;   // 16-byte chunks per thread per slab
+    static constexpr int B_IT = BN * 8 / THREADS;
+    // N-major B tile in LDS: BK rows of BN*ES bytes
+    static constexpr int BROW = BN * ES;
+    static constexpr int B_RC = BROW / 16;          // 16-byte chunks per k-row
+    static constexpr int SEG = (ES == 2) ? 64 : 32; // bytes one half-wave reads per k-row on the transposing read
+    static constexpr int WIN = BROW < 256 ? BROW : 256;
+    static constexpr int NSEG = WIN / SEG > 0 ? WIN / SEG : 1;
+    static constexpr int RPW = 256 / WIN;
+    static_assert(TM % 32 == 0 && TN % 32 == 0, "wave tile must be a multiple of the 32x32 MFMA block");
+    static_assert((BM * 8) % THREADS == 0 && (BN * 8) % THREADS == 0, "copy must divide evenly");
+    static_assert(THREADS % 8 == 0, "");
+    static_assert(BMODE != B_NMAJOR || (THREADS % B_RC == 0 && BROW >= SEG), "N-major copy shape");
+};
+
+}  // namespace tir

@@ -1,0 +1,109 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, rejects bad arguments before touching the device, and maps workgroup ids to
+output tiles bijectively."""
+import re
+from pathlib import Path
+
+import pytest
+
+from paper_2207_04296_amd import binding as B
+
+ROOT = Path(__file__).resolve().parent.parent
+
+
+def test_library_exports_every_declared_symbol():
+    header = (ROOT / "include" / "tir.h").read_text()
+    declared = set(re.findall(r"\b(tir_[a-z0-9_]+)\s*\(", header))
+    assert {"tir_gemm", "tir_batch_matmul", "tir_conv2d", "tir_last_error"} <= declared
+    L = B.lib()
+    for name in sorted(declared):
+        assert hasattr(L, name), f"libtir.so does not export {name}"
+    assert declared == set(B.EXPORTS)
+    assert B.tir_version() == "0.1"
+
+
+GOOD = dict(M=64, N=64, K=64, a_rs=64, a_cs=1, b_rs=64, b_cs=1, c_rs=64, c_cs=1, in_dtype="f16", out_dtype="f32")
+FAKE = 0x1000  # a non-null, 16-byte aligned "pointer"; never dereferenced because validation fails first
+
+
+def _gemm(**over):
+    a = dict(GOOD, **over)
+    return B.tir_gemm_status(a.pop("A", FAKE), a.pop("Bp", FAKE), a.pop("C", FAKE), a["M"], a["N"], a["K"], a["a_rs"],
+                             a["a_cs"], a["b_rs"], a["b_cs"], a["c_rs"], a["c_cs"], a["in_dtype"], a["out_dtype"])
+
+
+@pytest.mark.parametrize("over,status", [
+    (dict(M=-1), B.TIR_ERR_INVALID_ARG),
+    (dict(K=-5), B.TIR_ERR_INVALID_ARG),
+    (dict(a_rs=-64), B.TIR_ERR_INVALID_ARG),
+    (dict(C=0), B.TIR_ERR_INVALID_ARG),
+    (dict(A=0), B.TIR_ERR_INVALID_ARG),
+    (dict(c_rs=0, c_cs=0), B.TIR_ERR_INVALID_ARG),
+    (dict(in_dtype=7), B.TIR_ERR_INVALID_ARG),
+    (dict(in_dtype="f16", out_dtype="i32"), B.TIR_ERR_UNSUPPORTED),
+    (dict(in_dtype="i8", out_dtype="f32"), B.TIR_ERR_UNSUPPORTED),
+    (dict(in_dtype="f32", out_dtype="f32"), B.TIR_ERR_UNSUPPORTED),
+    (dict(in_dtype="bf16", out_dtype="f16"), B.TIR_ERR_UNSUPPORTED),
+    (dict(M=2 ** 31), B.TIR_ERR_UNSUPPORTED),
+    (dict(A=FAKE + 1), B.TIR_ERR_ALIGNMENT),
+    (dict(C=FAKE + 2), B.TIR_ERR_ALIGNMENT),
+])
+def test_gemm_rejects_bad_arguments(over, status):
+    assert _gemm(**over) == status
+    assert B.last_error() != ""
+
+
+def test_zero_sized_calls_are_noops_without_a_device():
+    assert _gemm(M=0) == B.TIR_OK
+    assert _gemm(N=0, A=0, Bp=0, C=0) == B.TIR_OK
+    assert B.tir_batch_matmul_status(FAKE, FAKE, FAKE, 0, 8, 8, 8, 64, 8, 1, 64, 8, 1, 64, 8, 1, "f16", "f32") == B.TIR_OK
+    assert B.tir_conv2d_status(FAKE, FAKE, FAKE, 0, 8, 8, 8, 8, 3, 3, 1, 1, 1, 1, 1, 1, 1, "f16", "f16") == B.TIR_OK
+
+
+def test_bmm_rejects_overlapping_outputs():
+    st = B.tir_batch_matmul_status(FAKE, FAKE, FAKE, 4, 8, 8, 8, 64, 8, 1, 64, 8, 1, 0, 8, 1, "f16", "f32")
+    assert st == B.TIR_ERR_INVALID_ARG and "overlap" in B.last_error()
+
+
+def _conv(**over):
+    a = dict(N=1, H=8, W=8, C=8, K=8, R=3, S=3, sh=1, sw=1, ph=1, pw=1, dh=1, dw=1, g=1, i="f16", o="f16")
+    a.update(over)
+    return B.tir_conv2d_status(a.get("x", FAKE), a.get("w", FAKE), a.get("y", FAKE), a["N"], a["H"], a["W"], a["C"], a["K"],
+                               a["R"], a["S"], a["sh"], a["sw"], a["ph"], a["pw"], a["dh"], a["dw"], a["g"], a["i"], a["o"])
+
+
+@pytest.mark.parametrize("over,status", [
+    (dict(g=3), B.TIR_ERR_INVALID_ARG),           # groups must divide C and K
+    (dict(g=0), B.TIR_ERR_INVALID_ARG),
+    (dict(C=8, K=12, g=8), B.TIR_ERR_INVALID_ARG),
+    (dict(sh=0), B.TIR_ERR_INVALID_ARG),
+    (dict(dw=0), B.TIR_ERR_INVALID_ARG),
+    (dict(ph=-1), B.TIR_ERR_INVALID_ARG),
+    (dict(H=2, W=2, ph=0, pw=0), B.TIR_ERR_INVALID_ARG),   # 3x3 filter does not fit: P <= 0
+    (dict(H=0), B.TIR_ERR_INVALID_ARG),
+    (dict(x=0), B.TIR_ERR_INVALID_ARG),
+    (dict(H=20000), B.TIR_ERR_UNSUPPORTED),
+    (dict(i="i8", o="f16"), B.TIR_ERR_UNSUPPORTED),
+])
+def test_conv_rejects_bad_arguments(over, status):
+    assert _conv(**over) == status
+    assert B.last_error() != ""
+
+
+@pytest.mark.parametrize("tiles", [(1, 1), (16, 16), (7, 5), (3, 100), (49, 1), (2, 4), (13, 24), (196, 1)])
+def test_block_to_tile_map_is_a_bijection(tiles):
+    # the binding of block iterators to workgroup ids must cover every tile exactly once
+    tm, tn = tiles
+    seen = {B.tir_debug_tile_of_block(b, tm, tn) for b in range(tm * tn)}
+    assert len(seen) == tm * tn
+    assert all(0 <= a < tm and 0 <= b < tn for a, b in seen)
+
+
+def test_variant_choice_reflects_layout():
+    # row-major B is read N-major, a transposed B K-major; odd K falls back to the general kernel
+    assert B.tir_gemm_variant(1, 4096, 4096, 4096, 4096, 1, 4096, 1, 4096, 1, "f16", "f32").endswith("ak_bn")
+    assert B.tir_gemm_variant(1, 4096, 4096, 4096, 4096, 1, 1, 4096, 4096, 1, "f16", "f32").endswith("ak_bk")
+    assert B.tir_gemm_variant(1, 100, 100, 37, 37, 1, 100, 1, 100, 1, "f16", "f32").endswith("generic")
+    assert "conv" in B.tir_conv2d_variant(16, 56, 56, 64, 64, 3, 3, 1, 1, 1, 1, 1, 1, 1, "f16", "f16")
+    assert B.tir_conv2d_variant(1, 8, 8, 3, 8, 3, 3, 1, 1, 1, 1, 1, 1, 1, "f16", "f16").endswith("conv_generic")
+    assert B.tir_gemm_variant(1, -1, 8, 8, 8, 1, 8, 1, 8, 1, "f16", "f32") == ""
