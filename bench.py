@@ -1,0 +1,202 @@
+#!/usr/bin/env python3
+"""Benchmark of the tensor-contraction hot path on one MI355X.
+
+    python bench.py --gpus 1 --steps K --warmup W [--workload NAME] [--hot] [--eager] [--no-operators]
+
+A step is one call of the C ABI for the headline workload (default: the fp16 NHWC conv2d
+16x56x56x64 -> 64, 3x3, stride 1, pad 1 with fp16 output), i.e. one pass of the whole path:
+fused-iterator decode, tile decomposition, global->LDS copy stage, MFMA accumulation, fused
+epilogue store.  Operands are resident in device memory before the timed region.  By default the
+K steps rotate over enough distinct operand / output sets to exceed the 256 MB memory-side cache
+plus L2, so every step reads its inputs from HBM ("cold"); --hot reuses one set.  The K launches
+are captured in one HIP graph (the kernels are microseconds long, a Python launch loop would
+measure the host), replayed once inside the timed region; --eager launches them one by one.
+
+Prints ONE JSON line.  `value` = algorithmic TFLOP/s of the whole run (2*M*N*K of the fused GEMM
+view per step).  `roofline` prices the kernel against the dense fp16 MFMA peak; `cpu_baseline`
+times the CPU oracle on the same workload on this machine's host cores; `operators` lists every other
+benchmark configuration (hot cache) for context.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+PEAK_TFLOPS = {"f16": 2516.6, "bf16": 2516.6, "i8": 5033.2}   # 256 CU x 2.4 GHz x 4096 (8192) flop/clk/CU
+HBM_GBS = 8000.0
+CACHE_BYTES = 256e6 + 8 * 4e6     # memory-side cache + the eight L2s
+
+# HBM bytes per launch of the headline kernel from rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled
+# by the same counters on a copy kernel of known size; see profiles/.  None until measured.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=480)
+    ap.add_argument("--warmup", type=int, default=48)
+    ap.add_argument("--workload", default="c2a_conv56x64_f16")
+    ap.add_argument("--hot", action="store_true", help="reuse one operand set (cache-resident inputs)")
+    ap.add_argument("--eager", action="store_true", help="launch step by step instead of one HIP graph")
+    ap.add_argument("--no-operators", action="store_true", help="skip the per-operator context table")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+def make_sets(B, wl, count):
+    a_bits, b_bits = wl.operands()
+    sets = []
+    for _ in range(count):
+        sets.append((B.to_device(a_bits, wl.dtype), B.to_device(b_bits, wl.dtype),
+                     B.empty_out(B.out_shape(wl), wl.out)))
+    return sets
+
+
+def timed_run(torch, B, wl, sets, steps, warmup, eager):
+    """Returns (wall seconds for `steps` launches, HIP-event seconds for the same region)."""
+    stream = torch.cuda.Stream()
+    n = len(sets)
+    with torch.cuda.stream(stream):
+        for i in range(warmup):
+            B.run_workload(wl, *sets[i % n], stream=stream)
+        torch.cuda.synchronize()
+        graph = None
+        if not eager:
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=stream):
+                for i in range(steps):
+                    B.run_workload(wl, *sets[i % n], stream=stream)
+            graph.replay()            # untimed: first replay uploads the graph
+            torch.cuda.synchronize()
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        e0.record(stream)
+        if graph is not None:
+            graph.replay()
+        else:
+            for i in range(steps):
+                B.run_workload(wl, *sets[i % n], stream=stream)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        return t1 - t0, e0.elapsed_time(e1) * 1e-3
+
+
+def variant_of(B, wl):
+    if wl.kind == "conv2d":
+        return B.tir_conv2d_variant(wl.n, wl.h, wl.w, wl.c, wl.k, wl.r, wl.s, *wl.stride, *wl.pad, *wl.dil,
+                                    wl.groups, wl.dtype, wl.out)
+    b_rs, b_cs = (1, wl.K) if wl.trans_b else (wl.N, 1)
+    return B.tir_gemm_variant(wl.batch, wl.M, wl.N, wl.K, wl.K, 1, b_rs, b_cs, wl.N, 1, wl.dtype, wl.out)
+
+
+def cpu_baseline(wl):
+    """The oracle, as it stands, on this machine's host cores; whole workload, repeated for ~seconds."""
+    import oracle
+    from tests.parity import run_oracle
+    a_bits, b_bits = wl.operands()
+    sample_note = "whole workload"
+    if wl.flops() > 4e10:     # 4096^3: 256 whole output rows are the bounded sample
+        import dataclasses
+        wl = dataclasses.replace(wl, M=256)
+        a_bits = a_bits[:256].copy()
+        sample_note = "256 of 4096 output rows"
+    run_oracle(wl, a_bits, b_bits, oracle)     # warm (page in, build)
+    reps, t = 0, 0.0
+    while t < 3.0 and reps < 20:
+        t0 = time.perf_counter()
+        run_oracle(wl, a_bits, b_bits, oracle)
+        t += time.perf_counter() - t0
+        reps += 1
+    return {"value": wl.flops() * reps / t / 1e12, "unit": "TFLOP/s", "cores": oracle.get_threads(),
+            "kind": "oracle", "sample": f"{sample_note}, {reps} repetitions, fp64 direct loops incl. sum|a*b|"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on exactly one GPU (every output tile is independent; see DESIGN.md "
+              "for how the path would shard). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+    sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+    import torch
+    from paper_2207_04296_amd import binding as B
+    from paper_2207_04296_amd import inputs as I
+
+    if not torch.cuda.is_available():
+        print("bench.py: no ROCm device visible", file=sys.stderr)
+        sys.exit(2)
+    B.lib()     # fails loudly if libtir.so was not built
+    torch.cuda.set_device(0)
+    wl = I.WORKLOADS[args.workload]
+
+    per_set = wl.min_bytes()
+    nsets = 1 if args.hot else max(2, int(CACHE_BYTES * 1.25 / per_set) + 1)
+    nsets = min(nsets, max(1, args.steps))
+    sets = make_sets(B, wl, nsets)
+    wall, ev = timed_run(torch, B, wl, sets, args.steps, args.warmup, args.eager)
+    ms_per_step = wall * 1e3 / args.steps
+    value = wl.flops() * args.steps / wall / 1e12
+    peak = PEAK_TFLOPS[wl.dtype]
+    launch_s = ev / args.steps
+    achieved = wl.flops() / launch_s / 1e12
+    traffic = MEASURED_TRAFFIC_BYTES.get(wl.name)
+
+    hot_value = None
+    if not args.hot:
+        w2, _ = timed_run(torch, B, wl, sets[:1], args.steps, args.warmup, args.eager)
+        hot_value = wl.flops() * args.steps / w2 / 1e12
+    del sets
+
+    operators = []
+    if not args.no_operators:
+        for name, o in I.WORKLOADS.items():
+            k = 20 if o.flops() > 4e10 else 200
+            s = make_sets(B, o, 1)
+            w_, e_ = timed_run(torch, B, o, s, k, 5, args.eager)
+            tf = o.flops() * k / e_ / 1e12
+            attain = min(PEAK_TFLOPS[o.dtype], o.flops() / o.min_bytes() * HBM_GBS / 1e3)
+            operators.append({"workload": name, "variant": variant_of(B, o), "us": round(e_ / k * 1e6, 3),
+                              "tflops": round(tf, 2), "frac_mfma_peak": round(tf / PEAK_TFLOPS[o.dtype], 4),
+                              "frac_attainable": round(tf / attain, 4),
+                              "gbs": round(o.min_bytes() * k / e_ / 1e9, 1), "cache": "hot"})
+            del s
+
+    out = {
+        "metric": "TFLOP/s and % of MI355X MFMA peak per operator (fp16 GEMM, conv2d)",
+        "value": round(value, 3),
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 6),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": {"f16": "f16", "bf16": "bf16", "i8": "i8"}[wl.dtype],
+        "data": "synthetic (seeded; ResNet-50- / BERT-base-shaped operator instances)",
+        "config": {"workload": wl.name, "kind": wl.kind, "gemm_view_bMNK": list(wl.gemm_view()),
+                   "out_dtype": wl.out, "variant": variant_of(B, wl),
+                   "launch": "hip_graph" if not args.eager else "eager",
+                   "cache": "hot (one operand set)" if args.hot else f"cold (rotating {nsets} operand sets)"},
+        "frac_mfma_peak": round(value / peak, 4),
+        "value_hot_cache": None if hot_value is None else round(hot_value, 3),
+        "roofline": {"bound": "mfma", "achieved": round(achieved, 3), "peak": peak, "unit": "TFLOP/s",
+                     "frac": round(achieved / peak, 4), "traffic": traffic,
+                     "kernel": variant_of(B, wl), "avg_launch_us": round(launch_s * 1e6, 3),
+                     "algorithmic_flop_per_launch": wl.flops(), "algorithmic_bytes_per_launch": wl.min_bytes()},
+        "operators": operators,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

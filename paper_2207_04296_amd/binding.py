@@ -37,6 +37,10 @@ def lib() -> ctypes.CDLL:
     if not _LIBPATH.exists():
         raise RuntimeError(f"{_LIBPATH} is missing: build it with `python -m paper_2207_04296_amd.buildlib` "
                            "(there is no fallback path)")
+    # The library must share the HIP runtime that owns the caller's device memory.  PyTorch ships
+    # its own libamdhip64 (same soname as the system one): importing torch first makes the dynamic
+    # loader bind libtir.so to that copy instead of loading a second runtime.
+    import torch  # noqa: F401
     L = ctypes.CDLL(str(_LIBPATH))
     i64, vp, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
     L.tir_gemm.argtypes = [vp, vp, vp] + [i64] * 9 + [ci, ci, vp]
