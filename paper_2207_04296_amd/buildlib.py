@@ -20,7 +20,7 @@ N_UNITS = 5
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-but-set-variable",
-         "-Wno-unused-variable", "-Wno-unused-local-typedef",
+         "-Wno-unused-variable", "-Wno-unused-local-typedef", "-Wno-inline-asm",
          # packed fp32 instructions are kept off for every kernel of this library
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          f"-I{INCLUDE}", f"-I{CSRC}"]

@@ -100,9 +100,14 @@ static tir_status plan_gemm(bool need_ptrs, const void* A, const void* B, void* 
     const bool k_vec = K % vec == 0;
     int amode = A_GENERIC, bmode = B_GENERIC;
     // fast copy modes need 16-byte vectors along the contiguous axis
-    if (a_cs == 1 && k_vec && a_rs % vec == 0 && a_bs % vec == 0 && aligned(A, 16) && a_rs * es * 256 < kMaxExtent) amode = A_KMAJOR;
-    if (b_rs == 1 && k_vec && b_cs % vec == 0 && b_bs % vec == 0 && aligned(B, 16) && b_cs * es * 256 < kMaxExtent) bmode = B_KMAJOR;
-    else if (b_cs == 1 && N % vec == 0 && b_rs % vec == 0 && b_bs % vec == 0 && aligned(B, 16)) bmode = B_NMAJOR;
+    // (rows must not overlap: the copy stage relies on "row r+1 starts after row r ends" to turn
+    // rows past the edge into out-of-range reads; byte offsets inside one tile must fit 31 bits)
+    if (a_cs == 1 && k_vec && a_rs % vec == 0 && a_bs % vec == 0 && aligned(A, 16) && (a_rs >= K || M == 1) &&
+        (a_rs * 256 + K) * es < kMaxExtent) amode = A_KMAJOR;
+    if (b_rs == 1 && k_vec && b_cs % vec == 0 && b_bs % vec == 0 && aligned(B, 16) && (b_cs >= K || N == 1) &&
+        (b_cs * 256 + K) * es < kMaxExtent) bmode = B_KMAJOR;
+    else if (b_cs == 1 && N % vec == 0 && b_rs % vec == 0 && b_bs % vec == 0 && aligned(B, 16) && b_rs >= N &&
+             (b_rs * 128 + N) * es < kMaxExtent) bmode = B_NMAJOR;
     if (amode == A_GENERIC || bmode == B_GENERIC) { amode = A_GENERIC; bmode = B_GENERIC; }
 
     const Variant* v = pick(in, out, amode, bmode, batch, M, N);
@@ -153,7 +158,10 @@ static tir_status plan_conv(bool need_ptrs, const void* x, const void* w, void* 
     const int es = elem_size(in);
     const int vec = 16 / es;
     int amode = A_CONV_GENERIC, bmode = B_GENERIC;
-    if (Cg % vec == 0 && aligned(x, 16) && aligned(w, 16)) { amode = A_CONV; bmode = B_KMAJOR; }
+    if (Cg % vec == 0 && aligned(x, 16) && aligned(w, 16) && N * H * W * C * es < kMaxExtent && (Kd * 256 + Kd) * es < kMaxExtent) {
+        amode = A_CONV;
+        bmode = B_KMAJOR;
+    }
     const Variant* v = pick(in, out, amode, bmode, groups, Mg, Kg);
     if (!v) return fail(TIR_ERR_UNSUPPORTED, "no kernel variant for this dtype / forced tile");
     Params& p = plan->p;
