@@ -47,21 +47,24 @@ def is_stale() -> bool:
     return any(s.stat().st_mtime > t for s in sources())
 
 
-def build(verbose: bool = True, jobs: int | None = None) -> Path:
+def build(verbose: bool = True, jobs: int | None = None, defines=(), lib: Path = LIB, tag: str = "") -> Path:
+    """Compile and link.  `defines`, `lib` and `tag` let experiments build instrumented copies
+    (extra -D flags, another output name) without touching the product library."""
     OBJ.mkdir(exist_ok=True)
-    jobs_list = [(CSRC / "tir_api.hip", OBJ / "tir_api.o", [])]
+    extra = [f"-D{d}" for d in defines]
+    jobs_list = [(CSRC / "tir_api.hip", OBJ / f"tir_api{tag}.o", extra)]
     for u in range(N_UNITS):
-        jobs_list.append((CSRC / "tir_inst.hip", OBJ / f"tir_inst{u}.o", [f"-DTIR_UNIT={u}"]))
+        jobs_list.append((CSRC / "tir_inst.hip", OBJ / f"tir_inst{u}{tag}.o", [f"-DTIR_UNIT={u}"] + extra))
     with ThreadPoolExecutor(max_workers=jobs or min(8, os.cpu_count() or 1)) as ex:
         for warn in ex.map(_compile, jobs_list):
             if verbose and warn.strip():
                 print(warn, file=sys.stderr)
     objs = [str(j[1]) for j in jobs_list]
-    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", str(LIB), *objs]
+    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", str(lib), *objs]
     subprocess.run(cmd, check=True)
     if verbose:
-        print(f"built {LIB}")
-    return LIB
+        print(f"built {lib}")
+    return lib
 
 
 if __name__ == "__main__":

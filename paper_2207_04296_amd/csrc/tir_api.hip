@@ -12,8 +12,8 @@
 namespace tir {
 
 // ------------------------------------------------------------------------------- variant table
-#define TIR_ROW(name, DT, OUT, BM, BN, WM, WN, AM, BMO) \
-    {name, DT, OUT, BM, BN, WM * WN * 64, AM, BMO, &launch_cfg<Cfg<DT, OUT, BM, BN, WM, WN, AM, BMO>>},
+#define TIR_ROW(name, DT, OUT, BM, BN, WM, WN, AM, BMO, RB, NS) \
+    {name, DT, OUT, BM, BN, WM * WN * 64, AM, BMO, &launch_cfg<Cfg<DT, OUT, BM, BN, WM, WN, AM, BMO, RB, NS>>},
 #define V0 TIR_ROW
 #define V1 TIR_ROW
 #define V2 TIR_ROW

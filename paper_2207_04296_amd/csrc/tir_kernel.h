@@ -13,7 +13,8 @@
 //   - accumulators start at zero (reduction init) and the epilogue converts and stores them
 //     straight from registers.
 //
-// One K-slab is 128 bytes of k per row (64 fp16/bf16 or 128 int8 values) = 4 MFMA k-steps.
+// One LDS stage holds ROWB = 64 or 128 bytes of k per row (e.g. 32 or 64 fp16 values) = 2 or 4 MFMA
+// k-steps; the stages form a ring that the copy stage fills NSTAGE-1 stages ahead of the MFMAs.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <type_traits>
@@ -83,12 +84,16 @@ template <> struct OutTraits<DT_BF16> {
     }
 };
 
-// Byte offset of 16-byte column `chunk` of `row` inside a [rows][128 B] K-major LDS tile.
-// Column index XOR (row/2 mod 8): 16 consecutive rows read at one logical column then touch all
-// 64 banks exactly once.  The XOR is its own inverse, so the copy stage uses the same expression
-// to find which logical column lands in a given physical slot.
-__device__ __forceinline__ int kmajor_swz(int row) { return (row >> 1) & 7; }
-__device__ __forceinline__ int kmajor_off(int row, int chunk) { return row * 128 + ((chunk ^ kmajor_swz(row)) << 4); }
+// K-major LDS tile: [rows][ROWB bytes], 16-byte columns XOR-swizzled by the row so that the 16
+// rows one ds_read_b128 phase touches at a fixed logical column fall on all 64 banks exactly once
+// (ROWB 128: column ^ (row/2 mod 8); ROWB 64: column ^ (row/4 mod 4)).  The XOR is its own inverse,
+// so the copy stage uses the same expression to find which logical column a physical slot holds.
+template <int ROWB> __device__ __forceinline__ int kmajor_swz(int row) {
+    return ROWB == 128 ? ((row >> 1) & 7) : ((row >> 2) & 3);
+}
+template <int ROWB> __device__ __forceinline__ int kmajor_off(int row, int chunk) {
+    return row * ROWB + ((chunk ^ kmajor_swz<ROWB>(row)) << 4);
+}
 
 // XOR applied to the byte offset inside k-row `k` of an N-major LDS tile so that the k-rows one
 // transposing read touches fall into different banks.
@@ -124,10 +129,10 @@ __device__ __forceinline__ void load_to_lds(const i32x4& rsrc, const char* lds_b
         : "memory", "m0");
 }
 
-// Workgroup barrier that also publishes this wave's global->LDS copies (counted by vmcnt) and
-// retires its LDS reads of the stage that is about to be overwritten.
-__device__ __forceinline__ void copy_barrier() {
-    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+// Workgroup barrier that also publishes this wave's global->LDS copies (counted by vmcnt; all but
+// the newest PENDING must have landed) and retires its LDS reads of the slot that is refilled next.
+template <int PENDING> __device__ __forceinline__ void copy_barrier() {
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(PENDING) : "memory");
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -138,22 +143,29 @@ template <class C> struct Frag {
     __device__ __forceinline__ Frag(int lane, int wm, int wn) {
         const int l31 = lane & 31;
         g = lane >> 5;
-        a_base = (wm * C::TM + l31) * 128;
-        b_base = (wn * C::TN + l31) * 128;
-        sw = kmajor_swz(l31);          // (row>>1)&7 is the same for every 32-row block of this lane
+        a_base = (wm * C::TM + l31) * C::ROWB;
+        b_base = (wn * C::TN + l31) * C::ROWB;
+        sw = kmajor_swz<C::ROWB>(l31);   // the swizzle repeats every 16 rows: same for every 32-row block
         blk = lane >> 4;
         s16 = lane & 15;
         wn_off = wn * C::TN;
     }
-    __device__ __forceinline__ void read_a(const char* sa, int kk, uint4* af) const {
+    __device__ __forceinline__ uint4 read_a1(const char* sa, int kk, int i) const {
         const int col = ((2 * kk + g) ^ sw) << 4;
+        return *(const uint4*)(sa + a_base + i * 32 * C::ROWB + col);
+    }
+    __device__ __forceinline__ void read_a(const char* sa, int kk, uint4* af) const {
 #pragma unroll
-        for (int i = 0; i < C::MI; ++i) af[i] = *(const uint4*)(sa + a_base + i * 32 * 128 + col);
+        for (int i = 0; i < C::MI; ++i) af[i] = read_a1(sa, kk, i);
     }
     __device__ __forceinline__ void read_b(const char* sb, int kk, uint4* bf) const {
-        if constexpr (C::BMODE == B_NMAJOR) {
 #pragma unroll
-            for (int j = 0; j < C::NI; ++j) {
+        for (int j = 0; j < C::NI; ++j) bf[j] = read_b1(sb, kk, j);
+    }
+    __device__ __forceinline__ uint4 read_b1(const char* sb, int kk, int j) const {
+        uint4 out;
+        if constexpr (C::BMODE == B_NMAJOR) {
+            {
                 if constexpr (C::ES == 2) {
                     // The transposing read works on groups of 16 lanes.  Group `blk` covers columns
                     // 16*(blk&1).. of the 32-wide block and the k-group blk>>1; lane s fetches 4 values
@@ -168,7 +180,7 @@ template <class C> struct Frag {
                         h[hh] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(TIR_LDS_PTR(i16x4, ptr));
                     }
                     const i32x2 lo = __builtin_bit_cast(i32x2, h[0]), hi = __builtin_bit_cast(i32x2, h[1]);
-                    bf[j] = make_uint4((unsigned)lo[0], (unsigned)lo[1], (unsigned)hi[0], (unsigned)hi[1]);
+                    out = make_uint4((unsigned)lo[0], (unsigned)lo[1], (unsigned)hi[0], (unsigned)hi[1]);
                 } else {
                     // int8: lane s fetches 8 values of k-row (s>>1) at columns 8*(s&1)..
                     const int nloc = wn_off + j * 32 + 16 * (blk & 1) + 8 * (s16 & 1);
@@ -179,14 +191,14 @@ template <class C> struct Frag {
                         const char* ptr = sb + k * C::BROW + (nloc ^ nmajor_xor<C>(k));
                         h[hh] = __builtin_amdgcn_ds_read_tr8_b64_v2i32(TIR_LDS_PTR(i32x2, ptr));
                     }
-                    bf[j] = make_uint4((unsigned)h[0][0], (unsigned)h[0][1], (unsigned)h[1][0], (unsigned)h[1][1]);
+                    out = make_uint4((unsigned)h[0][0], (unsigned)h[0][1], (unsigned)h[1][0], (unsigned)h[1][1]);
                 }
             }
         } else {
             const int col = ((2 * kk + g) ^ sw) << 4;
-#pragma unroll
-            for (int j = 0; j < C::NI; ++j) bf[j] = *(const uint4*)(sb + b_base + j * 32 * 128 + col);
+            out = *(const uint4*)(sb + b_base + j * 32 * C::ROWB + col);
         }
+        return out;
     }
 };
 
@@ -221,14 +233,26 @@ __device__ __forceinline__ void store_tile(const Params& p, long long bz, int m0
 }
 
 // ---------------------------------------------------------------------------------------------
-// Fast kernel: vector copy modes, global -> LDS without a register hop.
+// Fast kernel: vector copy modes, global -> LDS without a register hop, NSTAGE-deep copy ring.
+//
+// Stage h of the reduction lives in ring slot h % NSTAGE.  Iteration h of the main loop
+//   (1) multiplies k-steps 0 .. KSTEPS-2 of stage h while it requests the fragments of the next
+//       k-step from LDS and issues the global->LDS copy of stage h+NSTAGE-1 (its slot held stage
+//       h-1, which every wave finished reading before the previous barrier);
+//   (2) waits until this wave's copy of stage h+1 has landed and joins the workgroup barrier;
+//   (3) multiplies the last k-step of stage h while requesting the first fragments of stage h+1.
+// With one wave per SIMD nothing else hides latency, so MFMAs and side work (LDS reads, copy
+// issue) are interleaved one by one in program order and scheduling fences keep that order.
 // ---------------------------------------------------------------------------------------------
 template <class C>
 __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Params p) {
     typedef typename InTraits<C::DT>::acc_t acc_t;
-    constexpr int ES = C::ES, VEC = C::VEC, BK = C::BK;
+    constexpr int ES = C::ES, VEC = C::VEC, BK = C::BK, ROWB = C::ROWB, NSTAGE = C::NSTAGE, KSTEPS = C::KSTEPS;
+    constexpr int L = C::A_IT + C::B_IT;      // copy instructions per wave and stage
     static_assert(C::AMODE == A_KMAJOR || C::AMODE == A_CONV, "");
     static_assert(C::BMODE == B_KMAJOR || C::BMODE == B_NMAJOR, "");
+    static_assert((NSTAGE - 2) * L <= 63, "vmcnt range");
+    static_assert(KSTEPS % 2 == 0, "fragment sets alternate per k-step and must line up per stage");
 
     __shared__ __attribute__((aligned(1024))) char smem[C::LDS_BYTES];
 
@@ -244,14 +268,14 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
 
     const char* Ab = (const char*)p.A + bz * p.a_bs * ES;
     const char* Bb = (const char*)p.B + bz * p.b_bs * ES;
+    const int nh = (p.K + BK - 1) / BK;                 // stages of the reduction
+    const bool ktail = (p.K % BK) != 0;                 // last stage is partly beyond K
 
     // ------------------------------------------------------------ copy stage: A
-    // LDS slot q = tid + i*THREADS is row q/8, physical 16-byte column q%8 of the [BM][128 B]
+    // LDS slot q = tid + i*THREADS is row q/RCH, physical 16-byte column q%RCH of the [BM][ROWB]
     // tile; the lane fetches the logical column that the swizzle stores there.
-    constexpr int A_RSTEP = C::THREADS / 8;
-    const int a_r0 = tid >> 3;
-    const int a_lc = (tid & 7) ^ kmajor_swz(a_r0);      // same for every i: A_RSTEP is a multiple of 16
-    static_assert(A_RSTEP % 16 == 0, "");
+    const int a_r0 = tid / C::RCH;
+    const int a_lc = (tid % C::RCH) ^ kmajor_swz<ROWB>(a_r0);   // same for every i (K_RSTEP % 16 == 0)
     unsigned a_off[C::A_IT];
     int a_hw[C::A_IT];
     const char* a_base = Ab;
@@ -263,7 +287,7 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
         a_bytes = ((long long)(rows - 1) * p.a_rs + p.K) * ES;
 #pragma unroll
         for (int i = 0; i < C::A_IT; ++i)
-            a_off[i] = (unsigned)(a_r0 + i * A_RSTEP) * (unsigned)(p.a_rs * ES) + a_lc * 16;
+            a_off[i] = (unsigned)(a_r0 + i * C::K_RSTEP) * (unsigned)(p.a_rs * ES) + a_lc * 16;
     } else {
         // ReIndex: row m of A_t is output pixel (img, op, oq) = unfuse(m); keep the element offset of
         // its top-left input pixel and that pixel's coordinates.
@@ -271,7 +295,7 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
         const int PQ = p.P * p.Q;
 #pragma unroll
         for (int i = 0; i < C::A_IT; ++i) {
-            const int m = m0 + a_r0 + i * A_RSTEP;
+            const int m = m0 + a_r0 + i * C::K_RSTEP;
             int ih0 = -30000, iw0 = 0, img = 0;
             if (m < p.M) {
                 img = m / PQ;
@@ -286,49 +310,58 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
     }
 
     // ------------------------------------------------------------ copy stage: B
-    constexpr int B_RSTEP = (C::BMODE == B_NMAJOR) ? C::THREADS / C::B_RC : C::THREADS / 8;
-    const int b_r0 = (C::BMODE == B_NMAJOR) ? tid / C::B_RC : (tid >> 3);
-    const int b_pc = (C::BMODE == B_NMAJOR) ? tid % C::B_RC : (tid & 7);
+    const int b_r0 = (C::BMODE == B_NMAJOR) ? tid / C::B_RC : tid / C::RCH;
+    const int b_pc = (C::BMODE == B_NMAJOR) ? tid % C::B_RC : tid % C::RCH;
+    const int b_lc = b_pc ^ kmajor_swz<ROWB>(b_r0);     // K-major only
     unsigned b_off[C::B_IT];
     const char* b_base = Bb;
     long long b_bytes = 0;
-    long long b_slab_step = 128;    // bytes the base advances per K-slab
+    long long b_step = ROWB;    // bytes the base advances per stage
     if constexpr (C::BMODE == B_KMAJOR) {
-        static_assert(B_RSTEP % 16 == 0, "");
         b_base = Bb + (long long)n0 * p.b_cs * ES;
         const int rows = p.N - n0 < C::BN ? p.N - n0 : C::BN;
         b_bytes = ((long long)(rows - 1) * p.b_cs + p.K) * ES;
-        const int b_lc = b_pc ^ kmajor_swz(b_r0);
 #pragma unroll
         for (int i = 0; i < C::B_IT; ++i)
-            b_off[i] = (unsigned)(b_r0 + i * B_RSTEP) * (unsigned)(p.b_cs * ES) + b_lc * 16;
+            b_off[i] = (unsigned)(b_r0 + i * C::K_RSTEP) * (unsigned)(p.b_cs * ES) + b_lc * 16;
     } else {
-        // k-rows of the slab; rows past K start beyond the descriptor (b_rs >= N is checked by the
+        // k-rows of the stage; rows past K start beyond the descriptor (b_rs >= N is checked by the
         // host), columns past N are switched off per lane
         b_base = Bb + (long long)n0 * ES;
         b_bytes = ((long long)(p.K - 1) * p.b_rs + (p.N - n0)) * ES;
-        b_slab_step = (long long)BK * p.b_rs * ES;
+        b_step = (long long)BK * p.b_rs * ES;
 #pragma unroll
         for (int i = 0; i < C::B_IT; ++i) {
-            const int k = b_r0 + i * B_RSTEP;
+            const int k = b_r0 + i * C::N_RSTEP;
             const int lb = (b_pc * 16) ^ nmajor_xor<C>(k);      // logical byte inside the k-row
             b_off[i] = (n0 + lb / ES < p.N) ? (unsigned)k * (unsigned)(p.b_rs * ES) + lb : kOutOfRange;
         }
     }
 
-    auto issue = [&](int slab, int buf) {
-        char* sa = smem + buf * C::STAGE_BYTES + wave * 1024;
-        char* sb = sa + C::A_BYTES;
-        const int k0 = slab * BK;
+    // Per-stage copy state: descriptors (SGPRs) and, for the convolution, this stage's offsets.
+    i32x4 ra, rb;
+    unsigned a_voff[C::A_IT];
+    char* lds_dst = smem;    // wave-uniform destination of this wave's first A chunk
+
+    // Prepare the copy of `stage` (descriptors, predicates); the loads themselves are issued one
+    // by one through copy_unit() so that they can be interleaved with MFMAs.
+    auto copy_begin = [&](int stage) {
+        lds_dst = smem + (stage % NSTAGE) * C::STAGE_BYTES + wave * 1024;
+        const bool live = stage < nh;      // past the end: empty descriptors, the copies write zeros nobody reads
         if constexpr (C::AMODE == A_KMAJOR) {
-            const i32x4 ra = make_rsrc(a_base + (long long)k0 * ES, a_bytes - (long long)k0 * ES);
-            const bool kv = k0 + a_lc * VEC < p.K;      // K tail: the padding between rows is not zero
+            ra = make_rsrc(a_base + (long long)stage * ROWB, live ? a_bytes - (long long)stage * ROWB : 0);
+            if (ktail && stage == nh - 1) {
+                // K tail: the bytes between K and the row stride are not zero, switch those lanes off
+                const bool kv = stage * BK + a_lc * VEC < p.K;
 #pragma unroll
-            for (int i = 0; i < C::A_IT; ++i) load_to_lds(ra, sa + i * C::THREADS * 16, kv ? a_off[i] : kOutOfRange);
+                for (int i = 0; i < C::A_IT; ++i) a_off[i] = kv ? a_off[i] : kOutOfRange;
+            }
+#pragma unroll
+            for (int i = 0; i < C::A_IT; ++i) a_voff[i] = a_off[i];
         } else {
             // fuse(rh, rw, rc) -> (rh, rw, rc); a 16-byte vector never straddles a tap (Cg % VEC == 0)
-            const i32x4 ra = make_rsrc(Ab, a_bytes);
-            const int kb = k0 + a_lc * VEC;
+            ra = make_rsrc(Ab, live ? a_bytes : 0);
+            const int kb = stage * BK + a_lc * VEC;
             const int tap = kb / p.Cg;
             const int cc = kb - tap * p.Cg;
             const int fr = tap / p.S, fs = tap - fr * p.S;
@@ -340,20 +373,24 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
                 const int ih = (a_hw[i] >> 16) + dh;
                 const int iw = (int)(short)(a_hw[i] & 0xffff) + dw;
                 const bool ok = kv && (unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W;
-                load_to_lds(ra, sa + i * C::THREADS * 16, ok ? (a_off[i] + delta) * ES : kOutOfRange);
+                a_voff[i] = ok ? (a_off[i] + delta) * ES : kOutOfRange;
             }
         }
         if constexpr (C::BMODE == B_KMAJOR) {
-            const i32x4 rb = make_rsrc(b_base + (long long)k0 * ES, b_bytes - (long long)k0 * ES);
-            const int b_lc = b_pc ^ kmajor_swz(b_r0);
-            const bool kv = k0 + b_lc * VEC < p.K;
+            rb = make_rsrc(b_base + (long long)stage * ROWB, live ? b_bytes - (long long)stage * ROWB : 0);
+            if (ktail && stage == nh - 1) {
+                const bool kv = stage * BK + b_lc * VEC < p.K;
 #pragma unroll
-            for (int i = 0; i < C::B_IT; ++i) load_to_lds(rb, sb + i * C::THREADS * 16, kv ? b_off[i] : kOutOfRange);
+                for (int i = 0; i < C::B_IT; ++i) b_off[i] = kv ? b_off[i] : kOutOfRange;
+            }
         } else {
-            const i32x4 rb = make_rsrc(b_base + slab * b_slab_step, b_bytes - slab * b_slab_step);
-#pragma unroll
-            for (int i = 0; i < C::B_IT; ++i) load_to_lds(rb, sb + i * C::THREADS * 16, b_off[i]);
+            rb = make_rsrc(b_base + stage * b_step, live ? b_bytes - stage * b_step : 0);
         }
+    };
+    // u-th copy instruction of the prepared stage (u < L): A chunks first, then B chunks.
+    auto copy_unit = [&](int u) {
+        if (u < C::A_IT) load_to_lds(ra, lds_dst + u * C::THREADS * 16, a_voff[u]);
+        else load_to_lds(rb, lds_dst + C::A_BYTES + (u - C::A_IT) * C::THREADS * 16, b_off[u - C::A_IT]);
     };
 
     // ------------------------------------------------------------ MFMA stage
@@ -366,47 +403,62 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;   // reduction init
 
-    const int nslab = (p.K + BK - 1) / BK;
-    if (nslab > 0) {
-        uint4 af[2][C::MI], bf[2][C::NI];
-        issue(0, 0);
-        copy_barrier();
+    uint4 af[2][C::MI], bf[2][C::NI];
+
+    // One k-step: the MI*NI MFMAs on fragment set `set`, interleaved with `nside` units of side
+    // work: first the fragment reads of (ra_s, rb_s, rk) into the other set, then copy units
+    // [v0, v0 + nv).
+    auto kstep = [&](int set, const char* ra_s, const char* rb_s, int rk, int v0, int nv) {
+        constexpr int NM = C::MI * C::NI;
+        constexpr int NR = C::MI + C::NI;
+        const int nside = NR + nv;
+#pragma unroll
+        for (int t = 0; t < NM; ++t) {
+            acc[t / C::NI][t % C::NI] = InTraits<C::DT>::mfma(af[set][t / C::NI], bf[set][t % C::NI], acc[t / C::NI][t % C::NI]);
+            TIR_FENCE();
+#pragma unroll
+            for (int u = t * nside / NM; u < (t + 1) * nside / NM; ++u) {
+                if (u < C::MI) af[set ^ 1][u] = frag.read_a1(ra_s, rk, u);
+                else if (u < NR) bf[set ^ 1][u - C::MI] = frag.read_b1(rb_s, rk, u - C::MI);
+                else copy_unit(v0 + u - NR);
+                TIR_FENCE();
+            }
+        }
+    };
+
+    if (nh > 0) {
+        // prologue: fill NSTAGE-1 slots, wait for stage 0
+#pragma unroll
+        for (int st = 0; st < NSTAGE - 1; ++st) {
+            copy_begin(st);
+#pragma unroll
+            for (int u = 0; u < L; ++u) copy_unit(u);
+        }
+        copy_barrier<(NSTAGE - 2) * L>();
         frag.read_a(smem, 0, af[0]);
         frag.read_b(smem + C::A_BYTES, 0, bf[0]);
-        for (int s = 0; s < nslab; ++s) {
-            const int cur = s & 1;
-            const char* sa = smem + cur * C::STAGE_BYTES;
+        TIR_FENCE();
+
+        constexpr int VPK = (L + KSTEPS - 2) / (KSTEPS - 1);     // copy units per k-step of part (1)
+        for (int h = 0; h < nh; ++h) {
+            const char* sa = smem + (h % NSTAGE) * C::STAGE_BYTES;
             const char* sb = sa + C::A_BYTES;
-            // the other stage was last read before the barrier that ended the previous iteration;
-            // past the last slab the descriptors are empty and the copy writes zeros nobody reads
-            issue(s + 1, cur ^ 1);
-            // Fragments of k-step kk+1 are requested before the MFMAs of k-step kk are issued, so the
-            // LDS latency hides behind the matrix pipe; the scheduling fences keep that order.
+            const char* na = smem + ((h + 1) % NSTAGE) * C::STAGE_BYTES;
+            copy_begin(h + NSTAGE - 1);
             TIR_FENCE();
-            frag.read_a(sa, 1, af[1]);
-            frag.read_b(sb, 1, bf[1]);
-            TIR_FENCE();
-            mfma_block<C>(af[0], bf[0], acc);
-            TIR_FENCE();
-            frag.read_a(sa, 2, af[0]);
-            frag.read_b(sb, 2, bf[0]);
-            TIR_FENCE();
-            mfma_block<C>(af[1], bf[1], acc);
-            TIR_FENCE();
-            frag.read_a(sa, 3, af[1]);
-            frag.read_b(sb, 3, bf[1]);
-            TIR_FENCE();
-            mfma_block<C>(af[0], bf[0], acc);
-            TIR_FENCE();
-            // slab s+1 has landed and every wave is done reading slab s
-            copy_barrier();
-            const char* na = smem + (cur ^ 1) * C::STAGE_BYTES;
-            frag.read_a(na, 0, af[0]);
-            frag.read_b(na + C::A_BYTES, 0, bf[0]);
-            TIR_FENCE();
-            mfma_block<C>(af[1], bf[1], acc);
-            TIR_FENCE();
+#pragma unroll
+            for (int kk = 0; kk < KSTEPS - 1; ++kk) {
+                const int v0 = kk * VPK;
+                const int nv = v0 + VPK <= L ? VPK : (L > v0 ? L - v0 : 0);
+                kstep(kk & 1, sa, sb, kk + 1, v0, nv);
+            }
+            // this wave's copy of stage h+1 has landed; after the barrier everybody's has, and
+            // every wave is done reading stage h-1's slot ... and stage h (its last fragments are in registers)
+            copy_barrier<(NSTAGE - 2) * L>();
+            kstep((KSTEPS - 1) & 1, na, na + C::A_BYTES, 0, 0, 0);
         }
+        // the ring still has copies in flight (empty ones past the end): drain before the LDS is released
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     }
 
     store_tile<C>(p, bz, m0, n0, wm, wn, lane, acc);
@@ -421,7 +473,7 @@ __global__ void __launch_bounds__(C::THREADS) contract_staged_kernel(const Param
     typedef typename InTraits<C::DT>::acc_t acc_t;
     constexpr int ES = C::ES, VEC = C::VEC, BK = C::BK;
     static_assert(C::AMODE == A_GENERIC || C::AMODE == A_CONV_GENERIC, "");
-    static_assert(C::BMODE == B_GENERIC, "");
+    static_assert(C::BMODE == B_GENERIC && C::ROWB == 128 && C::NSTAGE == 2, "");
     typedef typename std::conditional<ES == 2, unsigned short, unsigned char>::type elem_t;
 
     __shared__ __attribute__((aligned(16))) char smem[C::LDS_BYTES];
@@ -508,9 +560,9 @@ __global__ void __launch_bounds__(C::THREADS) contract_staged_kernel(const Param
         char* sa = smem + buf * C::STAGE_BYTES;
         char* sb = sa + C::A_BYTES;
 #pragma unroll
-        for (int i = 0; i < C::A_IT; ++i) *(uint4*)(sa + kmajor_off(r0 + i * RSTEP, c8)) = ra[i];
+        for (int i = 0; i < C::A_IT; ++i) *(uint4*)(sa + kmajor_off<128>(r0 + i * RSTEP, c8)) = ra[i];
 #pragma unroll
-        for (int i = 0; i < C::B_IT; ++i) *(uint4*)(sb + kmajor_off(r0 + i * RSTEP, c8)) = rb[i];
+        for (int i = 0; i < C::B_IT; ++i) *(uint4*)(sb + kmajor_off<128>(r0 + i * RSTEP, c8)) = rb[i];
     };
 
     const Frag<C> frag(lane, wm, wn);
@@ -533,7 +585,7 @@ __global__ void __launch_bounds__(C::THREADS) contract_staged_kernel(const Param
             if (more) load_ab(s + 1);
             const char* sa = smem + cur * C::STAGE_BYTES;
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
+            for (int kk = 0; kk < C::KSTEPS; ++kk) {
                 uint4 af[C::MI], bf[C::NI];
                 frag.read_a(sa, kk, af);
                 frag.read_b(sa + C::A_BYTES, kk, bf);
