@@ -106,6 +106,11 @@ const char* tir_conv2d_variant(int64_t N, int64_t H, int64_t W, int64_t C, int64
  * of [0, tiles_m*tiles_n) that keeps the tiles of one L2 domain adjacent).
  */
 void tir_debug_force_tile(int bm, int bn);
+/* Force the first variant of the matching dtype / copy mode whose name contains name_part
+ * ("" or NULL restores the automatic choice); tir_debug_variant_name enumerates the names. */
+void tir_debug_force_variant(const char* name_part);
+int tir_debug_variant_count(void);
+const char* tir_debug_variant_name(int i);
 void tir_debug_tile_of_block(int bid, int tiles_m, int tiles_n, int* tm, int* tn);
 
 /* Library version as "major.minor". */

@@ -17,7 +17,8 @@ TIR_F16, TIR_BF16, TIR_I8, TIR_F32, TIR_I32 = range(5)
 DTYPE_CODES = {"f16": TIR_F16, "bf16": TIR_BF16, "i8": TIR_I8, "f32": TIR_F32, "i32": TIR_I32}
 
 EXPORTS = ["tir_gemm", "tir_batch_matmul", "tir_conv2d", "tir_last_error", "tir_gemm_variant",
-           "tir_conv2d_variant", "tir_debug_force_tile", "tir_debug_tile_of_block", "tir_version"]
+           "tir_conv2d_variant", "tir_debug_force_tile", "tir_debug_force_variant", "tir_debug_variant_count",
+           "tir_debug_variant_name", "tir_debug_tile_of_block", "tir_version"]
 
 
 class TirError(RuntimeError):
@@ -56,6 +57,11 @@ def lib() -> ctypes.CDLL:
     L.tir_conv2d_variant.restype = ctypes.c_char_p
     L.tir_debug_force_tile.argtypes = [ci, ci]
     L.tir_debug_force_tile.restype = None
+    L.tir_debug_force_variant.argtypes = [ctypes.c_char_p]
+    L.tir_debug_force_variant.restype = None
+    L.tir_debug_variant_count.restype = ci
+    L.tir_debug_variant_name.argtypes = [ci]
+    L.tir_debug_variant_name.restype = ctypes.c_char_p
     L.tir_debug_tile_of_block.argtypes = [ci, ci, ci, ctypes.POINTER(ci), ctypes.POINTER(ci)]
     L.tir_debug_tile_of_block.restype = None
     L.tir_version.restype = ctypes.c_char_p
@@ -142,6 +148,15 @@ def tir_conv2d_variant(N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w, di
 
 def tir_debug_force_tile(bm: int, bn: int) -> None:
     lib().tir_debug_force_tile(bm, bn)
+
+
+def tir_debug_force_variant(name_part: str) -> None:
+    lib().tir_debug_force_variant((name_part or "").encode())
+
+
+def tir_debug_variant_names():
+    L = lib()
+    return [L.tir_debug_variant_name(i).decode() for i in range(L.tir_debug_variant_count())]
 
 
 def tir_debug_tile_of_block(bid: int, tiles_m: int, tiles_n: int):

@@ -13,7 +13,7 @@ namespace tir {
 
 // ------------------------------------------------------------------------------- variant table
 #define TIR_ROW(name, DT, OUT, BM, BN, WM, WN, AM, BMO, RB, NS) \
-    {name, DT, OUT, BM, BN, WM * WN * 64, AM, BMO, &launch_cfg<Cfg<DT, OUT, BM, BN, WM, WN, AM, BMO, RB, NS>>},
+    {name, DT, OUT, BM, BN, WM, WN, AM, BMO, RB, NS, &launch_cfg<Cfg<DT, OUT, BM, BN, WM, WN, AM, BMO, RB, NS>>},
 #define V0 TIR_ROW
 #define V1 TIR_ROW
 #define V2 TIR_ROW
@@ -26,6 +26,7 @@ static const int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 
 static thread_local char g_err[512] = "";
 static int g_force_bm = 0, g_force_bn = 0;
+static char g_force_name[64] = "";
 
 static tir_status fail(tir_status st, const char* fmt, ...) {
     va_list ap;
@@ -36,7 +37,7 @@ static tir_status fail(tir_status st, const char* fmt, ...) {
 }
 
 static const int64_t kMaxExtent = 2147483647LL;
-static const int kTargetTiles = 256;  // one workgroup per CU
+static const double kCUs = 256.0;
 
 static bool dtype_pair_ok(int in, int out) {
     return (in == TIR_F16 && (out == TIR_F32 || out == TIR_F16)) ||
@@ -45,20 +46,43 @@ static bool dtype_pair_ok(int in, int out) {
 
 static bool aligned(const void* p, uintptr_t a) { return ((uintptr_t)p % a) == 0; }
 
-// Pick a tile for (dt, out, amode, bmode): the largest listed tile that still yields at least
-// one workgroup per CU, else the tile giving the most workgroups (the smallest).
-static const Variant* pick(int dt, int out, int amode, int bmode, int64_t batch, int64_t M, int64_t N) {
+// Pick a variant for (dt, out, amode, bmode).  This is the hand-made stand-in for the paper's
+// search over tilings (sec. 4.4): every listed tile is scored by
+//   padding efficiency  x  how evenly its workgroups fill the 256 CUs  x  bytes-per-flop factor,
+// where the last term favours tiles that need fewer global->LDS bytes per MFMA (bm*bn/(bm+bn),
+// saturating at the 256x256 tile).  Among equal tiles the ring depth is chosen by occupancy:
+// deep rings when one workgroup per CU must hide the global latency alone, shallow ones when
+// several workgroups share a CU (their LDS must fit side by side) or the reduction is short.
+static const Variant* pick(int dt, int out, int amode, int bmode, int64_t batch, int64_t M, int64_t N, int64_t K) {
     const Variant* best = nullptr;
-    const Variant* smallest = nullptr;
+    double best_score = -1.0;
+    const int es = elem_size(dt);
     for (int i = 0; i < kNumVariants; ++i) {
         const Variant* v = &kVariants[i];
         if (v->dt != dt || v->out != out || v->amode != amode || v->bmode != bmode) continue;
-        if (g_force_bm && v->bm == g_force_bm && v->bn == g_force_bn) return v;  // testing / tuning override
-        int64_t tiles = ((M + v->bm - 1) / v->bm) * ((N + v->bn - 1) / v->bn) * batch;
-        if (!smallest || v->bm * v->bn < smallest->bm * smallest->bn) smallest = v;
-        if (tiles >= kTargetTiles && (!best || v->bm * v->bn > best->bm * best->bn)) best = v;
+        if (g_force_name[0] && strstr(v->name, g_force_name)) return v;          // testing / tuning overrides
+        if (g_force_bm && v->bm == g_force_bm && v->bn == g_force_bn) return v;
+        const double tm = (double)((M + v->bm - 1) / v->bm), tn = (double)((N + v->bn - 1) / v->bn);
+        const double tiles = tm * tn * (double)batch;
+        const double eff = ((double)M * (double)N) / (tm * v->bm * tn * v->bn);
+        const double rounds = tiles <= kCUs ? 1.0 : (double)((int64_t)(tiles + kCUs - 1) / kCUs);
+        const double fill = tiles / (rounds * kCUs);
+        double intensity = (double)v->bm * v->bn / (double)(v->bm + v->bn) / 128.0;
+        if (intensity > 1.0) intensity = 1.0;
+        double score = eff * fill * (0.25 + 0.75 * intensity);
+        // ring depth: stages beyond the number of K-slabs are useless; with more than one
+        // workgroup per CU prefer rings that let two of them be resident (LDS <= 80 KB)
+        const int64_t nslab = (K * es + v->rowb - 1) / v->rowb;
+        const int lds = (v->bm + v->bn) * v->rowb * v->nstage;
+        double depth = 1.0;
+        if (nslab < v->nstage) depth -= 0.02 * (v->nstage - (int)nslab);
+        if (tiles > kCUs && lds > 80 * 1024) depth -= 0.03;
+        else if (tiles <= kCUs) depth += 0.01 * v->nstage;
+        else depth += 0.005 * v->nstage;
+        score *= depth;
+        if (score > best_score) { best_score = score; best = v; }
     }
-    return best ? best : smallest;
+    return best;
 }
 
 struct Plan {
@@ -110,7 +134,7 @@ static tir_status plan_gemm(bool need_ptrs, const void* A, const void* B, void* 
              (b_rs * 128 + N) * es < kMaxExtent) bmode = B_NMAJOR;
     if (amode == A_GENERIC || bmode == B_GENERIC) { amode = A_GENERIC; bmode = B_GENERIC; }
 
-    const Variant* v = pick(in, out, amode, bmode, batch, M, N);
+    const Variant* v = pick(in, out, amode, bmode, batch, M, N, K);
     if (!v) return fail(TIR_ERR_UNSUPPORTED, "no kernel variant for this dtype / layout / forced tile");
     Params& p = plan->p;
     memset(&p, 0, sizeof p);
@@ -162,7 +186,7 @@ static tir_status plan_conv(bool need_ptrs, const void* x, const void* w, void* 
         amode = A_CONV;
         bmode = B_KMAJOR;
     }
-    const Variant* v = pick(in, out, amode, bmode, groups, Mg, Kg);
+    const Variant* v = pick(in, out, amode, bmode, groups, Mg, Kg, Kd);
     if (!v) return fail(TIR_ERR_UNSUPPORTED, "no kernel variant for this dtype / forced tile");
     Params& p = plan->p;
     memset(&p, 0, sizeof p);
@@ -256,6 +280,14 @@ void tir_debug_force_tile(int bm, int bn) {
     g_force_bm = bm;
     g_force_bn = bn;
 }
+
+void tir_debug_force_variant(const char* name_part) {
+    snprintf(g_force_name, sizeof g_force_name, "%s", name_part ? name_part : "");
+}
+
+int tir_debug_variant_count(void) { return kNumVariants; }
+
+const char* tir_debug_variant_name(int i) { return (i >= 0 && i < kNumVariants) ? kVariants[i].name : ""; }
 
 void tir_debug_tile_of_block(int bid, int tiles_m, int tiles_n, int* tm, int* tn) { tile_of_block(bid, tiles_m, tiles_n, tm, tn); }
 

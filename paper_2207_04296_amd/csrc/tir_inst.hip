@@ -50,4 +50,10 @@ template <class C> hipError_t launch_cfg(const Params& p, hipStream_t stream) {
 #endif
 #include "tir_variants.def"
 
+#if defined(TIR_TRACE) && TIR_UNIT == 0
+extern "C" int tir_debug_read_trace(unsigned long long* host64x2) {
+    return (int)hipMemcpyFromSymbol(host64x2, HIP_SYMBOL(tir_trace_buf), sizeof(unsigned long long) * 128);
+}
+#endif
+
 }  // namespace tir

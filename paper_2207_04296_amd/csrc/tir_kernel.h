@@ -99,6 +99,18 @@ template <int ROWB> __device__ __forceinline__ int kmajor_off(int row, int chunk
 // transposing read touches fall into different banks.
 template <class C> __device__ __forceinline__ int nmajor_xor(int k) { return ((k / C::RPW) % C::NSEG) * C::SEG; }
 
+#ifdef TIR_TRACE
+// Debug builds only: blocks 0 and nb/2 record the shader clock at their barriers.
+__device__ unsigned long long tir_trace_buf[2 * 64];
+#define TIR_STAMP(idx)                                                                               \
+    do {                                                                                             \
+        if (threadIdx.x == 0 && blockIdx.y == 0 && (blockIdx.x == 0 || blockIdx.x == gridDim.x / 2) && (idx) < 64) \
+            tir_trace_buf[(blockIdx.x ? 64 : 0) + (idx)] = __builtin_readcyclecounter();              \
+    } while (0)
+#else
+#define TIR_STAMP(idx) do {} while (0)
+#endif
+
 constexpr unsigned kOutOfRange = 0x80000000u;   // buffer offset no descriptor of this library reaches
 
 // Raw buffer descriptor (4 SGPRs): base address, stride 0, byte count for the range check, and the
@@ -426,6 +438,7 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
         }
     };
 
+    TIR_STAMP(0);
     if (nh > 0) {
         // prologue: fill NSTAGE-1 slots, wait for stage 0
 #pragma unroll
@@ -435,6 +448,7 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
             for (int u = 0; u < L; ++u) copy_unit(u);
         }
         copy_barrier<(NSTAGE - 2) * L>();
+        TIR_STAMP(1);
         frag.read_a(smem, 0, af[0]);
         frag.read_b(smem + C::A_BYTES, 0, bf[0]);
         TIR_FENCE();
@@ -455,13 +469,16 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
             // this wave's copy of stage h+1 has landed; after the barrier everybody's has, and
             // every wave is done reading stage h-1's slot ... and stage h (its last fragments are in registers)
             copy_barrier<(NSTAGE - 2) * L>();
+            TIR_STAMP(2 + h);
             kstep((KSTEPS - 1) & 1, na, na + C::A_BYTES, 0, 0, 0);
         }
         // the ring still has copies in flight (empty ones past the end): drain before the LDS is released
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     }
 
+    TIR_STAMP(62);
     store_tile<C>(p, bz, m0, n0, wm, wn, lane, acc);
+    TIR_STAMP(63);
 }
 
 // ---------------------------------------------------------------------------------------------

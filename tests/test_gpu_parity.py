@@ -225,3 +225,37 @@ def test_conv_1x1_equals_gemm_on_gpu(B):
     B.tir_gemm(x, wt, g, n * h * w, k, c, c, 1, 1, c, k, 1, "f16", "f32")
     torch.cuda.synchronize()
     assert torch.equal(y.view(-1, k), g)
+
+
+# ------------------------------------------------------------------------------ every compiled variant
+@pytest.mark.parametrize("dtype,out", [("f16", "f32"), ("f16", "f16"), ("bf16", "f32"), ("bf16", "bf16"), ("i8", "i32")])
+def test_every_variant_on_ragged_problems(B, oracle, dtype, out):
+    """Each tile shape / ring depth / copy mode in the library on one problem per mode whose extents
+    are ragged against every tile (several tiles, partial tiles in M and N, a K tail, more K-slabs
+    than the deepest ring) - the oracle result is computed once per problem."""
+    names = B.tir_debug_variant_names()
+    tag = f"{dtype}_{out}_"
+    dist = "i" if dtype == "i8" else "u"
+    vec = 16 if dtype == "i8" else 8
+    M, N, K = 300, 24 * vec, 49 * vec                  # N, K multiples of the vector, nothing else
+    problems = {
+        "_ak_bn": I.Workload("v_nn", "gemm", dtype, out, dist, 8100, M=M, N=N, K=K),
+        "_ak_bk": I.Workload("v_nt", "gemm", dtype, out, dist, 8200, M=M, N=N, K=K, trans_b=True),
+        "_conv": I.Workload("v_conv", "conv2d", dtype, out, "i" if dtype == "i8" else "n0.1", 8300, n=2, h=13, w=11,
+                            c=4 * vec, k=80, r=3, s=3, stride=(1, 1), pad=(1, 1), dil=(1, 1), groups=2),
+    }
+    try:
+        for suffix, wl in problems.items():
+            a_bits, b_bits = wl.operands()
+            ref, S = PT.run_oracle(wl, a_bits, b_bits, oracle)
+            if out == "bf16":       # rounding to bf16 costs up to 2^-8 |c| on top of the accumulation bound
+                S = S + 2.0 ** -8 * np.abs(ref) / 2e-3
+            todo = [n for n in names if n.startswith(tag) and n.endswith(suffix)]
+            assert todo, f"no variant for {tag}*{suffix}"
+            for name in todo:
+                _say(f"{wl.name} {name}")
+                B.tir_debug_force_variant(name)
+                got = PT.run_gpu(wl, a_bits, b_bits)
+                PT.assert_close(got, ref, S, f"{wl.name} via {name}")
+    finally:
+        B.tir_debug_force_variant("")
