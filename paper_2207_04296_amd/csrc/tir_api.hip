@@ -146,6 +146,7 @@ static tir_status plan_gemm(bool need_ptrs, const void* A, const void* B, void* 
     if ((int64_t)p.tiles_m * p.tiles_n > kMaxExtent) return fail(TIR_ERR_UNSUPPORTED, "too many output tiles");
     p.a_bs = a_bs; p.b_bs = b_bs; p.c_bs = c_bs;
     p.a_rs = a_rs; p.a_cs = a_cs; p.b_rs = b_rs; p.b_cs = b_cs; p.c_rs = c_rs; p.c_cs = c_cs;
+    p.c_fast = (c_cs == 1 && (c_rs >= N || M == 1) && (c_rs * 256 + N) * elem_size(out) < kMaxExtent) ? 1 : 0;
     plan->v = v;
     return TIR_OK;
 }
@@ -201,6 +202,7 @@ static tir_status plan_conv(bool need_ptrs, const void* x, const void* w, void* 
     p.a_rs = 0; p.a_cs = 1;
     p.b_rs = 1; p.b_cs = Kd;          // B[k][y] = w[y][k]: the KRSC filter is B stored K-major
     p.c_rs = K; p.c_cs = 1;           // NHWC output is C_t[fuse(n,h,w)][co]
+    p.c_fast = ((K * 256 + Kg) * elem_size(out) < kMaxExtent) ? 1 : 0;
     p.H = (int)H; p.W = (int)W; p.Cin = (int)C; p.Cg = (int)Cg; p.P = (int)P; p.Q = (int)Q; p.R = (int)R; p.S = (int)S;
     p.stride_h = stride_h; p.stride_w = stride_w; p.pad_h = pad_h; p.pad_w = pad_w; p.dil_h = dil_h; p.dil_w = dil_w;
     plan->v = v;

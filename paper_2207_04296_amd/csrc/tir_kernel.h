@@ -223,13 +223,43 @@ __device__ __forceinline__ void mfma_block(const uint4* af, const uint4* bf, acc
 }
 
 // Fused epilogue: convert and store the accumulators (C is fully overwritten).
+// With a unit column stride the stores go through a buffer descriptor that covers exactly the valid
+// part of this workgroup's tile: rows past M fall outside it and are dropped by the hardware, columns
+// past N are switched off per lane, and the row offset is a scalar, so a store costs no vector ALU
+// work.  Other C strides take the element-wise path.
 template <class C, class acc_t>
 __device__ __forceinline__ void store_tile(const Params& p, long long bz, int m0, int n0, int wm, int wn, int lane,
                                            acc_t (&acc)[C::MI][C::NI]) {
     typedef OutTraits<C::OUT> OT;
     typedef typename OT::type out_t;
+    constexpr int OS = (int)sizeof(out_t);
     out_t* __restrict__ Cb = (out_t*)p.C + bz * p.c_bs;
     const int l31 = lane & 31, g = lane >> 5;
+    if (p.c_fast) {
+        const int rows = p.M - m0 < C::BM ? p.M - m0 : C::BM;
+        const int cols = p.N - n0 < C::BN ? p.N - n0 : C::BN;
+        const long long bytes = ((long long)(rows - 1) * p.c_rs + cols) * OS;
+        const __amdgpu_buffer_rsrc_t rc = __builtin_amdgcn_make_buffer_rsrc(
+            (void*)(Cb + (long long)m0 * p.c_rs + n0), 0, (int)(bytes > 0x7fffffffLL ? 0x7fffffffLL : bytes), 0x00020000);
+        const int row_bytes = (int)p.c_rs * OS;
+#pragma unroll
+        for (int i = 0; i < C::MI; ++i) {
+#pragma unroll
+            for (int j = 0; j < C::NI; ++j) {
+                const int col = wn * C::TN + j * 32 + l31;
+                const int row0 = wm * C::TM + i * 32 + 4 * g;
+                const unsigned voff = col < cols ? (unsigned)(row0 * row_bytes + col * OS) : kOutOfRange;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int soff = (8 * (r >> 2) + (r & 3)) * row_bytes;      // scalar
+                    const out_t v = OT::cvt(acc[i][j][r]);
+                    if constexpr (OS == 4) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), rc, (int)voff, soff, 0);
+                    else __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(unsigned short, v), rc, (int)voff, soff, 0);
+                }
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < C::MI; ++i) {
 #pragma unroll
@@ -350,7 +380,10 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
         }
     }
 
-    // Per-stage copy state: descriptors (SGPRs) and, for the convolution, this stage's offsets.
+    // Per-stage copy state: descriptors (SGPRs) and, for the convolution, this stage's offsets and
+    // the scalar tap cursor (filter row, filter column, channel offset of the next stage).
+    const bool conv_uniform_tap = (C::AMODE == A_CONV) && (p.Cg % BK == 0);
+    int conv_fr = 0, conv_fs = 0, conv_cc = 0;
     i32x4 ra, rb;
     unsigned a_voff[C::A_IT];
     char* lds_dst = smem;    // wave-uniform destination of this wave's first A chunk
@@ -373,19 +406,39 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
         } else {
             // fuse(rh, rw, rc) -> (rh, rw, rc); a 16-byte vector never straddles a tap (Cg % VEC == 0)
             ra = make_rsrc(Ab, live ? a_bytes : 0);
-            const int kb = stage * BK + a_lc * VEC;
-            const int tap = kb / p.Cg;
-            const int cc = kb - tap * p.Cg;
-            const int fr = tap / p.S, fs = tap - fr * p.S;
-            const int dh = fr * p.dil_h, dw = fs * p.dil_w;
-            const unsigned delta = (unsigned)((dh * p.W + dw) * p.Cin + cc);
-            const bool kv = kb < p.K;
+            if (conv_uniform_tap) {
+                // Cg is a multiple of the stage's k extent: the whole stage belongs to one tap, so the tap
+                // decode is scalar and advances incrementally (stages are prepared in order)
+                const int dh = conv_fr * p.dil_h, dw = conv_fs * p.dil_w;
+                const unsigned delta = (unsigned)((dh * p.W + dw) * p.Cin + conv_cc + a_lc * VEC);
+                const bool kv = live;       // K = R*S*Cg is a multiple of the stage extent here
 #pragma unroll
-            for (int i = 0; i < C::A_IT; ++i) {
-                const int ih = (a_hw[i] >> 16) + dh;
-                const int iw = (int)(short)(a_hw[i] & 0xffff) + dw;
-                const bool ok = kv && (unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W;
-                a_voff[i] = ok ? (a_off[i] + delta) * ES : kOutOfRange;
+                for (int i = 0; i < C::A_IT; ++i) {
+                    const int ih = (a_hw[i] >> 16) + dh;
+                    const int iw = (int)(short)(a_hw[i] & 0xffff) + dw;
+                    const bool ok = kv && (unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W;
+                    a_voff[i] = ok ? (a_off[i] + delta) * ES : kOutOfRange;
+                }
+                conv_cc += BK;
+                if (conv_cc >= p.Cg) {
+                    conv_cc = 0;
+                    if (++conv_fs == p.S) { conv_fs = 0; ++conv_fr; }
+                }
+            } else {
+                const int kb = stage * BK + a_lc * VEC;
+                const int tap = kb / p.Cg;
+                const int cc = kb - tap * p.Cg;
+                const int fr = tap / p.S, fs = tap - fr * p.S;
+                const int dh = fr * p.dil_h, dw = fs * p.dil_w;
+                const unsigned delta = (unsigned)((dh * p.W + dw) * p.Cin + cc);
+                const bool kv = kb < p.K;
+#pragma unroll
+                for (int i = 0; i < C::A_IT; ++i) {
+                    const int ih = (a_hw[i] >> 16) + dh;
+                    const int iw = (int)(short)(a_hw[i] & 0xffff) + dw;
+                    const bool ok = kv && (unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W;
+                    a_voff[i] = ok ? (a_off[i] + delta) * ES : kOutOfRange;
+                }
             }
         }
         if constexpr (C::BMODE == B_KMAJOR) {

@@ -27,6 +27,7 @@ struct Params {
     int M, N, K;      // extents of one contraction (per batch / per group)
     int batch;        // number of independent contractions (grid.y)
     int tiles_m, tiles_n;
+    int c_fast;       // C has unit column stride, disjoint rows and 31-bit tile offsets: buffer-store epilogue
     long long a_bs, b_bs, c_bs;                 // per-batch offsets, in elements
     long long a_rs, a_cs, b_rs, b_cs, c_rs, c_cs;  // element strides; for conv: a_* unused
     // convolution geometry (A_CONV*): x is [n][H][W][Cin], one group reads Cg channels
