@@ -96,6 +96,27 @@ def variant_of(B, wl):
     return B.tir_gemm_variant(wl.batch, wl.M, wl.N, wl.K, wl.K, 1, b_rs, b_cs, wl.N, 1, wl.dtype, wl.out)
 
 
+def mfma_ceiling(torch, B):
+    """Sustained rate of a register-only fp16 MFMA loop (TFLOP/s): the practical ceiling of the matrix
+    pipes under the power management, for constant and for random operands."""
+    sink = torch.zeros(4, device="cuda:0")
+    out = {}
+    for label, rnd in (("const_operands", False), ("random_operands", True)):
+        B.tir_probe_mfma_rate(sink, 200, rnd)
+        torch.cuda.synchronize()
+        best = 0.0
+        for _ in range(3):
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            e0.record()
+            flop = B.tir_probe_mfma_rate(sink, 2000, rnd)
+            e1.record()
+            torch.cuda.synchronize()
+            best = max(best, flop / (e0.elapsed_time(e1) * 1e-3) / 1e12)
+        out[label] = round(best, 1)
+    return out
+
+
 def cpu_baseline(wl):
     """The oracle, as it stands, on this machine's host cores; whole workload, repeated for ~seconds."""
     import oracle
@@ -192,6 +213,7 @@ def main():
                      "kernel": variant_of(B, wl), "avg_launch_us": round(launch_s * 1e6, 3),
                      "algorithmic_flop_per_launch": wl.flops(), "algorithmic_bytes_per_launch": wl.min_bytes()},
         "operators": operators,
+        "mfma_sustained_tflops": mfma_ceiling(torch, B),
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl)

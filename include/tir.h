@@ -113,6 +113,15 @@ int tir_debug_variant_count(void);
 const char* tir_debug_variant_name(int i);
 void tir_debug_tile_of_block(int bid, int tiles_m, int tiles_n, int* tm, int* tn);
 
+/*
+ * Measurement aid: enqueue a register-only fp16 MFMA loop (no memory traffic) of `iters` x 16 MFMAs
+ * per wave on 1024 workgroups and report its FLOP count in *flop (may be NULL).  Timed by the
+ * caller, it gives the rate the matrix pipes sustain at the clock the power management allows:
+ * operands are constants (random_operands = 0) or pseudo-random values in (-1, 1).  `sink` is a
+ * device pointer to at least 4 bytes that is practically never written.
+ */
+tir_status tir_probe_mfma_rate(void* sink, int iters, int random_operands, double* flop, tir_stream stream);
+
 /* Library version as "major.minor". */
 const char* tir_version(void);
 

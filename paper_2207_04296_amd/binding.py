@@ -18,7 +18,7 @@ DTYPE_CODES = {"f16": TIR_F16, "bf16": TIR_BF16, "i8": TIR_I8, "f32": TIR_F32, "
 
 EXPORTS = ["tir_gemm", "tir_batch_matmul", "tir_conv2d", "tir_last_error", "tir_gemm_variant",
            "tir_conv2d_variant", "tir_debug_force_tile", "tir_debug_force_variant", "tir_debug_variant_count",
-           "tir_debug_variant_name", "tir_debug_tile_of_block", "tir_version"]
+           "tir_debug_variant_name", "tir_debug_tile_of_block", "tir_probe_mfma_rate", "tir_version"]
 
 
 class TirError(RuntimeError):
@@ -64,6 +64,8 @@ def lib() -> ctypes.CDLL:
     L.tir_debug_variant_name.restype = ctypes.c_char_p
     L.tir_debug_tile_of_block.argtypes = [ci, ci, ci, ctypes.POINTER(ci), ctypes.POINTER(ci)]
     L.tir_debug_tile_of_block.restype = None
+    L.tir_probe_mfma_rate.argtypes = [vp, ci, ci, ctypes.POINTER(ctypes.c_double), vp]
+    L.tir_probe_mfma_rate.restype = ci
     L.tir_version.restype = ctypes.c_char_p
     _lib = L
     return L
@@ -163,6 +165,14 @@ def tir_debug_tile_of_block(bid: int, tiles_m: int, tiles_n: int):
     tm, tn = ctypes.c_int(), ctypes.c_int()
     lib().tir_debug_tile_of_block(bid, tiles_m, tiles_n, ctypes.byref(tm), ctypes.byref(tn))
     return tm.value, tn.value
+
+
+def tir_probe_mfma_rate(sink, iters: int, random_operands: bool, stream=None) -> float:
+    """Enqueue the MFMA-rate probe; returns its FLOP count (time it with events around the call)."""
+    flop = ctypes.c_double()
+    _check(lib().tir_probe_mfma_rate(_ptr(sink), int(iters), int(bool(random_operands)), ctypes.byref(flop),
+                                     _stream(stream)))
+    return flop.value
 
 
 def tir_version() -> str:

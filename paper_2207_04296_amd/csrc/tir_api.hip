@@ -11,6 +11,35 @@
 
 namespace tir {
 
+// ------------------------------------------------------------------------------- MFMA rate probe
+// Register-only MFMA loop: 4 waves per workgroup, 16 independent 32x32 accumulators per wave, no
+// memory traffic inside the loop.  What it sustains is the practical ceiling of the matrix pipes at
+// the clock the power management allows for the given operand statistics.
+typedef _Float16 probe_f16x8 __attribute__((ext_vector_type(8)));
+typedef float probe_f32x16 __attribute__((ext_vector_type(16)));
+
+__global__ void __launch_bounds__(256) mfma_probe_kernel(float* sink, int iters, int random_operands) {
+    probe_f32x16 acc[16];
+    for (int i = 0; i < 16; ++i)
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+    probe_f16x8 a, b;
+    unsigned x = threadIdx.x * 2654435761u + blockIdx.x * 40503u + 12345u;
+    for (int e = 0; e < 8; ++e) {
+        x ^= x >> 15; x *= 2246822519u; x ^= x >> 13;
+        a[e] = (_Float16)(random_operands ? ((x & 0xffff) / 32768.0f - 1.0f) : 1.0f);
+        x *= 3266489917u; x ^= x >> 16;
+        b[e] = (_Float16)(random_operands ? ((x & 0xffff) / 32768.0f - 1.0f) : 0.5f);
+    }
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, acc[i], 0, 0, 0);
+    }
+    float s = 0.f;
+    for (int i = 0; i < 16; ++i)
+        for (int r = 0; r < 16; ++r) s += acc[i][r];
+    if (s == 123.456f) sink[0] = s;      // keeps the loop alive, practically never stores
+}
+
 // ------------------------------------------------------------------------------- variant table
 #define TIR_ROW(name, DT, OUT, BM, BN, WM, WN, AM, BMO, RB, NS) \
     {name, DT, OUT, BM, BN, WM, WN, AM, BMO, RB, NS, &launch_cfg<Cfg<DT, OUT, BM, BN, WM, WN, AM, BMO, RB, NS>>},
@@ -292,6 +321,15 @@ int tir_debug_variant_count(void) { return kNumVariants; }
 const char* tir_debug_variant_name(int i) { return (i >= 0 && i < kNumVariants) ? kVariants[i].name : ""; }
 
 void tir_debug_tile_of_block(int bid, int tiles_m, int tiles_n, int* tm, int* tn) { tile_of_block(bid, tiles_m, tiles_n, tm, tn); }
+
+tir_status tir_probe_mfma_rate(void* sink, int iters, int random_operands, double* flop, tir_stream stream) {
+    if (!sink || iters <= 0) return fail(TIR_ERR_INVALID_ARG, "tir_probe_mfma_rate: sink is null or iters <= 0");
+    hipLaunchKernelGGL(mfma_probe_kernel, dim3(1024), dim3(256), 0, (hipStream_t)stream, (float*)sink, iters, random_operands);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(TIR_ERR_LAUNCH, "probe launch failed: %s", hipGetErrorString(e));
+    if (flop) *flop = 1024.0 * 4.0 * (double)iters * 16.0 * 32768.0;
+    return TIR_OK;
+}
 
 const char* tir_version(void) { return "0.1"; }
 
