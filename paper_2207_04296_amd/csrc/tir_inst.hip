@@ -12,7 +12,10 @@ namespace tir {
 
 template <class C> hipError_t launch_cfg(const Params& p, hipStream_t stream) {
     dim3 grid((unsigned)(p.tiles_m * p.tiles_n), (unsigned)p.batch, 1);
-    if constexpr (C::AMODE == A_GENERIC || C::AMODE == A_CONV_GENERIC)
+    if constexpr (C::AMODE == A_CONV_PATCH) {
+        grid.x = (unsigned)(p.batch_imgs * p.tiles_m * p.tiles_n);
+        hipLaunchKernelGGL((conv_patch_kernel<C::DT, C::OUT>), grid, dim3(256), 0, stream, p);
+    } else if constexpr (C::AMODE == A_GENERIC || C::AMODE == A_CONV_GENERIC)
         hipLaunchKernelGGL(contract_staged_kernel<C>, grid, dim3(C::THREADS), 0, stream, p);
     else
         hipLaunchKernelGGL(contract_direct_kernel<C>, grid, dim3(C::THREADS), 0, stream, p);

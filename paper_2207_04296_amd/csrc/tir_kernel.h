@@ -535,6 +535,198 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
 }
 
 // ---------------------------------------------------------------------------------------------
+// Convolution with an LDS-resident input patch (channels per group = 128 bytes per pixel).
+//
+// The implicit-GEMM kernel above sends the im2col matrix A_t through the global->LDS copy, i.e.
+// every input pixel R*S times.  Here the ReIndex step is applied on the LDS side instead: a
+// workgroup owns 256 consecutive output pixels of one image, copies the input rows they touch
+// (full width plus the zero halo, which out-of-range lanes of the copy deliver) into LDS once, and
+// the MFMA A-fragments of tap (rh, rw) are read from that patch at
+//     pixel(p*s_h + rh*d_h, q*s_w + rw*d_w)
+// - the same formula as the paper's A_r[n,h,w,rh,rw,rc], evaluated per LDS read.  The filter
+// streams through a 4-slot ring of [64 output channels][128 B] slabs, one slab per tap.
+// One LDS row per patch pixel, same XOR swizzle as the K-major tiles (keyed by the pixel index).
+// 4 waves; wave w owns output pixels [64w, 64w+64) x 64 output channels (2x2 MFMA blocks).
+// ---------------------------------------------------------------------------------------------
+template <int DT, int OUT>
+__global__ void __launch_bounds__(256) conv_patch_kernel(const Params p) {
+    typedef typename InTraits<DT>::acc_t acc_t;
+    typedef OutTraits<OUT> OT;
+    typedef typename OT::type out_t;
+    constexpr int ES = elem_size(DT), OS = (int)sizeof(out_t);
+    constexpr int SLAB = 64 * 128;              // one filter tap: 64 output channels x 128 B
+    constexpr int NSLOT = 4;
+    constexpr int PATCH_BYTES = 160 * 1024 - NSLOT * SLAB;
+
+    __shared__ __attribute__((aligned(1024))) char smem[160 * 1024];
+    char* const s_patch = smem;
+    char* const s_filt = smem + PATCH_BYTES;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l31 = lane & 31, g = lane >> 5;
+
+    // workgroup -> (image, pixel tile, channel tile); group = blockIdx.y
+    const int bid = blockIdx.x;
+    const int nt = bid % p.tiles_n;
+    const int rest = bid / p.tiles_n;
+    const int tix = rest % p.tiles_m;           // tiles_m = pixel tiles per image here
+    const int img = rest / p.tiles_m;
+    const int grp = blockIdx.y;
+    const int PQ = p.P * p.Q;
+    const int m_first = tix * 256;
+    const int m_cnt = PQ - m_first < 256 ? PQ - m_first : 256;
+    const int n0 = nt * 64;
+    const int ncols = p.N - n0 < 64 ? p.N - n0 : 64;          // N = output channels per group
+    const int RS = p.R * p.S;
+
+    // patch geometry: output rows p_a..p_b of this image, input rows ih_base .. ih_base + nrows - 1
+    const int p_a = m_first / p.Q, p_b = (m_first + m_cnt - 1) / p.Q;
+    const int ih_base = p_a * p.stride_h - p.pad_h;
+    const int nrows = (p_b - p_a) * p.stride_h + (p.R - 1) * p.dil_h + 1;
+    const int PW = p.PW;                        // (Q-1)*s_w + (S-1)*d_w + 1 patch columns, first is iw = -pad_w
+    const int npix = nrows * PW;
+
+    // ------------------------------------------------------------ copy: patch (once)
+    {
+        const i32x4 rx = make_rsrc((const char*)p.A, (long long)p.batch_imgs * p.H * p.W * p.Cin * ES);
+        const unsigned gofs = (unsigned)(grp * p.Cg * ES);
+        const int pc = tid & 7;
+        int px = tid >> 3;                      // 32 pixels per pass of the workgroup
+        int pr = px / PW, pcx = px - pr * PW;
+        const int d_r = 32 / PW, d_c = 32 - d_r * PW;
+        const int nit = (npix + 31) >> 5;
+        for (int it = 0; it < nit; ++it) {
+            const int lc = pc ^ kmajor_swz<128>(px);
+            const int ih = ih_base + pr, iw = pcx - p.pad_w;
+            const bool ok = px < npix && (unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W;
+            const unsigned voff = ok ? (unsigned)(((img * p.H + ih) * p.W + iw) * p.Cin) * ES + gofs + lc * 16 : kOutOfRange;
+            load_to_lds(rx, s_patch + it * 4096 + wave * 1024, voff);
+            px += 32;
+            pr += d_r;
+            pcx += d_c;
+            if (pcx >= PW) { pcx -= PW; ++pr; }
+        }
+    }
+
+    // ------------------------------------------------------------ copy: filter ring (one slab per tap)
+    const long long Kd = p.K;                                   // R*S*Cg
+    const char* wbase = (const char*)p.B + ((long long)grp * p.N + n0) * Kd * ES;
+    unsigned w_off[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int q2 = j * 256 + tid;
+        const int n = q2 >> 3;
+        const int lc = (q2 & 7) ^ kmajor_swz<128>(n);
+        w_off[j] = n < ncols ? (unsigned)(n * (int)Kd * ES) + lc * 16 : kOutOfRange;
+    }
+    auto issue_slab = [&](int t) {
+        const i32x4 rw = make_rsrc(wbase + (long long)t * p.Cg * ES, t < RS ? ((long long)(ncols - 1) * Kd + p.Cg) * ES : 0);
+        char* dst = s_filt + (t & (NSLOT - 1)) * SLAB + wave * 1024;
+        load_to_lds(rw, dst, w_off[0]);
+        load_to_lds(rw, dst + 4096, w_off[1]);
+    };
+    issue_slab(0);
+    issue_slab(1);
+    issue_slab(2);
+
+    // ------------------------------------------------------------ fragment addressing
+    // lane's output pixel of MFMA block i: m = 64*wave + 32*i + l31 -> patch pixel of tap (0,0)
+    int base_px[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        int m = wave * 64 + i * 32 + l31;
+        if (m >= m_cnt) m = m_cnt - 1;                         // rows past the tile re-read its last pixel; never stored
+        const int mm = m_first + m;
+        const int op = mm / p.Q, oq = mm - op * p.Q;
+        base_px[i] = (op - p_a) * p.stride_h * PW + oq * p.stride_w;
+    }
+    const int swn = kmajor_swz<128>(l31);
+    auto read_a = [&](int tap_px, int kk, int i) -> uint4 {
+        const int px = base_px[i] + tap_px;
+        return *(const uint4*)(s_patch + px * 128 + (((2 * kk + g) ^ kmajor_swz<128>(px)) << 4));
+    };
+    auto read_b = [&](int t, int kk, int j) -> uint4 {
+        return *(const uint4*)(s_filt + (t & (NSLOT - 1)) * SLAB + (j * 32 + l31) * 128 + (((2 * kk + g) ^ swn) << 4));
+    };
+
+    acc_t acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;       // reduction init
+
+    uint4 af[2][2], bf[2][2];
+    copy_barrier<2>();           // patch, slabs 0 and 1 have landed (slab 2 may still be in flight)
+    af[0][0] = read_a(0, 0, 0); af[0][1] = read_a(0, 0, 1);
+    bf[0][0] = read_b(0, 0, 0); bf[0][1] = read_b(0, 0, 1);
+    TIR_FENCE();
+
+    int fr = 0, fs = 0;                           // filter row / column of the current tap
+    for (int t = 0; t < RS; ++t) {
+        const int tap_px = fr * p.dil_h * PW + fs * p.dil_w;
+        int nfs = fs + 1, nfr = fr;
+        if (nfs == p.S) { nfs = 0; ++nfr; }
+        const int next_px = nfr * p.dil_h * PW + nfs * p.dil_w;   // past the last tap: still inside the patch rows read before
+        const bool last = t + 1 == RS;
+        issue_slab(t + 3);                        // its slot held tap t-1, released by the barrier below
+        TIR_FENCE();
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            const int set = kk & 1;
+            // fragments of the next k-step (or of the next tap's first k-step) are requested between the MFMAs
+            const int rk = kk == 3 ? 0 : kk + 1;
+            const int rpx = kk == 3 ? (last ? tap_px : next_px) : tap_px;
+            const int rt = kk == 3 ? (last ? t : t + 1) : t;
+            acc[0][0] = InTraits<DT>::mfma(af[set][0], bf[set][0], acc[0][0]);
+            TIR_FENCE();
+            af[set ^ 1][0] = read_a(rpx, rk, 0);
+            bf[set ^ 1][0] = read_b(rt, rk, 0);
+            TIR_FENCE();
+            acc[0][1] = InTraits<DT>::mfma(af[set][0], bf[set][1], acc[0][1]);
+            TIR_FENCE();
+            af[set ^ 1][1] = read_a(rpx, rk, 1);
+            bf[set ^ 1][1] = read_b(rt, rk, 1);
+            TIR_FENCE();
+            acc[1][0] = InTraits<DT>::mfma(af[set][1], bf[set][0], acc[1][0]);
+            acc[1][1] = InTraits<DT>::mfma(af[set][1], bf[set][1], acc[1][1]);
+            TIR_FENCE();
+        }
+        // slab t+2 has landed (only slab t+3 may be in flight); after the barrier every wave sees it and
+        // nobody reads slab t any more
+        copy_barrier<2>();
+        fr = nfr;
+        fs = nfs;
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+
+    // ------------------------------------------------------------ fused epilogue (NHWC rows are output pixels)
+    out_t* ybase = (out_t*)p.C + ((long long)img * PQ + m_first) * p.c_rs + (long long)grp * p.N + n0;
+    const long long bytes = ((long long)(m_cnt - 1) * p.c_rs + ncols) * OS;
+    const __amdgpu_buffer_rsrc_t rc = __builtin_amdgcn_make_buffer_rsrc((void*)ybase, 0, (int)bytes, 0x00020000);
+    const int row_bytes = (int)p.c_rs * OS;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int col = j * 32 + l31;
+            const int row0 = wave * 64 + i * 32 + 4 * g;
+            const unsigned voff = col < ncols ? (unsigned)(row0 * row_bytes + col * OS) : kOutOfRange;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int soff = (8 * (r >> 2) + (r & 3)) * row_bytes;
+                const out_t v = OT::cvt(acc[i][j][r]);
+                if constexpr (OS == 4) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), rc, (int)voff, soff, 0);
+                else __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(unsigned short, v), rc, (int)voff, soff, 0);
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // General kernel: any strides / any channel count, element-wise loads staged through registers.
 // Same LDS layout (both operands K-major) and the same MFMA stage as the fast kernel.
 // ---------------------------------------------------------------------------------------------

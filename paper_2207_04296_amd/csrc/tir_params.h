@@ -12,7 +12,8 @@ enum : int {
     A_KMAJOR = 0,   // A[x][k], k contiguous, 16-byte vectors
     A_CONV = 1,     // implicit im2col of an NHWC tensor, channel vectors of 16 bytes
     A_GENERIC = 2,  // any strides, element-wise loads
-    A_CONV_GENERIC = 3  // implicit im2col, element-wise (C/groups not a multiple of the vector)
+    A_CONV_GENERIC = 3,  // implicit im2col, element-wise (C/groups not a multiple of the vector)
+    A_CONV_PATCH = 4     // convolution reading its taps from an LDS-resident input patch (128 B per pixel)
 };
 enum : int {
     B_KMAJOR = 0,   // B stored [y][k], k contiguous (a "transposed" B, or a KRSC filter)
@@ -33,6 +34,8 @@ struct Params {
     // convolution geometry (A_CONV*): x is [n][H][W][Cin], one group reads Cg channels
     int H, W, Cin, Cg, P, Q, R, S;
     int stride_h, stride_w, pad_h, pad_w, dil_h, dil_w;
+    int PW;           // patch kernel: columns of the LDS-resident input patch
+    int batch_imgs;   // patch kernel: images in x (for the descriptor)
 };
 
 // Number of XCDs (L2 domains) workgroups are dealt to round-robin by the dispatcher.

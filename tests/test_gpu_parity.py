@@ -259,3 +259,40 @@ def test_every_variant_on_ragged_problems(B, oracle, dtype, out):
                 PT.assert_close(got, ref, S, f"{wl.name} via {name}")
     finally:
         B.tir_debug_force_variant("")
+
+
+# ------------------------------------------------------------------------------ LDS-resident-patch convolution
+PATCH_CASES = [
+    # n, h, w, c_per_group_bytes=128 -> c, k, r, s, stride, pad, dil, groups
+    (2, 20, 23, 1, 64, 3, 3, (1, 1), (1, 1), (1, 1)),       # several pixel tiles, ragged last tile
+    (1, 23, 29, 1, 96, 3, 3, (2, 2), (1, 1), (1, 1)),       # stride 2, 96 output channels = 1.5 channel tiles
+    (2, 17, 19, 2, 48, 3, 3, (1, 1), (2, 2), (2, 2)),       # dilation 2, 2 groups of 24 output channels
+    (1, 40, 12, 1, 64, 5, 1, (1, 2), (2, 0), (1, 1)),       # 5x1 filter, stride (1,2)
+    (3, 12, 12, 1, 32, 1, 1, (1, 1), (0, 0), (1, 1)),       # 1x1: a single tap
+    (1, 16, 16, 1, 64, 3, 3, (1, 1), (0, 0), (1, 1)),       # no padding
+    (1, 14, 100, 1, 64, 3, 3, (1, 1), (1, 1), (1, 1)),      # wide rows: few rows per tile
+]
+
+
+@pytest.mark.parametrize("dtype,out", [("f16", "f16"), ("f16", "f32"), ("bf16", "f32"), ("i8", "i32")])
+def test_conv_patch_kernel(B, oracle, dtype, out):
+    """Shapes with exactly 128 bytes of channels per pixel and group take the LDS-resident-patch kernel;
+    the same shapes are also pushed through the implicit-GEMM kernel."""
+    cg = 128 if dtype == "i8" else 64
+    for (n, h, w, groups, k, r, s, stride, pad, dil) in PATCH_CASES:
+        c = cg * groups
+        wl = I.Workload(f"patch_n{n}h{h}w{w}g{groups}k{k}r{r}s{s}_st{stride}_p{pad}_d{dil}_{dtype}_{out}", "conv2d", dtype, out,
+                        "i" if dtype == "i8" else "n0.1", 7600 + h + k, n=n, h=h, w=w, c=c, k=k, r=r, s=s, stride=stride,
+                        pad=pad, dil=dil, groups=groups)
+        a_bits, b_bits = wl.operands()
+        ref, S = PT.run_oracle(wl, a_bits, b_bits, oracle)
+        try:
+            for force in ("", "t128x64w2x2s3_conv"):
+                B.tir_debug_force_variant(force)
+                name = B.tir_conv2d_variant(n, h, w, c, k, r, s, *stride, *pad, *dil, groups, dtype, out)
+                _say(f"{wl.name} -> {name}")
+                assert ("patch" in name) == (force == ""), name
+                got = PT.run_gpu(wl, a_bits, b_bits)
+                PT.assert_close(got, ref, S, f"{wl.name} via {name}")
+        finally:
+            B.tir_debug_force_variant("")
