@@ -14,7 +14,7 @@ template <class C> hipError_t launch_cfg(const Params& p, hipStream_t stream) {
     dim3 grid((unsigned)(p.tiles_m * p.tiles_n), (unsigned)p.batch, 1);
     if constexpr (C::AMODE == A_CONV_PATCH) {
         grid.x = (unsigned)(p.batch_imgs * p.tiles_m * p.tiles_n);
-        hipLaunchKernelGGL((conv_patch_kernel<C::DT, C::OUT>), grid, dim3(256), 0, stream, p);
+        hipLaunchKernelGGL((conv_patch_kernel<C::DT, C::OUT>), grid, dim3(512), 0, stream, p);
     } else if constexpr (C::AMODE == A_GENERIC || C::AMODE == A_CONV_GENERIC)
         hipLaunchKernelGGL(contract_staged_kernel<C>, grid, dim3(C::THREADS), 0, stream, p);
     else
@@ -52,11 +52,5 @@ template <class C> hipError_t launch_cfg(const Params& p, hipStream_t stream) {
 #define V4 TIR_SKIP
 #endif
 #include "tir_variants.def"
-
-#if defined(TIR_TRACE) && TIR_UNIT == 0
-extern "C" int tir_debug_read_trace(unsigned long long* host64x2) {
-    return (int)hipMemcpyFromSymbol(host64x2, HIP_SYMBOL(tir_trace_buf), sizeof(unsigned long long) * 128);
-}
-#endif
 
 }  // namespace tir

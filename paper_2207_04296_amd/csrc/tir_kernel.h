@@ -99,17 +99,6 @@ template <int ROWB> __device__ __forceinline__ int kmajor_off(int row, int chunk
 // transposing read touches fall into different banks.
 template <class C> __device__ __forceinline__ int nmajor_xor(int k) { return ((k / C::RPW) % C::NSEG) * C::SEG; }
 
-#ifdef TIR_TRACE
-// Debug builds only: blocks 0 and nb/2 record the shader clock at their barriers.
-__device__ unsigned long long tir_trace_buf[2 * 64];
-#define TIR_STAMP(idx)                                                                               \
-    do {                                                                                             \
-        if (threadIdx.x == 0 && blockIdx.y == 0 && (blockIdx.x == 0 || blockIdx.x == gridDim.x / 2) && (idx) < 64) \
-            tir_trace_buf[(blockIdx.x ? 64 : 0) + (idx)] = __builtin_readcyclecounter();              \
-    } while (0)
-#else
-#define TIR_STAMP(idx) do {} while (0)
-#endif
 
 constexpr unsigned kOutOfRange = 0x80000000u;   // buffer offset no descriptor of this library reaches
 
@@ -118,10 +107,12 @@ constexpr unsigned kOutOfRange = 0x80000000u;   // buffer offset no descriptor o
 __device__ __forceinline__ i32x4 make_rsrc(const void* base, long long bytes) {
     const unsigned n = bytes <= 0 ? 0u : (bytes > 0x7fffffffLL ? 0x7fffffffu : (unsigned)bytes);
     const unsigned long long a = (unsigned long long)base;
+    // the descriptor must sit in scalar registers: readfirstlane is free for values the compiler already
+    // knows to be uniform and forces the others
     i32x4 r;
-    r[0] = (int)(unsigned)a;
-    r[1] = (int)((unsigned)(a >> 32) & 0xffffu);
-    r[2] = (int)n;
+    r[0] = __builtin_amdgcn_readfirstlane((int)(unsigned)a);
+    r[1] = __builtin_amdgcn_readfirstlane((int)((unsigned)(a >> 32) & 0xffffu));
+    r[2] = __builtin_amdgcn_readfirstlane((int)n);
     r[3] = 0x00020000;
     return r;
 }
@@ -145,6 +136,20 @@ __device__ __forceinline__ void load_to_lds(const i32x4& rsrc, const char* lds_b
 // the newest PENDING must have landed) and retires its LDS reads of the slot that is refilled next.
 template <int PENDING> __device__ __forceinline__ void copy_barrier() {
     asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(PENDING) : "memory");
+}
+
+// s_waitcnt takes an immediate; this waits until at most n (wave-uniform, rounded down to even, capped
+// at 62) vector-memory operations of the wave are outstanding.
+__device__ __forceinline__ void wait_vmcnt_upto(int n) {
+#define TIR_W(k) case k: asm volatile("s_waitcnt vmcnt(" #k ")" ::: "memory"); break;
+    switch (n < 0 ? 0 : (n > 62 ? 62 : (n & ~1))) {
+        TIR_W(0) TIR_W(2) TIR_W(4) TIR_W(6) TIR_W(8) TIR_W(10) TIR_W(12) TIR_W(14) TIR_W(16) TIR_W(18) TIR_W(20)
+        TIR_W(22) TIR_W(24) TIR_W(26) TIR_W(28) TIR_W(30) TIR_W(32) TIR_W(34) TIR_W(36) TIR_W(38) TIR_W(40)
+        TIR_W(42) TIR_W(44) TIR_W(46) TIR_W(48) TIR_W(50) TIR_W(52) TIR_W(54) TIR_W(56) TIR_W(58) TIR_W(60)
+        TIR_W(62)
+        default: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
+    }
+#undef TIR_W
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -491,7 +496,6 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
         }
     };
 
-    TIR_STAMP(0);
     if (nh > 0) {
         // prologue: fill NSTAGE-1 slots, wait for stage 0
 #pragma unroll
@@ -501,7 +505,6 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
             for (int u = 0; u < L; ++u) copy_unit(u);
         }
         copy_barrier<(NSTAGE - 2) * L>();
-        TIR_STAMP(1);
         frag.read_a(smem, 0, af[0]);
         frag.read_b(smem + C::A_BYTES, 0, bf[0]);
         TIR_FENCE();
@@ -522,16 +525,13 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
             // this wave's copy of stage h+1 has landed; after the barrier everybody's has, and
             // every wave is done reading stage h-1's slot ... and stage h (its last fragments are in registers)
             copy_barrier<(NSTAGE - 2) * L>();
-            TIR_STAMP(2 + h);
             kstep((KSTEPS - 1) & 1, na, na + C::A_BYTES, 0, 0, 0);
         }
         // the ring still has copies in flight (empty ones past the end): drain before the LDS is released
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     }
 
-    TIR_STAMP(62);
     store_tile<C>(p, bz, m0, n0, wm, wn, lane, acc);
-    TIR_STAMP(63);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -549,22 +549,25 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
 // 4 waves; wave w owns output pixels [64w, 64w+64) x 64 output channels (2x2 MFMA blocks).
 // ---------------------------------------------------------------------------------------------
 template <int DT, int OUT>
-__global__ void __launch_bounds__(256) conv_patch_kernel(const Params p) {
+__global__ void __launch_bounds__(512) conv_patch_kernel(const Params p) {
     typedef typename InTraits<DT>::acc_t acc_t;
     typedef OutTraits<OUT> OT;
     typedef typename OT::type out_t;
     constexpr int ES = elem_size(DT), OS = (int)sizeof(out_t);
     constexpr int SLAB = 64 * 128;              // one filter tap: 64 output channels x 128 B
-    constexpr int NSLOT = 4;
-    constexpr int PATCH_BYTES = 160 * 1024 - NSLOT * SLAB;
 
     __shared__ __attribute__((aligned(1024))) char smem[160 * 1024];
-    char* const s_patch = smem;
-    char* const s_filt = smem + PATCH_BYTES;
+    char* const s_filt = smem;                  // R*S slabs, then the patch (the host checked that both fit)
+    char* const s_patch = smem + p.R * p.S * SLAB;
 
-    const int tid = threadIdx.x;
+    // Waves 0-3 multiply, waves 4-7 only copy.  A global->LDS copy instruction occupies its wave for
+    // far longer than an MFMA does, and a wave issues in order: if the multiplying waves issued the
+    // copies themselves, the matrix pipes would idle behind every one of them.
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const bool copier = wave >= 4;
+    const int cw = wave & 3;                    // index within the role
+    const int tid = threadIdx.x & 255;          // thread index within the role
     const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l31 = lane & 31, g = lane >> 5;
 
     // workgroup -> (image, pixel tile, channel tile); group = blockIdx.y
@@ -588,55 +591,65 @@ __global__ void __launch_bounds__(256) conv_patch_kernel(const Params p) {
     const int PW = p.PW;                        // (Q-1)*s_w + (S-1)*d_w + 1 patch columns, first is iw = -pad_w
     const int npix = nrows * PW;
 
-    // ------------------------------------------------------------ copy: patch (once)
-    {
-        const i32x4 rx = make_rsrc((const char*)p.A, (long long)p.batch_imgs * p.H * p.W * p.Cin * ES);
-        const unsigned gofs = (unsigned)(grp * p.Cg * ES);
-        const int pc = tid & 7;
-        int px = tid >> 3;                      // 32 pixels per pass of the workgroup
-        int pr = px / PW, pcx = px - pr * PW;
-        const int d_r = 32 / PW, d_c = 32 - d_r * PW;
-        const int nit = (npix + 31) >> 5;
-        for (int it = 0; it < nit; ++it) {
-            const int lc = pc ^ kmajor_swz<128>(px);
-            const int ih = ih_base + pr, iw = pcx - p.pad_w;
-            const bool ok = px < npix && (unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W;
-            const unsigned voff = ok ? (unsigned)(((img * p.H + ih) * p.W + iw) * p.Cin) * ES + gofs + lc * 16 : kOutOfRange;
-            load_to_lds(rx, s_patch + it * 4096 + wave * 1024, voff);
-            px += 32;
-            pr += d_r;
-            pcx += d_c;
-            if (pcx >= PW) { pcx -= PW; ++pr; }
+    if (copier) {
+        // ------------------------------------------------------------ copy: patch, then one filter slab per tap
+        {
+            const i32x4 rx = make_rsrc((const char*)p.A, (long long)p.batch_imgs * p.H * p.W * p.Cin * ES);
+            const unsigned gofs = (unsigned)(grp * p.Cg * ES);
+            const int pc = tid & 7;
+            int px = tid >> 3;                  // 32 pixels per pass of the four copy waves
+            int pr = px / PW, pcx = px - pr * PW;
+            const int d_r = 32 / PW, d_c = 32 - d_r * PW;
+            const int nit = (npix + 31) >> 5;
+            for (int it = 0; it < nit; ++it) {
+                const int lc = pc ^ kmajor_swz<128>(px);
+                const int ih = ih_base + pr, iw = pcx - p.pad_w;
+                const bool ok = px < npix && (unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W;
+                const unsigned voff = ok ? (unsigned)(((img * p.H + ih) * p.W + iw) * p.Cin) * ES + gofs + lc * 16 : kOutOfRange;
+                load_to_lds(rx, s_patch + it * 4096 + cw * 1024, voff);
+                px += 32;
+                pr += d_r;
+                pcx += d_c;
+                if (pcx >= PW) { pcx -= PW; ++pr; }
+            }
         }
-    }
-
-    // ------------------------------------------------------------ copy: filter ring (one slab per tap)
-    const long long Kd = p.K;                                   // R*S*Cg
-    const char* wbase = (const char*)p.B + ((long long)grp * p.N + n0) * Kd * ES;
-    unsigned w_off[2];
+        const long long Kd = p.K;                               // R*S*Cg
+        const char* wbase = (const char*)p.B + ((long long)grp * p.N + n0) * Kd * ES;
+        unsigned w_off[2];
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const int q2 = j * 256 + tid;
-        const int n = q2 >> 3;
-        const int lc = (q2 & 7) ^ kmajor_swz<128>(n);
-        w_off[j] = n < ncols ? (unsigned)(n * (int)Kd * ES) + lc * 16 : kOutOfRange;
+        for (int j = 0; j < 2; ++j) {
+            const int q2 = j * 256 + tid;
+            const int n = q2 >> 3;
+            const int lc = (q2 & 7) ^ kmajor_swz<128>(n);
+            w_off[j] = n < ncols ? (unsigned)(n * (int)Kd * ES) + lc * 16 : kOutOfRange;
+        }
+        auto issue_slab = [&](int t) {
+            const i32x4 rw = make_rsrc(wbase + (long long)t * p.Cg * ES, ((long long)(ncols - 1) * Kd + p.Cg) * ES);
+            char* dst = s_filt + t * SLAB + cw * 1024;
+            load_to_lds(rw, dst, w_off[0]);
+            load_to_lds(rw, dst + 4096, w_off[1]);
+        };
+        // Barrier t releases tap t: it needs the patch and slabs <= t+1 (the tap's last k-steps already
+        // fetch fragments of tap t+1).  Copies complete in issue order, so "slab t+1 has landed" is "at
+        // most 2*(issued - (t+2)) copy instructions of this wave outstanding".  Slabs are issued a few
+        // taps ahead only, so that barrier 0 does not wait for the whole filter to be requested.
+        constexpr int AHEAD = 3;
+        int issued = 0;
+        for (int t = 0; t < RS; ++t) {
+            const int want = t + 2 + AHEAD < RS ? t + 2 + AHEAD : RS;
+            for (; issued < want; ++issued) issue_slab(issued);
+            wait_vmcnt_upto(2 * (issued - (t + 2)));
+            __builtin_amdgcn_s_barrier();
+        }
+        return;
     }
-    auto issue_slab = [&](int t) {
-        const i32x4 rw = make_rsrc(wbase + (long long)t * p.Cg * ES, t < RS ? ((long long)(ncols - 1) * Kd + p.Cg) * ES : 0);
-        char* dst = s_filt + (t & (NSLOT - 1)) * SLAB + wave * 1024;
-        load_to_lds(rw, dst, w_off[0]);
-        load_to_lds(rw, dst + 4096, w_off[1]);
-    };
-    issue_slab(0);
-    issue_slab(1);
-    issue_slab(2);
 
     // ------------------------------------------------------------ fragment addressing
-    // lane's output pixel of MFMA block i: m = 64*wave + 32*i + l31 -> patch pixel of tap (0,0)
+    // lane's output pixel of MFMA block i: m = 64*cw + 32*i + l31 -> patch pixel of tap (0,0)
     int base_px[2];
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
-        int m = wave * 64 + i * 32 + l31;
+        int m = cw * 64 + i * 32 + l31;
         if (m >= m_cnt) m = m_cnt - 1;                         // rows past the tile re-read its last pixel; never stored
         const int mm = m_first + m;
         const int op = mm / p.Q, oq = mm - op * p.Q;
@@ -648,7 +661,7 @@ __global__ void __launch_bounds__(256) conv_patch_kernel(const Params p) {
         return *(const uint4*)(s_patch + px * 128 + (((2 * kk + g) ^ kmajor_swz<128>(px)) << 4));
     };
     auto read_b = [&](int t, int kk, int j) -> uint4 {
-        return *(const uint4*)(s_filt + (t & (NSLOT - 1)) * SLAB + (j * 32 + l31) * 128 + (((2 * kk + g) ^ swn) << 4));
+        return *(const uint4*)(s_filt + t * SLAB + (j * 32 + l31) * 128 + (((2 * kk + g) ^ swn) << 4));
     };
 
     acc_t acc[2][2];
@@ -659,10 +672,18 @@ __global__ void __launch_bounds__(256) conv_patch_kernel(const Params p) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;       // reduction init
 
-    uint4 af[2][2], bf[2][2];
-    copy_barrier<2>();           // patch, slabs 0 and 1 have landed (slab 2 may still be in flight)
-    af[0][0] = read_a(0, 0, 0); af[0][1] = read_a(0, 0, 1);
-    bf[0][0] = read_b(0, 0, 0); bf[0][1] = read_b(0, 0, 1);
+    // Fragment sets: k-step kk of every tap uses set kk, fetched two k-steps ahead (a k-step is only
+    // four MFMAs long here, one k-step of lookahead would not cover the LDS latency).
+    uint4 af[4][2], bf[4][2];
+    __builtin_amdgcn_s_barrier();                 // barrier 0: patch, slabs 0 and 1 are in LDS
+    asm volatile("" ::: "memory");
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            af[kk][i] = read_a(0, kk, i);
+            bf[kk][i] = read_b(0, kk, i);
+        }
     TIR_FENCE();
 
     int fr = 0, fs = 0;                           // filter row / column of the current tap
@@ -670,38 +691,37 @@ __global__ void __launch_bounds__(256) conv_patch_kernel(const Params p) {
         const int tap_px = fr * p.dil_h * PW + fs * p.dil_w;
         int nfs = fs + 1, nfr = fr;
         if (nfs == p.S) { nfs = 0; ++nfr; }
-        const int next_px = nfr * p.dil_h * PW + nfs * p.dil_w;   // past the last tap: still inside the patch rows read before
         const bool last = t + 1 == RS;
-        issue_slab(t + 3);                        // its slot held tap t-1, released by the barrier below
+        const int next_px = last ? tap_px : nfr * p.dil_h * PW + nfs * p.dil_w;
+        const int next_t = last ? t : t + 1;
+        if (t > 0) {
+            __builtin_amdgcn_s_barrier();         // barrier t: slab t+1 is in LDS
+            asm volatile("" ::: "memory");
+        }
         TIR_FENCE();
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
-            const int set = kk & 1;
-            // fragments of the next k-step (or of the next tap's first k-step) are requested between the MFMAs
-            const int rk = kk == 3 ? 0 : kk + 1;
-            const int rpx = kk == 3 ? (last ? tap_px : next_px) : tap_px;
-            const int rt = kk == 3 ? (last ? t : t + 1) : t;
-            acc[0][0] = InTraits<DT>::mfma(af[set][0], bf[set][0], acc[0][0]);
+            // two k-steps ahead: same tap for kk < 2, the next tap's first k-steps otherwise
+            const int rk = (kk + 2) & 3;
+            const int rpx = kk < 2 ? tap_px : next_px;
+            const int rt = kk < 2 ? t : next_t;
+            acc[0][0] = InTraits<DT>::mfma(af[kk][0], bf[kk][0], acc[0][0]);
             TIR_FENCE();
-            af[set ^ 1][0] = read_a(rpx, rk, 0);
-            bf[set ^ 1][0] = read_b(rt, rk, 0);
+            af[rk][0] = read_a(rpx, rk, 0);
+            bf[rk][0] = read_b(rt, rk, 0);
             TIR_FENCE();
-            acc[0][1] = InTraits<DT>::mfma(af[set][0], bf[set][1], acc[0][1]);
+            acc[0][1] = InTraits<DT>::mfma(af[kk][0], bf[kk][1], acc[0][1]);
             TIR_FENCE();
-            af[set ^ 1][1] = read_a(rpx, rk, 1);
-            bf[set ^ 1][1] = read_b(rt, rk, 1);
+            af[rk][1] = read_a(rpx, rk, 1);
+            bf[rk][1] = read_b(rt, rk, 1);
             TIR_FENCE();
-            acc[1][0] = InTraits<DT>::mfma(af[set][1], bf[set][0], acc[1][0]);
-            acc[1][1] = InTraits<DT>::mfma(af[set][1], bf[set][1], acc[1][1]);
+            acc[1][0] = InTraits<DT>::mfma(af[kk][1], bf[kk][0], acc[1][0]);
+            acc[1][1] = InTraits<DT>::mfma(af[kk][1], bf[kk][1], acc[1][1]);
             TIR_FENCE();
         }
-        // slab t+2 has landed (only slab t+3 may be in flight); after the barrier every wave sees it and
-        // nobody reads slab t any more
-        copy_barrier<2>();
         fr = nfr;
         fs = nfs;
     }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
     // ------------------------------------------------------------ fused epilogue (NHWC rows are output pixels)
     out_t* ybase = (out_t*)p.C + ((long long)img * PQ + m_first) * p.c_rs + (long long)grp * p.N + n0;
@@ -713,7 +733,7 @@ __global__ void __launch_bounds__(256) conv_patch_kernel(const Params p) {
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             const int col = j * 32 + l31;
-            const int row0 = wave * 64 + i * 32 + 4 * g;
+            const int row0 = cw * 64 + i * 32 + 4 * g;
             const unsigned voff = col < ncols ? (unsigned)(row0 * row_bytes + col * OS) : kOutOfRange;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
