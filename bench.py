@@ -31,7 +31,10 @@ CACHE_BYTES = 256e6 + 8 * 4e6     # memory-side cache + the eight L2s
 
 # HBM bytes per launch of the headline kernel from rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled
 # by the same counters on a copy kernel of known size; see profiles/.  None until measured.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {
+    "c2a_conv56x64_f16": 11132600 + 6422528,     # FETCH_SIZE 5437.8 KiB x 1.9993, WRITE_SIZE 6272 KiB x 1.0
+    "c4a_gemm4096_f16": 201363000 + 67108864,    # FETCH_SIZE 98357 KiB x 1.9993, WRITE_SIZE 65536 KiB x 1.0
+}
 
 
 def parse():
@@ -44,6 +47,11 @@ def parse():
     ap.add_argument("--eager", action="store_true", help="launch step by step instead of one HIP graph")
     ap.add_argument("--no-operators", action="store_true", help="skip the per-operator context table")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--profile-run", action="store_true",
+                    help="only the headline timed region (for rocprofv3): no hot rerun, operator table, probe or oracle")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="instead of the workload, run 8 device-to-device copies of 64 MiB (a plain copy kernel of "
+                         "known size, to scale the FETCH_SIZE / WRITE_SIZE counters)")
     return ap.parse_args()
 
 
@@ -155,6 +163,17 @@ def main():
         sys.exit(2)
     B.lib()     # fails loudly if libtir.so was not built
     torch.cuda.set_device(0)
+    if args.copy_calibration:
+        src = torch.ones(64 << 20, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(8):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": {"bytes_read_per_dispatch": 64 << 20, "bytes_written_per_dispatch": 64 << 20,
+                                               "dispatches": 8}}))
+        return
+    if args.profile_run:
+        args.no_operators = args.no_cpu_baseline = True
     wl = I.WORKLOADS[args.workload]
 
     per_set = wl.min_bytes()
@@ -170,7 +189,7 @@ def main():
     traffic = MEASURED_TRAFFIC_BYTES.get(wl.name)
 
     hot_value = None
-    if not args.hot:
+    if not args.hot and not args.profile_run:
         w2, _ = timed_run(torch, B, wl, sets[:1], args.steps, args.warmup, args.eager)
         hot_value = wl.flops() * args.steps / w2 / 1e12
     del sets
@@ -213,7 +232,7 @@ def main():
                      "kernel": variant_of(B, wl), "avg_launch_us": round(launch_s * 1e6, 3),
                      "algorithmic_flop_per_launch": wl.flops(), "algorithmic_bytes_per_launch": wl.min_bytes()},
         "operators": operators,
-        "mfma_sustained_tflops": mfma_ceiling(torch, B),
+        "mfma_sustained_tflops": None if args.profile_run else mfma_ceiling(torch, B),
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl)
