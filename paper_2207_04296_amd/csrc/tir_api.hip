@@ -217,11 +217,12 @@ static tir_status plan_conv(bool need_ptrs, const void* x, const void* w, void* 
         bmode = B_KMAJOR;
     }
     // LDS-resident input patch: one pixel of one group is exactly one 128-byte LDS row, the input rows
-    // that 256 consecutive output pixels touch (plus one copy pass of slack) fit beside the R*S filter slabs
+    // that 256 consecutive output pixels touch (copied in passes of 64 pixels) fit beside the R*S filter slabs
     const int64_t span_out = (255 + Q - 1) / Q < P - 1 ? (255 + Q - 1) / Q : P - 1;   // output rows a tile can span, minus one
     const int64_t span_rows = span_out * stride_h + (R - 1) * dil_h + 1;
     const int64_t patch_w = (Q - 1) * stride_w + (S - 1) * dil_w + 1;
-    const bool patch_ok = amode == A_CONV && Cg * es == 128 && P * Q >= 128 && (span_rows * patch_w + 32) * 128 + R * S * 8192 <= 160 * 1024 &&
+    const bool patch_ok = amode == A_CONV && Cg * es == 128 && P * Q >= 128 && (span_rows * patch_w + 63) / 64 * 8192 + R * S * 8192 <= 160 * 1024 &&
+                          (K * 256 + Kg) * elem_size(out) < kMaxExtent &&
                           (!g_force_name[0] || strstr(g_force_name, "patch"));
     if (patch_ok) amode = A_CONV_PATCH;
     const Variant* v = pick(in, out, amode, bmode, amode == A_CONV_PATCH ? groups * N : groups, amode == A_CONV_PATCH ? P * Q : Mg, Kg, Kd);

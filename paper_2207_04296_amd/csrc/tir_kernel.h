@@ -20,6 +20,11 @@
 #include <type_traits>
 #include "tir_params.h"
 
+// Cache policy bits of the epilogue's buffer stores (0 = default write-back through L2).
+#ifndef TIR_STORE_AUX
+#define TIR_STORE_AUX 17
+#endif
+
 namespace tir {
 
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
@@ -138,17 +143,18 @@ template <int PENDING> __device__ __forceinline__ void copy_barrier() {
     asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(PENDING) : "memory");
 }
 
-// s_waitcnt takes an immediate; this waits until at most n (wave-uniform, rounded down to even, capped
-// at 62) vector-memory operations of the wave are outstanding.
+// s_waitcnt takes an immediate; this waits until at most n (wave-uniform, capped at 63) vector-memory
+// operations of the wave are outstanding.
 __device__ __forceinline__ void wait_vmcnt_upto(int n) {
 #define TIR_W(k) case k: asm volatile("s_waitcnt vmcnt(" #k ")" ::: "memory"); break;
-    switch (n < 0 ? 0 : (n > 62 ? 62 : (n & ~1))) {
-        TIR_W(0) TIR_W(2) TIR_W(4) TIR_W(6) TIR_W(8) TIR_W(10) TIR_W(12) TIR_W(14) TIR_W(16) TIR_W(18) TIR_W(20)
-        TIR_W(22) TIR_W(24) TIR_W(26) TIR_W(28) TIR_W(30) TIR_W(32) TIR_W(34) TIR_W(36) TIR_W(38) TIR_W(40)
-        TIR_W(42) TIR_W(44) TIR_W(46) TIR_W(48) TIR_W(50) TIR_W(52) TIR_W(54) TIR_W(56) TIR_W(58) TIR_W(60)
-        TIR_W(62)
+#define TIR_W4(k) TIR_W(k) TIR_W(k + 1) TIR_W(k + 2) TIR_W(k + 3)
+#define TIR_W16(k) TIR_W4(k) TIR_W4(k + 4) TIR_W4(k + 8) TIR_W4(k + 12)
+    switch (n < 0 ? 0 : (n > 63 ? 63 : n)) {
+        TIR_W16(0) TIR_W16(16) TIR_W16(32) TIR_W16(48)
         default: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
     }
+#undef TIR_W16
+#undef TIR_W4
 #undef TIR_W
 }
 
@@ -258,8 +264,8 @@ __device__ __forceinline__ void store_tile(const Params& p, long long bz, int m0
                 for (int r = 0; r < 16; ++r) {
                     const int soff = (8 * (r >> 2) + (r & 3)) * row_bytes;      // scalar
                     const out_t v = OT::cvt(acc[i][j][r]);
-                    if constexpr (OS == 4) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), rc, (int)voff, soff, 0);
-                    else __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(unsigned short, v), rc, (int)voff, soff, 0);
+                    if constexpr (OS == 4) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), rc, (int)voff, soff, TIR_STORE_AUX);
+                    else __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(unsigned short, v), rc, (int)voff, soff, TIR_STORE_AUX);
                 }
             }
         }
@@ -543,10 +549,12 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
 // (full width plus the zero halo, which out-of-range lanes of the copy deliver) into LDS once, and
 // the MFMA A-fragments of tap (rh, rw) are read from that patch at
 //     pixel(p*s_h + rh*d_h, q*s_w + rw*d_w)
-// - the same formula as the paper's A_r[n,h,w,rh,rw,rc], evaluated per LDS read.  The filter
-// streams through a 4-slot ring of [64 output channels][128 B] slabs, one slab per tap.
+// - the same formula as the paper's A_r[n,h,w,rh,rw,rc], evaluated per LDS read.  The filter of the
+// 64 output channels is LDS-resident too: R*S slabs of [64 output channels][128 B], requested a few
+// taps ahead.
 // One LDS row per patch pixel, same XOR swizzle as the K-major tiles (keyed by the pixel index).
-// 4 waves; wave w owns output pixels [64w, 64w+64) x 64 output channels (2x2 MFMA blocks).
+// 8 waves: four copy, four multiply; multiplying wave w owns output pixels [64w, 64w+64) x 64 output
+// channels (2x2 MFMA blocks).
 // ---------------------------------------------------------------------------------------------
 template <int DT, int OUT>
 __global__ void __launch_bounds__(512) conv_patch_kernel(const Params p) {
@@ -560,11 +568,12 @@ __global__ void __launch_bounds__(512) conv_patch_kernel(const Params p) {
     char* const s_filt = smem;                  // R*S slabs, then the patch (the host checked that both fit)
     char* const s_patch = smem + p.R * p.S * SLAB;
 
-    // Waves 0-3 multiply, waves 4-7 only copy.  A global->LDS copy instruction occupies its wave for
+    // Waves 0-3 only copy, waves 4-7 multiply.  A global->LDS copy instruction occupies its wave for
     // far longer than an MFMA does, and a wave issues in order: if the multiplying waves issued the
-    // copies themselves, the matrix pipes would idle behind every one of them.
+    // copies themselves, the matrix pipes would idle behind every one of them.  The copy role goes to
+    // the first four waves because the second wave of each SIMD starts ~0.3 us after the first.
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const bool copier = wave >= 4;
+    const bool copier = wave < 4;
     const int cw = wave & 3;                    // index within the role
     const int tid = threadIdx.x & 255;          // thread index within the role
     const int lane = tid & 63;
@@ -739,8 +748,8 @@ __global__ void __launch_bounds__(512) conv_patch_kernel(const Params p) {
             for (int r = 0; r < 16; ++r) {
                 const int soff = (8 * (r >> 2) + (r & 3)) * row_bytes;
                 const out_t v = OT::cvt(acc[i][j][r]);
-                if constexpr (OS == 4) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), rc, (int)voff, soff, 0);
-                else __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(unsigned short, v), rc, (int)voff, soff, 0);
+                if constexpr (OS == 4) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), rc, (int)voff, soff, TIR_STORE_AUX);
+                else __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(unsigned short, v), rc, (int)voff, soff, TIR_STORE_AUX);
             }
         }
     }
