@@ -41,8 +41,8 @@ __global__ void __launch_bounds__(256) mfma_probe_kernel(float* sink, int iters,
 }
 
 // ------------------------------------------------------------------------------- variant table
-#define TIR_ROW(name, DT, OUT, BM, BN, WM, WN, AM, BMO, RB, NS) \
-    {name, DT, OUT, BM, BN, WM, WN, AM, BMO, RB, NS, &launch_cfg<Cfg<DT, OUT, BM, BN, WM, WN, AM, BMO, RB, NS>>},
+#define TIR_ROW(name, DT, OUT, BM, BN, WM, WN, AM, BMO, RB, NS, KW) \
+    {name, DT, OUT, BM, BN, WM, WN, AM, BMO, RB, NS, KW, &launch_cfg<Cfg<DT, OUT, BM, BN, WM, WN, AM, BMO, RB, NS, KW>>},
 #define V0 TIR_ROW
 #define V1 TIR_ROW
 #define V2 TIR_ROW
@@ -90,7 +90,7 @@ static const Variant* pick(int dt, int out, int amode, int bmode, int64_t batch,
         const Variant* v = &kVariants[i];
         if (v->dt != dt || v->out != out || v->amode != amode || v->bmode != bmode) continue;
         if (g_force_name[0] && strstr(v->name, g_force_name)) return v;          // testing / tuning overrides
-        if (g_force_bm && v->bm == g_force_bm && v->bn == g_force_bn) return v;
+        if (g_force_bm && v->bm == g_force_bm && v->bn == g_force_bn && v->kw == 1) return v;
         const double tm = (double)((M + v->bm - 1) / v->bm), tn = (double)((N + v->bn - 1) / v->bn);
         const double tiles = tm * tn * (double)batch;
         const double eff = ((double)M * (double)N) / (tm * v->bm * tn * v->bn);
@@ -102,8 +102,14 @@ static const Variant* pick(int dt, int out, int amode, int bmode, int64_t batch,
         // ring depth: stages beyond the number of K-slabs are useless; with more than one
         // workgroup per CU prefer rings that let two of them be resident (LDS <= 80 KB)
         const int64_t nslab = (K * es + v->rowb - 1) / v->rowb;
-        const int lds = (v->bm + v->bn) * v->rowb * v->nstage;
+        const int lds = (v->bm + v->bn) * v->rowb * v->nstage * v->kw;
         double depth = 1.0;
+        if (v->kw > 1) {
+            // two reduction groups pay for the exchange of partial sums: only for small tiles in a single
+            // round of workgroups (nothing else on the CU hides the copy latency) facing a long reduction
+            if (tiles > kCUs || nslab < 4 * v->kw || v->bm * v->bn > 64 * 64) continue;
+            depth += 0.05;
+        }
         if (nslab < v->nstage) depth -= 0.02 * (v->nstage - (int)nslab);
         if (tiles > kCUs && lds > 80 * 1024) depth -= 0.03;
         else if (tiles <= kCUs) depth += 0.01 * v->nstage;

@@ -309,10 +309,14 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
 
     __shared__ __attribute__((aligned(1024))) char smem[C::LDS_BYTES];
 
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // reduction group kgrp owns the stages s with s % KW == kgrp; inside the group, thread tid of SUB
+    const int lane = threadIdx.x & 63;
+    const int wave_wg = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int kgrp = C::KW == 1 ? 0 : wave_wg / (C::WM * C::WN);
+    const int wave = wave_wg - kgrp * (C::WM * C::WN);
+    const int tid = (int)threadIdx.x - kgrp * C::SUB;
     const int wm = wave / C::WN, wn = wave % C::WN;
+    char* const ring = smem + kgrp * C::RING_BYTES;
 
     int tm, tn;
     tile_of_block(blockIdx.x, p.tiles_m, p.tiles_n, &tm, &tn);
@@ -321,7 +325,8 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
 
     const char* Ab = (const char*)p.A + bz * p.a_bs * ES;
     const char* Bb = (const char*)p.B + bz * p.b_bs * ES;
-    const int nh = (p.K + BK - 1) / BK;                 // stages of the reduction
+    const int nh_all = (p.K + BK - 1) / BK;             // stages of the reduction
+    const int nh = (nh_all + C::KW - 1) / C::KW;         // ... per group (the last one may be empty for some groups)
     const bool ktail = (p.K % BK) != 0;                 // last stage is partly beyond K
 
     // ------------------------------------------------------------ copy stage: A
@@ -395,15 +400,25 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
     // the scalar tap cursor (filter row, filter column, channel offset of the next stage).
     const bool conv_uniform_tap = (C::AMODE == A_CONV) && (p.Cg % BK == 0);
     int conv_fr = 0, conv_fs = 0, conv_cc = 0;
+    auto conv_advance = [&](int stages) {                // move the tap cursor `stages` stages ahead
+        conv_cc += stages * BK;
+        while (conv_cc >= p.Cg) {
+            conv_cc -= p.Cg;
+            if (++conv_fs == p.S) { conv_fs = 0; ++conv_fr; }
+        }
+    };
+    if (conv_uniform_tap && C::KW > 1) conv_advance(kgrp);
     i32x4 ra, rb;
     unsigned a_voff[C::A_IT];
-    char* lds_dst = smem;    // wave-uniform destination of this wave's first A chunk
+    char* lds_dst = ring;    // wave-uniform destination of this wave's first A chunk
 
     // Prepare the copy of `stage` (descriptors, predicates); the loads themselves are issued one
     // by one through copy_unit() so that they can be interleaved with MFMAs.
-    auto copy_begin = [&](int stage) {
-        lds_dst = smem + (stage % NSTAGE) * C::STAGE_BYTES + wave * 1024;
-        const bool live = stage < nh;      // past the end: empty descriptors, the copies write zeros nobody reads
+    auto copy_begin = [&](int slot_stage) {
+        lds_dst = ring + (slot_stage % NSTAGE) * C::STAGE_BYTES + wave * 1024;
+        const int stage = slot_stage * C::KW + kgrp;       // stage of the whole reduction
+        const int nh = nh_all;
+        const bool live = stage < nh;      // past the end: empty descriptors, the copies write zeros (they add nothing)
         if constexpr (C::AMODE == A_KMAJOR) {
             ra = make_rsrc(a_base + (long long)stage * ROWB, live ? a_bytes - (long long)stage * ROWB : 0);
             if (ktail && stage == nh - 1) {
@@ -430,11 +445,7 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
                     const bool ok = kv && (unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W;
                     a_voff[i] = ok ? (a_off[i] + delta) * ES : kOutOfRange;
                 }
-                conv_cc += BK;
-                if (conv_cc >= p.Cg) {
-                    conv_cc = 0;
-                    if (++conv_fs == p.S) { conv_fs = 0; ++conv_fr; }
-                }
+                conv_advance(C::KW);
             } else {
                 const int kb = stage * BK + a_lc * VEC;
                 const int tap = kb / p.Cg;
@@ -465,8 +476,8 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
     };
     // u-th copy instruction of the prepared stage (u < L): A chunks first, then B chunks.
     auto copy_unit = [&](int u) {
-        if (u < C::A_IT) load_to_lds(ra, lds_dst + u * C::THREADS * 16, a_voff[u]);
-        else load_to_lds(rb, lds_dst + C::A_BYTES + (u - C::A_IT) * C::THREADS * 16, b_off[u - C::A_IT]);
+        if (u < C::A_IT) load_to_lds(ra, lds_dst + u * C::SUB * 16, a_voff[u]);
+        else load_to_lds(rb, lds_dst + C::A_BYTES + (u - C::A_IT) * C::SUB * 16, b_off[u - C::A_IT]);
     };
 
     // ------------------------------------------------------------ MFMA stage
@@ -511,15 +522,15 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
             for (int u = 0; u < L; ++u) copy_unit(u);
         }
         copy_barrier<(NSTAGE - 2) * L>();
-        frag.read_a(smem, 0, af[0]);
-        frag.read_b(smem + C::A_BYTES, 0, bf[0]);
+        frag.read_a(ring, 0, af[0]);
+        frag.read_b(ring + C::A_BYTES, 0, bf[0]);
         TIR_FENCE();
 
         constexpr int VPK = (L + KSTEPS - 2) / (KSTEPS - 1);     // copy units per k-step of part (1)
         for (int h = 0; h < nh; ++h) {
-            const char* sa = smem + (h % NSTAGE) * C::STAGE_BYTES;
+            const char* sa = ring + (h % NSTAGE) * C::STAGE_BYTES;
             const char* sb = sa + C::A_BYTES;
-            const char* na = smem + ((h + 1) % NSTAGE) * C::STAGE_BYTES;
+            const char* na = ring + ((h + 1) % NSTAGE) * C::STAGE_BYTES;
             copy_begin(h + NSTAGE - 1);
             TIR_FENCE();
 #pragma unroll
@@ -537,6 +548,41 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     }
 
+    if constexpr (C::KW > 1) {
+        // The groups' partial sums meet in LDS (every copy has landed and, after the barrier, every
+        // wave is past its last fragment read): group 1 writes its accumulators, group 0 adds and stores.
+        typedef typename std::conditional<std::is_same<acc_t, f32x16>::value, float, int>::type acc_e;
+        typedef acc_e acc_e4 __attribute__((ext_vector_type(4)));
+        acc_e4* xch = (acc_e4*)(smem + wave * (C::MI * C::NI * 4096));
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        if (kgrp != 0) {
+#pragma unroll
+            for (int i = 0; i < C::MI; ++i)
+#pragma unroll
+                for (int j = 0; j < C::NI; ++j)
+#pragma unroll
+                    for (int r4 = 0; r4 < 4; ++r4) {
+                        acc_e4 v;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) v[e] = acc[i][j][r4 * 4 + e];
+                        xch[((i * C::NI + j) * 4 + r4) * 64 + lane] = v;
+                    }
+        }
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        if (kgrp != 0) return;
+#pragma unroll
+        for (int i = 0; i < C::MI; ++i)
+#pragma unroll
+            for (int j = 0; j < C::NI; ++j)
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    const acc_e4 v = xch[((i * C::NI + j) * 4 + r4) * 64 + lane];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc[i][j][r4 * 4 + e] += v[e];
+                }
+    }
     store_tile<C>(p, bz, m0, n0, wm, wn, lane, acc);
 }
 

@@ -12,7 +12,7 @@ typedef hipError_t (*launch_fn)(const Params&, hipStream_t);
 
 struct Variant {
     const char* name;
-    int dt, out, bm, bn, wm, wn, amode, bmode, rowb, nstage;
+    int dt, out, bm, bn, wm, wn, amode, bmode, rowb, nstage, kw;
     launch_fn fn;
 };
 
