@@ -6,7 +6,9 @@
 A step is one call of the C ABI for the headline workload (default: the fp16 NHWC conv2d
 16x56x56x64 -> 64, 3x3, stride 1, pad 1 with fp16 output), i.e. one pass of the whole path:
 fused-iterator decode, tile decomposition, global->LDS copy stage, MFMA accumulation, fused
-epilogue store.  Operands are resident in device memory before the timed region.  By default the
+epilogue store.  Before the timed region the variants are measured once (tir_tune_*, the paper's
+search reduced to a table; --no-tune keeps the built-in scoring rule).  Operands are resident in
+device memory before the timed region.  By default the
 K steps rotate over enough distinct operand / output sets to exceed the 256 MB memory-side cache
 plus L2, so every step reads its inputs from HBM ("cold"); --hot reuses one set.  The K launches
 are captured in one HIP graph (the kernels are microseconds long, a Python launch loop would
@@ -47,6 +49,8 @@ def parse():
     ap.add_argument("--eager", action="store_true", help="launch step by step instead of one HIP graph")
     ap.add_argument("--no-operators", action="store_true", help="skip the per-operator context table")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-tune", action="store_true",
+                    help="use the built-in scoring rule instead of measuring the variants first (tir_tune_*)")
     ap.add_argument("--profile-run", action="store_true",
                     help="only the headline timed region (for rocprofv3): no hot rerun, operator table, probe or oracle")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -180,6 +184,8 @@ def main():
     nsets = 1 if args.hot else max(2, int(CACHE_BYTES * 1.25 / per_set) + 1)
     nsets = min(nsets, max(1, args.steps))
     sets = make_sets(B, wl, nsets)
+    if not args.no_tune:      # untimed: measure the variants once, like a deployment that keeps its records
+        B.tune_workload(wl, *sets[0], reps=10)
     wall, ev = timed_run(torch, B, wl, sets, args.steps, args.warmup, args.eager)
     ms_per_step = wall * 1e3 / args.steps
     value = wl.flops() * args.steps / wall / 1e12
@@ -199,6 +205,8 @@ def main():
         for name, o in I.WORKLOADS.items():
             k = 20 if o.flops() > 4e10 else 200
             s = make_sets(B, o, 1)
+            if not args.no_tune:
+                B.tune_workload(o, *s[0], reps=5 if o.flops() > 4e10 else 10)
             w_, e_ = timed_run(torch, B, o, s, k, 5, args.eager)
             tf = o.flops() * k / e_ / 1e12
             attain = min(PEAK_TFLOPS[o.dtype], o.flops() / o.min_bytes() * HBM_GBS / 1e3)
@@ -224,6 +232,7 @@ def main():
         "config": {"workload": wl.name, "kind": wl.kind, "gemm_view_bMNK": list(wl.gemm_view()),
                    "out_dtype": wl.out, "variant": variant_of(B, wl),
                    "launch": "hip_graph" if not args.eager else "eager",
+                   "selection": "scoring rule" if args.no_tune else "measured (tir_tune_*, untimed, before the run)",
                    "cache": "hot (one operand set)" if args.hot else f"cold (rotating {nsets} operand sets)"},
         "frac_mfma_peak": round(value / peak, 4),
         "value_hot_cache": None if hot_value is None else round(hot_value, 3),

@@ -88,7 +88,7 @@ const char* tir_last_error(void);
 
 /*
  * Name of the kernel variant the next identical call would launch (for profiling harnesses), e.g.
- * "f16_f32_t256x256x64_akm_bnm".  Arguments as for tir_batch_matmul / tir_conv2d without pointers
+ * "f16_f32_t256x256w2x4s2_ak_bn".  Arguments as for tir_batch_matmul / tir_conv2d without pointers
  * being dereferenced; returns "" on invalid arguments.  The string is static.
  */
 const char* tir_gemm_variant(int64_t batch, int64_t M, int64_t N, int64_t K, int64_t a_rs, int64_t a_cs,
@@ -97,6 +97,41 @@ const char* tir_gemm_variant(int64_t batch, int64_t M, int64_t N, int64_t K, int
 const char* tir_conv2d_variant(int64_t N, int64_t H, int64_t W, int64_t C, int64_t K, int64_t R, int64_t S,
                                int stride_h, int stride_w, int pad_h, int pad_w, int dil_h, int dil_w,
                                int groups, tir_dtype in, tir_dtype out);
+
+/*
+ * Choice of kernel variant by measurement (TensorIR paper sec. 4.4: candidates that differ only in the
+ * loop structure around the fixed tensorized block are benchmarked on the device; the evaluation's
+ * tuning-time discussion: kept records make a second search of the same operator unnecessary).
+ *
+ * tir_tune_batch_matmul / tir_tune_conv2d take the arguments of tir_batch_matmul / tir_conv2d (batch = 1
+ * with zero batch strides tunes tir_gemm), launch every compiled variant that computes this problem
+ * `reps` times on `stream`, and record the fastest under the problem's signature (dtypes, copy
+ * modes implied by strides and alignment, extents, convolution geometry).  Later calls of the
+ * operator entry points with the same signature use the recorded variant instead of the built-in
+ * scoring rule.  Unlike every other call these BLOCK until the trial launches have finished, create
+ * and destroy HIP events and graphs (each trial is a captured graph of `reps` launches, so that short
+ * kernels are timed at the device's rate; with stream = NULL the trials run on a temporary stream
+ * after a device synchronisation), and must not be called during stream capture.  The output buffer ends
+ * up holding the operator's result (every variant computes the same values up to summation order).
+ * *best_us (may be NULL) receives the winner's time per launch in microseconds (0 for empty problems).
+ * reps must be in [1, 1000].
+ *
+ * Records are process-wide and thread-safe.  tir_tune_save writes them as text (one record per line,
+ * variant by name), tir_tune_load merges a file into the table; lines naming a variant this build
+ * does not have, or one that cannot compute the recorded signature, are skipped.
+ */
+tir_status tir_tune_batch_matmul(const void* A, const void* B, void* C, int64_t batch, int64_t M, int64_t N,
+                                 int64_t K, int64_t a_bs, int64_t a_rs, int64_t a_cs, int64_t b_bs, int64_t b_rs,
+                                 int64_t b_cs, int64_t c_bs, int64_t c_rs, int64_t c_cs, tir_dtype in,
+                                 tir_dtype out, int reps, double* best_us, tir_stream stream);
+tir_status tir_tune_conv2d(const void* x, const void* w, void* y, int64_t N, int64_t H, int64_t W, int64_t C,
+                           int64_t K, int64_t R, int64_t S, int stride_h, int stride_w, int pad_h, int pad_w,
+                           int dil_h, int dil_w, int groups, tir_dtype in, tir_dtype out, int reps,
+                           double* best_us, tir_stream stream);
+int tir_tune_count(void);                       /* number of records */
+void tir_tune_clear(void);                      /* forget every record */
+tir_status tir_tune_save(const char* path);     /* TIR_ERR_INVALID_ARG if the file cannot be written */
+tir_status tir_tune_load(const char* path);     /* TIR_ERR_INVALID_ARG if it cannot be read or is not a record file */
 
 /*
  * Testing / tuning hooks (process-wide, not thread-safe).

@@ -18,7 +18,9 @@ DTYPE_CODES = {"f16": TIR_F16, "bf16": TIR_BF16, "i8": TIR_I8, "f32": TIR_F32, "
 
 EXPORTS = ["tir_gemm", "tir_batch_matmul", "tir_conv2d", "tir_last_error", "tir_gemm_variant",
            "tir_conv2d_variant", "tir_debug_force_tile", "tir_debug_force_variant", "tir_debug_variant_count",
-           "tir_debug_variant_name", "tir_debug_tile_of_block", "tir_probe_mfma_rate", "tir_version"]
+           "tir_debug_variant_name", "tir_debug_tile_of_block", "tir_probe_mfma_rate", "tir_version",
+           "tir_tune_batch_matmul", "tir_tune_conv2d", "tir_tune_count", "tir_tune_clear", "tir_tune_save",
+           "tir_tune_load"]
 
 
 class TirError(RuntimeError):
@@ -67,6 +69,17 @@ def lib() -> ctypes.CDLL:
     L.tir_probe_mfma_rate.argtypes = [vp, ci, ci, ctypes.POINTER(ctypes.c_double), vp]
     L.tir_probe_mfma_rate.restype = ci
     L.tir_version.restype = ctypes.c_char_p
+    pd = ctypes.POINTER(ctypes.c_double)
+    L.tir_tune_batch_matmul.argtypes = [vp, vp, vp] + [i64] * 13 + [ci, ci, ci, pd, vp]
+    L.tir_tune_batch_matmul.restype = ci
+    L.tir_tune_conv2d.argtypes = [vp, vp, vp] + [i64] * 7 + [ci] * 7 + [ci, ci, ci, pd, vp]
+    L.tir_tune_conv2d.restype = ci
+    L.tir_tune_count.restype = ci
+    L.tir_tune_clear.restype = None
+    L.tir_tune_save.argtypes = [ctypes.c_char_p]
+    L.tir_tune_save.restype = ci
+    L.tir_tune_load.argtypes = [ctypes.c_char_p]
+    L.tir_tune_load.restype = ci
     _lib = L
     return L
 
@@ -179,6 +192,41 @@ def tir_version() -> str:
     return lib().tir_version().decode()
 
 
+def tir_tune_batch_matmul(A, B, C, batch, M, N, K, a_bs, a_rs, a_cs, b_bs, b_rs, b_cs, c_bs, c_rs, c_cs,
+                          in_dtype, out_dtype, reps=5, stream=None) -> float:
+    """Measure every variant for this problem and record the fastest; returns its microseconds per launch."""
+    us = ctypes.c_double()
+    _check(lib().tir_tune_batch_matmul(_ptr(A), _ptr(B), _ptr(C), batch, M, N, K, a_bs, a_rs, a_cs, b_bs, b_rs, b_cs,
+                                       c_bs, c_rs, c_cs, _code(in_dtype), _code(out_dtype), int(reps),
+                                       ctypes.byref(us), _stream(stream)))
+    return us.value
+
+
+def tir_tune_conv2d(x, w, y, N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, groups,
+                    in_dtype, out_dtype, reps=5, stream=None) -> float:
+    us = ctypes.c_double()
+    _check(lib().tir_tune_conv2d(_ptr(x), _ptr(w), _ptr(y), N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w,
+                                 dil_h, dil_w, groups, _code(in_dtype), _code(out_dtype), int(reps),
+                                 ctypes.byref(us), _stream(stream)))
+    return us.value
+
+
+def tir_tune_count() -> int:
+    return lib().tir_tune_count()
+
+
+def tir_tune_clear() -> None:
+    lib().tir_tune_clear()
+
+
+def tir_tune_save(path) -> None:
+    _check(lib().tir_tune_save(str(path).encode()))
+
+
+def tir_tune_load(path) -> None:
+    _check(lib().tir_tune_load(str(path).encode()))
+
+
 # ------------------------------------------------------------------------------------------------
 # device-memory plumbing for harnesses (bits <-> torch tensors); no arithmetic
 # ------------------------------------------------------------------------------------------------
@@ -211,6 +259,20 @@ def run_workload(wl, a_dev, b_dev, c_dev, stream=None) -> None:
     else:
         tir_batch_matmul(a_dev, b_dev, c_dev, wl.batch, M, N, K, M * K, K, 1, K * N, b_rs, b_cs, M * N, N, 1,
                          wl.dtype, wl.out, stream)
+
+
+def tune_workload(wl, a_dev, b_dev, c_dev, reps=5, stream=None) -> float:
+    """tir_tune_* for one paper_2207_04296_amd.inputs.Workload; returns the winner's microseconds per launch."""
+    if wl.kind == "conv2d":
+        return tir_tune_conv2d(a_dev, b_dev, c_dev, wl.n, wl.h, wl.w, wl.c, wl.k, wl.r, wl.s, wl.stride[0], wl.stride[1],
+                               wl.pad[0], wl.pad[1], wl.dil[0], wl.dil[1], wl.groups, wl.dtype, wl.out, reps, stream)
+    M, N, K = wl.M, wl.N, wl.K
+    b_rs, b_cs = (1, K) if wl.trans_b else (N, 1)
+    if wl.kind == "gemm":
+        return tir_tune_batch_matmul(a_dev, b_dev, c_dev, 1, M, N, K, 0, K, 1, 0, b_rs, b_cs, 0, N, 1, wl.dtype, wl.out,
+                                     reps, stream)
+    return tir_tune_batch_matmul(a_dev, b_dev, c_dev, wl.batch, M, N, K, M * K, K, 1, K * N, b_rs, b_cs, M * N, N, 1,
+                                 wl.dtype, wl.out, reps, stream)
 
 
 def out_shape(wl):

@@ -6,6 +6,10 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <map>
+#include <mutex>
+#include <tuple>
+
 #include "tir.h"
 #include "tir_launch.h"
 
@@ -75,6 +79,39 @@ static bool dtype_pair_ok(int in, int out) {
 
 static bool aligned(const void* p, uintptr_t a) { return ((uintptr_t)p % a) == 0; }
 
+// ------------------------------------------------------------------------------- measured choices
+// Records of tir_tune_*: for a problem signature, the variant that ran fastest on this device.
+// kind 0 = (batched) GEMM, 1 = convolution; geom packs the convolution geometry that the GEMM view
+// (batch, M, N, K) does not show.  A record only ever names a variant that computes the same result.
+struct TuneKey {
+    int kind, dt, out, amode, bmode;
+    int64_t batch, M, N, K;
+    uint64_t geom;
+    bool operator<(const TuneKey& o) const {
+        return std::tie(kind, dt, out, amode, bmode, batch, M, N, K, geom) <
+               std::tie(o.kind, o.dt, o.out, o.amode, o.bmode, o.batch, o.M, o.N, o.K, o.geom);
+    }
+};
+static std::mutex g_tune_mu;
+static std::map<TuneKey, const Variant*> g_tuned;
+// set by the tuner around its trial launches on the calling thread: the variant to plan with
+static thread_local const Variant* g_trial = nullptr;
+
+static const Variant* tuned_lookup(const TuneKey& k) {
+    std::lock_guard<std::mutex> lock(g_tune_mu);
+    auto it = g_tuned.find(k);
+    return it == g_tuned.end() ? nullptr : it->second;
+}
+
+static uint64_t conv_geom(int64_t N, int64_t groups, int64_t H, int64_t W, int64_t R, int64_t S, int sh, int sw, int ph, int pw, int dh, int dw) {
+    // the fields do not fit 64 bits side by side: mix them instead (FNV-1a)
+    const int64_t f[12] = {N, groups, H, W, R, S, sh, sw, ph, pw, dh, dw};
+    uint64_t h = 1469598103934665603ull;
+    for (int i = 0; i < 12; ++i)
+        for (int b = 0; b < 8; ++b) { h ^= (uint64_t)((f[i] >> (8 * b)) & 0xff); h *= 1099511628211ull; }
+    return h;
+}
+
 // Pick a variant for (dt, out, amode, bmode).  This is the hand-made stand-in for the paper's
 // search over tilings (sec. 4.4): every listed tile is scored by
 //   padding efficiency  x  how evenly its workgroups fill the 256 CUs  x  bytes-per-flop factor,
@@ -123,7 +160,19 @@ static const Variant* pick(int dt, int out, int amode, int bmode, int64_t batch,
 struct Plan {
     const Variant* v;
     Params p;
+    TuneKey key;        // signature of the problem for the measured-choice records
+    bool patch_ok;      // convolution: the LDS-resident-patch kernel may run this problem
 };
+
+// The variant a plan uses: the tuner's trial variant, else a measured record, else the scoring rule.
+static const Variant* choose(const TuneKey& key, int64_t batch, int64_t M, int64_t N, int64_t K) {
+    if (g_trial) return g_trial;
+    if (!g_force_name[0] && !g_force_bm) {
+        const Variant* t = tuned_lookup(key);
+        if (t) return t;
+    }
+    return pick(key.dt, key.out, key.amode, key.bmode, batch, M, N, K);
+}
 
 static tir_status check_common(const void* A, const void* B, const void* C, int in, int out) {
     if (in < 0 || in > TIR_I32 || out < 0 || out > TIR_I32) return fail(TIR_ERR_INVALID_ARG, "unknown dtype code (in=%d out=%d)", in, out);
@@ -169,7 +218,9 @@ static tir_status plan_gemm(bool need_ptrs, const void* A, const void* B, void* 
              (b_rs * 128 + N) * es < kMaxExtent) bmode = B_NMAJOR;
     if (amode == A_GENERIC || bmode == B_GENERIC) { amode = A_GENERIC; bmode = B_GENERIC; }
 
-    const Variant* v = pick(in, out, amode, bmode, batch, M, N, K);
+    plan->key = TuneKey{0, in, out, amode, bmode, batch, M, N, K, 0};
+    plan->patch_ok = false;
+    const Variant* v = choose(plan->key, batch, M, N, K);
     if (!v) return fail(TIR_ERR_UNSUPPORTED, "no kernel variant for this dtype / layout / forced tile");
     Params& p = plan->p;
     memset(&p, 0, sizeof p);
@@ -228,10 +279,20 @@ static tir_status plan_conv(bool need_ptrs, const void* x, const void* w, void* 
     const int64_t span_rows = span_out * stride_h + (R - 1) * dil_h + 1;
     const int64_t patch_w = (Q - 1) * stride_w + (S - 1) * dil_w + 1;
     const bool patch_ok = amode == A_CONV && Cg * es == 128 && P * Q >= 128 && (span_rows * patch_w + 63) / 64 * 8192 + R * S * 8192 <= 160 * 1024 &&
-                          (K * 256 + Kg) * elem_size(out) < kMaxExtent &&
-                          (!g_force_name[0] || strstr(g_force_name, "patch"));
-    if (patch_ok) amode = A_CONV_PATCH;
-    const Variant* v = pick(in, out, amode, bmode, amode == A_CONV_PATCH ? groups * N : groups, amode == A_CONV_PATCH ? P * Q : Mg, Kg, Kd);
+                          (K * 256 + Kg) * elem_size(out) < kMaxExtent;
+    plan->patch_ok = patch_ok;
+    // records are kept under the implicit-GEMM signature; a record (or a trial) may name either kernel family
+    plan->key = TuneKey{1, in, out, amode, bmode, groups * N, P * Q, Kg, Kd, conv_geom(N, groups, H, W, R, S, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w)};
+    const Variant* v = nullptr;
+    if (g_trial) v = g_trial;
+    else if (!g_force_name[0] && !g_force_bm) v = tuned_lookup(plan->key);
+    if (v && v->amode == A_CONV_PATCH && !patch_ok) v = nullptr;
+    if (!v) {
+        const bool use_patch = patch_ok && (!g_force_name[0] || strstr(g_force_name, "patch"));
+        if (use_patch) v = pick(in, out, A_CONV_PATCH, bmode, groups * N, P * Q, Kg, Kd);
+        else v = pick(in, out, amode, bmode, groups, Mg, Kg, Kd);
+    }
+    if (v && v->amode == A_CONV_PATCH) amode = A_CONV_PATCH;
     if (!v) return fail(TIR_ERR_UNSUPPORTED, "no kernel variant for this dtype / forced tile");
     Params& p = plan->p;
     memset(&p, 0, sizeof p);
@@ -271,6 +332,108 @@ static tir_status run(const Plan& plan, hipStream_t stream) {
         p.C = (char*)plan.p.C + (long long)b0 * p.c_bs * os;
         hipError_t e = plan.v->fn(p, stream);
         if (e != hipSuccess) return fail(TIR_ERR_LAUNCH, "launch of %s failed: %s", plan.v->name, hipGetErrorString(e));
+    }
+    return TIR_OK;
+}
+
+// ------------------------------------------------------------------------------- tuning by measurement
+static bool record_fits(const TuneKey& k, const Variant* v) {
+    if (v->dt != k.dt || v->out != k.out) return false;
+    if (v->amode == k.amode && v->bmode == k.bmode) return true;
+    return k.kind == 1 && k.amode == A_CONV && k.bmode == B_KMAJOR && v->amode == A_CONV_PATCH;   // re-checked against the shape when used
+}
+
+struct TrialGuard {
+    ~TrialGuard() { g_trial = nullptr; }
+};
+
+// Run every variant that can compute the problem `make_plan` describes, `reps` times each, and record
+// the fastest.  make_plan(Plan*) builds the launch plan honouring g_trial.
+template <class MakePlan>
+static tir_status tune_problem(MakePlan make_plan, int reps, hipStream_t stream, double* best_us, const char** best_name) {
+    if (best_us) *best_us = 0.0;
+    if (best_name) *best_name = "";
+    if (reps <= 0 || reps > 1000) return fail(TIR_ERR_INVALID_ARG, "reps must be in [1, 1000]");
+    if (g_force_name[0] || g_force_bm) return fail(TIR_ERR_INVALID_ARG, "tuning while a variant or tile is forced");
+    Plan base;
+    g_trial = nullptr;
+    tir_status st = make_plan(&base);
+    if (st != TIR_OK) return st;
+    if (!base.v) return TIR_OK;                       // zero-sized problem: nothing to measure
+    hipEvent_t e0, e1;
+    hipError_t ce = hipEventCreate(&e0);
+    if (ce != hipSuccess) return fail(TIR_ERR_LAUNCH, "hipEventCreate failed: %s", hipGetErrorString(ce));
+    ce = hipEventCreate(&e1);
+    if (ce != hipSuccess) {
+        (void)hipEventDestroy(e0);
+        return fail(TIR_ERR_LAUNCH, "hipEventCreate failed: %s", hipGetErrorString(ce));
+    }
+    // the legacy default stream cannot be captured: trials then run on a stream of their own
+    hipStream_t own = nullptr;
+    if (!stream) {
+        ce = hipStreamCreateWithFlags(&own, hipStreamNonBlocking);
+        if (ce == hipSuccess) ce = hipDeviceSynchronize();      // work already queued on the default stream comes first
+        if (ce != hipSuccess) {
+            (void)hipEventDestroy(e0);
+            (void)hipEventDestroy(e1);
+            if (own) (void)hipStreamDestroy(own);
+            return fail(TIR_ERR_LAUNCH, "tuning: cannot create a stream: %s", hipGetErrorString(ce));
+        }
+        stream = own;
+    }
+    TrialGuard guard;
+    const Variant* best = nullptr;
+    float best_ms = 0.f;
+    for (int i = 0; i < kNumVariants && st == TIR_OK; ++i) {
+        const Variant* v = &kVariants[i];
+        if (!record_fits(base.key, v) || (v->amode == A_CONV_PATCH && !base.patch_ok)) continue;
+        g_trial = v;
+        Plan pl;
+        st = make_plan(&pl);
+        if (st != TIR_OK) break;
+        // two launches first (a variant several times slower than the best so far is not worth `reps`
+        // more), then the measured batch; every HIP call is checked, the first failure ends the tuning
+        float ms = 0.f;
+        // The n launches are captured into one HIP graph and replayed: launched one by one, kernels of
+        // a few microseconds would be timed at the host's launch rate, not the device's.
+        auto timed = [&](int n) -> tir_status {
+            hipGraph_t graph = nullptr;
+            hipGraphExec_t exec = nullptr;
+            hipError_t e = hipStreamBeginCapture(stream, hipStreamCaptureModeThreadLocal);
+            if (e != hipSuccess) return fail(TIR_ERR_LAUNCH, "tuning: stream capture failed: %s", hipGetErrorString(e));
+            tir_status s2 = TIR_OK;
+            for (int r = 0; r < n && s2 == TIR_OK; ++r) s2 = run(pl, stream);
+            e = hipStreamEndCapture(stream, &graph);
+            if (s2 == TIR_OK && e == hipSuccess) e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+            if (s2 == TIR_OK && e == hipSuccess) e = hipGraphLaunch(exec, stream);            // upload + first run, untimed
+            if (s2 == TIR_OK && e == hipSuccess) e = hipEventRecord(e0, stream);
+            if (s2 == TIR_OK && e == hipSuccess) e = hipGraphLaunch(exec, stream);
+            if (s2 == TIR_OK && e == hipSuccess) e = hipEventRecord(e1, stream);
+            if (s2 == TIR_OK && e == hipSuccess) e = hipEventSynchronize(e1);
+            if (s2 == TIR_OK && e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+            if (exec) (void)hipGraphExecDestroy(exec);
+            if (graph) (void)hipGraphDestroy(graph);
+            if (s2 != TIR_OK) return s2;
+            if (e != hipSuccess) return fail(TIR_ERR_LAUNCH, "tuning run of %s failed: %s", v->name, hipGetErrorString(e));
+            ms /= (float)n;
+            return TIR_OK;
+        };
+        st = timed(1);
+        if (st != TIR_OK) break;
+        if (best && ms > 4.f * best_ms + 0.05f) continue;
+        st = timed(reps);
+        if (st != TIR_OK) break;
+        if (!best || ms < best_ms) { best = v; best_ms = ms; }
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (own) (void)hipStreamDestroy(own);
+    if (st != TIR_OK) return st;
+    if (best) {
+        std::lock_guard<std::mutex> lock(g_tune_mu);
+        g_tuned[base.key] = best;
+        if (best_us) *best_us = (double)best_ms * 1e3;
+        if (best_name) *best_name = best->name;
     }
     return TIR_OK;
 }
@@ -348,6 +511,81 @@ tir_status tir_probe_mfma_rate(void* sink, int iters, int random_operands, doubl
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(TIR_ERR_LAUNCH, "probe launch failed: %s", hipGetErrorString(e));
     if (flop) *flop = 1024.0 * 4.0 * (double)iters * 16.0 * 32768.0;
+    return TIR_OK;
+}
+
+tir_status tir_tune_batch_matmul(const void* A, const void* B, void* C, int64_t batch, int64_t M, int64_t N, int64_t K,
+                                 int64_t a_bs, int64_t a_rs, int64_t a_cs, int64_t b_bs, int64_t b_rs, int64_t b_cs,
+                                 int64_t c_bs, int64_t c_rs, int64_t c_cs, tir_dtype in, tir_dtype out, int reps,
+                                 double* best_us, tir_stream stream) {
+    auto make = [&](Plan* pl) {
+        return plan_gemm(true, A, B, C, batch, M, N, K, a_bs, a_rs, a_cs, b_bs, b_rs, b_cs, c_bs, c_rs, c_cs, (int)in, (int)out, pl);
+    };
+    return tune_problem(make, reps, (hipStream_t)stream, best_us, nullptr);
+}
+
+tir_status tir_tune_conv2d(const void* x, const void* w, void* y, int64_t N, int64_t H, int64_t W, int64_t C, int64_t K,
+                           int64_t R, int64_t S, int stride_h, int stride_w, int pad_h, int pad_w, int dil_h, int dil_w,
+                           int groups, tir_dtype in, tir_dtype out, int reps, double* best_us, tir_stream stream) {
+    auto make = [&](Plan* pl) {
+        return plan_conv(true, x, w, y, N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, groups, (int)in, (int)out, pl);
+    };
+    return tune_problem(make, reps, (hipStream_t)stream, best_us, nullptr);
+}
+
+int tir_tune_count(void) {
+    std::lock_guard<std::mutex> lock(g_tune_mu);
+    return (int)g_tuned.size();
+}
+
+void tir_tune_clear(void) {
+    std::lock_guard<std::mutex> lock(g_tune_mu);
+    g_tuned.clear();
+}
+
+tir_status tir_tune_save(const char* path) {
+    if (!path) return fail(TIR_ERR_INVALID_ARG, "path is null");
+    FILE* f = fopen(path, "w");
+    if (!f) return fail(TIR_ERR_INVALID_ARG, "cannot open %s for writing", path);
+    std::lock_guard<std::mutex> lock(g_tune_mu);
+    fprintf(f, "tir-tune-records 1\n");
+    for (const auto& kv : g_tuned) {
+        const TuneKey& k = kv.first;
+        fprintf(f, "%d %d %d %d %d %lld %lld %lld %lld %llu %s\n", k.kind, k.dt, k.out, k.amode, k.bmode, (long long)k.batch,
+                (long long)k.M, (long long)k.N, (long long)k.K, (unsigned long long)k.geom, kv.second->name);
+    }
+    const bool ok = fclose(f) == 0;
+    return ok ? TIR_OK : fail(TIR_ERR_INVALID_ARG, "writing %s failed", path);
+}
+
+tir_status tir_tune_load(const char* path) {
+    if (!path) return fail(TIR_ERR_INVALID_ARG, "path is null");
+    FILE* f = fopen(path, "r");
+    if (!f) return fail(TIR_ERR_INVALID_ARG, "cannot open %s", path);
+    char line[512];
+    int version = 0;
+    if (!fgets(line, sizeof line, f) || sscanf(line, "tir-tune-records %d", &version) != 1 || version != 1) {
+        fclose(f);
+        return fail(TIR_ERR_INVALID_ARG, "%s is not a version-1 record file", path);
+    }
+    std::lock_guard<std::mutex> lock(g_tune_mu);
+    while (fgets(line, sizeof line, f)) {
+        TuneKey k;
+        long long b, m, n, kk;
+        unsigned long long geom;
+        char name[128];
+        if (sscanf(line, "%d %d %d %d %d %lld %lld %lld %lld %llu %127s", &k.kind, &k.dt, &k.out, &k.amode, &k.bmode, &b, &m, &n, &kk,
+                   &geom, name) != 11)
+            continue;                                   // malformed line: ignored
+        k.batch = b; k.M = m; k.N = n; k.K = kk; k.geom = geom;
+        // records of another build may name variants this one does not have, or that do not fit the key
+        for (int i = 0; i < kNumVariants; ++i)
+            if (strcmp(kVariants[i].name, name) == 0 && record_fits(k, &kVariants[i])) {
+                g_tuned[k] = &kVariants[i];
+                break;
+            }
+    }
+    fclose(f);
     return TIR_OK;
 }
 

@@ -71,3 +71,14 @@ def check_workload(wl, oracle, what=None):
     got = run_gpu(wl, a_bits, b_bits)
     ref, S = run_oracle(wl, a_bits, b_bits, oracle)
     return assert_close(got, ref, S, what or wl.name)
+
+
+def variant_name(B, wl):
+    """Name of the variant the library would launch for workload wl."""
+    if wl.kind == "conv2d":
+        return B.tir_conv2d_variant(wl.n, wl.h, wl.w, wl.c, wl.k, wl.r, wl.s, *wl.stride, *wl.pad, *wl.dil, wl.groups,
+                                    wl.dtype, wl.out)
+    b_rs, b_cs = (1, wl.K) if wl.trans_b else (wl.N, 1)
+    return B.tir_gemm_variant(wl.batch if wl.kind == "bmm" else 1, wl.M, wl.N, wl.K, wl.K, 1, b_rs, b_cs, wl.N, 1,
+                              wl.dtype, wl.out)
+

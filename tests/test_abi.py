@@ -107,3 +107,77 @@ def test_variant_choice_reflects_layout():
     assert "conv" in B.tir_conv2d_variant(16, 56, 56, 64, 64, 3, 3, 1, 1, 1, 1, 1, 1, 1, "f16", "f16")
     assert B.tir_conv2d_variant(1, 8, 8, 3, 8, 3, 3, 1, 1, 1, 1, 1, 1, 1, "f16", "f16").endswith("conv_generic")
     assert B.tir_gemm_variant(1, -1, 8, 8, 8, 1, 8, 1, 8, 1, "f16", "f32") == ""
+
+
+# ------------------------------------------------------------------------------ measured-choice records
+def _gemm_variant_512():
+    return B.tir_gemm_variant(1, 512, 512, 512, 512, 1, 512, 1, 512, 1, "f16", "f32")
+
+
+def test_tuning_records_load_save_and_steer_the_choice(tmp_path):
+    """A record file names the variant per problem signature: loading it changes what the planner
+    picks for exactly that signature, saving writes it back, clearing restores the scoring rule.
+    (Record lines: kind dt out amode bmode batch M N K geom variant; row-major f16 -> f32 GEMM is
+    dt 0, out 3, A k-major 0, B n-major 1.)"""
+    B.tir_tune_clear()
+    try:
+        default = _gemm_variant_512()
+        other = "f16_f32_t64x32w2x1s4_ak_bn"
+        assert default and default != other and other in B.tir_debug_variant_names()
+        rec = tmp_path / "records.txt"
+        rec.write_text("tir-tune-records 1\n"
+                       f"0 0 3 0 1 1 512 512 512 0 {other}\n"
+                       "0 0 3 0 1 1 640 512 512 0 no_such_variant\n"              # unknown name: skipped
+                       "0 0 3 0 1 1 768 512 512 0 i8_i32_t64x64w2x2s2_ak_bn\n"    # wrong dtype for the key: skipped
+                       "0 0 3 0 1 1 896 512 512 0 f16_f32_t64x64w2x2s2_ak_bk\n"   # wrong copy mode for the key: skipped
+                       "garbage line\n")
+        B.tir_tune_load(rec)
+        assert B.tir_tune_count() == 1
+        assert _gemm_variant_512() == other
+        # another signature (batch 2) is untouched
+        B.tir_debug_force_variant("")
+        batch2 = B.tir_gemm_variant(2, 512, 512, 512, 512, 1, 512, 1, 512, 1, "f16", "f32")
+        assert batch2 and batch2 != other
+        # a forced variant wins over a record
+        B.tir_debug_force_variant("t128x128w2x2s2_")
+        assert "t128x128w2x2s2_" in _gemm_variant_512()
+        B.tir_debug_force_variant("")
+        # save / clear / load round trip
+        out = tmp_path / "saved.txt"
+        B.tir_tune_save(out)
+        lines = out.read_text().splitlines()
+        assert lines[0] == "tir-tune-records 1" and lines[1:] == [f"0 0 3 0 1 1 512 512 512 0 {other}"]
+        B.tir_tune_clear()
+        assert B.tir_tune_count() == 0 and _gemm_variant_512() == default
+        B.tir_tune_load(out)
+        assert _gemm_variant_512() == other
+    finally:
+        B.tir_debug_force_variant("")
+        B.tir_tune_clear()
+
+
+def test_tuning_record_files_are_validated(tmp_path):
+    bad = tmp_path / "bad.txt"
+    bad.write_text("something else\n")
+    with pytest.raises(B.TirError) as e:
+        B.tir_tune_load(bad)
+    assert e.value.status == B.TIR_ERR_INVALID_ARG
+    with pytest.raises(B.TirError):
+        B.tir_tune_load(tmp_path / "missing.txt")
+    with pytest.raises(B.TirError):
+        B.tir_tune_save(tmp_path / "no_such_dir" / "x.txt")
+    assert B.tir_tune_count() == 0
+
+
+def test_tuning_rejects_bad_arguments_before_touching_the_device():
+    import ctypes
+    L = B.lib()
+    us = ctypes.c_double(-1.0)
+    # reps out of range, then an invalid problem: status codes, no launch
+    st = L.tir_tune_batch_matmul(FAKE, FAKE, FAKE, 1, 64, 64, 64, 0, 64, 1, 0, 64, 1, 0, 64, 1, 0, 3, 0, ctypes.byref(us), None)
+    assert st == B.TIR_ERR_INVALID_ARG and "reps" in B.last_error()
+    st = L.tir_tune_batch_matmul(FAKE, FAKE, FAKE, 1, -4, 64, 64, 0, 64, 1, 0, 64, 1, 0, 64, 1, 0, 3, 3, ctypes.byref(us), None)
+    assert st == B.TIR_ERR_INVALID_ARG
+    # zero-sized problems are a successful no-op
+    st = L.tir_tune_batch_matmul(FAKE, FAKE, FAKE, 1, 0, 64, 64, 0, 64, 1, 0, 64, 1, 0, 64, 1, 0, 3, 3, ctypes.byref(us), None)
+    assert st == B.TIR_OK and us.value == 0.0 and B.tir_tune_count() == 0

@@ -306,3 +306,51 @@ def test_conv_patch_kernel(B, oracle, dtype, out):
                 PT.assert_close(got, ref, S, f"{wl.name} via {name}")
         finally:
             B.tir_debug_force_variant("")
+
+
+# ------------------------------------------------------------------------------ choice by measurement
+def test_tuning_measures_records_and_keeps_results_correct(B, oracle, tmp_path):
+    """tir_tune_* runs every variant that can compute the problem, records the fastest, and the
+    operator entry points then use it: the result still matches the oracle, the record survives a
+    save / clear / load round trip, and other signatures keep the built-in choice."""
+    import torch
+    B.tir_tune_clear()
+    try:
+        cases = [
+            I.Workload("tune_gemm", "gemm", "f16", "f32", "u", 9100, M=300, N=256, K=1152),
+            I.Workload("tune_bmm_nt", "bmm", "bf16", "f32", "u", 9200, batch=3, M=130, N=72, K=64, trans_b=True),
+            I.Workload("tune_conv_patch", "conv2d", "f16", "f16", "n0.1", 9300, n=2, h=20, w=23, c=64, k=64, r=3, s=3,
+                       stride=(1, 1), pad=(1, 1), dil=(1, 1), groups=1),
+            I.Workload("tune_conv_i8", "conv2d", "i8", "i32", "i", 9400, n=1, h=14, w=14, c=64, k=48, r=3, s=3,
+                       stride=(2, 2), pad=(1, 1), dil=(1, 1), groups=2),
+        ]
+        names = set(B.tir_debug_variant_names())
+        chosen = {}
+        for n_rec, wl in enumerate(cases, start=1):
+            a_bits, b_bits = wl.operands()
+            ref, S = PT.run_oracle(wl, a_bits, b_bits, oracle)
+            a, b = B.to_device(a_bits, wl.dtype), B.to_device(b_bits, wl.dtype)
+            c = B.empty_out(B.out_shape(wl), wl.out)
+            _say(f"tuning {wl.name}")
+            us = B.tune_workload(wl, a, b, c, reps=2)
+            torch.cuda.synchronize()
+            assert us > 0.0 and B.tir_tune_count() == n_rec
+            name = PT.variant_name(B, wl)
+            assert name in names and name.startswith(f"{wl.dtype}_{wl.out}_")
+            chosen[wl.name] = name
+            # the tuner's last trial left a valid result in c; a fresh call uses the record
+            PT.assert_close(PT.gpu_to_f64(c), ref, S, f"{wl.name} after tuning")
+            c.zero_()
+            B.run_workload(wl, a, b, c)
+            torch.cuda.synchronize()
+            PT.assert_close(PT.gpu_to_f64(c), ref, S, f"{wl.name} via tuned {name}")
+        rec = tmp_path / "rec.txt"
+        B.tir_tune_save(rec)
+        B.tir_tune_clear()
+        assert B.tir_tune_count() == 0
+        B.tir_tune_load(rec)
+        assert B.tir_tune_count() == len(cases)
+        for wl in cases:
+            assert PT.variant_name(B, wl) == chosen[wl.name]
+    finally:
+        B.tir_tune_clear()
