@@ -51,6 +51,9 @@ def _load():
         lib.oracle_conv_out_extent.restype = i64
         lib.oracle_decode.argtypes = [ctypes.c_int, vp, i64, dp]
         lib.oracle_decode.restype = ctypes.c_int
+        lib.oracle_epilogue_float.argtypes = [dp, dp, i64, i64, ctypes.POINTER(ctypes.c_float), ctypes.c_int]
+        lib.oracle_epilogue_int.argtypes = [ctypes.POINTER(ctypes.c_int64), i64, i64, ctypes.POINTER(ctypes.c_int32),
+                                            ctypes.c_int, ctypes.c_int, ctypes.c_float]
         lib.oracle_set_threads.argtypes = [ctypes.c_int]
         lib.oracle_get_threads.restype = ctypes.c_int
         _lib = lib
@@ -157,3 +160,42 @@ def conv2d(dtype: str, x: np.ndarray, w: np.ndarray, stride=(1, 1), pad=(0, 0), 
     if rc:
         raise RuntimeError(f"oracle_conv2d failed with {rc}")
     return y, Sabs
+
+
+def epilogue(C: np.ndarray, S, bias=None, relu: bool = False, scale: float = 0.0):
+    """Fused consumer applied to an operator result C (last axis = output column / channel): bias add,
+    ReLU and, for integer C with scale > 0, requantisation to int8 codes.  Returns new (C, S)."""
+    N = C.shape[-1]
+    rows = C.size // N if N else 0
+    lib = _load()
+    if C.dtype == np.float64:
+        if scale:
+            raise ValueError("oracle.epilogue: requantisation is defined for int8 inputs only")
+        C2 = np.ascontiguousarray(C).copy()
+        S2 = None if S is None else np.ascontiguousarray(S).copy()
+        b = None
+        if bias is not None:
+            b = np.ascontiguousarray(bias, dtype=np.float32)
+            if b.shape != (N,):
+                raise ValueError("oracle.epilogue: bias must have one float32 per output column")
+        rc = lib.oracle_epilogue_float(C2.ctypes.data_as(ctypes.POINTER(ctypes.c_double)),
+                                       None if S2 is None else S2.ctypes.data_as(ctypes.POINTER(ctypes.c_double)),
+                                       rows, N, None if b is None else b.ctypes.data_as(ctypes.POINTER(ctypes.c_float)),
+                                       int(bool(relu)))
+        if rc:
+            raise RuntimeError(f"oracle_epilogue_float failed with {rc}")
+        return C2, S2
+    if C.dtype != np.int64:
+        raise ValueError("oracle.epilogue: C must be the float64 or int64 result of an oracle operator")
+    C2 = np.ascontiguousarray(C).copy()
+    b = None
+    if bias is not None:
+        b = np.ascontiguousarray(bias)
+        if b.dtype != np.int32 or b.shape != (N,):
+            raise ValueError("oracle.epilogue: bias must have one int32 per output column")
+    rc = lib.oracle_epilogue_int(C2.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)), rows, N,
+                                 None if b is None else b.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
+                                 int(bool(relu)), int(scale != 0.0), float(scale))
+    if rc:
+        raise RuntimeError(f"oracle_epilogue_int failed with {rc} (sum beyond int32, or scale not finite and positive)")
+    return C2, None

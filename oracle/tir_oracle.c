@@ -30,7 +30,9 @@
  * own decode; brute-force per-element gathers on tiny shapes; identity matrices; conv ==
  * explicit im2col + matmul; 1x1 conv == GEMM; linearity; delta and all-ones closed forms; groups
  * == independent convs; fp64 library convolution (torch CPU) on strided/dilated/padded/grouped
- * cases; closed forms C = K and C = K*i*j.  No function in this file is "parity unpinned".
+ * cases; closed forms C = K and C = K*i*j; the fused consumers against hand-worked values (ties,
+ * saturation, signs) and against the same arithmetic carried out in numpy's float32 / int64.
+ * No function in this file is "parity unpinned".
  */
 #include <math.h>
 #include <stdint.h>
@@ -254,5 +256,58 @@ int oracle_conv2d(int dtype, const void* x, const void* w, int64_t N, int64_t H,
                     else { ((double*)y)[o] = accf; if (Sabs) Sabs[o] = accs; }
                 }
     free(xf); free(wf); free(xi); free(wi);
+    return ORACLE_OK;
+}
+
+/*
+ * Fused consumers of the contraction (the paper's running example in its section-4 overview figure is a
+ * matmul followed by ReLU; the consumer is computed behind the tensorized block instead of in a second
+ * pass).  Both functions work in place on the row-major [rows][N] result of one of the operators above;
+ * column j is the output column / output channel.
+ *
+ * Floating inputs:  t = C[i,j] + bias[j];  if relu: t = max(t, 0).  In fp64; S[i,j] (if given) grows by
+ *   |bias[j]|, one more term of the sum the parity bound is expressed in.  bias may be NULL.
+ * int8 inputs:      t = C[i,j] + bias[j] in int64 (must fit int32: else ORACLE_BAD_ARG);
+ *   if relu: t = max(t, 0).  With requantise != 0 the value is then mapped to an int8 code in
+ *   SINGLE precision, the precision the decision is taken in on the device as well:
+ *       f = (float)(int32)t        (int32 -> binary32, round to nearest even)
+ *       f = f * scale              (one binary32 multiplication)
+ *       q = nearest integer to f, ties to even;  q = min(max(q, -128), 127)
+ *   and C[i,j] = q.  scale must be finite and > 0.
+ */
+int oracle_epilogue_float(double* C, double* S, int64_t rows, int64_t N, const float* bias, int relu) {
+    if (!C || rows < 0 || N < 0) return ORACLE_BAD_ARG;
+    for (int64_t i = 0; i < rows; ++i)
+        for (int64_t j = 0; j < N; ++j) {
+            double t = C[i * N + j];
+            if (bias) {
+                t += (double)bias[j];
+                if (S) S[i * N + j] += fabs((double)bias[j]);
+            }
+            if (relu && t < 0.0) t = 0.0;
+            C[i * N + j] = t;
+        }
+    return ORACLE_OK;
+}
+
+int oracle_epilogue_int(int64_t* C, int64_t rows, int64_t N, const int32_t* bias, int relu, int requantise, float scale) {
+    if (!C || rows < 0 || N < 0) return ORACLE_BAD_ARG;
+    if (requantise && !(scale > 0.0f && scale <= 3.4028234663852886e38f)) return ORACLE_BAD_ARG;
+    for (int64_t i = 0; i < rows; ++i)
+        for (int64_t j = 0; j < N; ++j) {
+            int64_t t = C[i * N + j];
+            if (bias) t += (int64_t)bias[j];
+            if (t < INT32_MIN || t > INT32_MAX) return ORACLE_BAD_ARG;
+            if (relu && t < 0) t = 0;
+            if (requantise) {
+                volatile float f = (float)(int32_t)t;   /* volatile: each step is rounded to binary32, never kept wider */
+                volatile float g = f * scale;
+                float q = nearbyintf(g);                /* default rounding mode: to nearest, ties to even */
+                if (q < -128.0f) q = -128.0f;
+                if (q > 127.0f) q = 127.0f;
+                t = (int64_t)q;
+            }
+            C[i * N + j] = t;
+        }
     return ORACLE_OK;
 }

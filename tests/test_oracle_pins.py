@@ -368,3 +368,69 @@ def test_conv_linearity_in_each_input(oracle):
     f = lambda x, w: oracle.conv2d("f16", enc(x), enc(w), (1, 1), (1, 1), (2, 2), 2)[0]
     assert np.array_equal(f(2 * X1 + X2, W1), 2 * f(X1, W1) + f(X2, W1))
     assert np.array_equal(f(X1, 2 * W1 + W2), 2 * f(X1, W1) + f(X1, W2))
+
+
+# ------------------------------------------------------------------------------ fused consumers
+def test_epilogue_float_hand_worked(oracle):
+    """bias add and ReLU on a result small enough to check by eye; S grows by |bias| (the bias is one
+    more term of the sum the tolerance is expressed in)."""
+    C = np.array([[1.5, -2.0], [0.0, -0.25]])
+    S = np.array([[3.0, 2.0], [1.0, 0.5]])
+    bias = np.array([0.5, -1.0], dtype=np.float32)
+    out, S2 = oracle.epilogue(C, S, bias=bias)
+    assert out.tolist() == [[2.0, -3.0], [0.5, -1.25]]
+    assert S2.tolist() == [[3.5, 3.0], [1.5, 1.5]]
+    out, S2 = oracle.epilogue(C, S, bias=bias, relu=True)
+    assert out.tolist() == [[2.0, 0.0], [0.5, 0.0]]
+    out, S2 = oracle.epilogue(C, S, relu=True)
+    assert out.tolist() == [[1.5, 0.0], [0.0, 0.0]] and S2.tolist() == S.tolist()
+    out, _ = oracle.epilogue(C, None)
+    assert out.tolist() == C.tolist() and out is not C
+    # the bias is applied per output column of an N-d result (last axis)
+    y = np.zeros((2, 3, 4, 2))
+    out, _ = oracle.epilogue(y, None, bias=bias)
+    assert np.all(out[..., 0] == 0.5) and np.all(out[..., 1] == -1.0)
+
+
+def test_epilogue_int_hand_worked(oracle):
+    """Requantisation: ties go to the even code, both signs, saturation at -128 / 127, ReLU comes
+    before the scaling, the bias before the ReLU."""
+    t = np.array([[1, 3, 5, -1, -3, 1000, -1000, 0]], dtype=np.int64)
+    q, _ = oracle.epilogue(t, None, scale=0.5)
+    assert q.tolist() == [[0, 2, 2, 0, -2, 127, -128, 0]]
+    q, _ = oracle.epilogue(t, None, relu=True, scale=0.5)
+    assert q.tolist() == [[0, 2, 2, 0, 0, 127, 0, 0]]
+    bias = np.array([2, -2, 0, 1, 3, 0, 0, -7], dtype=np.int32)
+    q, _ = oracle.epilogue(t, None, bias=bias)
+    assert q.tolist() == [[3, 1, 5, 0, 0, 1000, -1000, -7]]
+    q, _ = oracle.epilogue(t, None, bias=bias, relu=True, scale=1.0)
+    assert q.tolist() == [[3, 1, 5, 0, 0, 127, 0, 0]]
+    # the scaling is a binary32 product: 25 * 0.1f rounds to 2.5 exactly (-> 2), in binary64 it would be
+    # 2.50000003... (-> 3)
+    q, _ = oracle.epilogue(np.array([[25, 35]], dtype=np.int64), None, scale=float(np.float32(0.1)))
+    assert q.tolist() == [[2, 4]]
+    with pytest.raises(RuntimeError):
+        oracle.epilogue(np.array([[2 ** 31 - 1]], dtype=np.int64), None, bias=np.array([1], dtype=np.int32))
+    with pytest.raises(RuntimeError):
+        oracle.epilogue(t, None, scale=-1.0)
+    with pytest.raises(RuntimeError):
+        oracle.epilogue(t, None, scale=float("inf"))
+
+
+@pytest.mark.parametrize("scale", [0.0123, 1.0 / 3.0, 0.5, 2.0, 7.3e-4])
+def test_epilogue_int_matches_numpy_float32(oracle, scale):
+    """The same definition carried out by numpy: int32 -> float32, one float32 product, rint (ties to
+    even), clip.  Values spread over both the linear and the saturated range."""
+    rng = np.random.default_rng(int(scale * 1e6) + 5)
+    span = int(min(2 ** 31 - 1, 400.0 / scale))
+    t = rng.integers(-span, span, size=(37, 53), dtype=np.int64)
+    bias = rng.integers(-1000, 1000, size=53).astype(np.int32)
+    for relu in (False, True):
+        got, _ = oracle.epilogue(t, None, bias=bias, relu=relu, scale=scale)
+        u = t + bias.astype(np.int64)
+        if relu:
+            u = np.maximum(u, 0)
+        f = u.astype(np.int32).astype(np.float32) * np.float32(scale)
+        want = np.clip(np.rint(f), -128, 127).astype(np.int64)
+        assert np.array_equal(got, want)
+        assert got.min() == (-128 if not relu else 0) and got.max() == 127      # both regimes were exercised
