@@ -17,7 +17,8 @@ measure the host), replayed once inside the timed region; --eager launches them 
 Prints ONE JSON line.  `value` = algorithmic TFLOP/s of the whole run (2*M*N*K of the fused GEMM
 view per step).  `roofline` prices the kernel against the dense fp16 MFMA peak; `cpu_baseline`
 times the CPU oracle on the same workload on this machine's host cores; `operators` lists every other
-benchmark configuration (hot cache) for context.
+benchmark configuration, plain and with a fused consumer (bias / ReLU / down-cast / int8
+requantisation), hot cache, for context.
 """
 from __future__ import annotations
 
@@ -61,10 +62,11 @@ def parse():
 
 def make_sets(B, wl, count):
     a_bits, b_bits = wl.operands()
+    bias = B.bias_to_device(wl)          # a few hundred bytes: shared by every set
     sets = []
     for _ in range(count):
         sets.append((B.to_device(a_bits, wl.dtype), B.to_device(b_bits, wl.dtype),
-                     B.empty_out(B.out_shape(wl), wl.out)))
+                     B.empty_out(B.out_shape(wl), wl.out), bias))
     return sets
 
 
@@ -101,6 +103,7 @@ def timed_run(torch, B, wl, sets, steps, warmup, eager):
 
 
 def variant_of(B, wl):
+    # (the variant query takes the output dtype; int8 output selects the requantising kernels)
     if wl.kind == "conv2d":
         return B.tir_conv2d_variant(wl.n, wl.h, wl.w, wl.c, wl.k, wl.r, wl.s, *wl.stride, *wl.pad, *wl.dil,
                                     wl.groups, wl.dtype, wl.out)
@@ -202,7 +205,7 @@ def main():
 
     operators = []
     if not args.no_operators:
-        for name, o in I.WORKLOADS.items():
+        for name, o in list(I.WORKLOADS.items()) + list(I.FUSED_WORKLOADS.items()):
             k = 20 if o.flops() > 4e10 else 200
             s = make_sets(B, o, 1)
             if not args.no_tune:
@@ -210,7 +213,9 @@ def main():
             w_, e_ = timed_run(torch, B, o, s, k, 5, args.eager)
             tf = o.flops() * k / e_ / 1e12
             attain = min(PEAK_TFLOPS[o.dtype], o.flops() / o.min_bytes() * HBM_GBS / 1e3)
-            operators.append({"workload": name, "variant": variant_of(B, o), "us": round(e_ / k * 1e6, 3),
+            operators.append({"workload": name, "variant": variant_of(B, o), "out": o.out,
+                              "fused": ("bias " if o.ep_bias else "") + ("relu " if o.ep_relu else "") + ("requant" if o.ep_scale else ""),
+                              "us": round(e_ / k * 1e6, 3),
                               "tflops": round(tf, 2), "frac_mfma_peak": round(tf / PEAK_TFLOPS[o.dtype], 4),
                               "frac_attainable": round(tf / attain, 4),
                               "gbs": round(o.min_bytes() * k / e_ / 1e9, 1), "cache": "hot"})

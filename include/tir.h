@@ -82,6 +82,39 @@ tir_status tir_conv2d(const void* x, const void* w, void* y, int64_t N, int64_t 
                       int64_t K, int64_t R, int64_t S, int stride_h, int stride_w, int pad_h, int pad_w,
                       int dil_h, int dil_w, int groups, tir_dtype in, tir_dtype out, tir_stream stream);
 
+/*
+ * Fused consumers (the paper's running example, the overview figure of sec. 4, is a matmul followed by
+ * ReLU: the element-wise consumer is computed behind the tensorized block, in the same kernel, instead
+ * of in a second pass over C).  The *_fused entry points take the arguments of the plain ones plus an
+ * epilogue; ep == NULL is the plain operator.  With t = the operator's sum for output column j
+ * (GEMM / batched matmul: column of C, the same bias for every batch; conv2d: output channel k):
+ *     t = t + bias[j]          if bias != NULL   (fp32 for F16 / BF16 inputs, int32 for I8 inputs;
+ *                                                 device pointer, 4-byte aligned, N resp. K elements)
+ *     t = max(t, 0)            if relu != 0
+ *     out = convert(t)         F32 / I32: unchanged; F16 / BF16: round to nearest even;
+ *                              I8 (inputs I8 only): clamp(rint((float)t * scale), -128, 127), the
+ *                              product and the rounding in binary32, ties to even; scale must be
+ *                              finite and > 0.  The int32 sum t must not overflow.
+ * (I8, I8) is an allowed (in, out) pair for the fused entry points only; scale is ignored otherwise.
+ */
+typedef struct tir_epilogue {
+    const void* bias;
+    int relu;
+    float scale;
+} tir_epilogue;
+
+tir_status tir_gemm_fused(const void* A, const void* B, void* C, int64_t M, int64_t N, int64_t K, int64_t a_rs,
+                          int64_t a_cs, int64_t b_rs, int64_t b_cs, int64_t c_rs, int64_t c_cs, tir_dtype in,
+                          tir_dtype out, const tir_epilogue* ep, tir_stream stream);
+tir_status tir_batch_matmul_fused(const void* A, const void* B, void* C, int64_t batch, int64_t M, int64_t N,
+                                  int64_t K, int64_t a_bs, int64_t a_rs, int64_t a_cs, int64_t b_bs,
+                                  int64_t b_rs, int64_t b_cs, int64_t c_bs, int64_t c_rs, int64_t c_cs,
+                                  tir_dtype in, tir_dtype out, const tir_epilogue* ep, tir_stream stream);
+tir_status tir_conv2d_fused(const void* x, const void* w, void* y, int64_t N, int64_t H, int64_t W, int64_t C,
+                            int64_t K, int64_t R, int64_t S, int stride_h, int stride_w, int pad_h, int pad_w,
+                            int dil_h, int dil_w, int groups, tir_dtype in, tir_dtype out,
+                            const tir_epilogue* ep, tir_stream stream);
+
 /* Message for the calling thread's last failed call ("" if none).  Never NULL; valid until the
  * thread's next failing call. */
 const char* tir_last_error(void);
@@ -89,7 +122,8 @@ const char* tir_last_error(void);
 /*
  * Name of the kernel variant the next identical call would launch (for profiling harnesses), e.g.
  * "f16_f32_t256x256w2x4s2_ak_bn".  Arguments as for tir_batch_matmul / tir_conv2d without pointers
- * being dereferenced; returns "" on invalid arguments.  The string is static.
+ * being dereferenced; returns "" on invalid arguments.  The string is static.  out = TIR_I8 asks for the
+ * requantising variant of the fused entry points.
  */
 const char* tir_gemm_variant(int64_t batch, int64_t M, int64_t N, int64_t K, int64_t a_rs, int64_t a_cs,
                              int64_t b_rs, int64_t b_cs, int64_t c_rs, int64_t c_cs, tir_dtype in,
@@ -103,8 +137,8 @@ const char* tir_conv2d_variant(int64_t N, int64_t H, int64_t W, int64_t C, int64
  * loop structure around the fixed tensorized block are benchmarked on the device; the evaluation's
  * tuning-time discussion: kept records make a second search of the same operator unnecessary).
  *
- * tir_tune_batch_matmul / tir_tune_conv2d take the arguments of tir_batch_matmul / tir_conv2d (batch = 1
- * with zero batch strides tunes tir_gemm), launch every compiled variant that computes this problem
+ * tir_tune_batch_matmul / tir_tune_conv2d take the arguments of tir_batch_matmul_fused / tir_conv2d_fused
+ * (batch = 1 with zero batch strides tunes tir_gemm; ep may be NULL), launch every compiled variant that computes this problem
  * `reps` times on `stream`, and record the fastest under the problem's signature (dtypes, copy
  * modes implied by strides and alignment, extents, convolution geometry).  Later calls of the
  * operator entry points with the same signature use the recorded variant instead of the built-in
@@ -123,11 +157,12 @@ const char* tir_conv2d_variant(int64_t N, int64_t H, int64_t W, int64_t C, int64
 tir_status tir_tune_batch_matmul(const void* A, const void* B, void* C, int64_t batch, int64_t M, int64_t N,
                                  int64_t K, int64_t a_bs, int64_t a_rs, int64_t a_cs, int64_t b_bs, int64_t b_rs,
                                  int64_t b_cs, int64_t c_bs, int64_t c_rs, int64_t c_cs, tir_dtype in,
-                                 tir_dtype out, int reps, double* best_us, tir_stream stream);
+                                 tir_dtype out, const tir_epilogue* ep, int reps, double* best_us,
+                                 tir_stream stream);
 tir_status tir_tune_conv2d(const void* x, const void* w, void* y, int64_t N, int64_t H, int64_t W, int64_t C,
                            int64_t K, int64_t R, int64_t S, int stride_h, int stride_w, int pad_h, int pad_w,
-                           int dil_h, int dil_w, int groups, tir_dtype in, tir_dtype out, int reps,
-                           double* best_us, tir_stream stream);
+                           int dil_h, int dil_w, int groups, tir_dtype in, tir_dtype out,
+                           const tir_epilogue* ep, int reps, double* best_us, tir_stream stream);
 int tir_tune_count(void);                       /* number of records */
 void tir_tune_clear(void);                      /* forget every record */
 tir_status tir_tune_save(const char* path);     /* TIR_ERR_INVALID_ARG if the file cannot be written */

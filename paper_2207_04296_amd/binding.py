@@ -20,7 +20,19 @@ EXPORTS = ["tir_gemm", "tir_batch_matmul", "tir_conv2d", "tir_last_error", "tir_
            "tir_conv2d_variant", "tir_debug_force_tile", "tir_debug_force_variant", "tir_debug_variant_count",
            "tir_debug_variant_name", "tir_debug_tile_of_block", "tir_probe_mfma_rate", "tir_version",
            "tir_tune_batch_matmul", "tir_tune_conv2d", "tir_tune_count", "tir_tune_clear", "tir_tune_save",
-           "tir_tune_load"]
+           "tir_tune_load", "tir_gemm_fused", "tir_batch_matmul_fused", "tir_conv2d_fused"]
+
+
+class Epilogue(ctypes.Structure):
+    """struct tir_epilogue: bias pointer, relu flag, requantisation scale."""
+    _fields_ = [("bias", ctypes.c_void_p), ("relu", ctypes.c_int), ("scale", ctypes.c_float)]
+
+
+def make_epilogue(bias=None, relu=False, scale=0.0):
+    """ctypes tir_epilogue, or None when nothing is fused (the plain operator)."""
+    if bias is None and not relu and not scale:
+        return None
+    return Epilogue(_ptr(bias) or None, int(bool(relu)), float(scale))
 
 
 class TirError(RuntimeError):
@@ -70,9 +82,16 @@ def lib() -> ctypes.CDLL:
     L.tir_probe_mfma_rate.restype = ci
     L.tir_version.restype = ctypes.c_char_p
     pd = ctypes.POINTER(ctypes.c_double)
-    L.tir_tune_batch_matmul.argtypes = [vp, vp, vp] + [i64] * 13 + [ci, ci, ci, pd, vp]
+    pe = ctypes.POINTER(Epilogue)
+    L.tir_gemm_fused.argtypes = [vp, vp, vp] + [i64] * 9 + [ci, ci, pe, vp]
+    L.tir_gemm_fused.restype = ci
+    L.tir_batch_matmul_fused.argtypes = [vp, vp, vp] + [i64] * 13 + [ci, ci, pe, vp]
+    L.tir_batch_matmul_fused.restype = ci
+    L.tir_conv2d_fused.argtypes = [vp, vp, vp] + [i64] * 7 + [ci] * 7 + [ci, ci, pe, vp]
+    L.tir_conv2d_fused.restype = ci
+    L.tir_tune_batch_matmul.argtypes = [vp, vp, vp] + [i64] * 13 + [ci, ci, pe, ci, pd, vp]
     L.tir_tune_batch_matmul.restype = ci
-    L.tir_tune_conv2d.argtypes = [vp, vp, vp] + [i64] * 7 + [ci] * 7 + [ci, ci, ci, pd, vp]
+    L.tir_tune_conv2d.argtypes = [vp, vp, vp] + [i64] * 7 + [ci] * 7 + [ci, ci, pe, ci, pd, vp]
     L.tir_tune_conv2d.restype = ci
     L.tir_tune_count.restype = ci
     L.tir_tune_clear.restype = None
@@ -192,21 +211,45 @@ def tir_version() -> str:
     return lib().tir_version().decode()
 
 
+def _ep_arg(ep):
+    return None if ep is None else ctypes.byref(ep)
+
+
+def tir_gemm_fused(A, B, C, M, N, K, a_rs, a_cs, b_rs, b_cs, c_rs, c_cs, in_dtype, out_dtype, ep=None, stream=None) -> None:
+    """ep: an Epilogue from make_epilogue(), or None for the plain operator."""
+    _check(lib().tir_gemm_fused(_ptr(A), _ptr(B), _ptr(C), M, N, K, a_rs, a_cs, b_rs, b_cs, c_rs, c_cs, _code(in_dtype),
+                                _code(out_dtype), _ep_arg(ep), _stream(stream)))
+
+
+def tir_batch_matmul_fused(A, B, C, batch, M, N, K, a_bs, a_rs, a_cs, b_bs, b_rs, b_cs, c_bs, c_rs, c_cs,
+                           in_dtype, out_dtype, ep=None, stream=None) -> None:
+    _check(lib().tir_batch_matmul_fused(_ptr(A), _ptr(B), _ptr(C), batch, M, N, K, a_bs, a_rs, a_cs, b_bs, b_rs, b_cs,
+                                        c_bs, c_rs, c_cs, _code(in_dtype), _code(out_dtype), _ep_arg(ep),
+                                        _stream(stream)))
+
+
+def tir_conv2d_fused(x, w, y, N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, groups,
+                     in_dtype, out_dtype, ep=None, stream=None) -> None:
+    _check(lib().tir_conv2d_fused(_ptr(x), _ptr(w), _ptr(y), N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w,
+                                  dil_h, dil_w, groups, _code(in_dtype), _code(out_dtype), _ep_arg(ep),
+                                  _stream(stream)))
+
+
 def tir_tune_batch_matmul(A, B, C, batch, M, N, K, a_bs, a_rs, a_cs, b_bs, b_rs, b_cs, c_bs, c_rs, c_cs,
-                          in_dtype, out_dtype, reps=5, stream=None) -> float:
+                          in_dtype, out_dtype, ep=None, reps=5, stream=None) -> float:
     """Measure every variant for this problem and record the fastest; returns its microseconds per launch."""
     us = ctypes.c_double()
     _check(lib().tir_tune_batch_matmul(_ptr(A), _ptr(B), _ptr(C), batch, M, N, K, a_bs, a_rs, a_cs, b_bs, b_rs, b_cs,
-                                       c_bs, c_rs, c_cs, _code(in_dtype), _code(out_dtype), int(reps),
+                                       c_bs, c_rs, c_cs, _code(in_dtype), _code(out_dtype), _ep_arg(ep), int(reps),
                                        ctypes.byref(us), _stream(stream)))
     return us.value
 
 
 def tir_tune_conv2d(x, w, y, N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, groups,
-                    in_dtype, out_dtype, reps=5, stream=None) -> float:
+                    in_dtype, out_dtype, ep=None, reps=5, stream=None) -> float:
     us = ctypes.c_double()
     _check(lib().tir_tune_conv2d(_ptr(x), _ptr(w), _ptr(y), N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w,
-                                 dil_h, dil_w, groups, _code(in_dtype), _code(out_dtype), int(reps),
+                                 dil_h, dil_w, groups, _code(in_dtype), _code(out_dtype), _ep_arg(ep), int(reps),
                                  ctypes.byref(us), _stream(stream)))
     return us.value
 
@@ -242,37 +285,52 @@ def to_device(bits, dtype: str, device="cuda:0"):
 
 def empty_out(shape, out_dtype: str, device="cuda:0"):
     import torch
-    dt = {"f32": torch.float32, "i32": torch.int32, "f16": torch.float16, "bf16": torch.bfloat16}[out_dtype]
+    dt = {"f32": torch.float32, "i32": torch.int32, "f16": torch.float16, "bf16": torch.bfloat16, "i8": torch.int8}[out_dtype]
     return torch.empty(shape, dtype=dt, device=device)
 
 
-def run_workload(wl, a_dev, b_dev, c_dev, stream=None) -> None:
+def bias_to_device(wl, device="cuda:0"):
+    """Device tensor of the workload's seeded bias (float32 / int32), or None."""
+    import torch
+    b = wl.bias_values()
+    return None if b is None else torch.from_numpy(b).to(device)
+
+
+def _wl_epilogue(wl, bias_dev):
+    if wl.ep_bias and bias_dev is None:
+        raise ValueError(f"{wl.name} has a fused bias: pass its device tensor (bias_to_device)")
+    return make_epilogue(bias_dev if wl.ep_bias else None, wl.ep_relu, wl.ep_scale)
+
+
+def run_workload(wl, a_dev, b_dev, c_dev, bias_dev=None, stream=None) -> None:
     """Launch one paper_2207_04296_amd.inputs.Workload on resident operands."""
+    ep = _wl_epilogue(wl, bias_dev)
     if wl.kind == "conv2d":
-        tir_conv2d(a_dev, b_dev, c_dev, wl.n, wl.h, wl.w, wl.c, wl.k, wl.r, wl.s, wl.stride[0], wl.stride[1],
-                   wl.pad[0], wl.pad[1], wl.dil[0], wl.dil[1], wl.groups, wl.dtype, wl.out, stream)
+        tir_conv2d_fused(a_dev, b_dev, c_dev, wl.n, wl.h, wl.w, wl.c, wl.k, wl.r, wl.s, wl.stride[0], wl.stride[1],
+                         wl.pad[0], wl.pad[1], wl.dil[0], wl.dil[1], wl.groups, wl.dtype, wl.out, ep, stream)
         return
     M, N, K = wl.M, wl.N, wl.K
     b_rs, b_cs = (1, K) if wl.trans_b else (N, 1)
     if wl.kind == "gemm":
-        tir_gemm(a_dev, b_dev, c_dev, M, N, K, K, 1, b_rs, b_cs, N, 1, wl.dtype, wl.out, stream)
+        tir_gemm_fused(a_dev, b_dev, c_dev, M, N, K, K, 1, b_rs, b_cs, N, 1, wl.dtype, wl.out, ep, stream)
     else:
-        tir_batch_matmul(a_dev, b_dev, c_dev, wl.batch, M, N, K, M * K, K, 1, K * N, b_rs, b_cs, M * N, N, 1,
-                         wl.dtype, wl.out, stream)
+        tir_batch_matmul_fused(a_dev, b_dev, c_dev, wl.batch, M, N, K, M * K, K, 1, K * N, b_rs, b_cs, M * N, N, 1,
+                               wl.dtype, wl.out, ep, stream)
 
 
-def tune_workload(wl, a_dev, b_dev, c_dev, reps=5, stream=None) -> float:
+def tune_workload(wl, a_dev, b_dev, c_dev, bias_dev=None, reps=5, stream=None) -> float:
     """tir_tune_* for one paper_2207_04296_amd.inputs.Workload; returns the winner's microseconds per launch."""
+    ep = _wl_epilogue(wl, bias_dev)
     if wl.kind == "conv2d":
         return tir_tune_conv2d(a_dev, b_dev, c_dev, wl.n, wl.h, wl.w, wl.c, wl.k, wl.r, wl.s, wl.stride[0], wl.stride[1],
-                               wl.pad[0], wl.pad[1], wl.dil[0], wl.dil[1], wl.groups, wl.dtype, wl.out, reps, stream)
+                               wl.pad[0], wl.pad[1], wl.dil[0], wl.dil[1], wl.groups, wl.dtype, wl.out, ep, reps, stream)
     M, N, K = wl.M, wl.N, wl.K
     b_rs, b_cs = (1, K) if wl.trans_b else (N, 1)
     if wl.kind == "gemm":
         return tir_tune_batch_matmul(a_dev, b_dev, c_dev, 1, M, N, K, 0, K, 1, 0, b_rs, b_cs, 0, N, 1, wl.dtype, wl.out,
-                                     reps, stream)
+                                     ep, reps, stream)
     return tir_tune_batch_matmul(a_dev, b_dev, c_dev, wl.batch, M, N, K, M * K, K, 1, K * N, b_rs, b_cs, M * N, N, 1,
-                                 wl.dtype, wl.out, reps, stream)
+                                 wl.dtype, wl.out, ep, reps, stream)
 
 
 def out_shape(wl):

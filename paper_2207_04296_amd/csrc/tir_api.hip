@@ -52,6 +52,7 @@ __global__ void __launch_bounds__(256) mfma_probe_kernel(float* sink, int iters,
 #define V2 TIR_ROW
 #define V3 TIR_ROW
 #define V4 TIR_ROW
+#define V5 TIR_ROW
 static const Variant kVariants[] = {
 #include "tir_variants.def"
 };
@@ -72,10 +73,14 @@ static tir_status fail(tir_status st, const char* fmt, ...) {
 static const int64_t kMaxExtent = 2147483647LL;
 static const double kCUs = 256.0;
 
-static bool dtype_pair_ok(int in, int out) {
+static bool dtype_pair_ok(int in, int out, bool fused) {
     return (in == TIR_F16 && (out == TIR_F32 || out == TIR_F16)) ||
-           (in == TIR_BF16 && (out == TIR_F32 || out == TIR_BF16)) || (in == TIR_I8 && out == TIR_I32);
+           (in == TIR_BF16 && (out == TIR_F32 || out == TIR_BF16)) || (in == TIR_I8 && out == TIR_I32) ||
+           (fused && in == TIR_I8 && out == TIR_I8);
 }
+
+// The epilogue variant queries assume for int8 output.
+static const tir_epilogue kQueryRequant = {nullptr, 0, 1.0f};
 
 static bool aligned(const void* p, uintptr_t a) { return ((uintptr_t)p % a) == 0; }
 
@@ -174,9 +179,14 @@ static const Variant* choose(const TuneKey& key, int64_t batch, int64_t M, int64
     return pick(key.dt, key.out, key.amode, key.bmode, batch, M, N, K);
 }
 
-static tir_status check_common(const void* A, const void* B, const void* C, int in, int out) {
+static tir_status check_common(const void* A, const void* B, const void* C, int in, int out, const tir_epilogue* ep) {
     if (in < 0 || in > TIR_I32 || out < 0 || out > TIR_I32) return fail(TIR_ERR_INVALID_ARG, "unknown dtype code (in=%d out=%d)", in, out);
-    if (!dtype_pair_ok(in, out)) return fail(TIR_ERR_UNSUPPORTED, "unsupported (in, out) dtype pair (%d, %d)", in, out);
+    if (!dtype_pair_ok(in, out, ep != nullptr)) return fail(TIR_ERR_UNSUPPORTED, "unsupported (in, out) dtype pair (%d, %d)", in, out);
+    if (ep) {
+        if (!aligned(ep->bias, 4)) return fail(TIR_ERR_ALIGNMENT, "bias pointer not aligned to 4 bytes");
+        if (out == TIR_I8 && !(ep->scale > 0.0f && ep->scale <= 3.402823466e38f))
+            return fail(TIR_ERR_INVALID_ARG, "int8 output needs a finite scale > 0");
+    }
     const int es = elem_size(in), os = elem_size(out);
     if (!aligned(A, es) || !aligned(B, es)) return fail(TIR_ERR_ALIGNMENT, "input pointer not aligned to its element size");
     if (!aligned(C, os)) return fail(TIR_ERR_ALIGNMENT, "output pointer not aligned to its element size");
@@ -186,9 +196,10 @@ static tir_status check_common(const void* A, const void* B, const void* C, int 
 // Build the launch plan of a (batched) GEMM.  Pointers may be null only for planning (variant query).
 static tir_status plan_gemm(bool need_ptrs, const void* A, const void* B, void* C, int64_t batch, int64_t M, int64_t N,
                             int64_t K, int64_t a_bs, int64_t a_rs, int64_t a_cs, int64_t b_bs, int64_t b_rs,
-                            int64_t b_cs, int64_t c_bs, int64_t c_rs, int64_t c_cs, int in, int out, Plan* plan) {
+                            int64_t b_cs, int64_t c_bs, int64_t c_rs, int64_t c_cs, int in, int out, const tir_epilogue* ep,
+                            Plan* plan) {
     plan->v = nullptr;
-    tir_status st = check_common(A, B, C, in, out);
+    tir_status st = check_common(A, B, C, in, out, ep);
     if (st != TIR_OK) return st;
     if (batch < 0 || M < 0 || N < 0 || K < 0) return fail(TIR_ERR_INVALID_ARG, "negative extent (batch=%lld M=%lld N=%lld K=%lld)", (long long)batch, (long long)M, (long long)N, (long long)K);
     if (a_bs < 0 || a_rs < 0 || a_cs < 0 || b_bs < 0 || b_rs < 0 || b_cs < 0 || c_bs < 0 || c_rs < 0 || c_cs < 0)
@@ -233,6 +244,7 @@ static tir_status plan_gemm(bool need_ptrs, const void* A, const void* B, void* 
     p.a_bs = a_bs; p.b_bs = b_bs; p.c_bs = c_bs;
     p.a_rs = a_rs; p.a_cs = a_cs; p.b_rs = b_rs; p.b_cs = b_cs; p.c_rs = c_rs; p.c_cs = c_cs;
     p.c_fast = (c_cs == 1 && (c_rs >= N || M == 1) && (c_rs * 256 + N) * elem_size(out) < kMaxExtent) ? 1 : 0;
+    if (ep) { p.bias = ep->bias; p.bias_bs = 0; p.relu = ep->relu != 0; p.scale = ep->scale; }
     plan->v = v;
     return TIR_OK;
 }
@@ -244,9 +256,9 @@ static int64_t conv_extent(int64_t in, int64_t filt, int64_t stride, int64_t pad
 
 static tir_status plan_conv(bool need_ptrs, const void* x, const void* w, void* y, int64_t N, int64_t H, int64_t W,
                             int64_t C, int64_t K, int64_t R, int64_t S, int stride_h, int stride_w, int pad_h,
-                            int pad_w, int dil_h, int dil_w, int groups, int in, int out, Plan* plan) {
+                            int pad_w, int dil_h, int dil_w, int groups, int in, int out, const tir_epilogue* ep, Plan* plan) {
     plan->v = nullptr;
-    tir_status st = check_common(x, w, y, in, out);
+    tir_status st = check_common(x, w, y, in, out, ep);
     if (st != TIR_OK) return st;
     if (N < 0 || H <= 0 || W <= 0 || C <= 0 || K <= 0 || R <= 0 || S <= 0)
         return fail(TIR_ERR_INVALID_ARG, "non-positive extent (N=%lld H=%lld W=%lld C=%lld K=%lld R=%lld S=%lld)", (long long)N, (long long)H, (long long)W, (long long)C, (long long)K, (long long)R, (long long)S);
@@ -313,6 +325,7 @@ static tir_status plan_conv(bool need_ptrs, const void* x, const void* w, void* 
     p.b_rs = 1; p.b_cs = Kd;          // B[k][y] = w[y][k]: the KRSC filter is B stored K-major
     p.c_rs = K; p.c_cs = 1;           // NHWC output is C_t[fuse(n,h,w)][co]
     p.c_fast = ((K * 256 + Kg) * elem_size(out) < kMaxExtent) ? 1 : 0;
+    if (ep) { p.bias = ep->bias; p.bias_bs = Kg; p.relu = ep->relu != 0; p.scale = ep->scale; }
     p.H = (int)H; p.W = (int)W; p.Cin = (int)C; p.Cg = (int)Cg; p.P = (int)P; p.Q = (int)Q; p.R = (int)R; p.S = (int)S;
     p.stride_h = stride_h; p.stride_w = stride_w; p.pad_h = pad_h; p.pad_w = pad_w; p.dil_h = dil_h; p.dil_w = dil_w;
     plan->v = v;
@@ -330,6 +343,7 @@ static tir_status run(const Plan& plan, hipStream_t stream) {
         p.A = (const char*)plan.p.A + (long long)b0 * p.a_bs * es;
         p.B = (const char*)plan.p.B + (long long)b0 * p.b_bs * es;
         p.C = (char*)plan.p.C + (long long)b0 * p.c_bs * os;
+        if (p.bias) p.bias = (const char*)plan.p.bias + (long long)b0 * p.bias_bs * 4;
         hipError_t e = plan.v->fn(p, stream);
         if (e != hipSuccess) return fail(TIR_ERR_LAUNCH, "launch of %s failed: %s", plan.v->name, hipGetErrorString(e));
     }
@@ -444,32 +458,51 @@ using namespace tir;
 
 extern "C" {
 
+tir_status tir_gemm_fused(const void* A, const void* B, void* C, int64_t M, int64_t N, int64_t K, int64_t a_rs,
+                          int64_t a_cs, int64_t b_rs, int64_t b_cs, int64_t c_rs, int64_t c_cs, tir_dtype in,
+                          tir_dtype out, const tir_epilogue* ep, tir_stream stream) {
+    Plan plan;
+    tir_status st = plan_gemm(true, A, B, C, 1, M, N, K, 0, a_rs, a_cs, 0, b_rs, b_cs, 0, c_rs, c_cs, (int)in, (int)out, ep, &plan);
+    if (st != TIR_OK) return st;
+    return run(plan, (hipStream_t)stream);
+}
+
+tir_status tir_batch_matmul_fused(const void* A, const void* B, void* C, int64_t batch, int64_t M, int64_t N, int64_t K,
+                                  int64_t a_bs, int64_t a_rs, int64_t a_cs, int64_t b_bs, int64_t b_rs, int64_t b_cs,
+                                  int64_t c_bs, int64_t c_rs, int64_t c_cs, tir_dtype in, tir_dtype out,
+                                  const tir_epilogue* ep, tir_stream stream) {
+    Plan plan;
+    tir_status st = plan_gemm(true, A, B, C, batch, M, N, K, a_bs, a_rs, a_cs, b_bs, b_rs, b_cs, c_bs, c_rs, c_cs, (int)in, (int)out, ep, &plan);
+    if (st != TIR_OK) return st;
+    return run(plan, (hipStream_t)stream);
+}
+
+tir_status tir_conv2d_fused(const void* x, const void* w, void* y, int64_t N, int64_t H, int64_t W, int64_t C, int64_t K,
+                            int64_t R, int64_t S, int stride_h, int stride_w, int pad_h, int pad_w, int dil_h, int dil_w,
+                            int groups, tir_dtype in, tir_dtype out, const tir_epilogue* ep, tir_stream stream) {
+    Plan plan;
+    tir_status st = plan_conv(true, x, w, y, N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, groups, (int)in, (int)out, ep, &plan);
+    if (st != TIR_OK) return st;
+    return run(plan, (hipStream_t)stream);
+}
+
 tir_status tir_gemm(const void* A, const void* B, void* C, int64_t M, int64_t N, int64_t K, int64_t a_rs,
                     int64_t a_cs, int64_t b_rs, int64_t b_cs, int64_t c_rs, int64_t c_cs, tir_dtype in,
                     tir_dtype out, tir_stream stream) {
-    Plan plan;
-    tir_status st = plan_gemm(true, A, B, C, 1, M, N, K, 0, a_rs, a_cs, 0, b_rs, b_cs, 0, c_rs, c_cs, (int)in, (int)out, &plan);
-    if (st != TIR_OK) return st;
-    return run(plan, (hipStream_t)stream);
+    return tir_gemm_fused(A, B, C, M, N, K, a_rs, a_cs, b_rs, b_cs, c_rs, c_cs, in, out, nullptr, stream);
 }
 
 tir_status tir_batch_matmul(const void* A, const void* B, void* C, int64_t batch, int64_t M, int64_t N, int64_t K,
                             int64_t a_bs, int64_t a_rs, int64_t a_cs, int64_t b_bs, int64_t b_rs, int64_t b_cs,
                             int64_t c_bs, int64_t c_rs, int64_t c_cs, tir_dtype in, tir_dtype out,
                             tir_stream stream) {
-    Plan plan;
-    tir_status st = plan_gemm(true, A, B, C, batch, M, N, K, a_bs, a_rs, a_cs, b_bs, b_rs, b_cs, c_bs, c_rs, c_cs, (int)in, (int)out, &plan);
-    if (st != TIR_OK) return st;
-    return run(plan, (hipStream_t)stream);
+    return tir_batch_matmul_fused(A, B, C, batch, M, N, K, a_bs, a_rs, a_cs, b_bs, b_rs, b_cs, c_bs, c_rs, c_cs, in, out, nullptr, stream);
 }
 
 tir_status tir_conv2d(const void* x, const void* w, void* y, int64_t N, int64_t H, int64_t W, int64_t C, int64_t K,
                       int64_t R, int64_t S, int stride_h, int stride_w, int pad_h, int pad_w, int dil_h, int dil_w,
                       int groups, tir_dtype in, tir_dtype out, tir_stream stream) {
-    Plan plan;
-    tir_status st = plan_conv(true, x, w, y, N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, groups, (int)in, (int)out, &plan);
-    if (st != TIR_OK) return st;
-    return run(plan, (hipStream_t)stream);
+    return tir_conv2d_fused(x, w, y, N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, groups, in, out, nullptr, stream);
 }
 
 const char* tir_last_error(void) { return g_err; }
@@ -478,7 +511,7 @@ const char* tir_gemm_variant(int64_t batch, int64_t M, int64_t N, int64_t K, int
                              int64_t b_cs, int64_t c_rs, int64_t c_cs, tir_dtype in, tir_dtype out) {
     Plan plan;
     // batch strides of dense operands, only their divisibility matters for the choice
-    tir_status st = plan_gemm(false, nullptr, nullptr, nullptr, batch, M, N, K, M * K, a_rs, a_cs, K * N, b_rs, b_cs, M * N, c_rs, c_cs, (int)in, (int)out, &plan);
+    tir_status st = plan_gemm(false, nullptr, nullptr, nullptr, batch, M, N, K, M * K, a_rs, a_cs, K * N, b_rs, b_cs, M * N, c_rs, c_cs, (int)in, (int)out, out == TIR_I8 ? &kQueryRequant : nullptr, &plan);
     return (st == TIR_OK && plan.v) ? plan.v->name : "";
 }
 
@@ -486,7 +519,7 @@ const char* tir_conv2d_variant(int64_t N, int64_t H, int64_t W, int64_t C, int64
                                int stride_h, int stride_w, int pad_h, int pad_w, int dil_h, int dil_w, int groups,
                                tir_dtype in, tir_dtype out) {
     Plan plan;
-    tir_status st = plan_conv(false, nullptr, nullptr, nullptr, N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, groups, (int)in, (int)out, &plan);
+    tir_status st = plan_conv(false, nullptr, nullptr, nullptr, N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, groups, (int)in, (int)out, out == TIR_I8 ? &kQueryRequant : nullptr, &plan);
     return (st == TIR_OK && plan.v) ? plan.v->name : "";
 }
 
@@ -516,19 +549,20 @@ tir_status tir_probe_mfma_rate(void* sink, int iters, int random_operands, doubl
 
 tir_status tir_tune_batch_matmul(const void* A, const void* B, void* C, int64_t batch, int64_t M, int64_t N, int64_t K,
                                  int64_t a_bs, int64_t a_rs, int64_t a_cs, int64_t b_bs, int64_t b_rs, int64_t b_cs,
-                                 int64_t c_bs, int64_t c_rs, int64_t c_cs, tir_dtype in, tir_dtype out, int reps,
-                                 double* best_us, tir_stream stream) {
+                                 int64_t c_bs, int64_t c_rs, int64_t c_cs, tir_dtype in, tir_dtype out,
+                                 const tir_epilogue* ep, int reps, double* best_us, tir_stream stream) {
     auto make = [&](Plan* pl) {
-        return plan_gemm(true, A, B, C, batch, M, N, K, a_bs, a_rs, a_cs, b_bs, b_rs, b_cs, c_bs, c_rs, c_cs, (int)in, (int)out, pl);
+        return plan_gemm(true, A, B, C, batch, M, N, K, a_bs, a_rs, a_cs, b_bs, b_rs, b_cs, c_bs, c_rs, c_cs, (int)in, (int)out, ep, pl);
     };
     return tune_problem(make, reps, (hipStream_t)stream, best_us, nullptr);
 }
 
 tir_status tir_tune_conv2d(const void* x, const void* w, void* y, int64_t N, int64_t H, int64_t W, int64_t C, int64_t K,
                            int64_t R, int64_t S, int stride_h, int stride_w, int pad_h, int pad_w, int dil_h, int dil_w,
-                           int groups, tir_dtype in, tir_dtype out, int reps, double* best_us, tir_stream stream) {
+                           int groups, tir_dtype in, tir_dtype out, const tir_epilogue* ep, int reps, double* best_us,
+                           tir_stream stream) {
     auto make = [&](Plan* pl) {
-        return plan_conv(true, x, w, y, N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, groups, (int)in, (int)out, pl);
+        return plan_conv(true, x, w, y, N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, groups, (int)in, (int)out, ep, pl);
     };
     return tune_problem(make, reps, (hipStream_t)stream, best_us, nullptr);
 }

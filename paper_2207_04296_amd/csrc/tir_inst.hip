@@ -51,6 +51,11 @@ template <class C> hipError_t launch_cfg(const Params& p, hipStream_t stream) {
 #else
 #define V4 TIR_SKIP
 #endif
+#if TIR_UNIT == 5
+#define V5 TIR_DEFINE
+#else
+#define V5 TIR_SKIP
+#endif
 #include "tir_variants.def"
 
 }  // namespace tir

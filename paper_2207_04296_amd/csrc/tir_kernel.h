@@ -89,6 +89,54 @@ template <> struct OutTraits<DT_BF16> {
     }
 };
 
+template <> struct OutTraits<DT_I8> {
+    typedef signed char type;       // requantised int8 codes; produced by finish_value(), which needs the scale
+};
+
+// The fused consumer behind the tensorized block: bias add, ReLU, conversion to the output type.
+// For int8 output the int32 sum is scaled in binary32 and rounded to the nearest code, ties to even
+// (v_rndne_f32), then saturated.
+template <class E> __device__ __forceinline__ E consumer(E acc, E bias, int relu) {
+    E t = acc + bias;
+    if (relu) t = t < (E)0 ? (E)0 : t;
+    return t;
+}
+template <int OUT, class E> __device__ __forceinline__ typename OutTraits<OUT>::type finish_value(E t, float scale) {
+    if constexpr (OUT == DT_I8) {
+        float f = (float)t * scale;
+        f = __builtin_rintf(f);
+        f = f < -128.0f ? -128.0f : f;
+        f = f > 127.0f ? 127.0f : f;
+        return (signed char)(int)f;
+    } else {
+        return OutTraits<OUT>::cvt(t);
+    }
+}
+// One output value through the buffer descriptor rc (1, 2 or 4 bytes).
+template <class T> __device__ __forceinline__ void store_value(T v, __amdgpu_buffer_rsrc_t rc, int voff, int soff) {
+    if constexpr (sizeof(T) == 4) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), rc, voff, soff, TIR_STORE_AUX);
+    else if constexpr (sizeof(T) == 2) __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(unsigned short, v), rc, voff, soff, TIR_STORE_AUX);
+    else __builtin_amdgcn_raw_buffer_store_b8(__builtin_bit_cast(unsigned char, v), rc, voff, soff, TIR_STORE_AUX);
+}
+
+// Convert and store the 16 accumulator registers of one 32x32 block (register r is row
+// 8*(r/4) + r%4 of the lane's row group).  The plain operator sends its accumulators to the store
+// unit with at most a type conversion; the consumer's extra instructions only run when one is fused
+// (`fused` is uniform).
+template <int OUT, class ACC, class E>
+__device__ __forceinline__ void store_block(const ACC& a, bool fused, E bias, int relu, float scale,
+                                            __amdgpu_buffer_rsrc_t rc, int voff, int row_bytes) {
+    if (fused) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+            store_value(finish_value<OUT>(consumer((E)a[r], bias, relu), scale), rc, voff, (8 * (r >> 2) + (r & 3)) * row_bytes);
+    } else {
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+            store_value(finish_value<OUT>((E)a[r], scale), rc, voff, (8 * (r >> 2) + (r & 3)) * row_bytes);
+    }
+}
+
 // K-major LDS tile: [rows][ROWB bytes], 16-byte columns XOR-swizzled by the row so that the 16
 // rows one ds_read_b128 phase touches at a fixed logical column fall on all 64 banks exactly once
 // (ROWB 128: column ^ (row/2 mod 8); ROWB 64: column ^ (row/4 mod 4)).  The XOR is its own inverse,
@@ -135,6 +183,15 @@ __device__ __forceinline__ void load_to_lds(const i32x4& rsrc, const char* lds_b
         :
         : "s"(lds_addr), "v"(voffset), "s"(rsrc)
         : "memory", "m0");
+}
+
+// Kernel arguments are fetched lazily, a few at a time, each fetch an exposed scalar-memory latency
+// of several hundred cycles.  Naming the fields a kernel needs before its first copy in one asm
+// statement makes the compiler fetch them in one batch at the very start.
+__device__ __forceinline__ void prefetch_args(const Params& p) {
+    asm volatile("" ::"s"(p.A), "s"(p.B), "s"(p.C), "s"(p.bias), "s"(p.M), "s"(p.N), "s"(p.K), "s"(p.tiles_m), "s"(p.tiles_n),
+                 "s"(p.c_fast), "s"(p.relu), "s"(p.scale));
+    asm volatile("" ::"s"(p.a_bs), "s"(p.b_bs), "s"(p.c_bs), "s"(p.a_rs), "s"(p.b_rs), "s"(p.b_cs), "s"(p.c_rs), "s"(p.c_cs), "s"(p.bias_bs));
 }
 
 // Workgroup barrier that also publishes this wave's global->LDS copies (counted by vmcnt; all but
@@ -233,6 +290,22 @@ __device__ __forceinline__ void mfma_block(const uint4* af, const uint4* bf, acc
         for (int j = 0; j < C::NI; ++j) acc[i][j] = InTraits<C::DT>::mfma(af[i], bf[j], acc[i][j]);
 }
 
+// The lane's bias values (one per 32-column block of its wave tile), requested at kernel start: the
+// vector usually misses every cache, and a load in the epilogue would expose that whole latency.
+template <class C, class E>
+__device__ __forceinline__ void load_bias(const Params& p, long long bz, int n0, int wn, int lane, E (&bias_r)[C::NI]) {
+    // through a buffer descriptor that covers the tile's valid columns, or nothing at all without a
+    // bias: lanes outside it read 0 and no branch is needed
+    const int cols = p.N - n0 < C::BN ? p.N - n0 : C::BN;
+    const E* base = (const E*)p.bias + bz * p.bias_bs + n0;
+    const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, p.bias ? cols * 4 : 0, 0x00020000);
+#pragma unroll
+    for (int j = 0; j < C::NI; ++j) {
+        const int col = wn * C::TN + j * 32 + (lane & 31);
+        bias_r[j] = __builtin_bit_cast(E, __builtin_amdgcn_raw_buffer_load_b32(rb, col * 4, 0, 0));
+    }
+}
+
 // Fused epilogue: convert and store the accumulators (C is fully overwritten).
 // With a unit column stride the stores go through a buffer descriptor that covers exactly the valid
 // part of this workgroup's tile: rows past M fall outside it and are dropped by the hardware, columns
@@ -240,15 +313,22 @@ __device__ __forceinline__ void mfma_block(const uint4* af, const uint4* bf, acc
 // work.  Other C strides take the element-wise path.
 template <class C, class acc_t>
 __device__ __forceinline__ void store_tile(const Params& p, long long bz, int m0, int n0, int wm, int wn, int lane,
-                                           acc_t (&acc)[C::MI][C::NI]) {
+                                           acc_t (&acc)[C::MI][C::NI],
+                                           const typename std::conditional<std::is_same<acc_t, f32x16>::value, float, int>::type (&bias_r)[C::NI]) {
     typedef OutTraits<C::OUT> OT;
     typedef typename OT::type out_t;
+    typedef typename std::conditional<std::is_same<acc_t, f32x16>::value, float, int>::type acc_e;
     constexpr int OS = (int)sizeof(out_t);
     out_t* __restrict__ Cb = (out_t*)p.C + bz * p.c_bs;
     const int l31 = lane & 31, g = lane >> 5;
+    const int cols = p.N - n0 < C::BN ? p.N - n0 : C::BN;
+    const bool fused = p.bias != nullptr || p.relu != 0;      // uniform; int8 output alone only changes finish_value
+    // Loads and stores retire through one counter, in order: the wait for the bias values (requested
+    // at kernel start) must sit before the first store, or it would wait for stores as well.
+#pragma unroll
+    for (int j = 0; j < C::NI; ++j) asm volatile("" ::"v"(bias_r[j]));
     if (p.c_fast) {
         const int rows = p.M - m0 < C::BM ? p.M - m0 : C::BM;
-        const int cols = p.N - n0 < C::BN ? p.N - n0 : C::BN;
         const long long bytes = ((long long)(rows - 1) * p.c_rs + cols) * OS;
         const __amdgpu_buffer_rsrc_t rc = __builtin_amdgcn_make_buffer_rsrc(
             (void*)(Cb + (long long)m0 * p.c_rs + n0), 0, (int)(bytes > 0x7fffffffLL ? 0x7fffffffLL : bytes), 0x00020000);
@@ -260,13 +340,7 @@ __device__ __forceinline__ void store_tile(const Params& p, long long bz, int m0
                 const int col = wn * C::TN + j * 32 + l31;
                 const int row0 = wm * C::TM + i * 32 + 4 * g;
                 const unsigned voff = col < cols ? (unsigned)(row0 * row_bytes + col * OS) : kOutOfRange;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int soff = (8 * (r >> 2) + (r & 3)) * row_bytes;      // scalar
-                    const out_t v = OT::cvt(acc[i][j][r]);
-                    if constexpr (OS == 4) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), rc, (int)voff, soff, TIR_STORE_AUX);
-                    else __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(unsigned short, v), rc, (int)voff, soff, TIR_STORE_AUX);
-                }
+                store_block<C::OUT>(acc[i][j], fused, bias_r[j], p.relu, p.scale, rc, (int)voff, row_bytes);
             }
         }
         return;
@@ -276,10 +350,12 @@ __device__ __forceinline__ void store_tile(const Params& p, long long bz, int m0
 #pragma unroll
         for (int j = 0; j < C::NI; ++j) {
             const int col = n0 + wn * C::TN + j * 32 + l31;
+            const acc_e b = bias_r[j];
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int row = m0 + wm * C::TM + i * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
-                if (row < p.M && col < p.N) Cb[(long long)row * p.c_rs + (long long)col * p.c_cs] = OT::cvt(acc[i][j][r]);
+                if (row < p.M && col < p.N)
+                    Cb[(long long)row * p.c_rs + (long long)col * p.c_cs] = finish_value<C::OUT>(consumer(acc[i][j][r], b, p.relu), p.scale);
             }
         }
     }
@@ -308,6 +384,7 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
     static_assert(KSTEPS % 2 == 0, "fragment sets alternate per k-step and must line up per stage");
 
     __shared__ __attribute__((aligned(1024))) char smem[C::LDS_BYTES];
+    prefetch_args(p);
 
     // reduction group kgrp owns the stages s with s % KW == kgrp; inside the group, thread tid of SUB
     const int lane = threadIdx.x & 63;
@@ -490,6 +567,10 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;   // reduction init
 
+    typedef typename std::conditional<std::is_same<acc_t, f32x16>::value, float, int>::type acc_e;
+    acc_e bias_r[C::NI];
+    load_bias<C>(p, bz, n0, wn, lane, bias_r);
+
     uint4 af[2][C::MI], bf[2][C::NI];
 
     // One k-step: the MI*NI MFMAs on fragment set `set`, interleaved with `nside` units of side
@@ -583,7 +664,7 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
                     for (int e = 0; e < 4; ++e) acc[i][j][r4 * 4 + e] += v[e];
                 }
     }
-    store_tile<C>(p, bz, m0, n0, wm, wn, lane, acc);
+    store_tile<C>(p, bz, m0, n0, wm, wn, lane, acc, bias_r);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -727,6 +808,16 @@ __global__ void __launch_bounds__(512) conv_patch_kernel(const Params p) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;       // reduction init
 
+    // the lane's two bias values, requested now: in the epilogue the load's latency would be exposed
+    typedef typename std::conditional<std::is_same<acc_t, f32x16>::value, float, int>::type acc_e;
+    acc_e bias_r[2];
+    {
+        const acc_e* base = (const acc_e*)p.bias + (long long)grp * p.bias_bs + n0;
+        const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, p.bias ? ncols * 4 : 0, 0x00020000);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) bias_r[j] = __builtin_bit_cast(acc_e, __builtin_amdgcn_raw_buffer_load_b32(rb, (j * 32 + l31) * 4, 0, 0));
+    }
+
     // Fragment sets: k-step kk of every tap uses set kk, fetched two k-steps ahead (a k-step is only
     // four MFMAs long here, one k-step of lookahead would not cover the LDS latency).
     uint4 af[4][2], bf[4][2];
@@ -780,6 +871,9 @@ __global__ void __launch_bounds__(512) conv_patch_kernel(const Params p) {
 
     // ------------------------------------------------------------ fused epilogue (NHWC rows are output pixels)
     out_t* ybase = (out_t*)p.C + ((long long)img * PQ + m_first) * p.c_rs + (long long)grp * p.N + n0;
+    const bool fused = p.bias != nullptr || p.relu != 0;
+    // (loads and stores retire through one counter, in order: wait for the bias before the first store)
+    asm volatile("" ::"v"(bias_r[0]), "v"(bias_r[1]));
     const long long bytes = ((long long)(m_cnt - 1) * p.c_rs + ncols) * OS;
     const __amdgpu_buffer_rsrc_t rc = __builtin_amdgcn_make_buffer_rsrc((void*)ybase, 0, (int)bytes, 0x00020000);
     const int row_bytes = (int)p.c_rs * OS;
@@ -790,13 +884,7 @@ __global__ void __launch_bounds__(512) conv_patch_kernel(const Params p) {
             const int col = j * 32 + l31;
             const int row0 = cw * 64 + i * 32 + 4 * g;
             const unsigned voff = col < ncols ? (unsigned)(row0 * row_bytes + col * OS) : kOutOfRange;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int soff = (8 * (r >> 2) + (r & 3)) * row_bytes;
-                const out_t v = OT::cvt(acc[i][j][r]);
-                if constexpr (OS == 4) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), rc, (int)voff, soff, TIR_STORE_AUX);
-                else __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(unsigned short, v), rc, (int)voff, soff, TIR_STORE_AUX);
-            }
+            store_block<OUT>(acc[i][j], fused, bias_r[j], p.relu, p.scale, rc, (int)voff, row_bytes);
         }
     }
 }
@@ -911,6 +999,10 @@ __global__ void __launch_bounds__(C::THREADS) contract_staged_kernel(const Param
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;   // reduction init
 
+    typedef typename std::conditional<std::is_same<acc_t, f32x16>::value, float, int>::type acc_e;
+    acc_e bias_r[C::NI];
+    load_bias<C>(p, bz, n0, wn, lane, bias_r);
+
     const int nslab = (p.K + BK - 1) / BK;
     if (nslab > 0) {
         load_ab(0);
@@ -933,7 +1025,7 @@ __global__ void __launch_bounds__(C::THREADS) contract_staged_kernel(const Param
         }
     }
 
-    store_tile<C>(p, bz, m0, n0, wm, wn, lane, acc);
+    store_tile<C>(p, bz, m0, n0, wm, wn, lane, acc, bias_r);
 }
 
 }  // namespace tir

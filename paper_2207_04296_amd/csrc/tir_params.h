@@ -36,6 +36,11 @@ struct Params {
     int stride_h, stride_w, pad_h, pad_w, dil_h, dil_w;
     int PW;           // patch kernel: columns of the LDS-resident input patch
     int batch_imgs;   // patch kernel: images in x (for the descriptor)
+    // fused consumer: out = cvt(relu(acc + bias[column])); bias is fp32 (float inputs) or int32 (int8 inputs)
+    const void* bias;    // null: no bias
+    long long bias_bs;   // bias elements between consecutive grid.y slices (conv groups: channels per group; batches: 0)
+    int relu;
+    float scale;         // int8 output only: code = clamp(rint(float(t) * scale), -128, 127)
 };
 
 // Number of XCDs (L2 domains) workgroups are dealt to round-robin by the dispatcher.

@@ -96,7 +96,7 @@ class Workload:
     name: str
     kind: str
     dtype: str            # 'f16' | 'bf16' | 'i8'
-    out: str              # 'f32' | 'f16' | 'bf16' | 'i32'
+    out: str              # 'f32' | 'f16' | 'bf16' | 'i32' | 'i8' (requantised, needs ep_scale)
     dist: str
     seed: int
     # gemm / bmm: C[batch,M,N] = A[batch,M,K] . B[batch,K,N]; trans_b: B stored [batch,N,K]
@@ -117,7 +117,28 @@ class Workload:
     pad: tuple = (0, 0)
     dil: tuple = (1, 1)
     groups: int = 1
+    # fused consumer: bias per output column / channel, ReLU, requantisation scale (int8 output)
+    ep_bias: bool = False
+    ep_relu: bool = False
+    ep_scale: float = 0.0
     note: str = field(default="", compare=False)
+
+    @property
+    def fused(self) -> bool:
+        return self.ep_bias or self.ep_relu or self.ep_scale != 0.0
+
+    def out_cols(self) -> int:
+        return self.k if self.kind == "conv2d" else self.N
+
+    def bias_values(self):
+        """Seeded bias, one per output column: float32 N(0,1)*0.1 for float inputs, int32 multiples of 64
+        in [-8128, 8128] for int8 inputs; None without ep_bias."""
+        if not self.ep_bias:
+            return None
+        n = self.out_cols()
+        if self.dtype == "i8":
+            return int8_uniform(self.seed + 2, n).astype(np.int32) * np.int32(64)
+        return normal(self.seed + 2, n, 0.1).astype(np.float32)
 
     def out_hw(self):
         p = (self.h + 2 * self.pad[0] - self.dil[0] * (self.r - 1) - 1) // self.stride[0] + 1
@@ -138,12 +159,13 @@ class Workload:
     def min_bytes(self) -> float:
         """Compulsory traffic: each operand read once, the output written once."""
         isz = 1 if self.dtype == "i8" else 2
-        osz = {"f32": 4, "i32": 4, "f16": 2, "bf16": 2}[self.out]
+        osz = {"f32": 4, "i32": 4, "f16": 2, "bf16": 2, "i8": 1}[self.out]
+        extra = 4 * self.out_cols() if self.ep_bias else 0
         if self.kind == "conv2d":
             p, q = self.out_hw()
             return (isz * (self.n * self.h * self.w * self.c + self.k * self.r * self.s * (self.c // self.groups))
-                    + osz * self.n * p * q * self.k)
-        return isz * self.batch * (self.M * self.K + self.K * self.N) + osz * self.batch * self.M * self.N
+                    + osz * self.n * p * q * self.k + extra)
+        return isz * self.batch * (self.M * self.K + self.K * self.N) + osz * self.batch * self.M * self.N + extra
 
     def operands(self):
         """Raw-bit host operands (a, b) of this workload, seeded."""
@@ -177,4 +199,24 @@ def _cfgs():
     return {x.name: x for x in w}
 
 
+def _fused_cfgs():
+    """The same operator instances with a fused consumer (bias + ReLU, down-cast, int8 requantisation):
+    the output bytes, which dominate the attention matmuls and the int8 convolution, shrink."""
+    import dataclasses
+    base = _cfgs()
+    w = [
+        dataclasses.replace(base["c2a_conv56x64_f16"], name="c2a_conv56x64_f16_bias_relu", ep_bias=True, ep_relu=True),
+        dataclasses.replace(base["c3a_bmm_qkT_f16"], name="c3a_bmm_qkT_f16_out16", out="f16"),
+        dataclasses.replace(base["c3b_bmm_pv_f16"], name="c3b_bmm_pv_f16_out16", out="f16"),
+        dataclasses.replace(base["c4b_gemm_ffn_f16"], name="c4b_gemm_ffn_f16_bias_relu_out16", out="f16", ep_bias=True,
+                            ep_relu=True),
+        dataclasses.replace(base["c5a_gemm2048_i8"], name="c5a_gemm2048_i8_requant", out="i8", ep_bias=True,
+                            ep_scale=1.0 / 4000.0),
+        dataclasses.replace(base["c5b_conv_g8d2_i8"], name="c5b_conv_g8d2_i8_relu_requant", out="i8", ep_bias=True,
+                            ep_relu=True, ep_scale=1.0 / 1500.0),
+    ]
+    return {x.name: x for x in w}
+
+
 WORKLOADS = _cfgs()
+FUSED_WORKLOADS = _fused_cfgs()

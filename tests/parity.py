@@ -50,20 +50,26 @@ def run_gpu(wl, a_bits, b_bits, prefill=True):
         if c.dtype.is_floating_point:
             c.fill_(float("nan"))
         else:
-            c.fill_(-123456789)
-    B.run_workload(wl, a, b, c)
+            c.fill_(-77 if c.dtype == torch.int8 else -123456789)
+    B.run_workload(wl, a, b, c, B.bias_to_device(wl))
     torch.cuda.synchronize()
     return gpu_to_f64(c)
 
 
 def run_oracle(wl, a_bits, b_bits, oracle):
+    """(result, S) of the workload incl. its fused consumer; S is None for integer results."""
     if wl.kind == "conv2d":
-        return oracle.conv2d(wl.dtype, a_bits, b_bits, wl.stride, wl.pad, wl.dil, wl.groups)
-    b_rs, b_cs = (1, wl.K) if wl.trans_b else (wl.N, 1)
-    if wl.kind == "gemm":
-        return oracle.gemm(wl.dtype, a_bits, b_bits, wl.M, wl.N, wl.K, wl.K, 1, b_rs, b_cs)
-    return oracle.batch_matmul(wl.dtype, a_bits, b_bits, wl.batch, wl.M, wl.N, wl.K, wl.M * wl.K, wl.K, 1,
-                               wl.K * wl.N, b_rs, b_cs)
+        C, S = oracle.conv2d(wl.dtype, a_bits, b_bits, wl.stride, wl.pad, wl.dil, wl.groups)
+    else:
+        b_rs, b_cs = (1, wl.K) if wl.trans_b else (wl.N, 1)
+        if wl.kind == "gemm":
+            C, S = oracle.gemm(wl.dtype, a_bits, b_bits, wl.M, wl.N, wl.K, wl.K, 1, b_rs, b_cs)
+        else:
+            C, S = oracle.batch_matmul(wl.dtype, a_bits, b_bits, wl.batch, wl.M, wl.N, wl.K, wl.M * wl.K, wl.K, 1,
+                                       wl.K * wl.N, b_rs, b_cs)
+    if wl.fused:
+        C, S = oracle.epilogue(C, S, bias=wl.bias_values(), relu=wl.ep_relu, scale=wl.ep_scale)
+    return C, S
 
 
 def check_workload(wl, oracle, what=None):

@@ -174,10 +174,31 @@ def test_tuning_rejects_bad_arguments_before_touching_the_device():
     L = B.lib()
     us = ctypes.c_double(-1.0)
     # reps out of range, then an invalid problem: status codes, no launch
-    st = L.tir_tune_batch_matmul(FAKE, FAKE, FAKE, 1, 64, 64, 64, 0, 64, 1, 0, 64, 1, 0, 64, 1, 0, 3, 0, ctypes.byref(us), None)
+    st = L.tir_tune_batch_matmul(FAKE, FAKE, FAKE, 1, 64, 64, 64, 0, 64, 1, 0, 64, 1, 0, 64, 1, 0, 3, None, 0, ctypes.byref(us), None)
     assert st == B.TIR_ERR_INVALID_ARG and "reps" in B.last_error()
-    st = L.tir_tune_batch_matmul(FAKE, FAKE, FAKE, 1, -4, 64, 64, 0, 64, 1, 0, 64, 1, 0, 64, 1, 0, 3, 3, ctypes.byref(us), None)
+    st = L.tir_tune_batch_matmul(FAKE, FAKE, FAKE, 1, -4, 64, 64, 0, 64, 1, 0, 64, 1, 0, 64, 1, 0, 3, None, 3, ctypes.byref(us), None)
     assert st == B.TIR_ERR_INVALID_ARG
     # zero-sized problems are a successful no-op
-    st = L.tir_tune_batch_matmul(FAKE, FAKE, FAKE, 1, 0, 64, 64, 0, 64, 1, 0, 64, 1, 0, 64, 1, 0, 3, 3, ctypes.byref(us), None)
+    st = L.tir_tune_batch_matmul(FAKE, FAKE, FAKE, 1, 0, 64, 64, 0, 64, 1, 0, 64, 1, 0, 64, 1, 0, 3, None, 3, ctypes.byref(us), None)
     assert st == B.TIR_OK and us.value == 0.0 and B.tir_tune_count() == 0
+
+
+def test_fused_entry_points_validate_the_epilogue_on_the_host():
+    """Epilogue errors are status codes before any launch: int8 output only through the fused entry
+    points and only with a finite positive scale; the bias pointer must be 4-byte aligned."""
+    import ctypes
+    L = B.lib()
+    def gemm_fused(out, ep):
+        return L.tir_gemm_fused(FAKE, FAKE, FAKE, 64, 64, 64, 64, 1, 64, 1, 64, 1, B.TIR_I8, out,
+                                None if ep is None else ctypes.byref(ep), None)
+    assert gemm_fused(B.TIR_I8, None) == B.TIR_ERR_UNSUPPORTED
+    assert gemm_fused(B.TIR_I8, B.Epilogue(None, 0, 0.0)) == B.TIR_ERR_INVALID_ARG
+    assert gemm_fused(B.TIR_I8, B.Epilogue(None, 0, float("nan"))) == B.TIR_ERR_INVALID_ARG
+    assert gemm_fused(B.TIR_I32, B.Epilogue(FAKE + 2, 0, 0.0)) == B.TIR_ERR_ALIGNMENT
+    assert gemm_fused(B.TIR_F16, B.Epilogue(None, 1, 1.0)) == B.TIR_ERR_UNSUPPORTED        # (I8, F16) is no pair
+    assert B.tir_gemm_status(FAKE, FAKE, FAKE, 64, 64, 64, 64, 1, 64, 1, 64, 1, "i8", B.TIR_I8) == B.TIR_ERR_UNSUPPORTED
+    # zero-sized fused calls are no-ops as well
+    assert L.tir_gemm_fused(FAKE, FAKE, FAKE, 0, 64, 64, 64, 1, 64, 1, 64, 1, B.TIR_I8, B.TIR_I8,
+                            ctypes.byref(B.Epilogue(None, 1, 0.5)), None) == B.TIR_OK
+    # the variant query knows the requantising kernels
+    assert B.tir_gemm_variant(1, 512, 512, 512, 512, 1, 512, 1, 512, 1, "i8", B.TIR_I8).startswith("i8_i8_")

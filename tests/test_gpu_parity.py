@@ -43,6 +43,16 @@ def test_config_full_size(B, oracle, name):
     _say(f"{name} max err/tol {ratio:.3g}")
 
 
+@pytest.mark.parametrize("name", list(I.FUSED_WORKLOADS))
+def test_config_full_size_with_fused_consumer(B, oracle, name):
+    """The benchmark operators with a consumer fused behind the tensorized block: bias + ReLU, down-cast
+    to fp16, int8 requantisation (codes must match the oracle exactly)."""
+    wl = I.FUSED_WORKLOADS[name]
+    _say(f"{name} variant auto")
+    ratio = PT.check_workload(wl, oracle)
+    _say(f"{name} max err/tol {ratio:.3g}")
+
+
 @pytest.mark.parametrize("name", ["c4a_gemm4096_f16", "c4a_gemm4096_bf16"])
 def test_config_4096_sampled_rows_and_columns(B, oracle, name):
     wl = I.WORKLOADS[name]
@@ -354,3 +364,66 @@ def test_tuning_measures_records_and_keeps_results_correct(B, oracle, tmp_path):
             assert PT.variant_name(B, wl) == chosen[wl.name]
     finally:
         B.tir_tune_clear()
+
+
+# ------------------------------------------------------------------------------ fused consumers, small and ragged
+FUSED_SMALL = [
+    # kind, dtype, out, bias, relu, scale, shape kwargs
+    ("gemm", "f16", "f32", True, True, 0.0, dict(M=300, N=264, K=200)),
+    ("gemm", "f16", "f16", True, False, 0.0, dict(M=129, N=136, K=72)),
+    ("gemm", "bf16", "f32", False, True, 0.0, dict(M=70, N=40, K=64)),
+    ("gemm", "f16", "f32", True, True, 0.0, dict(M=33, N=27, K=19)),                       # element-wise kernel
+    ("gemm", "i8", "i32", True, True, 0.0, dict(M=200, N=144, K=160)),
+    ("gemm", "i8", "i8", True, False, 1.0 / 900.0, dict(M=200, N=144, K=160)),
+    ("gemm", "i8", "i8", False, True, 1.0 / 64.0, dict(M=65, N=33, K=31)),                  # element-wise kernel, saturating
+    ("bmm", "f16", "f16", True, True, 0.0, dict(batch=5, M=130, N=72, K=64, trans_b=True)),
+    ("bmm", "i8", "i8", True, True, 1.0 / 500.0, dict(batch=3, M=100, N=48, K=96)),
+    ("conv2d", "f16", "f16", True, True, 0.0, dict(n=2, h=20, w=23, c=64, k=64, r=3, s=3, pad=(1, 1))),          # patch kernel
+    ("conv2d", "f16", "f32", True, False, 0.0, dict(n=2, h=13, w=11, c=16, k=40, r=3, s=3, stride=(2, 1), pad=(1, 2))),
+    ("conv2d", "i8", "i8", True, True, 1.0 / 700.0, dict(n=2, h=14, w=14, c=64, k=48, r=3, s=3, pad=(1, 1), groups=2)),
+    ("conv2d", "i8", "i8", True, False, 1.0 / 300.0, dict(n=1, h=20, w=20, c=256, k=96, r=3, s=3, pad=(2, 2), dil=(2, 2), groups=2)),  # patch kernel, groups
+    ("conv2d", "bf16", "bf16", True, True, 0.0, dict(n=1, h=9, w=9, c=6, k=10, r=3, s=3, pad=(1, 1), groups=2)),   # element-wise conv
+]
+
+
+@pytest.mark.parametrize("case", FUSED_SMALL, ids=lambda c: f"{c[0]}-{c[1]}-{c[2]}-b{int(c[3])}r{int(c[4])}s{c[5]:.3g}")
+def test_fused_consumers_on_small_ragged_problems(B, oracle, case):
+    kind, dtype, out, bias, relu, scale, kw = case
+    dist = "i" if dtype == "i8" else ("n0.1" if kind == "conv2d" else "u")
+    wl = I.Workload(f"fused_{kind}_{dtype}_{out}", kind, dtype, out, dist, 9700 + len(str(kw)), ep_bias=bias, ep_relu=relu,
+                    ep_scale=scale, **kw)
+    _say(f"{wl.name} {kw} -> {PT.variant_name(B, wl)}")
+    a_bits, b_bits = wl.operands()
+    ref, S = PT.run_oracle(wl, a_bits, b_bits, oracle)
+    got = PT.run_gpu(wl, a_bits, b_bits)
+    if out == "bf16":
+        # rounding to bfloat16 alone is up to 2^-9 |value|: the bar applies where that is inside it
+        easy = np.abs(ref) * 2.0 ** -8 <= PT.RTOL_S * S
+        assert easy.mean() > 0.2
+        PT.assert_close(np.where(easy, got, ref), ref, S, wl.name)
+        assert np.all(np.abs(got - ref) <= PT.RTOL_S * S + PT.ATOL + np.abs(ref) * 2.0 ** -8)
+    else:
+        PT.assert_close(got, ref, S, wl.name)
+    if out == "i8":
+        assert got.min() >= -128 and got.max() <= 127
+        if scale > 1.0 / 100.0:
+            assert got.max() == 127            # the saturating case saturates
+
+
+def test_fused_consumer_argument_checks(B):
+    import torch
+    a = torch.zeros(64 * 64, dtype=torch.int8, device="cuda")
+    c8 = torch.zeros(64 * 64, dtype=torch.int8, device="cuda")
+    c32 = torch.zeros(64 * 64, dtype=torch.int32, device="cuda")
+    bias = torch.zeros(65, dtype=torch.int32, device="cuda")
+    def call(out, cbuf, ep):
+        return B.lib().tir_gemm_fused(a.data_ptr(), a.data_ptr(), cbuf.data_ptr(), 64, 64, 64, 64, 1, 64, 1, 64, 1, B.TIR_I8,
+                                      B.DTYPE_CODES.get(out, 2), None if ep is None else __import__("ctypes").byref(ep), None)
+    assert call("i8out", c8, None) == B.TIR_ERR_UNSUPPORTED                       # int8 output without an epilogue
+    assert call("i8out", c8, B.Epilogue(None, 0, 0.0)) == B.TIR_ERR_INVALID_ARG   # ... without a scale
+    assert call("i8out", c8, B.Epilogue(None, 0, float("inf"))) == B.TIR_ERR_INVALID_ARG
+    assert call("i8out", c8, B.Epilogue(None, 0, -1.0)) == B.TIR_ERR_INVALID_ARG
+    assert call("i32", c32, B.Epilogue(bias.data_ptr() + 2, 0, 0.0)) == B.TIR_ERR_ALIGNMENT
+    assert call("i8out", c8, B.Epilogue(bias.data_ptr(), 1, 0.5)) == B.TIR_OK
+    assert B.tir_gemm_status(a, a, c8, 64, 64, 64, 64, 1, 64, 1, 64, 1, "i8", 2) == B.TIR_ERR_UNSUPPORTED   # plain entry point
+    torch.cuda.synchronize()
