@@ -35,8 +35,8 @@ CACHE_BYTES = 256e6 + 8 * 4e6     # memory-side cache + the eight L2s
 # HBM bytes per launch of the headline kernel from rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled
 # by the same counters on a copy kernel of known size; see profiles/.  None until measured.
 MEASURED_TRAFFIC_BYTES = {
-    "c2a_conv56x64_f16": 11132600 + 6422528,     # FETCH_SIZE 5437.8 KiB x 1.9993, WRITE_SIZE 6272 KiB x 1.0
-    "c4a_gemm4096_f16": 201363000 + 67108864,    # FETCH_SIZE 98357 KiB x 1.9993, WRITE_SIZE 65536 KiB x 1.0
+    "c2a_conv56x64_f16": 11182900 + 6422528,     # FETCH_SIZE 5462.3 KiB x 1.9993, WRITE_SIZE 6272 KiB x 1.0
+    "c4a_gemm4096_f16": 201415700 + 67108864,    # FETCH_SIZE 98382 KiB x 1.9993, WRITE_SIZE 65536 KiB x 1.0
 }
 
 
@@ -53,7 +53,7 @@ def parse():
     ap.add_argument("--no-tune", action="store_true",
                     help="use the built-in scoring rule instead of measuring the variants first (tir_tune_*)")
     ap.add_argument("--profile-run", action="store_true",
-                    help="only the headline timed region (for rocprofv3): no hot rerun, operator table, probe or oracle")
+                    help="only the headline timed region (for rocprofv3): no tuning trials, hot rerun, operator table, probe or oracle")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="instead of the workload, run 8 device-to-device copies of 64 MiB (a plain copy kernel of "
                          "known size, to scale the FETCH_SIZE / WRITE_SIZE counters)")
@@ -180,7 +180,7 @@ def main():
                                                "dispatches": 8}}))
         return
     if args.profile_run:
-        args.no_operators = args.no_cpu_baseline = True
+        args.no_operators = args.no_cpu_baseline = args.no_tune = True
     wl = I.WORKLOADS[args.workload]
 
     per_set = wl.min_bytes()
