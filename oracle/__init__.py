@@ -54,6 +54,7 @@ def _load():
         lib.oracle_epilogue_float.argtypes = [dp, dp, i64, i64, ctypes.POINTER(ctypes.c_float), ctypes.c_int]
         lib.oracle_epilogue_int.argtypes = [ctypes.POINTER(ctypes.c_int64), i64, i64, ctypes.POINTER(ctypes.c_int32),
                                             ctypes.c_int, ctypes.c_int, ctypes.c_float]
+        lib.oracle_attention.argtypes = [ctypes.c_int, vp, vp, vp] + [i64] * 5 + [ctypes.c_double, dp, dp]
         lib.oracle_set_threads.argtypes = [ctypes.c_int]
         lib.oracle_get_threads.restype = ctypes.c_int
         _lib = lib
@@ -199,3 +200,24 @@ def epilogue(C: np.ndarray, S, bias=None, relu: bool = False, scale: float = 0.0
     if rc:
         raise RuntimeError(f"oracle_epilogue_int failed with {rc} (sum beyond int32, or scale not finite and positive)")
     return C2, None
+
+
+def attention(dtype: str, Q: np.ndarray, K: np.ndarray, V: np.ndarray, scale: float, want_T: bool = True):
+    """softmax(scale * Q K^T) V per batch.  Q: bits [batch, M, d], K: [batch, N, d], V: [batch, N, dv].
+    Returns (O [batch, M, dv] float64, T or None) with T = sum_j P |V|."""
+    if dtype not in ("f16", "bf16"):
+        raise ValueError("oracle.attention: f16 or bf16 inputs")
+    Q = np.ascontiguousarray(_check_bits(Q, dtype))
+    K = np.ascontiguousarray(_check_bits(K, dtype))
+    V = np.ascontiguousarray(_check_bits(V, dtype))
+    batch, M, d = Q.shape
+    _, N, dv = V.shape
+    if K.shape != (batch, N, d) or V.shape[0] != batch or N < 1:
+        raise ValueError("oracle.attention: inconsistent shapes")
+    O = np.empty((batch, M, dv), dtype=np.float64)
+    T = np.empty((batch, M, dv), dtype=np.float64) if want_T else None
+    rc = _load().oracle_attention(_code(dtype), _ptr(Q), _ptr(K), _ptr(V), batch, M, N, d, dv, float(scale), _ptr(O),
+                                  _ptr(T) if T is not None else None)
+    if rc:
+        raise RuntimeError(f"oracle_attention failed with {rc}")
+    return O, T

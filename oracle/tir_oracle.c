@@ -31,7 +31,9 @@
  * explicit im2col + matmul; 1x1 conv == GEMM; linearity; delta and all-ones closed forms; groups
  * == independent convs; fp64 library convolution (torch CPU) on strided/dilated/padded/grouped
  * cases; closed forms C = K and C = K*i*j; the fused consumers against hand-worked values (ties,
- * saturation, signs) and against the same arithmetic carried out in numpy's float32 / int64.
+ * saturation, signs) and against the same arithmetic carried out in numpy's float32 / int64; the
+ * attention head against closed forms (uniform attention, one dominant key, a single key), key
+ * permutation invariance, shift invariance of the softmax, and scipy's softmax between two matmuls.
  * No function in this file is "parity unpinned".
  */
 #include <math.h>
@@ -310,4 +312,56 @@ int oracle_epilogue_int(int64_t* C, int64_t rows, int64_t N, const int32_t* bias
             C[i * N + j] = t;
         }
     return ORACLE_OK;
+}
+
+/*
+ * One attention head per batch: two contractions (Eq. 1 twice) with the row-wise softmax between
+ * them computed in place - the two tensorized blocks of the paper's batched-matmul workload share one
+ * tile instead of meeting in memory (sec. 2 and 3.2: blocks isolate sub-problems, which does not
+ * prevent cooperation across blocks).  The softmax itself is the textbook definition, not the paper's.
+ *
+ *   S[b,i,j] = scale * sum_c Q[b,i,c] * K[b,j,c]          (K stored [N][d]: "Q . K^T")
+ *   P[b,i,j] = exp(S[b,i,j] - max_j S[b,i,:]) / sum_j exp(S[b,i,j] - max_j S[b,i,:])
+ *   O[b,i,e] = sum_j P[b,i,j] * V[b,j,e]
+ *
+ * Q: [batch][M][d], K: [batch][N][d], V: [batch][N][dv], dense, raw binary16 / bfloat16 bits.
+ * Everything in fp64.  T[b,i,e] = sum_j P[b,i,j] * |V[b,j,e]| is the side output the parity bound is
+ * expressed in (the probabilities are where the device rounds to 16 bits before the second product).
+ * N must be >= 1.
+ */
+int oracle_attention(int dtype, const void* Q, const void* K, const void* V, int64_t batch, int64_t M, int64_t N,
+                     int64_t d, int64_t dv, double scale, double* O, double* T) {
+    if (dtype != ORACLE_F16 && dtype != ORACLE_BF16) return ORACLE_BAD_ARG;
+    if (batch < 0 || M < 0 || N < 1 || d < 0 || dv < 0 || !O) return ORACLE_BAD_ARG;
+    int failed = 0;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(static) num_threads(oracle_get_threads())
+#endif
+    for (int64_t bi = 0; bi < batch * M; ++bi) {
+        const int64_t b = bi / M, i = bi % M;
+        double* s = (double*)malloc((size_t)N * sizeof(double));
+        if (!s) { failed = 1; continue; }
+        double mx = 0.0;
+        for (int64_t j = 0; j < N; ++j) {
+            double acc = 0.0;
+            for (int64_t c = 0; c < d; ++c)
+                acc += load_float(dtype, Q, (b * M + i) * d + c) * load_float(dtype, K, (b * N + j) * d + c);
+            s[j] = scale * acc;
+            if (j == 0 || s[j] > mx) mx = s[j];
+        }
+        double denom = 0.0;
+        for (int64_t j = 0; j < N; ++j) { s[j] = exp(s[j] - mx); denom += s[j]; }
+        for (int64_t e = 0; e < dv; ++e) {
+            double o = 0.0, t = 0.0;
+            for (int64_t j = 0; j < N; ++j) {
+                const double p = s[j] / denom, v = load_float(dtype, V, (b * N + j) * dv + e);
+                o += p * v;
+                t += p * fabs(v);
+            }
+            O[(b * M + i) * dv + e] = o;
+            if (T) T[(b * M + i) * dv + e] = t;
+        }
+        free(s);
+    }
+    return failed ? ORACLE_NO_MEMORY : ORACLE_OK;
 }

@@ -434,3 +434,74 @@ def test_epilogue_int_matches_numpy_float32(oracle, scale):
         want = np.clip(np.rint(f), -128, 127).astype(np.int64)
         assert np.array_equal(got, want)
         assert got.min() == (-128 if not relu else 0) and got.max() == 127      # both regimes were exercised
+
+
+# ------------------------------------------------------------------------------ attention head
+def _f16(v):
+    return I.to_f16_bits(np.asarray(v, dtype=np.float64))
+
+
+def _dec16(bits):
+    return bits.view(np.float16).astype(np.float64)
+
+
+def test_attention_closed_forms(oracle):
+    rng = np.random.default_rng(42)
+    b, M, N, d, dv = 2, 5, 7, 8, 6
+    V = _f16(rng.uniform(-1, 1, (b, N, dv)))
+    K = _f16(rng.uniform(-1, 1, (b, N, d)))
+    # Q = 0: every score is 0, the probabilities are uniform, the output is the mean of V's rows
+    O, T = oracle.attention("f16", _f16(np.zeros((b, M, d))), K, V, 0.37)
+    assert np.allclose(O, np.broadcast_to(_dec16(V).mean(axis=1, keepdims=True), O.shape), rtol=0, atol=1e-15)
+    assert np.allclose(T, np.broadcast_to(np.abs(_dec16(V)).mean(axis=1, keepdims=True), T.shape), rtol=0, atol=1e-15)
+    # a single key: the output is that key's value row, whatever the scores
+    O1, _ = oracle.attention("f16", _f16(rng.uniform(-1, 1, (b, M, d))), K[:, :1], V[:, :1], 3.0)
+    assert np.array_equal(O1, np.broadcast_to(_dec16(V[:, :1]), O1.shape))
+    # one dominant key: queries equal to key 3 times a large scale pick value row 3
+    Kd = np.zeros((1, N, d)); Kd[0, np.arange(N), np.arange(N)] = 1.0      # orthonormal keys
+    Qd = np.zeros((1, 2, d)); Qd[0, 0, 3] = 1.0; Qd[0, 1, 5] = 1.0
+    Od, _ = oracle.attention("f16", _f16(Qd), _f16(Kd), V[:1], 2000.0)
+    assert np.allclose(Od[0, 0], _dec16(V)[0, 3], rtol=0, atol=1e-300) and np.allclose(Od[0, 1], _dec16(V)[0, 5], rtol=0, atol=1e-300)
+    # two keys, scores 0 and ln 3 apart: probabilities 1/4 and 3/4
+    K2 = np.zeros((1, 2, 2)); K2[0, 1, 0] = 1.0
+    Q2 = np.zeros((1, 1, 2)); Q2[0, 0, 0] = 1.0
+    V2 = np.array([[[8.0], [-4.0]]])
+    O2, T2 = oracle.attention("f16", _f16(Q2), _f16(K2), _f16(V2), float(np.log(3.0)))
+    assert abs(O2[0, 0, 0] - (0.25 * 8.0 + 0.75 * -4.0)) < 1e-14 and abs(T2[0, 0, 0] - (0.25 * 8.0 + 0.75 * 4.0)) < 1e-14
+
+
+def test_attention_invariances(oracle):
+    rng = np.random.default_rng(7)
+    b, M, N, d, dv = 3, 9, 11, 16, 5
+    Q = _f16(rng.uniform(-1, 1, (b, M, d))); K = _f16(rng.uniform(-1, 1, (b, N, d))); V = _f16(rng.uniform(-1, 1, (b, N, dv)))
+    O, T = oracle.attention("f16", Q, K, V, 0.25)
+    # the keys are a set: permuting keys and values together changes nothing (up to fp64 summation order)
+    perm = rng.permutation(N)
+    Op, Tp = oracle.attention("f16", Q, K[:, perm], V[:, perm], 0.25)
+    assert np.allclose(O, Op, rtol=0, atol=1e-14) and np.allclose(T, Tp, rtol=0, atol=1e-14)
+    # batches and query rows are independent
+    O1, _ = oracle.attention("f16", Q[1:2, 2:5], K[1:2], V[1:2], 0.25)
+    assert np.array_equal(O1[0], O[1, 2:5])
+    # the output is a convex combination of value rows: inside their range, and T >= |O|
+    vdec = _dec16(V)
+    assert np.all(O <= vdec.max(axis=1, keepdims=True) + 1e-15) and np.all(O >= vdec.min(axis=1, keepdims=True) - 1e-15)
+    assert np.all(T + 1e-15 >= np.abs(O))
+    # scale 0 is uniform attention again
+    O0, _ = oracle.attention("f16", Q, K, V, 0.0)
+    assert np.allclose(O0, np.broadcast_to(vdec.mean(axis=1, keepdims=True), O0.shape), rtol=0, atol=1e-15)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_attention_matches_library_softmax_between_matmuls(oracle, dtype):
+    """scipy's softmax between two numpy matmuls in fp64 (library routines, a different arrangement of
+    the same definition), on shapes like one BERT head and on ragged ones."""
+    from scipy.special import softmax
+    for (b, M, N, d, dv, scale, seed) in [(2, 128, 128, 64, 64, 0.125, 1), (3, 17, 29, 24, 40, 0.3, 2), (1, 1, 300, 8, 8, 1.7, 3)]:
+        Q = I.make_tensor(dtype, "u", 100 + seed, (b, M, d)); K = I.make_tensor(dtype, "u", 200 + seed, (b, N, d))
+        V = I.make_tensor(dtype, "u", 300 + seed, (b, N, dv))
+        q, k, v = oracle.decode(dtype, Q), oracle.decode(dtype, K), oracle.decode(dtype, V)
+        P = softmax(scale * np.einsum("bic,bjc->bij", q, k), axis=-1)
+        O, T = oracle.attention(dtype, Q, K, V, scale)
+        assert np.allclose(O, P @ v, rtol=0, atol=1e-13)
+        assert np.allclose(T, P @ np.abs(v), rtol=0, atol=1e-13)
+        assert np.allclose(P.sum(axis=-1), 1.0, rtol=0, atol=1e-14)
