@@ -132,6 +132,42 @@ def mfma_ceiling(torch, B):
     return out
 
 
+def attention_row(torch, B, I):
+    """The two attention matmuls of configs[2] (QK^T, then PV) as ONE kernel with the softmax between them:
+    192 heads of 128 x 128 x 64, fp16 in and out.  FLOPs count both matmuls; bytes Q, K, V and O once."""
+    batch, M, N, d = 192, 128, 128, 64
+    q = B.to_device(I.make_tensor("f16", "u", 3000, (batch, M, d)), "f16")
+    k = B.to_device(I.make_tensor("f16", "u", 3001, (batch, N, d)), "f16")
+    v = B.to_device(I.make_tensor("f16", "u", 3101, (batch, N, d)), "f16")
+    o = B.empty_out((batch, M, d), "f16")
+    stream = torch.cuda.Stream()
+    steps = 200
+    with torch.cuda.stream(stream):
+        for _ in range(5):
+            B.tir_attention(q, k, v, o, batch, M, N, d, 0.125, "f16", "f16", stream=stream)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            for _ in range(steps):
+                B.tir_attention(q, k, v, o, batch, M, N, d, 0.125, "f16", "f16", stream=stream)
+        graph.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        graph.replay()
+        e1.record(stream)
+        torch.cuda.synchronize()
+    sec = e0.elapsed_time(e1) * 1e-3 / steps
+    flops = 2.0 * batch * M * N * d * 2
+    nbytes = 2.0 * batch * (M * d + 2 * N * d + M * d)
+    tf = flops / sec / 1e12
+    return {"workload": "c3_attention_f16 (QK^T, softmax, PV in one kernel)", "variant": "attention_kernel<f16,f16,64>",
+            "out": "f16", "fused": "softmax", "us": round(sec * 1e6, 3), "tflops": round(tf, 2),
+            "frac_mfma_peak": round(tf / PEAK_TFLOPS["f16"], 4),
+            "frac_attainable": round(tf / min(PEAK_TFLOPS["f16"], flops / nbytes * HBM_GBS / 1e3), 4),
+            "gbs": round(nbytes / sec / 1e9, 1), "cache": "hot"}
+
+
 def cpu_baseline(wl):
     """The oracle, as it stands, on this machine's host cores; whole workload, repeated for ~seconds."""
     import oracle
@@ -220,6 +256,7 @@ def main():
                               "frac_attainable": round(tf / attain, 4),
                               "gbs": round(o.min_bytes() * k / e_ / 1e9, 1), "cache": "hot"})
             del s
+        operators.append(attention_row(torch, B, I))
 
     out = {
         "metric": "TFLOP/s and % of MI355X MFMA peak per operator (fp16 GEMM, conv2d)",

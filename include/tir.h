@@ -115,6 +115,22 @@ tir_status tir_conv2d_fused(const void* x, const void* w, void* y, int64_t N, in
                             int dil_h, int dil_w, int groups, tir_dtype in, tir_dtype out,
                             const tir_epilogue* ep, tir_stream stream);
 
+/*
+ * One attention head per batch, both contractions and the softmax between them in one kernel (the
+ * two tensorized blocks of the batched-matmul workload share a tile; sec. 2 / 3.2 of the paper on blocks
+ * as isolated sub-problems that still cooperate; the softmax is the textbook definition):
+ *     S[b,i,j] = scale * sum_c Q[b,i,c] * K[b,j,c]
+ *     P[b,i,:] = softmax over j of S[b,i,:]
+ *     O[b,i,e] = sum_j P[b,i,j] * V[b,j,e]
+ * Q: [batch][M][d], K: [batch][N][d], V: [batch][N][d], O: [batch][M][d], all dense, 16-byte aligned
+ * device pointers.  d must be 64 or 128 (TIR_ERR_UNSUPPORTED otherwise).  in = F16 or BF16; out = the
+ * same type or F32.  Scores and the softmax are fp32; the probabilities are rounded to the input type
+ * before the second product, which accumulates in fp32.  N = 0 is an error (no keys), M = 0 or
+ * batch = 0 a no-op.  scale must be finite.
+ */
+tir_status tir_attention(const void* Q, const void* K, const void* V, void* O, int64_t batch, int64_t M, int64_t N,
+                         int64_t d, float scale, tir_dtype in, tir_dtype out, tir_stream stream);
+
 /* Message for the calling thread's last failed call ("" if none).  Never NULL; valid until the
  * thread's next failing call. */
 const char* tir_last_error(void);

@@ -20,7 +20,7 @@ EXPORTS = ["tir_gemm", "tir_batch_matmul", "tir_conv2d", "tir_last_error", "tir_
            "tir_conv2d_variant", "tir_debug_force_tile", "tir_debug_force_variant", "tir_debug_variant_count",
            "tir_debug_variant_name", "tir_debug_tile_of_block", "tir_probe_mfma_rate", "tir_version",
            "tir_tune_batch_matmul", "tir_tune_conv2d", "tir_tune_count", "tir_tune_clear", "tir_tune_save",
-           "tir_tune_load", "tir_gemm_fused", "tir_batch_matmul_fused", "tir_conv2d_fused"]
+           "tir_tune_load", "tir_gemm_fused", "tir_batch_matmul_fused", "tir_conv2d_fused", "tir_attention"]
 
 
 class Epilogue(ctypes.Structure):
@@ -89,6 +89,8 @@ def lib() -> ctypes.CDLL:
     L.tir_batch_matmul_fused.restype = ci
     L.tir_conv2d_fused.argtypes = [vp, vp, vp] + [i64] * 7 + [ci] * 7 + [ci, ci, pe, vp]
     L.tir_conv2d_fused.restype = ci
+    L.tir_attention.argtypes = [vp, vp, vp, vp] + [i64] * 4 + [ctypes.c_float, ci, ci, vp]
+    L.tir_attention.restype = ci
     L.tir_tune_batch_matmul.argtypes = [vp, vp, vp] + [i64] * 13 + [ci, ci, pe, ci, pd, vp]
     L.tir_tune_batch_matmul.restype = ci
     L.tir_tune_conv2d.argtypes = [vp, vp, vp] + [i64] * 7 + [ci] * 7 + [ci, ci, pe, ci, pd, vp]
@@ -233,6 +235,16 @@ def tir_conv2d_fused(x, w, y, N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pa
     _check(lib().tir_conv2d_fused(_ptr(x), _ptr(w), _ptr(y), N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w,
                                   dil_h, dil_w, groups, _code(in_dtype), _code(out_dtype), _ep_arg(ep),
                                   _stream(stream)))
+
+
+def tir_attention_status(Q, K, V, O, batch, M, N, d, scale, in_dtype, out_dtype, stream=0) -> int:
+    return lib().tir_attention(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), batch, M, N, d, float(scale), _code(in_dtype),
+                               _code(out_dtype), stream)
+
+
+def tir_attention(Q, K, V, O, batch, M, N, d, scale, in_dtype, out_dtype, stream=None) -> None:
+    """O[b] = softmax(scale * Q[b] K[b]^T) V[b]; Q [batch, M, d], K and V [batch, N, d], d in (64, 128)."""
+    _check(tir_attention_status(Q, K, V, O, batch, M, N, d, scale, in_dtype, out_dtype, _stream(stream)))
 
 
 def tir_tune_batch_matmul(A, B, C, batch, M, N, K, a_bs, a_rs, a_cs, b_bs, b_rs, b_cs, c_bs, c_rs, c_cs,

@@ -52,7 +52,8 @@ def build(verbose: bool = True, jobs: int | None = None, defines=(), lib: Path =
     (extra -D flags, another output name) without touching the product library."""
     OBJ.mkdir(exist_ok=True)
     extra = [f"-D{d}" for d in defines]
-    jobs_list = [(CSRC / "tir_api.hip", OBJ / f"tir_api{tag}.o", extra)]
+    jobs_list = [(CSRC / "tir_api.hip", OBJ / f"tir_api{tag}.o", extra),
+                 (CSRC / "tir_attn.hip", OBJ / f"tir_attn{tag}.o", extra)]
     for u in range(N_UNITS):
         jobs_list.append((CSRC / "tir_inst.hip", OBJ / f"tir_inst{u}{tag}.o", [f"-DTIR_UNIT={u}"] + extra))
     with ThreadPoolExecutor(max_workers=jobs or min(8, os.cpu_count() or 1)) as ex:

@@ -12,6 +12,7 @@
 
 #include "tir.h"
 #include "tir_launch.h"
+#include "tir_attention.h"
 
 namespace tir {
 
@@ -620,6 +621,31 @@ tir_status tir_tune_load(const char* path) {
             }
     }
     fclose(f);
+    return TIR_OK;
+}
+
+tir_status tir_attention(const void* Q, const void* K, const void* V, void* O, int64_t batch, int64_t M, int64_t N,
+                         int64_t d, float scale, tir_dtype in, tir_dtype out, tir_stream stream) {
+    if ((int)in < 0 || (int)in > TIR_I32 || (int)out < 0 || (int)out > TIR_I32) return fail(TIR_ERR_INVALID_ARG, "unknown dtype code (in=%d out=%d)", (int)in, (int)out);
+    if (!((in == TIR_F16 && (out == TIR_F16 || out == TIR_F32)) || (in == TIR_BF16 && (out == TIR_BF16 || out == TIR_F32))))
+        return fail(TIR_ERR_UNSUPPORTED, "attention: unsupported (in, out) dtype pair (%d, %d)", (int)in, (int)out);
+    if (batch < 0 || M < 0 || N < 0 || d < 0) return fail(TIR_ERR_INVALID_ARG, "negative extent (batch=%lld M=%lld N=%lld d=%lld)", (long long)batch, (long long)M, (long long)N, (long long)d);
+    if (d != 64 && d != 128) return fail(TIR_ERR_UNSUPPORTED, "attention: head dimension %lld (64 and 128 are compiled)", (long long)d);
+    if (!(scale == scale) || scale > 3.0e38f || scale < -3.0e38f) return fail(TIR_ERR_INVALID_ARG, "attention: scale must be finite");
+    if (batch == 0 || M == 0) return TIR_OK;
+    if (N == 0) return fail(TIR_ERR_INVALID_ARG, "attention: the softmax over zero keys is undefined (N = 0)");
+    if (!Q || !K || !V || !O) return fail(TIR_ERR_INVALID_ARG, "Q, K, V or O is null");
+    if (!aligned(Q, 16) || !aligned(K, 16) || !aligned(V, 16) || !aligned(O, 16)) return fail(TIR_ERR_ALIGNMENT, "attention: Q, K, V and O must be 16-byte aligned");
+    const int64_t tiles_m = (M + 127) / 128;
+    if (M > kMaxExtent || N > kMaxExtent || batch * tiles_m > kMaxExtent) return fail(TIR_ERR_UNSUPPORTED, "extent beyond 2^31-1");
+    attn_launch_fn fn = attention_launcher((int)in, (int)out, (int)d);
+    if (!fn) return fail(TIR_ERR_UNSUPPORTED, "attention: no kernel for this dtype pair / head dimension");
+    AttnParams p;
+    p.Q = Q; p.K = K; p.V = V; p.O = O;
+    p.M = (int)M; p.N = (int)N; p.batch = (int)batch; p.tiles_m = (int)tiles_m;
+    p.scale_log2e = scale * 1.44269504088896340736f;
+    hipError_t e = fn(p, (hipStream_t)stream);
+    if (e != hipSuccess) return fail(TIR_ERR_LAUNCH, "attention launch failed: %s", hipGetErrorString(e));
     return TIR_OK;
 }
 

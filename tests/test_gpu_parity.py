@@ -427,3 +427,63 @@ def test_fused_consumer_argument_checks(B):
     assert call("i8out", c8, B.Epilogue(bias.data_ptr(), 1, 0.5)) == B.TIR_OK
     assert B.tir_gemm_status(a, a, c8, 64, 64, 64, 64, 1, 64, 1, 64, 1, "i8", 2) == B.TIR_ERR_UNSUPPORTED   # plain entry point
     torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------------------ fused attention head
+ATTN_CASES = [
+    # batch, M, N, d, scale
+    (192, 128, 128, 64, 0.125),      # the benchmark's BERT-base head: 16 sequences x 12 heads, one key chunk
+    (3, 130, 200, 64, 0.125),        # two query tiles, two key chunks, both ragged
+    (2, 1, 1, 64, 1.0),              # a single key: the output is its value row
+    (2, 77, 129, 64, 0.5),           # one key in the second chunk
+    (1, 300, 512, 128, 0.0884),      # head dimension 128, four chunks
+    (2, 64, 384, 64, 3.0),           # peaked softmax
+    (2, 40, 100, 128, 0.0),          # scale 0: uniform attention
+]
+
+
+@pytest.mark.parametrize("dtype,out,rtol", [("f16", "f16", 2e-3), ("f16", "f32", 2e-3), ("bf16", "f32", 6e-3), ("bf16", "bf16", 6e-3)])
+def test_attention_matches_oracle(B, oracle, dtype, out, rtol):
+    """|gpu - oracle| <= rtol * T + 1e-5 with T = sum_j P |V|.  The probabilities are rounded to the
+    input type before the second product: up to 2^-11 each for fp16 (inside 2e-3 T together with the
+    output rounding), up to 2^-9 each for bfloat16, hence its wider bound; bfloat16 output adds its own
+    2^-9 |O|."""
+    import torch
+    for (batch, M, N, d, scale) in ATTN_CASES:
+        _say(f"attention {dtype}->{out} batch={batch} M={M} N={N} d={d} scale={scale}")
+        Qb = I.make_tensor(dtype, "u", 9800 + M, (batch, M, d))
+        Kb = I.make_tensor(dtype, "u", 9801 + N, (batch, N, d))
+        Vb = I.make_tensor(dtype, "u", 9802 + d, (batch, N, d))
+        ref, T = oracle.attention(dtype, Qb, Kb, Vb, scale)
+        q, k, v = B.to_device(Qb, dtype), B.to_device(Kb, dtype), B.to_device(Vb, dtype)
+        o = B.empty_out((batch, M, d), out)
+        o.fill_(float("nan"))
+        B.tir_attention(q, k, v, o, batch, M, N, d, scale, dtype, out)
+        torch.cuda.synchronize()
+        got = PT.gpu_to_f64(o)
+        assert np.all(np.isfinite(got)), "non-finite output"
+        tol = rtol * T + 1e-5 + (np.abs(ref) * 2.0 ** -8 if out == "bf16" else 0.0)
+        ratio = np.abs(got - ref) / tol
+        worst = int(np.argmax(ratio))
+        assert ratio.ravel()[worst] <= 1.0, f"max err/tol {ratio.ravel()[worst]:.3g} at {np.unravel_index(worst, ratio.shape)}: gpu={got.ravel()[worst]} oracle={ref.ravel()[worst]}"
+        _say(f"   max err/tol {ratio.max():.3g}")
+
+
+def test_attention_argument_checks(B):
+    import torch
+    x = torch.zeros(128 * 64, dtype=torch.float16, device="cuda")
+    def st(**kw):
+        a = dict(Q=x, K=x, V=x, O=x, batch=1, M=128, N=128, d=64, scale=0.125, i="f16", o="f16")
+        a.update(kw)
+        return B.tir_attention_status(a["Q"], a["K"], a["V"], a["O"], a["batch"], a["M"], a["N"], a["d"], a["scale"], a["i"], a["o"])
+    assert st(d=96) == B.TIR_ERR_UNSUPPORTED
+    assert st(N=0) == B.TIR_ERR_INVALID_ARG
+    assert st(M=-1) == B.TIR_ERR_INVALID_ARG
+    assert st(scale=float("nan")) == B.TIR_ERR_INVALID_ARG
+    assert st(i="i8", o="i32") == B.TIR_ERR_UNSUPPORTED
+    assert st(i="f16", o="bf16") == B.TIR_ERR_UNSUPPORTED
+    assert st(Q=0) == B.TIR_ERR_INVALID_ARG
+    assert st(K=x.data_ptr() + 2) == B.TIR_ERR_ALIGNMENT
+    assert st(M=0) == B.TIR_OK and st(batch=0) == B.TIR_OK
+    assert st() == B.TIR_OK
+    torch.cuda.synchronize()
