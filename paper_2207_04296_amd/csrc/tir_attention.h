@@ -110,7 +110,9 @@ __global__ void __launch_bounds__(256) attention_kernel(const AttnParams p) {
     };
     copy_kmajor(Qb, (long long)rows_q * ROW, s_q);
     copy_chunk(0);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    // Q and the first keys are enough to start on the scores: the first values (the newest 4*HALVES
+    // copies of this wave) may still be in flight, they are waited for before the second product
+    wait_vmcnt_upto(4 * HALVES);
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
 
@@ -182,6 +184,12 @@ __global__ void __launch_bounds__(256) attention_kernel(const AttnParams p) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc_o[db][r] *= alpha;
 
+        if (c == 0) {
+            // the first values: everything but the next chunk's copies (issued after them) has landed
+            wait_vmcnt_upto(nchunk > 1 ? 8 * HALVES : 0);
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+        }
         // O^T += V^T P^T.  Position (g, 4*hh + e) of k-step s in key block jb is key
         // 32*jb + 16*s + 8*hh + 4*g + e - the order the probabilities sit in the registers above.
 #pragma unroll
