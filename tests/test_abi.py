@@ -202,3 +202,19 @@ def test_fused_entry_points_validate_the_epilogue_on_the_host():
                             ctypes.byref(B.Epilogue(None, 1, 0.5)), None) == B.TIR_OK
     # the variant query knows the requantising kernels
     assert B.tir_gemm_variant(1, 512, 512, 512, 512, 1, 512, 1, 512, 1, "i8", B.TIR_I8).startswith("i8_i8_")
+
+
+def test_attention_rejects_bad_arguments_on_the_host():
+    def st(**kw):
+        a = dict(Q=FAKE, K=FAKE, V=FAKE, O=FAKE, batch=1, M=128, N=128, d=64, scale=0.125, i="f16", o="f16")
+        a.update(kw)
+        return B.tir_attention_status(a["Q"], a["K"], a["V"], a["O"], a["batch"], a["M"], a["N"], a["d"], a["scale"], a["i"], a["o"])
+    assert st(d=96) == B.TIR_ERR_UNSUPPORTED and "head dimension" in B.last_error()
+    assert st(N=0) == B.TIR_ERR_INVALID_ARG
+    assert st(M=-1) == B.TIR_ERR_INVALID_ARG
+    assert st(scale=float("inf")) == B.TIR_ERR_INVALID_ARG
+    assert st(i="i8", o="i32") == B.TIR_ERR_UNSUPPORTED
+    assert st(i="bf16", o="f16") == B.TIR_ERR_UNSUPPORTED
+    assert st(V=0) == B.TIR_ERR_INVALID_ARG
+    assert st(O=FAKE + 8) == B.TIR_ERR_ALIGNMENT
+    assert st(M=0) == B.TIR_OK and st(batch=0) == B.TIR_OK          # nothing to do: no launch, no device needed

@@ -487,3 +487,54 @@ def test_attention_argument_checks(B):
     assert st(M=0) == B.TIR_OK and st(batch=0) == B.TIR_OK
     assert st() == B.TIR_OK
     torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------------------ seeded random problems
+def _random_workloads(seed, count):
+    """Seeded random operator instances: every kind, dtype pair and fused-consumer combination, extents
+    that are ragged against the tiles, strides / dilations / groups within what the API accepts."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for i in range(count):
+        dtype = ["f16", "bf16", "i8"][int(rng.integers(3))]
+        if dtype == "i8":
+            o, scale = (("i8", float(rng.choice([1 / 300.0, 1 / 2000.0]))) if rng.random() < 0.4 else ("i32", 0.0))
+        else:
+            o, scale = (dtype if rng.random() < 0.4 and dtype == "f16" else "f32"), 0.0
+        bias, relu = bool(rng.random() < 0.5), bool(rng.random() < 0.5)
+        kind = ["gemm", "bmm", "conv2d"][int(rng.integers(3))]
+        vec = 16 if dtype == "i8" else 8
+        if kind == "conv2d":
+            groups = int(rng.choice([1, 1, 2, 4]))
+            cg = int(rng.choice([vec, 2 * vec, 64 // (2 if dtype != "i8" else 1), 3]))     # fast paths, the patch kernel's 128 B, and an odd count
+            kg = int(rng.choice([8, 24, 40, 64, 72]))
+            r, s = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+            st = (int(rng.integers(1, 3)), int(rng.integers(1, 3)))
+            dil = (int(rng.integers(1, 3)), int(rng.integers(1, 3)))
+            pad = (int(rng.integers(0, 3)), int(rng.integers(0, 3)))
+            h, w = int(rng.integers(6, 24)), int(rng.integers(6, 24))
+            if (h + 2 * pad[0] - dil[0] * (r - 1) - 1) < 0 or (w + 2 * pad[1] - dil[1] * (s - 1) - 1) < 0:
+                continue
+            kw = dict(n=int(rng.integers(1, 4)), h=h, w=w, c=cg * groups, k=kg * groups, r=r, s=s, stride=st, pad=pad, dil=dil, groups=groups)
+            dist = "i" if dtype == "i8" else "n0.1"
+        else:
+            kw = dict(M=int(rng.integers(1, 330)), N=int(rng.integers(1, 40)) * int(rng.choice([1, vec])),
+                      K=int(rng.integers(1, 60)) * int(rng.choice([1, vec])), trans_b=bool(rng.random() < 0.5))
+            if kind == "bmm":
+                kw["batch"] = int(rng.integers(1, 5))
+            dist = "i" if dtype == "i8" else "u"
+        out.append(I.Workload(f"rand{seed}_{i}_{kind}_{dtype}_{o}", kind, dtype, o, dist, 20000 + 10 * i, ep_bias=bias, ep_relu=relu,
+                              ep_scale=scale, **kw))
+    return out
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_seeded_random_problems(B, oracle, seed):
+    for wl in _random_workloads(seed, 40):
+        desc = {f: getattr(wl, f) for f in ("batch", "M", "N", "K", "trans_b", "n", "h", "w", "c", "k", "r", "s", "stride", "pad", "dil", "groups",
+                                            "ep_bias", "ep_relu", "ep_scale")}
+        _say(f"{wl.name} {desc} -> {PT.variant_name(B, wl)}")
+        a_bits, b_bits = wl.operands()
+        ref, S = PT.run_oracle(wl, a_bits, b_bits, oracle)
+        got = PT.run_gpu(wl, a_bits, b_bits)
+        PT.assert_close(got, ref, S, wl.name)
