@@ -54,6 +54,12 @@ def _load():
         lib.oracle_epilogue_float.argtypes = [dp, dp, i64, i64, ctypes.POINTER(ctypes.c_float), ctypes.c_int]
         lib.oracle_epilogue_int.argtypes = [ctypes.POINTER(ctypes.c_int64), i64, i64, ctypes.POINTER(ctypes.c_int32),
                                             ctypes.c_int, ctypes.c_int, ctypes.c_float]
+        pi64 = ctypes.POINTER(ctypes.c_int64)
+        lib.oracle_conv1d.argtypes = [ctypes.c_int, vp, vp] + [i64] * 9 + [vp, dp]
+        lib.oracle_conv3d.argtypes = [ctypes.c_int, vp, vp, i64, pi64, i64, i64, pi64, pi64, pi64, pi64, i64, vp, dp]
+        lib.oracle_conv2d_transpose.argtypes = [ctypes.c_int, vp, vp] + [i64] * 7 + [pi64, pi64, pi64, pi64, i64, vp, dp]
+        lib.oracle_conv_transpose_out_extent.restype = ctypes.c_int64
+        lib.oracle_conv_transpose_out_extent.argtypes = [i64] * 6
         lib.oracle_attention.argtypes = [ctypes.c_int, vp, vp, vp] + [i64] * 5 + [ctypes.c_double, dp, dp]
         lib.oracle_set_threads.argtypes = [ctypes.c_int]
         lib.oracle_get_threads.restype = ctypes.c_int
@@ -221,3 +227,76 @@ def attention(dtype: str, Q: np.ndarray, K: np.ndarray, V: np.ndarray, scale: fl
     if rc:
         raise RuntimeError(f"oracle_attention failed with {rc}")
     return O, T
+
+
+def _i64arr(v):
+    return (ctypes.c_int64 * len(v))(*[int(e) for e in v])
+
+
+def _conv_out(is_int, shape, want_S):
+    y = np.empty(shape, dtype=np.int64 if is_int else np.float64)
+    S = None if (is_int or not want_S) else np.empty(shape, dtype=np.float64)
+    return y, S
+
+
+def conv1d(dtype: str, x: np.ndarray, w: np.ndarray, stride: int = 1, pad: int = 0, dil: int = 1, groups: int = 1,
+           want_S: bool = True):
+    """x: bits [N,L,C]; w: bits [K,R,C/groups]; returns (y [N,P,K], Sabs or None)."""
+    x = np.ascontiguousarray(_check_bits(x, dtype)); w = np.ascontiguousarray(_check_bits(w, dtype))
+    N, L, C = x.shape
+    K, R, Cg = w.shape
+    if groups <= 0 or C % groups or K % groups or Cg != C // groups:
+        raise ValueError("oracle.conv1d: inconsistent groups / channel counts")
+    P = conv_out_extent(L, R, stride, pad, dil)
+    if P <= 0:
+        raise ValueError("oracle.conv1d: empty output")
+    y, S = _conv_out(dtype == "i8", (N, P, K), want_S)
+    rc = _load().oracle_conv1d(_code(dtype), _ptr(x), _ptr(w), N, L, C, K, R, stride, pad, dil, groups, _ptr(y),
+                               _ptr(S) if S is not None else None)
+    if rc:
+        raise RuntimeError(f"oracle_conv1d failed with {rc}")
+    return y, S
+
+
+def conv3d(dtype: str, x: np.ndarray, w: np.ndarray, stride=(1, 1, 1), pad=(0, 0, 0), dil=(1, 1, 1), groups: int = 1,
+           want_S: bool = True):
+    """x: bits [N,D,H,W,C]; w: bits [K,T,R,S,C/groups]; returns (y [N,OD,P,Q,K], Sabs or None)."""
+    x = np.ascontiguousarray(_check_bits(x, dtype)); w = np.ascontiguousarray(_check_bits(w, dtype))
+    N, D, H, W, C = x.shape
+    K, T, R, S_, Cg = w.shape
+    if groups <= 0 or C % groups or K % groups or Cg != C // groups:
+        raise ValueError("oracle.conv3d: inconsistent groups / channel counts")
+    out = [conv_out_extent(i, f, s, p, d) for i, f, s, p, d in zip((D, H, W), (T, R, S_), stride, pad, dil)]
+    if min(out) <= 0:
+        raise ValueError("oracle.conv3d: empty output")
+    y, S = _conv_out(dtype == "i8", (N, *out, K), want_S)
+    rc = _load().oracle_conv3d(_code(dtype), _ptr(x), _ptr(w), N, _i64arr((D, H, W)), C, K, _i64arr((T, R, S_)), _i64arr(stride),
+                               _i64arr(pad), _i64arr(dil), groups, _ptr(y), _ptr(S) if S is not None else None)
+    if rc:
+        raise RuntimeError(f"oracle_conv3d failed with {rc}")
+    return y, S
+
+
+def conv_transpose_out_extent(inp: int, filt: int, stride: int, pad: int, dil: int, outpad: int) -> int:
+    return int(_load().oracle_conv_transpose_out_extent(inp, filt, stride, pad, dil, outpad))
+
+
+def conv2d_transpose(dtype: str, x: np.ndarray, w: np.ndarray, stride=(1, 1), pad=(0, 0), dil=(1, 1), outpad=(0, 0),
+                     groups: int = 1, want_S: bool = True):
+    """x: bits [N,H,W,C]; w: bits [K,R,S,C/groups] (output channel k, tap (r,s), input channel c of k's group);
+    returns (y [N,P,Q,K], Sabs or None)."""
+    x = np.ascontiguousarray(_check_bits(x, dtype)); w = np.ascontiguousarray(_check_bits(w, dtype))
+    N, H, W, C = x.shape
+    K, R, S_, Cg = w.shape
+    if groups <= 0 or C % groups or K % groups or Cg != C // groups:
+        raise ValueError("oracle.conv2d_transpose: inconsistent groups / channel counts")
+    P = conv_transpose_out_extent(H, R, stride[0], pad[0], dil[0], outpad[0])
+    Q = conv_transpose_out_extent(W, S_, stride[1], pad[1], dil[1], outpad[1])
+    if P <= 0 or Q <= 0:
+        raise ValueError("oracle.conv2d_transpose: empty output")
+    y, S = _conv_out(dtype == "i8", (N, P, Q, K), want_S)
+    rc = _load().oracle_conv2d_transpose(_code(dtype), _ptr(x), _ptr(w), N, H, W, C, K, R, S_, _i64arr(stride), _i64arr(pad),
+                                         _i64arr(dil), _i64arr(outpad), groups, _ptr(y), _ptr(S) if S is not None else None)
+    if rc:
+        raise RuntimeError(f"oracle_conv2d_transpose failed with {rc}")
+    return y, S

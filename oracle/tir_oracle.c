@@ -365,3 +365,141 @@ int oracle_attention(int dtype, const void* Q, const void* K, const void* V, int
     }
     return failed ? ORACLE_NO_MEMORY : ORACLE_OK;
 }
+
+/*
+ * The remaining convolution forms of the paper's operator set (sec. 5.1: 1D, 3D and transposed 2D
+ * convolution next to the 2D, dilated and grouped ones above).  Same readings as oracle_conv2d: zero
+ * padding, cross-correlation, channels-last activations, filter stored output-channel-major with the
+ * channel innermost, contiguous channel groups, floor rule for the output extent.
+ *
+ * conv1d:  x [N][L][C],        w [K][R][C/g]         y[n,p,k] = sum_{r,c} x[n, p*s - pad + r*d, g*Cg + c] * w[k,r,c]
+ * conv3d:  x [N][D][H][W][C],  w [K][T][R][S][C/g]   y[n,o,p,q,k] = sum_{t,r,s,c} x[n, o*s_d - pad_d + t*d_d, p*s_h - pad_h + r*d_h,
+ *                                                                                  q*s_w - pad_w + s*d_w, g*Cg + c] * w[k,t,r,s,c]
+ * conv2d_transpose (the adjoint of a strided convolution, written as the scatter that defines it):
+ *          x [N][H][W][C],     w [K][R][S][C/g]      for every input pixel (ih, iw), tap (r, s) and channel c of group g:
+ *              y[n, ih*s_h - pad_h + r*d_h, iw*s_w - pad_w + s*d_w, k] += x[n,ih,iw,g*Cg + c] * w[k,r,s,c]     (targets outside y dropped)
+ *          output extent (H-1)*s_h - 2*pad_h + d_h*(R-1) + outpad_h + 1, likewise for the width.
+ * S (float inputs) accumulates |x*w| over the same terms.  Arguments: int64 arrays dims / strides / pads / dils
+ * of the spatial rank (1, 3 or 2).
+ */
+int oracle_conv1d(int dtype, const void* x, const void* w, int64_t N, int64_t L, int64_t C, int64_t K, int64_t R,
+                  int64_t stride, int64_t pad, int64_t dil, int64_t groups, void* y, double* Sabs) {
+    if (N < 0 || L <= 0 || C <= 0 || K <= 0 || R <= 0 || stride <= 0 || dil <= 0 || pad < 0 || groups <= 0 || C % groups || K % groups) return ORACLE_BAD_ARG;
+    const int64_t P = oracle_conv_out_extent(L, R, stride, pad, dil);
+    if (P <= 0) return ORACLE_BAD_ARG;
+    const int is_int = dtype == ORACLE_I8;
+    const int64_t Cg = C / groups, Kg = K / groups;
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t p = 0; p < P; ++p)
+            for (int64_t k = 0; k < K; ++k) {
+                const int64_t g = k / Kg;
+                double accf = 0.0, accs = 0.0;
+                int64_t acci = 0;
+                for (int64_t r = 0; r < R; ++r) {
+                    const int64_t il = p * stride - pad + r * dil;
+                    if (il < 0 || il >= L) continue;
+                    for (int64_t c = 0; c < Cg; ++c) {
+                        const int64_t xo = (n * L + il) * C + g * Cg + c, wo = (k * R + r) * Cg + c;
+                        if (is_int) acci += (int64_t)((const int8_t*)x)[xo] * (int64_t)((const int8_t*)w)[wo];
+                        else { const double t = load_float(dtype, x, xo) * load_float(dtype, w, wo); accf += t; accs += fabs(t); }
+                    }
+                }
+                const int64_t o = (n * P + p) * K + k;
+                if (is_int) ((int64_t*)y)[o] = acci;
+                else { ((double*)y)[o] = accf; if (Sabs) Sabs[o] = accs; }
+            }
+    return ORACLE_OK;
+}
+
+int oracle_conv3d(int dtype, const void* x, const void* w, int64_t N, const int64_t* in_dhw, int64_t C, int64_t K,
+                  const int64_t* filt_trs, const int64_t* stride, const int64_t* pad, const int64_t* dil, int64_t groups,
+                  void* y, double* Sabs) {
+    if (N < 0 || C <= 0 || K <= 0 || groups <= 0 || C % groups || K % groups) return ORACLE_BAD_ARG;
+    int64_t out[3];
+    for (int a = 0; a < 3; ++a) {
+        if (in_dhw[a] <= 0 || filt_trs[a] <= 0 || stride[a] <= 0 || dil[a] <= 0 || pad[a] < 0) return ORACLE_BAD_ARG;
+        out[a] = oracle_conv_out_extent(in_dhw[a], filt_trs[a], stride[a], pad[a], dil[a]);
+        if (out[a] <= 0) return ORACLE_BAD_ARG;
+    }
+    const int is_int = dtype == ORACLE_I8;
+    const int64_t D = in_dhw[0], H = in_dhw[1], W = in_dhw[2], T = filt_trs[0], R = filt_trs[1], S = filt_trs[2];
+    const int64_t Cg = C / groups, Kg = K / groups;
+#ifdef _OPENMP
+#pragma omp parallel for collapse(2) schedule(static) num_threads(oracle_get_threads())
+#endif
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t o = 0; o < out[0]; ++o)
+            for (int64_t p = 0; p < out[1]; ++p)
+                for (int64_t q = 0; q < out[2]; ++q)
+                    for (int64_t k = 0; k < K; ++k) {
+                        const int64_t g = k / Kg;
+                        double accf = 0.0, accs = 0.0;
+                        int64_t acci = 0;
+                        for (int64_t t = 0; t < T; ++t) {
+                            const int64_t id = o * stride[0] - pad[0] + t * dil[0];
+                            if (id < 0 || id >= D) continue;
+                            for (int64_t r = 0; r < R; ++r) {
+                                const int64_t ih = p * stride[1] - pad[1] + r * dil[1];
+                                if (ih < 0 || ih >= H) continue;
+                                for (int64_t s = 0; s < S; ++s) {
+                                    const int64_t iw = q * stride[2] - pad[2] + s * dil[2];
+                                    if (iw < 0 || iw >= W) continue;
+                                    const int64_t xo = (((n * D + id) * H + ih) * W + iw) * C + g * Cg;
+                                    const int64_t wo = (((k * T + t) * R + r) * S + s) * Cg;
+                                    for (int64_t c = 0; c < Cg; ++c) {
+                                        if (is_int) acci += (int64_t)((const int8_t*)x)[xo + c] * (int64_t)((const int8_t*)w)[wo + c];
+                                        else { const double v = load_float(dtype, x, xo + c) * load_float(dtype, w, wo + c); accf += v; accs += fabs(v); }
+                                    }
+                                }
+                            }
+                        }
+                        const int64_t oo = (((n * out[0] + o) * out[1] + p) * out[2] + q) * K + k;
+                        if (is_int) ((int64_t*)y)[oo] = acci;
+                        else { ((double*)y)[oo] = accf; if (Sabs) Sabs[oo] = accs; }
+                    }
+    return ORACLE_OK;
+}
+
+int64_t oracle_conv_transpose_out_extent(int64_t in, int64_t filt, int64_t stride, int64_t pad, int64_t dil, int64_t outpad) {
+    return (in - 1) * stride - 2 * pad + dil * (filt - 1) + outpad + 1;
+}
+
+int oracle_conv2d_transpose(int dtype, const void* x, const void* w, int64_t N, int64_t H, int64_t W, int64_t C, int64_t K,
+                            int64_t R, int64_t S, const int64_t* stride, const int64_t* pad, const int64_t* dil,
+                            const int64_t* outpad, int64_t groups, void* y, double* Sabs) {
+    if (N < 0 || H <= 0 || W <= 0 || C <= 0 || K <= 0 || R <= 0 || S <= 0 || groups <= 0 || C % groups || K % groups) return ORACLE_BAD_ARG;
+    for (int a = 0; a < 2; ++a)
+        if (stride[a] <= 0 || dil[a] <= 0 || pad[a] < 0 || outpad[a] < 0) return ORACLE_BAD_ARG;
+    const int64_t P = oracle_conv_transpose_out_extent(H, R, stride[0], pad[0], dil[0], outpad[0]);
+    const int64_t Q = oracle_conv_transpose_out_extent(W, S, stride[1], pad[1], dil[1], outpad[1]);
+    if (P <= 0 || Q <= 0) return ORACLE_BAD_ARG;
+    const int is_int = dtype == ORACLE_I8;
+    const int64_t Cg = C / groups, Kg = K / groups, total = N * P * Q * K;
+    if (is_int) memset(y, 0, (size_t)total * sizeof(int64_t));
+    else { memset(y, 0, (size_t)total * sizeof(double)); if (Sabs) memset(Sabs, 0, (size_t)total * sizeof(double)); }
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t ih = 0; ih < H; ++ih)
+            for (int64_t iw = 0; iw < W; ++iw)
+                for (int64_t r = 0; r < R; ++r) {
+                    const int64_t oh = ih * stride[0] - pad[0] + r * dil[0];
+                    if (oh < 0 || oh >= P) continue;
+                    for (int64_t s = 0; s < S; ++s) {
+                        const int64_t ow = iw * stride[1] - pad[1] + s * dil[1];
+                        if (ow < 0 || ow >= Q) continue;
+                        for (int64_t k = 0; k < K; ++k) {
+                            const int64_t g = k / Kg;
+                            const int64_t xo = ((n * H + ih) * W + iw) * C + g * Cg, wo = ((k * R + r) * S + s) * Cg;
+                            const int64_t oo = ((n * P + oh) * Q + ow) * K + k;
+                            for (int64_t c = 0; c < Cg; ++c) {
+                                if (is_int) ((int64_t*)y)[oo] += (int64_t)((const int8_t*)x)[xo + c] * (int64_t)((const int8_t*)w)[wo + c];
+                                else {
+                                    const double v = load_float(dtype, x, xo + c) * load_float(dtype, w, wo + c);
+                                    ((double*)y)[oo] += v;
+                                    if (Sabs) Sabs[oo] += fabs(v);
+                                }
+                            }
+                        }
+                    }
+                }
+    return ORACLE_OK;
+}

@@ -505,3 +505,109 @@ def test_attention_matches_library_softmax_between_matmuls(oracle, dtype):
         assert np.allclose(O, P @ v, rtol=0, atol=1e-13)
         assert np.allclose(T, P @ np.abs(v), rtol=0, atol=1e-13)
         assert np.allclose(P.sum(axis=-1), 1.0, rtol=0, atol=1e-14)
+
+
+# ------------------------------------------------------------------------------ conv1d / conv3d / transposed conv2d
+def _smallint_bits(rng, shape):
+    """fp16 bits of small integers: every product and sum below is exact in fp64."""
+    return I.to_f16_bits(rng.integers(-3, 4, size=shape).astype(np.float64))
+
+
+def test_conv1d_is_numpy_correlate_and_conv2d_with_unit_height(oracle):
+    rng = np.random.default_rng(11)
+    # one channel, one filter, no padding: numpy's own cross-correlation
+    x = _smallint_bits(rng, (1, 40, 1)); w = _smallint_bits(rng, (1, 5, 1))
+    y, _ = oracle.conv1d("f16", x, w)
+    assert np.array_equal(y[0, :, 0], np.correlate(_dec16(x)[0, :, 0], _dec16(w)[0, :, 0], mode="valid"))
+    # general case: the same numbers as the 2-D operator on an image of height 1
+    for (stride, pad, dil, groups) in [(1, 0, 1, 1), (2, 3, 1, 2), (1, 2, 2, 4), (3, 1, 3, 1)]:
+        x = _smallint_bits(rng, (2, 23, 8)); w = _smallint_bits(rng, (12, 3, 8 // groups))
+        y, S = oracle.conv1d("f16", x, w, stride, pad, dil, groups)
+        y2, S2 = oracle.conv2d("f16", x[:, None], w[:, None], (1, stride), (0, pad), (1, dil), groups)
+        assert np.array_equal(y, y2[:, 0]) and np.array_equal(S, S2[:, 0])
+    xi = rng.integers(-127, 128, size=(2, 17, 4)).astype(np.int8); wi = rng.integers(-127, 128, size=(6, 4, 2)).astype(np.int8)
+    yi, _ = oracle.conv1d("i8", xi, wi, 2, 1, 1, 2)
+    yi2, _ = oracle.conv2d("i8", xi[:, None], wi[:, None], (1, 2), (0, 1), (1, 1), 2)
+    assert np.array_equal(yi, yi2[:, 0])
+
+
+def test_conv3d_reduces_to_conv2d_and_to_a_sum_over_depth_taps(oracle):
+    rng = np.random.default_rng(12)
+    # depth 1, one depth tap: the 2-D operator
+    x = _smallint_bits(rng, (2, 1, 9, 8, 6)); w = _smallint_bits(rng, (4, 1, 3, 2, 3))
+    y, S = oracle.conv3d("f16", x, w, (1, 2, 1), (0, 1, 1), (1, 1, 2), 2)
+    y2, S2 = oracle.conv2d("f16", x[:, 0], w[:, 0], (2, 1), (1, 1), (1, 2), 2)
+    assert np.array_equal(y[:, 0], y2) and np.array_equal(S[:, 0], S2)
+    # general: output depth o is the sum over depth taps t of 2-D convolutions of input slice o*s - pad + t*d
+    N, D, H, W, C, K, T, R, S_ = 1, 7, 6, 5, 4, 6, 3, 2, 3
+    sd, pd, dd = 2, 1, 2
+    x = _smallint_bits(rng, (N, D, H, W, C)); w = _smallint_bits(rng, (K, T, R, S_, C))
+    y, _ = oracle.conv3d("f16", x, w, (sd, 1, 2), (pd, 1, 0), (dd, 1, 1))
+    OD = oracle.conv_out_extent(D, T, sd, pd, dd)
+    assert y.shape[1] == OD == 3
+    for o in range(OD):
+        acc = 0.0
+        for t in range(T):
+            i_d = o * sd - pd + t * dd
+            if 0 <= i_d < D:
+                acc = acc + oracle.conv2d("f16", x[:, i_d], w[:, t], (1, 2), (1, 0), (1, 1))[0]
+        assert np.array_equal(y[:, o], acc)
+
+
+@pytest.mark.parametrize("case", [((1, 1, 1), (0, 0, 0), (1, 1, 1), 1), ((2, 1, 2), (1, 0, 2), (1, 2, 1), 1), ((1, 2, 1), (1, 1, 1), (2, 1, 1), 2)])
+def test_conv3d_matches_torch_fp64_library(oracle, case):
+    import torch
+    stride, pad, dil, groups = case
+    rng = np.random.default_rng(13)
+    xb = I.make_tensor("f16", "u", 31, (2, 6, 7, 8, 4)); wb = I.make_tensor("f16", "u", 32, (6, 3, 2, 3, 4 // groups))
+    y, _ = oracle.conv3d("f16", xb, wb, stride, pad, dil, groups)
+    xt = torch.from_numpy(_dec16(xb)).permute(0, 4, 1, 2, 3); wt = torch.from_numpy(_dec16(wb)).permute(0, 4, 1, 2, 3)
+    ref = torch.nn.functional.conv3d(xt, wt, None, stride, pad, dil, groups).permute(0, 2, 3, 4, 1).numpy()
+    assert np.allclose(y, ref, rtol=0, atol=1e-12)
+
+
+def test_conv2d_transpose_is_the_adjoint_of_conv2d(oracle):
+    """<conv2d(x, w), y> == <x, conv2d_transpose(y, w^T)> for every x and y (exact on small integers), where w^T swaps
+    the roles of the filter's channel axes; with it the transposed operator is pinned to the forward one."""
+    rng = np.random.default_rng(14)
+    for (stride, pad, dil, groups, H, W) in [((1, 1), (0, 0), (1, 1), 1, 6, 7), ((2, 2), (1, 1), (1, 1), 1, 9, 8), ((2, 3), (1, 0), (2, 1), 2, 11, 10),
+                                              ((3, 1), (2, 1), (1, 2), 1, 10, 7)]:
+        N, C, K, R, S_ = 2, 4, 6, 3, 2
+        Cg, Kg = C // groups, K // groups
+        xb = _smallint_bits(rng, (N, H, W, C)); wb = _smallint_bits(rng, (K, R, S_, Cg))
+        fwd, _ = oracle.conv2d("f16", xb, wb, stride, pad, dil, groups)                    # [N,P,Q,K]
+        P, Q = fwd.shape[1:3]
+        yb = _smallint_bits(rng, (N, P, Q, K))
+        # transposed filter: output channels of the adjoint are the forward input channels, group by group
+        wf = _dec16(wb).reshape(groups, Kg, R, S_, Cg)
+        wT = I.to_f16_bits(np.ascontiguousarray(wf.transpose(0, 4, 2, 3, 1)).reshape(C, R, S_, Kg))
+        outpad = ((H + 2 * pad[0] - dil[0] * (R - 1) - 1) % stride[0], (W + 2 * pad[1] - dil[1] * (S_ - 1) - 1) % stride[1])
+        back, _ = oracle.conv2d_transpose("f16", yb, wT, stride, pad, dil, outpad, groups)   # [N,H,W,C]
+        assert back.shape == (N, H, W, C)
+        assert np.sum(fwd * _dec16(yb)) == np.sum(_dec16(xb) * back)
+
+
+@pytest.mark.parametrize("case", [((1, 1), (0, 0), (1, 1), (0, 0), 1), ((2, 2), (1, 1), (1, 1), (1, 1), 1), ((3, 2), (0, 2), (2, 1), (2, 0), 2)])
+def test_conv2d_transpose_matches_torch_fp64_library(oracle, case):
+    import torch
+    stride, pad, dil, outpad, groups = case
+    N, H, W, C, K, R, S_ = 2, 5, 6, 4, 6, 3, 2
+    xb = I.make_tensor("f16", "u", 41, (N, H, W, C)); wb = I.make_tensor("f16", "u", 42, (K, R, S_, C // groups))
+    y, S = oracle.conv2d_transpose("f16", xb, wb, stride, pad, dil, outpad, groups)
+    # torch's layout: input [N,C,H,W], weight [C_in, C_out/groups, R, S]
+    Cg, Kg = C // groups, K // groups
+    wt = _dec16(wb).reshape(groups, Kg, R, S_, Cg).transpose(0, 4, 1, 2, 3).reshape(C, Kg, R, S_)
+    ref = torch.nn.functional.conv_transpose2d(torch.from_numpy(_dec16(xb)).permute(0, 3, 1, 2), torch.from_numpy(np.ascontiguousarray(wt)),
+                                               None, stride, pad, outpad, groups, dil).permute(0, 2, 3, 1).numpy()
+    assert y.shape == ref.shape and np.allclose(y, ref, rtol=0, atol=1e-12)
+    assert np.all(S + 1e-12 >= np.abs(y))
+    # a single 1 in the input stamps the filter (times nothing else) into the output at stride spacing
+    xd = np.zeros((1, H, W, C)); xd[0, 2, 3, 1] = 1.0
+    yd, _ = oracle.conv2d_transpose("f16", I.to_f16_bits(xd), wb, stride, pad, dil, outpad, groups)
+    g = 1 // Cg
+    for r in range(R):
+        for s in range(S_):
+            oh, ow = 2 * stride[0] - pad[0] + r * dil[0], 3 * stride[1] - pad[1] + s * dil[1]
+            if 0 <= oh < yd.shape[1] and 0 <= ow < yd.shape[2]:
+                assert np.array_equal(yd[0, oh, ow, g * Kg:(g + 1) * Kg], _dec16(wb)[g * Kg:(g + 1) * Kg, r, s, 1 % Cg])
+    assert np.count_nonzero(yd) <= R * S_ * Kg
