@@ -116,6 +116,36 @@ tir_status tir_conv2d_fused(const void* x, const void* w, void* y, int64_t N, in
                             const tir_epilogue* ep, tir_stream stream);
 
 /*
+ * The other convolution forms of the paper's operator set (sec. 5.1 evaluates 1-D, 3-D and transposed 2-D
+ * convolution next to the 2-D, dilated and grouped ones).  Same conventions as tir_conv2d: channels-last
+ * activations, filter stored output-channel-major with the channel innermost, zero padding,
+ * cross-correlation, contiguous channel groups; ep (may be NULL) fuses a consumer as in tir_conv2d_fused.
+ *
+ * tir_conv1d:  x [N,L,C], w [K,R,C/groups], y [N,P,K], P = floor((L + 2*pad - dil*(R-1) - 1)/stride) + 1;
+ *     y[n,p,k] = sum_{r,c} x[n, p*stride - pad + r*dil, g*C/groups + c] * w[k,r,c].
+ * tir_conv3d:  x [N,D,H,W,C], w [K,T,R,S,C/groups], y [N,OD,P,Q,K] with the floor rule per axis;
+ *     y[n,o,p,q,k] = sum_{t,r,s,c} x[n, o*stride_d - pad_d + t*dil_d, p*stride_h - pad_h + r*dil_h,
+ *                                    q*stride_w - pad_w + s*dil_w, g*C/groups + c] * w[k,t,r,s,c].
+ * tir_conv2d_transpose: the adjoint of a strided convolution.  x [N,H,W,C], w [K,R,S,C/groups] (output
+ *     channel k, tap (r,s), input channel c of k's group), y [N,P,Q,K] with
+ *     P = (H-1)*stride_h - 2*pad_h + dil_h*(R-1) + outpad_h + 1 (Q alike; outpad >= 0 only adds rows /
+ *     columns that receive no or fewer contributions).  Every input pixel (ih, iw) adds
+ *     x[n,ih,iw,g*C/groups + c] * w[k,r,s,c] to y[n, ih*stride_h - pad_h + r*dil_h, iw*stride_w - pad_w + s*dil_w, k]
+ *     (targets outside y are dropped).  Computed as a gather: no atomics, the result is deterministic.
+ */
+tir_status tir_conv1d(const void* x, const void* w, void* y, int64_t N, int64_t L, int64_t C, int64_t K, int64_t R,
+                      int stride, int pad, int dil, int groups, tir_dtype in, tir_dtype out, const tir_epilogue* ep,
+                      tir_stream stream);
+tir_status tir_conv3d(const void* x, const void* w, void* y, int64_t N, int64_t D, int64_t H, int64_t W, int64_t C,
+                      int64_t K, int64_t T, int64_t R, int64_t S, int stride_d, int stride_h, int stride_w, int pad_d,
+                      int pad_h, int pad_w, int dil_d, int dil_h, int dil_w, int groups, tir_dtype in, tir_dtype out,
+                      const tir_epilogue* ep, tir_stream stream);
+tir_status tir_conv2d_transpose(const void* x, const void* w, void* y, int64_t N, int64_t H, int64_t W, int64_t C,
+                                int64_t K, int64_t R, int64_t S, int stride_h, int stride_w, int pad_h, int pad_w,
+                                int dil_h, int dil_w, int outpad_h, int outpad_w, int groups, tir_dtype in,
+                                tir_dtype out, const tir_epilogue* ep, tir_stream stream);
+
+/*
  * One attention head per batch, both contractions and the softmax between them in one kernel (the
  * two tensorized blocks of the batched-matmul workload share a tile; sec. 2 / 3.2 of the paper on blocks
  * as isolated sub-problems that still cooperate; the softmax is the textbook definition):

@@ -20,7 +20,8 @@ EXPORTS = ["tir_gemm", "tir_batch_matmul", "tir_conv2d", "tir_last_error", "tir_
            "tir_conv2d_variant", "tir_debug_force_tile", "tir_debug_force_variant", "tir_debug_variant_count",
            "tir_debug_variant_name", "tir_debug_tile_of_block", "tir_probe_mfma_rate", "tir_version",
            "tir_tune_batch_matmul", "tir_tune_conv2d", "tir_tune_count", "tir_tune_clear", "tir_tune_save",
-           "tir_tune_load", "tir_gemm_fused", "tir_batch_matmul_fused", "tir_conv2d_fused", "tir_attention"]
+           "tir_tune_load", "tir_gemm_fused", "tir_batch_matmul_fused", "tir_conv2d_fused", "tir_attention",
+           "tir_conv1d", "tir_conv3d", "tir_conv2d_transpose"]
 
 
 class Epilogue(ctypes.Structure):
@@ -89,6 +90,12 @@ def lib() -> ctypes.CDLL:
     L.tir_batch_matmul_fused.restype = ci
     L.tir_conv2d_fused.argtypes = [vp, vp, vp] + [i64] * 7 + [ci] * 7 + [ci, ci, pe, vp]
     L.tir_conv2d_fused.restype = ci
+    L.tir_conv1d.argtypes = [vp, vp, vp] + [i64] * 5 + [ci] * 4 + [ci, ci, pe, vp]
+    L.tir_conv1d.restype = ci
+    L.tir_conv3d.argtypes = [vp, vp, vp] + [i64] * 9 + [ci] * 10 + [ci, ci, pe, vp]
+    L.tir_conv3d.restype = ci
+    L.tir_conv2d_transpose.argtypes = [vp, vp, vp] + [i64] * 7 + [ci] * 9 + [ci, ci, pe, vp]
+    L.tir_conv2d_transpose.restype = ci
     L.tir_attention.argtypes = [vp, vp, vp, vp] + [i64] * 4 + [ctypes.c_float, ci, ci, vp]
     L.tir_attention.restype = ci
     L.tir_tune_batch_matmul.argtypes = [vp, vp, vp] + [i64] * 13 + [ci, ci, pe, ci, pd, vp]
@@ -235,6 +242,24 @@ def tir_conv2d_fused(x, w, y, N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pa
     _check(lib().tir_conv2d_fused(_ptr(x), _ptr(w), _ptr(y), N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w,
                                   dil_h, dil_w, groups, _code(in_dtype), _code(out_dtype), _ep_arg(ep),
                                   _stream(stream)))
+
+
+def tir_conv1d(x, w, y, N, L, C, K, R, stride, pad, dil, groups, in_dtype, out_dtype, ep=None, stream=None) -> None:
+    _check(lib().tir_conv1d(_ptr(x), _ptr(w), _ptr(y), N, L, C, K, R, stride, pad, dil, groups, _code(in_dtype),
+                            _code(out_dtype), _ep_arg(ep), _stream(stream)))
+
+
+def tir_conv3d(x, w, y, N, D, H, W, C, K, T, R, S, stride, pad, dil, groups, in_dtype, out_dtype, ep=None, stream=None) -> None:
+    """stride, pad, dil: (depth, height, width) triples."""
+    _check(lib().tir_conv3d(_ptr(x), _ptr(w), _ptr(y), N, D, H, W, C, K, T, R, S, *stride, *pad, *dil, groups,
+                            _code(in_dtype), _code(out_dtype), _ep_arg(ep), _stream(stream)))
+
+
+def tir_conv2d_transpose(x, w, y, N, H, W, C, K, R, S, stride, pad, dil, outpad, groups, in_dtype, out_dtype, ep=None,
+                         stream=None) -> None:
+    """stride, pad, dil, outpad: (height, width) pairs."""
+    _check(lib().tir_conv2d_transpose(_ptr(x), _ptr(w), _ptr(y), N, H, W, C, K, R, S, *stride, *pad, *dil, *outpad, groups,
+                                      _code(in_dtype), _code(out_dtype), _ep_arg(ep), _stream(stream)))
 
 
 def tir_attention_status(Q, K, V, O, batch, M, N, d, scale, in_dtype, out_dtype, stream=0) -> int:

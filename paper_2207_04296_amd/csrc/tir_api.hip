@@ -109,11 +109,10 @@ static const Variant* tuned_lookup(const TuneKey& k) {
     return it == g_tuned.end() ? nullptr : it->second;
 }
 
-static uint64_t conv_geom(int64_t N, int64_t groups, int64_t H, int64_t W, int64_t R, int64_t S, int sh, int sw, int ph, int pw, int dh, int dw) {
-    // the fields do not fit 64 bits side by side: mix them instead (FNV-1a)
-    const int64_t f[12] = {N, groups, H, W, R, S, sh, sw, ph, pw, dh, dw};
+static uint64_t hash_fields(const int64_t* f, int n) {
+    // the fields of a convolution's geometry do not fit 64 bits side by side: mix them instead (FNV-1a)
     uint64_t h = 1469598103934665603ull;
-    for (int i = 0; i < 12; ++i)
+    for (int i = 0; i < n; ++i)
         for (int b = 0; b < 8; ++b) { h ^= (uint64_t)((f[i] >> (8 * b)) & 0xff); h *= 1099511628211ull; }
     return h;
 }
@@ -255,47 +254,72 @@ static int64_t conv_extent(int64_t in, int64_t filt, int64_t stride, int64_t pad
     return span < 0 ? 0 : span / stride + 1;
 }
 
-static tir_status plan_conv(bool need_ptrs, const void* x, const void* w, void* y, int64_t N, int64_t H, int64_t W,
-                            int64_t C, int64_t K, int64_t R, int64_t S, int stride_h, int stride_w, int pad_h,
-                            int pad_w, int dil_h, int dil_w, int groups, int in, int out, const tir_epilogue* ep, Plan* plan) {
+// Geometry of a convolution in the general form the kernels decode: a depth axis (D = T = 1 for 1-D / 2-D) and the
+// transposed 2-D form (the adjoint of a strided convolution).
+struct ConvGeom {
+    int64_t N, D, H, W, C, K, T, R, S;
+    int stride_d, stride_h, stride_w, pad_d, pad_h, pad_w, dil_d, dil_h, dil_w;
+    int groups;
+    bool transposed;
+    int outpad_h, outpad_w;      // transposed only
+};
+
+static tir_status plan_conv_geom(bool need_ptrs, const void* x, const void* w, void* y, const ConvGeom& g, int in, int out,
+                                 const tir_epilogue* ep, Plan* plan) {
     plan->v = nullptr;
     tir_status st = check_common(x, w, y, in, out, ep);
     if (st != TIR_OK) return st;
-    if (N < 0 || H <= 0 || W <= 0 || C <= 0 || K <= 0 || R <= 0 || S <= 0)
-        return fail(TIR_ERR_INVALID_ARG, "non-positive extent (N=%lld H=%lld W=%lld C=%lld K=%lld R=%lld S=%lld)", (long long)N, (long long)H, (long long)W, (long long)C, (long long)K, (long long)R, (long long)S);
-    if (stride_h <= 0 || stride_w <= 0 || dil_h <= 0 || dil_w <= 0 || pad_h < 0 || pad_w < 0)
+    const int64_t N = g.N, D = g.D, H = g.H, W = g.W, C = g.C, K = g.K, T = g.T, R = g.R, S = g.S;
+    const int groups = g.groups;
+    if (N < 0 || D <= 0 || H <= 0 || W <= 0 || C <= 0 || K <= 0 || T <= 0 || R <= 0 || S <= 0)
+        return fail(TIR_ERR_INVALID_ARG, "non-positive extent (N=%lld D=%lld H=%lld W=%lld C=%lld K=%lld T=%lld R=%lld S=%lld)", (long long)N, (long long)D, (long long)H, (long long)W, (long long)C, (long long)K, (long long)T, (long long)R, (long long)S);
+    if (g.stride_d <= 0 || g.stride_h <= 0 || g.stride_w <= 0 || g.dil_d <= 0 || g.dil_h <= 0 || g.dil_w <= 0 || g.pad_d < 0 || g.pad_h < 0 || g.pad_w < 0)
         return fail(TIR_ERR_INVALID_ARG, "stride and dilation must be positive, padding non-negative");
+    if (g.transposed && (g.outpad_h < 0 || g.outpad_w < 0)) return fail(TIR_ERR_INVALID_ARG, "output padding must be non-negative");
     if (groups <= 0 || C % groups != 0 || K % groups != 0)
         return fail(TIR_ERR_INVALID_ARG, "groups=%d must divide C=%lld and K=%lld", groups, (long long)C, (long long)K);
-    const int64_t P = conv_extent(H, R, stride_h, pad_h, dil_h), Q = conv_extent(W, S, stride_w, pad_w, dil_w);
-    if (P <= 0 || Q <= 0) return fail(TIR_ERR_INVALID_ARG, "empty output: the dilated filter does not fit the padded input");
+    int64_t OD = 1, P, Q;
+    if (g.transposed) {
+        // extent of the adjoint: (in - 1) * stride - 2 * pad + dil * (filt - 1) + outpad + 1
+        P = (H - 1) * g.stride_h - 2 * g.pad_h + (int64_t)g.dil_h * (R - 1) + g.outpad_h + 1;
+        Q = (W - 1) * g.stride_w - 2 * g.pad_w + (int64_t)g.dil_w * (S - 1) + g.outpad_w + 1;
+    } else {
+        OD = conv_extent(D, T, g.stride_d, g.pad_d, g.dil_d);
+        P = conv_extent(H, R, g.stride_h, g.pad_h, g.dil_h);
+        Q = conv_extent(W, S, g.stride_w, g.pad_w, g.dil_w);
+    }
+    if (OD <= 0 || P <= 0 || Q <= 0) return fail(TIR_ERR_INVALID_ARG, "empty output: the dilated filter does not fit the padded input");
     // the kernels keep input coordinates in 16 bits and element offsets in 32 bits
-    if (H > 16383 || W > 16383 || pad_h > 8191 || pad_w > 8191 || (R - 1) * dil_h > 8191 || (S - 1) * dil_w > 8191)
+    if (D > 16383 || H > 16383 || W > 16383 || g.pad_d > 8191 || g.pad_h > 8191 || g.pad_w > 8191 || (T - 1) * g.dil_d > 8191 ||
+        (R - 1) * g.dil_h > 8191 || (S - 1) * g.dil_w > 8191 || P + g.pad_h > 32000 || Q + g.pad_w > 32000)
         return fail(TIR_ERR_UNSUPPORTED, "spatial extent, padding or dilated filter span too large");
     const int64_t Cg = C / groups, Kg = K / groups;
-    const int64_t Mg = N * P * Q, Kd = R * S * Cg;
-    if (N * H * W * C > kMaxExtent || Mg > kMaxExtent || Kd > kMaxExtent || N * P * Q * K > (int64_t)1 << 40)
+    const int64_t Mg = N * OD * P * Q, Kd = T * R * S * Cg;
+    if (N * D * H * W * C > kMaxExtent || Mg > kMaxExtent || Kd > kMaxExtent || Mg * K > (int64_t)1 << 40)
         return fail(TIR_ERR_UNSUPPORTED, "tensor too large for 32-bit element offsets");
     if (N == 0) return TIR_OK;
     if (need_ptrs && (!x || !w || !y)) return fail(TIR_ERR_INVALID_ARG, "x, w or y is null");
 
     const int es = elem_size(in);
     const int vec = 16 / es;
+    const bool plain2d = !g.transposed && D == 1 && T == 1;      // the 2-D kernels (scalar tap cursor, LDS-resident patch) apply
     int amode = A_CONV_GENERIC, bmode = B_GENERIC;
-    if (Cg % vec == 0 && aligned(x, 16) && aligned(w, 16) && N * H * W * C * es < kMaxExtent && (Kd * 256 + Kd) * es < kMaxExtent) {
-        amode = A_CONV;
+    if (Cg % vec == 0 && aligned(x, 16) && aligned(w, 16) && N * D * H * W * C * es < kMaxExtent && (Kd * 256 + Kd) * es < kMaxExtent) {
+        amode = plain2d ? A_CONV : A_CONVX;
         bmode = B_KMAJOR;
     }
     // LDS-resident input patch: one pixel of one group is exactly one 128-byte LDS row, the input rows
     // that 256 consecutive output pixels touch (copied in passes of 64 pixels) fit beside the R*S filter slabs
     const int64_t span_out = (255 + Q - 1) / Q < P - 1 ? (255 + Q - 1) / Q : P - 1;   // output rows a tile can span, minus one
-    const int64_t span_rows = span_out * stride_h + (R - 1) * dil_h + 1;
-    const int64_t patch_w = (Q - 1) * stride_w + (S - 1) * dil_w + 1;
+    const int64_t span_rows = span_out * g.stride_h + (R - 1) * g.dil_h + 1;
+    const int64_t patch_w = (Q - 1) * g.stride_w + (S - 1) * g.dil_w + 1;
     const bool patch_ok = amode == A_CONV && Cg * es == 128 && P * Q >= 128 && (span_rows * patch_w + 63) / 64 * 8192 + R * S * 8192 <= 160 * 1024 &&
                           (K * 256 + Kg) * elem_size(out) < kMaxExtent;
     plan->patch_ok = patch_ok;
     // records are kept under the implicit-GEMM signature; a record (or a trial) may name either kernel family
-    plan->key = TuneKey{1, in, out, amode, bmode, groups * N, P * Q, Kg, Kd, conv_geom(N, groups, H, W, R, S, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w)};
+    const int64_t geom[21] = {N, groups, D, H, W, T, R, S, g.stride_d, g.stride_h, g.stride_w, g.pad_d, g.pad_h, g.pad_w, g.dil_d, g.dil_h, g.dil_w,
+                              g.transposed ? 1 : 0, g.transposed ? g.outpad_h : 0, g.transposed ? g.outpad_w : 0, 0};
+    plan->key = TuneKey{1, in, out, amode, bmode, groups * N, OD * P * Q, Kg, Kd, hash_fields(geom, 21)};
     const Variant* v = nullptr;
     if (g_trial) v = g_trial;
     else if (!g_force_name[0] && !g_force_bm) v = tuned_lookup(plan->key);
@@ -323,14 +347,31 @@ static tir_status plan_conv(bool need_ptrs, const void* x, const void* w, void* 
     p.b_bs = Kg * Kd;       // filters of one group are contiguous
     p.c_bs = Kg;
     p.a_rs = 0; p.a_cs = 1;
-    p.b_rs = 1; p.b_cs = Kd;          // B[k][y] = w[y][k]: the KRSC filter is B stored K-major
-    p.c_rs = K; p.c_cs = 1;           // NHWC output is C_t[fuse(n,h,w)][co]
+    p.b_rs = 1; p.b_cs = Kd;          // B[k][y] = w[y][k]: the filter (output channel major, channel innermost) is B stored K-major
+    p.c_rs = K; p.c_cs = 1;           // the channels-last output is C_t[fuse(n,o,h,w)][co]
     p.c_fast = ((K * 256 + Kg) * elem_size(out) < kMaxExtent) ? 1 : 0;
     if (ep) { p.bias = ep->bias; p.bias_bs = Kg; p.relu = ep->relu != 0; p.scale = ep->scale; }
     p.H = (int)H; p.W = (int)W; p.Cin = (int)C; p.Cg = (int)Cg; p.P = (int)P; p.Q = (int)Q; p.R = (int)R; p.S = (int)S;
-    p.stride_h = stride_h; p.stride_w = stride_w; p.pad_h = pad_h; p.pad_w = pad_w; p.dil_h = dil_h; p.dil_w = dil_w;
+    p.D = (int)D; p.T = (int)T; p.OD = (int)OD;
+    p.stride_d = g.stride_d; p.pad_d = g.pad_d; p.dil_d = g.dil_d;
+    p.dil_h = g.dil_h; p.dil_w = g.dil_w;
+    if (g.transposed) {
+        // gather form of the adjoint: output pixel oh reads input (oh + pad - r*dil) / stride where that is an integer
+        p.stride_h = 1; p.stride_w = 1; p.pad_h = -g.pad_h; p.pad_w = -g.pad_w;
+        p.tap_sign = -1; p.up_h = g.stride_h; p.up_w = g.stride_w;
+    } else {
+        p.stride_h = g.stride_h; p.stride_w = g.stride_w; p.pad_h = g.pad_h; p.pad_w = g.pad_w;
+        p.tap_sign = 1; p.up_h = 1; p.up_w = 1;
+    }
     plan->v = v;
     return TIR_OK;
+}
+
+static tir_status plan_conv(bool need_ptrs, const void* x, const void* w, void* y, int64_t N, int64_t H, int64_t W,
+                            int64_t C, int64_t K, int64_t R, int64_t S, int stride_h, int stride_w, int pad_h,
+                            int pad_w, int dil_h, int dil_w, int groups, int in, int out, const tir_epilogue* ep, Plan* plan) {
+    const ConvGeom g = {N, 1, H, W, C, K, 1, R, S, 1, stride_h, stride_w, 0, pad_h, pad_w, 1, dil_h, dil_w, groups, false, 0, 0};
+    return plan_conv_geom(need_ptrs, x, w, y, g, in, out, ep, plan);
 }
 
 static tir_status run(const Plan& plan, hipStream_t stream) {
@@ -647,6 +688,38 @@ tir_status tir_attention(const void* Q, const void* K, const void* V, void* O, i
     hipError_t e = fn(p, (hipStream_t)stream);
     if (e != hipSuccess) return fail(TIR_ERR_LAUNCH, "attention launch failed: %s", hipGetErrorString(e));
     return TIR_OK;
+}
+
+tir_status tir_conv1d(const void* x, const void* w, void* y, int64_t N, int64_t L, int64_t C, int64_t K, int64_t R,
+                      int stride, int pad, int dil, int groups, tir_dtype in, tir_dtype out, const tir_epilogue* ep,
+                      tir_stream stream) {
+    // a 1-D convolution is the 2-D one on an image of height 1 with a filter of height 1
+    Plan plan;
+    tir_status st = plan_conv(true, x, w, y, N, 1, L, C, K, 1, R, 1, stride, 0, pad, 1, dil, groups, (int)in, (int)out, ep, &plan);
+    if (st != TIR_OK) return st;
+    return run(plan, (hipStream_t)stream);
+}
+
+tir_status tir_conv3d(const void* x, const void* w, void* y, int64_t N, int64_t D, int64_t H, int64_t W, int64_t C,
+                      int64_t K, int64_t T, int64_t R, int64_t S, int stride_d, int stride_h, int stride_w, int pad_d,
+                      int pad_h, int pad_w, int dil_d, int dil_h, int dil_w, int groups, tir_dtype in, tir_dtype out,
+                      const tir_epilogue* ep, tir_stream stream) {
+    const ConvGeom g = {N, D, H, W, C, K, T, R, S, stride_d, stride_h, stride_w, pad_d, pad_h, pad_w, dil_d, dil_h, dil_w, groups, false, 0, 0};
+    Plan plan;
+    tir_status st = plan_conv_geom(true, x, w, y, g, (int)in, (int)out, ep, &plan);
+    if (st != TIR_OK) return st;
+    return run(plan, (hipStream_t)stream);
+}
+
+tir_status tir_conv2d_transpose(const void* x, const void* w, void* y, int64_t N, int64_t H, int64_t W, int64_t C,
+                                int64_t K, int64_t R, int64_t S, int stride_h, int stride_w, int pad_h, int pad_w,
+                                int dil_h, int dil_w, int outpad_h, int outpad_w, int groups, tir_dtype in, tir_dtype out,
+                                const tir_epilogue* ep, tir_stream stream) {
+    const ConvGeom g = {N, 1, H, W, C, K, 1, R, S, 1, stride_h, stride_w, 0, pad_h, pad_w, 1, dil_h, dil_w, groups, true, outpad_h, outpad_w};
+    Plan plan;
+    tir_status st = plan_conv_geom(true, x, w, y, g, (int)in, (int)out, ep, &plan);
+    if (st != TIR_OK) return st;
+    return run(plan, (hipStream_t)stream);
 }
 
 const char* tir_version(void) { return "0.1"; }

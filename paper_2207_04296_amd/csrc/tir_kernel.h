@@ -378,7 +378,7 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
     typedef typename InTraits<C::DT>::acc_t acc_t;
     constexpr int ES = C::ES, VEC = C::VEC, BK = C::BK, ROWB = C::ROWB, NSTAGE = C::NSTAGE, KSTEPS = C::KSTEPS;
     constexpr int L = C::A_IT + C::B_IT;      // copy instructions per wave and stage
-    static_assert(C::AMODE == A_KMAJOR || C::AMODE == A_CONV, "");
+    static_assert(C::AMODE == A_KMAJOR || C::AMODE == A_CONV || C::AMODE == A_CONVX, "");
     static_assert(C::BMODE == B_KMAJOR || C::BMODE == B_NMAJOR, "");
     static_assert((NSTAGE - 2) * L <= 63, "vmcnt range");
     static_assert(KSTEPS % 2 == 0, "fragment sets alternate per k-step and must line up per stage");
@@ -413,6 +413,7 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
     const int a_lc = (tid % C::RCH) ^ kmajor_swz<ROWB>(a_r0);   // same for every i (K_RSTEP % 16 == 0)
     unsigned a_off[C::A_IT];
     int a_hw[C::A_IT];
+    int a_dz[C::AMODE == A_CONVX ? C::A_IT : 1];       // general decode: first input depth of the row's output pixel
     const char* a_base = Ab;
     long long a_bytes = 0;     // valid bytes from a_base (at k = 0)
     if constexpr (C::AMODE == A_KMAJOR) {
@@ -423,6 +424,28 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
 #pragma unroll
         for (int i = 0; i < C::A_IT; ++i)
             a_off[i] = (unsigned)(a_r0 + i * C::K_RSTEP) * (unsigned)(p.a_rs * ES) + a_lc * 16;
+    } else if constexpr (C::AMODE == A_CONVX) {
+        // ReIndex with a depth axis: row m of A_t is output pixel (img, od, op, oq) = unfuse(m); keep the
+        // pixel index of the image's first pixel and the (possibly up-sampled) coordinates of tap (0,0,0)
+        const int PQ = p.P * p.Q, OPQ = p.OD * PQ;
+        a_bytes = ((long long)p.M / OPQ) * p.D * p.H * p.W * p.Cin * ES - bz * p.a_bs * ES;
+#pragma unroll
+        for (int i = 0; i < C::A_IT; ++i) {
+            const int m = m0 + a_r0 + i * C::K_RSTEP;
+            int id0 = 0, ih0 = -30000, iw0 = 0, img = 0;
+            if (m < p.M) {
+                img = m / OPQ;
+                const int rem = m - img * OPQ;
+                const int od = rem / PQ, rem2 = rem - od * PQ;
+                const int op = rem2 / p.Q, oq = rem2 - op * p.Q;
+                id0 = od * p.stride_d - p.pad_d;
+                ih0 = op * p.stride_h - p.pad_h;
+                iw0 = oq * p.stride_w - p.pad_w;
+            }
+            a_off[i] = (unsigned)img * (unsigned)(p.D * p.H * p.W);
+            a_dz[i] = id0;
+            a_hw[i] = (ih0 << 16) | (iw0 & 0xffff);
+        }
     } else {
         // ReIndex: row m of A_t is output pixel (img, op, oq) = unfuse(m); keep the element offset of
         // its top-left input pixel and that pixel's coordinates.
@@ -506,6 +529,34 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
             }
 #pragma unroll
             for (int i = 0; i < C::A_IT; ++i) a_voff[i] = a_off[i];
+        } else if constexpr (C::AMODE == A_CONVX) {
+            // fuse(rt, rh, rw, rc) -> (rt, rh, rw, rc), per lane; taps step by tap_sign, and with up > 1 only
+            // coordinates divisible by it are input pixels (the transposed convolution read as a gather)
+            ra = make_rsrc(Ab, live ? a_bytes : 0);
+            const int kb = stage * BK + a_lc * VEC;
+            const int tap = kb / p.Cg;
+            const int cc = kb - tap * p.Cg;
+            const int RS = p.R * p.S;
+            const int ft = tap / RS, rs = tap - ft * RS;
+            const int fr = rs / p.S, fs = rs - fr * p.S;
+            const int dd = ft * p.dil_d, dh = p.tap_sign * fr * p.dil_h, dw = p.tap_sign * fs * p.dil_w;
+            const bool kv = kb < p.K;
+            const bool up = p.up_h > 1 || p.up_w > 1;
+#pragma unroll
+            for (int i = 0; i < C::A_IT; ++i) {
+                const int idn = a_dz[i] + dd;
+                int ih = (a_hw[i] >> 16) + dh;
+                int iw = (int)(short)(a_hw[i] & 0xffff) + dw;
+                bool ok = kv && (unsigned)idn < (unsigned)p.D && ih >= 0 && iw >= 0;
+                if (up) {
+                    const int qh = ih / p.up_h, qw = iw / p.up_w;
+                    ok = ok && qh * p.up_h == ih && qw * p.up_w == iw;
+                    ih = qh;
+                    iw = qw;
+                }
+                ok = ok && ih < p.H && iw < p.W;
+                a_voff[i] = ok ? ((a_off[i] + (unsigned)((idn * p.H + ih) * p.W + iw)) * (unsigned)p.Cin + (unsigned)cc) * ES : kOutOfRange;
+            }
         } else {
             // fuse(rh, rw, rc) -> (rh, rw, rc); a 16-byte vector never straddles a tap (Cg % VEC == 0)
             ra = make_rsrc(Ab, live ? a_bytes : 0);
@@ -920,21 +971,25 @@ __global__ void __launch_bounds__(C::THREADS) contract_staged_kernel(const Param
     const int r0 = tid >> 3;
     constexpr int RSTEP = C::THREADS / 8;
     unsigned a_off[C::A_IT];
-    int a_hw[C::A_IT];
+    int a_hw[C::A_IT], a_dz[C::A_IT];
     if constexpr (C::AMODE == A_CONV_GENERIC) {
-        const int PQ = p.P * p.Q;
+        // general decode (depth axis, transposed form); a plain 2-D convolution has OD = D = T = 1, up = 1
+        const int PQ = p.P * p.Q, OPQ = p.OD * PQ;
 #pragma unroll
         for (int i = 0; i < C::A_IT; ++i) {
             const int m = m0 + r0 + i * RSTEP;
-            int ih0 = -30000, iw0 = 0, img = 0;
+            int id0 = 0, ih0 = -30000, iw0 = 0, img = 0;
             if (m < p.M) {
-                img = m / PQ;
-                const int rem = m - img * PQ;
-                const int op = rem / p.Q, oq = rem - op * p.Q;
+                img = m / OPQ;
+                const int rem = m - img * OPQ;
+                const int od = rem / PQ, rem2 = rem - od * PQ;
+                const int op = rem2 / p.Q, oq = rem2 - op * p.Q;
+                id0 = od * p.stride_d - p.pad_d;
                 ih0 = op * p.stride_h - p.pad_h;
                 iw0 = oq * p.stride_w - p.pad_w;
             }
-            a_off[i] = (((unsigned)img * (unsigned)p.H + (unsigned)ih0) * (unsigned)p.W + (unsigned)iw0) * (unsigned)p.Cin;
+            a_off[i] = (unsigned)img * (unsigned)(p.D * p.H * p.W);
+            a_dz[i] = id0;
             a_hw[i] = (ih0 << 16) | (iw0 & 0xffff);
         }
     }
@@ -959,12 +1014,16 @@ __global__ void __launch_bounds__(C::THREADS) contract_staged_kernel(const Param
                     const int kb = k0 + c8 * VEC + e;
                     const int tap = kb / p.Cg;
                     const int cc = kb - tap * p.Cg;
-                    const int fr = tap / p.S, fs = tap - fr * p.S;
-                    const int dh = fr * p.dil_h, dw = fs * p.dil_w;
-                    const int ih = (a_hw[i] >> 16) + dh;
-                    const int iw = (int)(short)(a_hw[i] & 0xffff) + dw;
-                    const bool ok = kb < p.K && (unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W;
-                    v[e] = ok ? A[(long long)(int)(a_off[i] + (unsigned)((dh * p.W + dw) * p.Cin + cc))] : (elem_t)0;
+                    const int RS = p.R * p.S;
+                    const int ft = tap / RS, rs = tap - ft * RS;
+                    const int fr = rs / p.S, fs = rs - fr * p.S;
+                    const int idn = a_dz[i] + ft * p.dil_d;
+                    int ih = (a_hw[i] >> 16) + p.tap_sign * fr * p.dil_h;
+                    int iw = (int)(short)(a_hw[i] & 0xffff) + p.tap_sign * fs * p.dil_w;
+                    bool ok = kb < p.K && (unsigned)idn < (unsigned)p.D && ih >= 0 && iw >= 0;
+                    const int qh = ih / p.up_h, qw = iw / p.up_w;
+                    ok = ok && qh * p.up_h == ih && qw * p.up_w == iw && qh < p.H && qw < p.W;
+                    v[e] = ok ? A[(long long)(a_off[i] + (unsigned)((idn * p.H + qh) * p.W + qw)) * p.Cin + cc] : (elem_t)0;
                 }
             }
             ra[i] = *(const uint4*)v;

@@ -13,7 +13,9 @@ enum : int {
     A_CONV = 1,     // implicit im2col of an NHWC tensor, channel vectors of 16 bytes
     A_GENERIC = 2,  // any strides, element-wise loads
     A_CONV_GENERIC = 3,  // implicit im2col, element-wise (C/groups not a multiple of the vector)
-    A_CONV_PATCH = 4     // convolution reading its taps from an LDS-resident input patch (128 B per pixel)
+    A_CONV_PATCH = 4,    // convolution reading its taps from an LDS-resident input patch (128 B per pixel)
+    A_CONVX = 5          // implicit im2col with the general coordinate decode: a depth axis (3-D convolution) and the
+                         // transposed form (taps step backwards, only every up-th coordinate is an input pixel)
 };
 enum : int {
     B_KMAJOR = 0,   // B stored [y][k], k contiguous (a "transposed" B, or a KRSC filter)
@@ -34,6 +36,12 @@ struct Params {
     // convolution geometry (A_CONV*): x is [n][H][W][Cin], one group reads Cg channels
     int H, W, Cin, Cg, P, Q, R, S;
     int stride_h, stride_w, pad_h, pad_w, dil_h, dil_w;
+    // general convolution decode (A_CONVX, A_CONV_GENERIC); a plain 2-D convolution has D = T = OD = 1, stride_d = dil_d = 1,
+    // pad_d = 0, tap_sign = 1, up_h = up_w = 1.  Input coordinate of output pixel (o, p, q) and tap (t, r, s):
+    //   depth  o*stride_d - pad_d + t*dil_d
+    //   height (p*stride_h - pad_h + tap_sign*r*dil_h) / up_h   if divisible by up_h, else the tap reads zero; width alike
+    int D, T, OD, stride_d, pad_d, dil_d;
+    int tap_sign, up_h, up_w;
     int PW;           // patch kernel: columns of the LDS-resident input patch
     int batch_imgs;   // patch kernel: images in x (for the descriptor)
     // fused consumer: out = cvt(relu(acc + bias[column])); bias is fp32 (float inputs) or int32 (int8 inputs)

@@ -218,3 +218,39 @@ def test_attention_rejects_bad_arguments_on_the_host():
     assert st(V=0) == B.TIR_ERR_INVALID_ARG
     assert st(O=FAKE + 8) == B.TIR_ERR_ALIGNMENT
     assert st(M=0) == B.TIR_OK and st(batch=0) == B.TIR_OK          # nothing to do: no launch, no device needed
+
+
+def test_conv1d_conv3d_and_transposed_conv_validate_on_the_host():
+    L = B.lib()
+    def c1(**kw):
+        a = dict(N=1, L=32, C=16, K=16, R=3, stride=1, pad=1, dil=1, groups=1)
+        a.update(kw)
+        return L.tir_conv1d(FAKE, FAKE, FAKE, a["N"], a["L"], a["C"], a["K"], a["R"], a["stride"], a["pad"], a["dil"], a["groups"],
+                            B.TIR_F16, B.TIR_F32, None, None)
+    assert c1(stride=0) == B.TIR_ERR_INVALID_ARG
+    assert c1(groups=3) == B.TIR_ERR_INVALID_ARG
+    assert c1(L=2, R=5, pad=0) == B.TIR_ERR_INVALID_ARG          # empty output
+    assert c1(N=0) == B.TIR_OK
+
+    def c3(**kw):
+        a = dict(N=1, D=4, H=8, W=8, C=16, K=16, T=3, R=3, S=3, s=(1, 1, 1), p=(1, 1, 1), d=(1, 1, 1), groups=1)
+        a.update(kw)
+        return L.tir_conv3d(FAKE, FAKE, FAKE, a["N"], a["D"], a["H"], a["W"], a["C"], a["K"], a["T"], a["R"], a["S"], *a["s"], *a["p"], *a["d"],
+                            a["groups"], B.TIR_F16, B.TIR_F16, None, None)
+    assert c3(D=0) == B.TIR_ERR_INVALID_ARG
+    assert c3(d=(0, 1, 1)) == B.TIR_ERR_INVALID_ARG
+    assert c3(p=(-1, 0, 0)) == B.TIR_ERR_INVALID_ARG
+    assert c3(D=2, T=5, p=(0, 1, 1)) == B.TIR_ERR_INVALID_ARG    # empty output along the depth
+    assert c3(D=20000) == B.TIR_ERR_UNSUPPORTED
+    assert c3(N=0) == B.TIR_OK
+
+    def ct(**kw):
+        a = dict(N=1, H=8, W=8, C=16, K=16, R=3, S=3, s=(2, 2), p=(1, 1), d=(1, 1), op=(1, 1), groups=1)
+        a.update(kw)
+        return L.tir_conv2d_transpose(FAKE, FAKE, FAKE, a["N"], a["H"], a["W"], a["C"], a["K"], a["R"], a["S"], *a["s"], *a["p"], *a["d"], *a["op"],
+                                      a["groups"], B.TIR_I8, B.TIR_I32, None, None)
+    assert ct(op=(-1, 0)) == B.TIR_ERR_INVALID_ARG
+    assert ct(s=(0, 1)) == B.TIR_ERR_INVALID_ARG
+    assert ct(H=1, W=1, R=1, S=1, p=(1, 1), op=(0, 0), s=(1, 1)) == B.TIR_ERR_INVALID_ARG   # extent (1-1)*1 - 2 + 0 + 0 + 1 < 1
+    assert ct(K=15, groups=2) == B.TIR_ERR_INVALID_ARG
+    assert ct(N=0) == B.TIR_OK

@@ -538,3 +538,79 @@ def test_seeded_random_problems(B, oracle, seed):
         ref, S = PT.run_oracle(wl, a_bits, b_bits, oracle)
         got = PT.run_gpu(wl, a_bits, b_bits)
         PT.assert_close(got, ref, S, wl.name)
+
+
+# ------------------------------------------------------------------------------ conv1d / conv3d / transposed conv2d
+def _gpu_out(B, shape, out):
+    o = B.empty_out(shape, out)
+    if o.dtype.is_floating_point:
+        o.fill_(float("nan"))
+    else:
+        o.fill_(-77)
+    return o
+
+
+@pytest.mark.parametrize("dtype,out", [("f16", "f16"), ("bf16", "f32"), ("i8", "i32")])
+def test_conv1d_matches_oracle(B, oracle, dtype, out):
+    import torch
+    dist = "i" if dtype == "i8" else "n0.1"
+    for (N, L, C, K, R, stride, pad, dil, groups) in [(3, 300, 32, 48, 5, 1, 2, 1, 1), (2, 129, 64, 40, 3, 2, 1, 2, 2), (1, 50, 6, 10, 7, 3, 3, 1, 2),
+                                                      (2, 1000, 16, 16, 9, 1, 4, 1, 1)]:
+        _say(f"conv1d {dtype} N={N} L={L} C={C} K={K} R={R} s={stride} p={pad} d={dil} g={groups}")
+        xb = I.make_tensor(dtype, dist, 9900 + L, (N, L, C)); wb = I.make_tensor(dtype, dist, 9901 + K, (K, R, C // groups))
+        ref, S = oracle.conv1d(dtype, xb, wb, stride, pad, dil, groups)
+        y = _gpu_out(B, ref.shape, out)
+        B.tir_conv1d(B.to_device(xb, dtype), B.to_device(wb, dtype), y, N, L, C, K, R, stride, pad, dil, groups, dtype, out)
+        torch.cuda.synchronize()
+        PT.assert_close(PT.gpu_to_f64(y), ref, S, "conv1d")
+
+
+@pytest.mark.parametrize("dtype,out", [("f16", "f16"), ("f16", "f32"), ("bf16", "f32"), ("i8", "i32")])
+def test_conv3d_matches_oracle(B, oracle, dtype, out):
+    import torch
+    dist = "i" if dtype == "i8" else "n0.1"
+    vec = 16 if dtype == "i8" else 8
+    cases = [
+        # N, D, H, W, C, K, T, R, S, stride, pad, dil, groups
+        (2, 6, 9, 10, 2 * vec, 40, 3, 3, 3, (1, 1, 1), (1, 1, 1), (1, 1, 1), 1),      # vector path, several tiles
+        (1, 8, 7, 12, 4 * vec, 48, 2, 3, 2, (2, 1, 2), (0, 1, 1), (2, 1, 1), 2),      # strides, dilation in depth, groups
+        (2, 5, 6, 7, 6, 10, 3, 2, 2, (1, 2, 1), (1, 0, 1), (1, 1, 2), 2),             # odd channel count: element-wise kernel
+        (1, 1, 12, 12, vec, 24, 1, 3, 3, (1, 1, 1), (0, 1, 1), (1, 1, 1), 1),         # depth 1: must equal conv2d
+        (1, 10, 16, 16, 8 * vec, 64, 3, 3, 3, (1, 1, 1), (1, 1, 1), (1, 1, 1), 1),    # a ResNet-3D-like block
+    ]
+    for (N, D, H, W, C, K, T, R, S_, stride, pad, dil, groups) in cases:
+        _say(f"conv3d {dtype}->{out} N={N} D={D} H={H} W={W} C={C} K={K} T={T} R={R} S={S_} s={stride} p={pad} d={dil} g={groups}")
+        xb = I.make_tensor(dtype, dist, 9910 + H, (N, D, H, W, C)); wb = I.make_tensor(dtype, dist, 9911 + K, (K, T, R, S_, C // groups))
+        ref, S = oracle.conv3d(dtype, xb, wb, stride, pad, dil, groups)
+        y = _gpu_out(B, ref.shape, out)
+        B.tir_conv3d(B.to_device(xb, dtype), B.to_device(wb, dtype), y, N, D, H, W, C, K, T, R, S_, stride, pad, dil, groups, dtype, out)
+        torch.cuda.synchronize()
+        PT.assert_close(PT.gpu_to_f64(y), ref, S, "conv3d")
+        if D == 1 and T == 1:
+            y2 = _gpu_out(B, ref.shape[:1] + ref.shape[2:], out)
+            B.tir_conv2d(B.to_device(xb[:, 0], dtype), B.to_device(wb[:, 0], dtype), y2, N, H, W, C, K, R, S_, *stride[1:], *pad[1:], *dil[1:], groups, dtype, out)
+            torch.cuda.synchronize()
+            PT.assert_close(PT.gpu_to_f64(y2), ref[:, 0], S if S is None else S[:, 0], "conv3d depth 1 vs conv2d")
+
+
+@pytest.mark.parametrize("dtype,out", [("f16", "f16"), ("f16", "f32"), ("bf16", "f32"), ("i8", "i32")])
+def test_conv2d_transpose_matches_oracle(B, oracle, dtype, out):
+    import torch
+    dist = "i" if dtype == "i8" else "n0.1"
+    vec = 16 if dtype == "i8" else 8
+    cases = [
+        # N, H, W, C, K, R, S, stride, pad, dil, outpad, groups
+        (2, 14, 14, 4 * vec, 48, 3, 3, (2, 2), (1, 1), (1, 1), (1, 1), 1),      # the usual 2x up-sampling block
+        (1, 9, 11, 2 * vec, 40, 4, 4, (2, 2), (1, 1), (1, 1), (0, 0), 1),       # 4x4 filter, stride 2
+        (2, 7, 8, 4 * vec, 32, 3, 2, (3, 2), (0, 1), (2, 1), (2, 0), 2),        # uneven strides, dilation, groups
+        (1, 12, 12, vec, 24, 3, 3, (1, 1), (1, 1), (1, 1), (0, 0), 1),          # stride 1: a convolution with the taps reversed
+        (2, 6, 5, 6, 10, 2, 3, (2, 3), (0, 0), (1, 1), (1, 2), 2),              # odd channel count: element-wise kernel
+    ]
+    for (N, H, W, C, K, R, S_, stride, pad, dil, outpad, groups) in cases:
+        _say(f"conv2d_transpose {dtype}->{out} N={N} H={H} W={W} C={C} K={K} R={R} S={S_} s={stride} p={pad} d={dil} op={outpad} g={groups}")
+        xb = I.make_tensor(dtype, dist, 9920 + H, (N, H, W, C)); wb = I.make_tensor(dtype, dist, 9921 + K, (K, R, S_, C // groups))
+        ref, S = oracle.conv2d_transpose(dtype, xb, wb, stride, pad, dil, outpad, groups)
+        y = _gpu_out(B, ref.shape, out)
+        B.tir_conv2d_transpose(B.to_device(xb, dtype), B.to_device(wb, dtype), y, N, H, W, C, K, R, S_, stride, pad, dil, outpad, groups, dtype, out)
+        torch.cuda.synchronize()
+        PT.assert_close(PT.gpu_to_f64(y), ref, S, "conv2d_transpose")
