@@ -241,7 +241,7 @@ def main():
 
     operators = []
     if not args.no_operators:
-        for name, o in list(I.WORKLOADS.items()) + list(I.FUSED_WORKLOADS.items()):
+        for name, o in list(I.WORKLOADS.items()) + list(I.FUSED_WORKLOADS.items()) + list(I.MORE_WORKLOADS.items()):
             k = 20 if o.flops() > 4e10 else 200
             s = make_sets(B, o, 1)
             if not args.no_tune:

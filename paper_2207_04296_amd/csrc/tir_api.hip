@@ -13,6 +13,7 @@
 #include "tir.h"
 #include "tir_launch.h"
 #include "tir_attention.h"
+#include "tir_depthwise.h"
 
 namespace tir {
 
@@ -58,6 +59,24 @@ static const Variant kVariants[] = {
 #include "tir_variants.def"
 };
 static const int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
+
+// The depth-wise kernel is not a tile variant: one entry per dtype pair, filled on first use.
+static const Variant* depthwise_variant(int dt, int out) {
+    static Variant table[6] = {
+        {"f16_f16_depthwise", DT_F16, DT_F16, 0, 0, 0, 0, A_DEPTHWISE, B_GENERIC, 0, 0, 1, nullptr},
+        {"f16_f32_depthwise", DT_F16, DT_F32, 0, 0, 0, 0, A_DEPTHWISE, B_GENERIC, 0, 0, 1, nullptr},
+        {"bf16_bf16_depthwise", DT_BF16, DT_BF16, 0, 0, 0, 0, A_DEPTHWISE, B_GENERIC, 0, 0, 1, nullptr},
+        {"bf16_f32_depthwise", DT_BF16, DT_F32, 0, 0, 0, 0, A_DEPTHWISE, B_GENERIC, 0, 0, 1, nullptr},
+        {"i8_i32_depthwise", DT_I8, DT_I32, 0, 0, 0, 0, A_DEPTHWISE, B_GENERIC, 0, 0, 1, nullptr},
+        {"i8_i8_depthwise", DT_I8, DT_I8, 0, 0, 0, 0, A_DEPTHWISE, B_GENERIC, 0, 0, 1, nullptr},
+    };
+    for (Variant& v : table)
+        if (v.dt == dt && v.out == out) {
+            if (!v.fn) v.fn = depthwise_launcher(dt, out);      // idempotent: racing threads store the same pointer
+            return v.fn ? &v : nullptr;
+        }
+    return nullptr;
+}
 
 static thread_local char g_err[512] = "";
 static int g_force_bm = 0, g_force_bn = 0;
@@ -321,7 +340,14 @@ static tir_status plan_conv_geom(bool need_ptrs, const void* x, const void* w, v
                               g.transposed ? 1 : 0, g.transposed ? g.outpad_h : 0, g.transposed ? g.outpad_w : 0, 0};
     plan->key = TuneKey{1, in, out, amode, bmode, groups * N, OD * P * Q, Kg, Kd, hash_fields(geom, 21)};
     const Variant* v = nullptr;
-    if (g_trial) v = g_trial;
+    // depth-wise (one input and one output channel per group): the direct kernel, unless a test forces a tile variant
+    if (plain2d && Cg == 1 && Kg == 1 && C % vec == 0 && R * S <= kDwMaxTaps && aligned(x, 16) && aligned(w, 16) && aligned(y, 16) &&
+        N * H * W * C * es < kMaxExtent && Mg * K * elem_size(out) < kMaxExtent && !g_trial &&
+        !g_force_name[0] && !g_force_bm)
+        v = depthwise_variant(in, out);
+    const bool depthwise = v != nullptr;
+    if (depthwise) amode = A_DEPTHWISE;
+    else if (g_trial) v = g_trial;
     else if (!g_force_name[0] && !g_force_bm) v = tuned_lookup(plan->key);
     if (v && v->amode == A_CONV_PATCH && !patch_ok) v = nullptr;
     if (!v) {
@@ -335,14 +361,14 @@ static tir_status plan_conv_geom(bool need_ptrs, const void* x, const void* w, v
     memset(&p, 0, sizeof p);
     p.A = x; p.B = w; p.C = y;
     p.M = (int)Mg; p.N = (int)Kg; p.K = (int)Kd;
-    p.batch = groups;
-    p.tiles_m = (int)((Mg + v->bm - 1) / v->bm);
-    p.tiles_n = (int)((Kg + v->bn - 1) / v->bn);
+    p.batch = depthwise ? 1 : groups;                 // the depth-wise kernel covers every channel in one launch
+    p.tiles_m = depthwise ? 1 : (int)((Mg + v->bm - 1) / v->bm);
+    p.tiles_n = depthwise ? 1 : (int)((Kg + v->bn - 1) / v->bn);
     if (amode == A_CONV_PATCH) {
         p.tiles_m = (int)((P * Q + 255) / 256);      // pixel tiles per image
         p.PW = (int)patch_w;
-        p.batch_imgs = (int)N;
     }
+    p.batch_imgs = (int)N;
     p.a_bs = Cg;            // a group starts Cg channels further
     p.b_bs = Kg * Kd;       // filters of one group are contiguous
     p.c_bs = Kg;

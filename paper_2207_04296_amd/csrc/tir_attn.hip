@@ -1,5 +1,7 @@
-// Instantiations of the fused attention kernel and the table the dispatcher picks from.
+// Instantiations of the kernels outside the tile-variant table (fused attention, depth-wise
+// convolution) and the tables the dispatcher picks from.
 #include "tir_attention.h"
+#include "tir_depthwise.h"
 
 namespace tir {
 
@@ -14,6 +16,23 @@ attn_launch_fn attention_launcher(int dt, int out, int dh) {
     TIR_ATTN(DT_F16, DT_F16, 64) TIR_ATTN(DT_F16, DT_F32, 64) TIR_ATTN(DT_F16, DT_F16, 128) TIR_ATTN(DT_F16, DT_F32, 128)
     TIR_ATTN(DT_BF16, DT_BF16, 64) TIR_ATTN(DT_BF16, DT_F32, 64) TIR_ATTN(DT_BF16, DT_BF16, 128) TIR_ATTN(DT_BF16, DT_F32, 128)
 #undef TIR_ATTN
+    return nullptr;
+}
+
+template <int DT, int OUT> static hipError_t launch_dw(const Params& p, hipStream_t stream) {
+    constexpr int VEC = 16 / elem_size(DT);
+    constexpr int PP = 256 / (kDwChannels / VEC);
+    dim3 grid((unsigned)((p.M + kDwPixPerThread * PP - 1) / (kDwPixPerThread * PP)), (unsigned)((p.Cin + kDwChannels - 1) / kDwChannels));
+    if (p.R == 3 && p.S == 3) hipLaunchKernelGGL((depthwise_kernel<DT, OUT, true>), grid, dim3(256), 0, stream, p);
+    else hipLaunchKernelGGL((depthwise_kernel<DT, OUT, false>), grid, dim3(256), 0, stream, p);
+    return hipGetLastError();
+}
+
+dw_launch_fn depthwise_launcher(int dt, int out) {
+#define TIR_DW(DT, OUT) \
+    if (dt == DT && out == OUT) return &launch_dw<DT, OUT>;
+    TIR_DW(DT_F16, DT_F16) TIR_DW(DT_F16, DT_F32) TIR_DW(DT_BF16, DT_BF16) TIR_DW(DT_BF16, DT_F32) TIR_DW(DT_I8, DT_I32) TIR_DW(DT_I8, DT_I8)
+#undef TIR_DW
     return nullptr;
 }
 

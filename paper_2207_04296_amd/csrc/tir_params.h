@@ -14,6 +14,7 @@ enum : int {
     A_GENERIC = 2,  // any strides, element-wise loads
     A_CONV_GENERIC = 3,  // implicit im2col, element-wise (C/groups not a multiple of the vector)
     A_CONV_PATCH = 4,    // convolution reading its taps from an LDS-resident input patch (128 B per pixel)
+    A_DEPTHWISE = 6,     // depth-wise 2-D convolution (one filter per channel): direct kernel, no matrix intrinsic
     A_CONVX = 5          // implicit im2col with the general coordinate decode: a depth axis (3-D convolution) and the
                          // transposed form (taps step backwards, only every up-th coordinate is an input pixel)
 };

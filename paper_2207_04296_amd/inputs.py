@@ -218,5 +218,18 @@ def _fused_cfgs():
     return {x.name: x for x in w}
 
 
+def _more_cfgs():
+    """Operators of the paper's evaluation set beyond the five benchmark configurations that fit the 2-D
+    convolution entry point: the depth-wise convolution of a MobileNet-style block (groups = channels)."""
+    w = [
+        Workload("dep_conv56x128_f16", "conv2d", "f16", "f16", "n0.1", 6000, n=16, h=56, w=56, c=128, k=128, r=3, s=3,
+                 stride=(1, 1), pad=(1, 1), groups=128),
+        Workload("dep_conv112x32s2_i8_requant", "conv2d", "i8", "i8", "i", 6100, n=16, h=112, w=112, c=32, k=32, r=3, s=3,
+                 stride=(2, 2), pad=(1, 1), groups=32, ep_bias=True, ep_relu=True, ep_scale=1.0 / 400.0),
+    ]
+    return {x.name: x for x in w}
+
+
 WORKLOADS = _cfgs()
 FUSED_WORKLOADS = _fused_cfgs()
+MORE_WORKLOADS = _more_cfgs()

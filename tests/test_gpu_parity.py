@@ -43,11 +43,11 @@ def test_config_full_size(B, oracle, name):
     _say(f"{name} max err/tol {ratio:.3g}")
 
 
-@pytest.mark.parametrize("name", list(I.FUSED_WORKLOADS))
+@pytest.mark.parametrize("name", list(I.FUSED_WORKLOADS) + list(I.MORE_WORKLOADS))
 def test_config_full_size_with_fused_consumer(B, oracle, name):
     """The benchmark operators with a consumer fused behind the tensorized block: bias + ReLU, down-cast
-    to fp16, int8 requantisation (codes must match the oracle exactly)."""
-    wl = I.FUSED_WORKLOADS[name]
+    to fp16, int8 requantisation (codes must match the oracle exactly); and the depth-wise blocks."""
+    wl = I.FUSED_WORKLOADS.get(name) or I.MORE_WORKLOADS[name]
     _say(f"{name} variant auto")
     ratio = PT.check_workload(wl, oracle)
     _say(f"{name} max err/tol {ratio:.3g}")
@@ -614,3 +614,35 @@ def test_conv2d_transpose_matches_oracle(B, oracle, dtype, out):
         B.tir_conv2d_transpose(B.to_device(xb, dtype), B.to_device(wb, dtype), y, N, H, W, C, K, R, S_, stride, pad, dil, outpad, groups, dtype, out)
         torch.cuda.synchronize()
         PT.assert_close(PT.gpu_to_f64(y), ref, S, "conv2d_transpose")
+
+
+# ------------------------------------------------------------------------------ depth-wise convolution
+DEPTHWISE_CASES = [
+    # dtype, out, n, h, w, c, r, s, stride, pad, dil, bias, relu, scale
+    ("f16", "f16", 2, 20, 23, 64, 3, 3, (1, 1), (1, 1), (1, 1), False, False, 0.0),
+    ("f16", "f32", 1, 17, 19, 24, 5, 5, (2, 2), (2, 2), (1, 1), True, True, 0.0),        # 24 channels: part of a 64-channel block
+    ("bf16", "f32", 2, 15, 15, 136, 3, 3, (1, 2), (2, 1), (2, 2), True, False, 0.0),    # three channel blocks, the last partial
+    ("bf16", "bf16", 1, 9, 9, 8, 3, 1, (1, 1), (1, 0), (1, 1), False, True, 0.0),
+    ("i8", "i32", 2, 14, 14, 32, 3, 3, (1, 1), (1, 1), (1, 1), True, False, 0.0),
+    ("i8", "i8", 3, 28, 28, 80, 3, 3, (2, 2), (1, 1), (1, 1), True, True, 1.0 / 300.0),
+    ("f16", "f16", 1, 10, 10, 20, 3, 3, (1, 1), (1, 1), (1, 1), False, False, 0.0),     # 20 channels: not a whole vector, general kernel
+    ("f16", "f32", 1, 12, 12, 16, 3, 3, (1, 1), (1, 1), (1, 1), False, False, 0.0),
+]
+
+
+@pytest.mark.parametrize("case", DEPTHWISE_CASES, ids=lambda c: f"{c[0]}-{c[1]}-c{c[5]}-{c[6]}x{c[7]}")
+def test_depthwise_convolution(B, oracle, case):
+    dtype, out, n, h, w, c, r, s, stride, pad, dil, bias, relu, scale = case
+    wl = I.Workload(f"dw_{dtype}_{out}_c{c}", "conv2d", dtype, out, "i" if dtype == "i8" else "n0.1", 9950 + c, n=n, h=h, w=w, c=c, k=c,
+                    r=r, s=s, stride=stride, pad=pad, dil=dil, groups=c, ep_bias=bias, ep_relu=relu, ep_scale=scale)
+    name = PT.variant_name(B, wl)
+    _say(f"{wl.name} -> {name}")
+    vec = 16 if dtype == "i8" else 8
+    assert ("depthwise" in name) == (c % vec == 0), name
+    a_bits, b_bits = wl.operands()
+    ref, S = PT.run_oracle(wl, a_bits, b_bits, oracle)
+    got = PT.run_gpu(wl, a_bits, b_bits)
+    if out == "bf16":
+        assert np.all(np.abs(got - ref) <= PT.RTOL_S * S + PT.ATOL + np.abs(ref) * 2.0 ** -8)
+    else:
+        PT.assert_close(got, ref, S, wl.name)
