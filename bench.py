@@ -168,6 +168,55 @@ def attention_row(torch, B, I):
             "gbs": round(nbytes / sec / 1e9, 1), "cache": "hot"}
 
 
+def _graph_time(torch, fn, steps=100):
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        for _ in range(5):
+            fn(stream)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            for _ in range(steps):
+                fn(stream)
+        graph.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        graph.replay()
+        e1.record(stream)
+        torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e-3 / steps
+
+
+def other_conv_rows(torch, B, I):
+    """1-D, 3-D and transposed 2-D convolution (the rest of the paper's operator set), fp16, synthetic shapes."""
+    rows = []
+
+    def row(name, variant, sec, flops, nbytes):
+        tf = flops / sec / 1e12
+        rows.append({"workload": name, "variant": variant, "out": "f16", "fused": "",
+                     "us": round(sec * 1e6, 3), "tflops": round(tf, 2), "frac_mfma_peak": round(tf / PEAK_TFLOPS["f16"], 4),
+                     "frac_attainable": round(tf / min(PEAK_TFLOPS["f16"], flops / nbytes * HBM_GBS / 1e3), 4),
+                     "gbs": round(nbytes / sec / 1e9, 1), "cache": "hot"})
+    dev = lambda shape, seed: B.to_device(I.make_tensor("f16", "n0.1", seed, shape), "f16")
+    # conv1d: 16 x 4096 x 128 -> 128, 9 taps
+    N, L, C, K, R = 16, 4096, 128, 128, 9
+    x, w, y = dev((N, L, C), 7000), dev((K, R, C), 7001), B.empty_out((N, L, K), "f16")
+    sec = _graph_time(torch, lambda st: B.tir_conv1d(x, w, y, N, L, C, K, R, 1, 4, 1, 1, "f16", "f16", stream=st))
+    row("c1d_16x4096x128_k9_f16", B.tir_conv2d_variant(N, 1, L, C, K, 1, R, 1, 1, 0, 4, 1, 1, 1, "f16", "f16"), sec, 2.0 * N * L * K * R * C, 2.0 * (N * L * C + K * R * C + N * L * K))
+    # conv3d: 1 x 10 x 16 x 16 x 128 -> 64, 3x3x3
+    N, D, H, W, C, K = 1, 10, 16, 16, 128, 64
+    x, w, y = dev((N, D, H, W, C), 7010), dev((K, 3, 3, 3, C), 7011), B.empty_out((N, D, H, W, K), "f16")
+    sec = _graph_time(torch, lambda st: B.tir_conv3d(x, w, y, N, D, H, W, C, K, 3, 3, 3, (1, 1, 1), (1, 1, 1), (1, 1, 1), 1, "f16", "f16", stream=st))
+    row("c3d_10x16x16x128_k3_f16", "general convolution decode (depth axis)", sec, 2.0 * N * D * H * W * K * 27 * C, 2.0 * (N * D * H * W * (C + K) + K * 27 * C))
+    # transposed conv2d: 16 x 28 x 28 x 64 -> 56 x 56 x 64, 4x4, stride 2 (FLOPs of the taps that exist, not of the gather's zeros)
+    N, H, W, C, K = 16, 28, 28, 64, 64
+    x, w, y = dev((N, H, W, C), 7020), dev((K, 4, 4, C), 7021), B.empty_out((N, 56, 56, K), "f16")
+    sec = _graph_time(torch, lambda st: B.tir_conv2d_transpose(x, w, y, N, H, W, C, K, 4, 4, (2, 2), (1, 1), (1, 1), (0, 0), 1, "f16", "f16", stream=st))
+    row("t2d_28x28x64_k4s2_f16", "general convolution decode (transposed, gather form)", sec, 2.0 * N * H * W * K * 16 * C, 2.0 * (N * H * W * C + K * 16 * C + N * 56 * 56 * K))
+    return rows
+
+
 def cpu_baseline(wl):
     """The oracle, as it stands, on this machine's host cores; whole workload, repeated for ~seconds."""
     import oracle
@@ -257,6 +306,7 @@ def main():
                               "gbs": round(o.min_bytes() * k / e_ / 1e9, 1), "cache": "hot"})
             del s
         operators.append(attention_row(torch, B, I))
+        operators.extend(other_conv_rows(torch, B, I))
 
     out = {
         "metric": "TFLOP/s and % of MI355X MFMA peak per operator (fp16 GEMM, conv2d)",

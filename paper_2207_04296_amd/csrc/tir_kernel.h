@@ -498,13 +498,19 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
 
     // Per-stage copy state: descriptors (SGPRs) and, for the convolution, this stage's offsets and
     // the scalar tap cursor (filter row, filter column, channel offset of the next stage).
-    const bool conv_uniform_tap = (C::AMODE == A_CONV) && (p.Cg % BK == 0);
-    int conv_fr = 0, conv_fs = 0, conv_cc = 0;
+    const bool conv_uniform_tap = (C::AMODE == A_CONV || C::AMODE == A_CONVX) && (p.Cg % BK == 0);
+    int conv_ft = 0, conv_fr = 0, conv_fs = 0, conv_cc = 0;
     auto conv_advance = [&](int stages) {                // move the tap cursor `stages` stages ahead
         conv_cc += stages * BK;
         while (conv_cc >= p.Cg) {
             conv_cc -= p.Cg;
-            if (++conv_fs == p.S) { conv_fs = 0; ++conv_fr; }
+            if (++conv_fs == p.S) {
+                conv_fs = 0;
+                ++conv_fr;
+                if constexpr (C::AMODE == A_CONVX) {
+                    if (conv_fr == p.R) { conv_fr = 0; ++conv_ft; }
+                }
+            }
         }
     };
     if (conv_uniform_tap && C::KW > 1) conv_advance(kgrp);
@@ -533,14 +539,26 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
             // fuse(rt, rh, rw, rc) -> (rt, rh, rw, rc), per lane; taps step by tap_sign, and with up > 1 only
             // coordinates divisible by it are input pixels (the transposed convolution read as a gather)
             ra = make_rsrc(Ab, live ? a_bytes : 0);
-            const int kb = stage * BK + a_lc * VEC;
-            const int tap = kb / p.Cg;
-            const int cc = kb - tap * p.Cg;
-            const int RS = p.R * p.S;
-            const int ft = tap / RS, rs = tap - ft * RS;
-            const int fr = rs / p.S, fs = rs - fr * p.S;
+            int ft, fr, fs, cc;
+            bool kv;
+            if (conv_uniform_tap) {
+                // Cg is a multiple of the stage's k extent: one tap per stage, decoded by the scalar cursor
+                ft = conv_ft; fr = conv_fr; fs = conv_fs;
+                cc = conv_cc + a_lc * VEC;
+                kv = live;
+                conv_advance(C::KW);
+            } else {
+                const int kb = stage * BK + a_lc * VEC;
+                const int tap = kb / p.Cg;
+                cc = kb - tap * p.Cg;
+                const int RS = p.R * p.S;
+                ft = tap / RS;
+                const int rs = tap - ft * RS;
+                fr = rs / p.S;
+                fs = rs - fr * p.S;
+                kv = kb < p.K;
+            }
             const int dd = ft * p.dil_d, dh = p.tap_sign * fr * p.dil_h, dw = p.tap_sign * fs * p.dil_w;
-            const bool kv = kb < p.K;
             const bool up = p.up_h > 1 || p.up_w > 1;
 #pragma unroll
             for (int i = 0; i < C::A_IT; ++i) {
