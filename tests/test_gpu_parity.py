@@ -646,3 +646,13 @@ def test_depthwise_convolution(B, oracle, case):
         assert np.all(np.abs(got - ref) <= PT.RTOL_S * S + PT.ATOL + np.abs(ref) * 2.0 ** -8)
     else:
         PT.assert_close(got, ref, S, wl.name)
+
+
+# ------------------------------------------------------------------------------ more batches than one grid dimension holds
+@pytest.mark.parametrize("K,bias", [(16, False), (24, True), (5, True)])
+def test_batch_count_beyond_one_launch(B, oracle, K, bias):
+    """The batch index is the second grid dimension (at most 65535 per launch): 70001 small matmuls run as
+    two launches whose operand, output and bias pointers are advanced by the host."""
+    wl = I.Workload(f"bmm_many_k{K}", "bmm", "f16", "f32", "u", 9990 + K, batch=70001, M=16, N=16, K=K, trans_b=(K == 24), ep_bias=bias)
+    _say(f"{wl.name} -> {PT.variant_name(B, wl)}")
+    PT.check_workload(wl, oracle)
