@@ -764,7 +764,7 @@ __global__ void __launch_bounds__(512) conv_patch_kernel(const Params p) {
     char* const s_filt = smem;                  // R*S slabs, then the patch (the host checked that both fit)
     char* const s_patch = smem + p.R * p.S * SLAB;
 
-    // Waves 0-3 only copy, waves 4-7 multiply.  A global->LDS copy instruction occupies its wave for
+    // Waves 0-3 copy (half of the patch, then the filter), waves 4-7 copy the other half of the patch and multiply.  A global->LDS copy instruction occupies its wave for
     // far longer than an MFMA does, and a wave issues in order: if the multiplying waves issued the
     // copies themselves, the matrix pipes would idle behind every one of them.  The copy role goes to
     // the first four waves because the second wave of each SIMD starts ~0.3 us after the first.
@@ -796,28 +796,34 @@ __global__ void __launch_bounds__(512) conv_patch_kernel(const Params p) {
     const int PW = p.PW;                        // (Q-1)*s_w + (S-1)*d_w + 1 patch columns, first is iw = -pad_w
     const int npix = nrows * PW;
 
+    // Passes [first, last) of the patch copy; a pass is 32 pixels x 128 B, written by the four waves of one role.
+    const int nit = (npix + 31) >> 5;
+    // The multiplying waves are idle until the patch is in: they copy its second half (measured 3/8 .. 8/8 for
+    // the copy waves' share: one half each is fastest, 7.8 vs 8.45 us on the 56x56x64 benchmark convolution).
+    const int nsplit = (nit + 1) / 2;
+    auto copy_patch = [&](int first, int last) {
+        const i32x4 rx = make_rsrc((const char*)p.A, (long long)p.batch_imgs * p.H * p.W * p.Cin * ES);
+        const unsigned gofs = (unsigned)(grp * p.Cg * ES);
+        const int pc = tid & 7;
+        int px = first * 32 + (tid >> 3);
+        int pr = px / PW, pcx = px - pr * PW;
+        const int d_r = 32 / PW, d_c = 32 - d_r * PW;
+        for (int it = first; it < last; ++it) {
+            const int lc = pc ^ kmajor_swz<128>(px);
+            const int ih = ih_base + pr, iw = pcx - p.pad_w;
+            const bool ok = px < npix && (unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W;
+            const unsigned voff = ok ? (unsigned)(((img * p.H + ih) * p.W + iw) * p.Cin) * ES + gofs + lc * 16 : kOutOfRange;
+            load_to_lds(rx, s_patch + it * 4096 + cw * 1024, voff);
+            px += 32;
+            pr += d_r;
+            pcx += d_c;
+            if (pcx >= PW) { pcx -= PW; ++pr; }
+        }
+    };
+
     if (copier) {
         // ------------------------------------------------------------ copy: patch, then one filter slab per tap
-        {
-            const i32x4 rx = make_rsrc((const char*)p.A, (long long)p.batch_imgs * p.H * p.W * p.Cin * ES);
-            const unsigned gofs = (unsigned)(grp * p.Cg * ES);
-            const int pc = tid & 7;
-            int px = tid >> 3;                  // 32 pixels per pass of the four copy waves
-            int pr = px / PW, pcx = px - pr * PW;
-            const int d_r = 32 / PW, d_c = 32 - d_r * PW;
-            const int nit = (npix + 31) >> 5;
-            for (int it = 0; it < nit; ++it) {
-                const int lc = pc ^ kmajor_swz<128>(px);
-                const int ih = ih_base + pr, iw = pcx - p.pad_w;
-                const bool ok = px < npix && (unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W;
-                const unsigned voff = ok ? (unsigned)(((img * p.H + ih) * p.W + iw) * p.Cin) * ES + gofs + lc * 16 : kOutOfRange;
-                load_to_lds(rx, s_patch + it * 4096 + cw * 1024, voff);
-                px += 32;
-                pr += d_r;
-                pcx += d_c;
-                if (pcx >= PW) { pcx -= PW; ++pr; }
-            }
-        }
+        copy_patch(0, nsplit);
         const long long Kd = p.K;                               // R*S*Cg
         const char* wbase = (const char*)p.B + ((long long)grp * p.N + n0) * Kd * ES;
         unsigned w_off[2];
@@ -848,6 +854,8 @@ __global__ void __launch_bounds__(512) conv_patch_kernel(const Params p) {
         }
         return;
     }
+
+    copy_patch(nsplit, nit);                      // this role's share of the patch (empty unless the roles split it)
 
     // ------------------------------------------------------------ fragment addressing
     // lane's output pixel of MFMA block i: m = 64*cw + 32*i + l31 -> patch pixel of tap (0,0)
@@ -890,6 +898,7 @@ __global__ void __launch_bounds__(512) conv_patch_kernel(const Params p) {
     // Fragment sets: k-step kk of every tap uses set kk, fetched two k-steps ahead (a k-step is only
     // four MFMAs long here, one k-step of lookahead would not cover the LDS latency).
     uint4 af[4][2], bf[4][2];
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");          // this wave's patch copies (and its bias) have landed
     __builtin_amdgcn_s_barrier();                 // barrier 0: patch, slabs 0 and 1 are in LDS
     asm volatile("" ::: "memory");
 #pragma unroll
