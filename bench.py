@@ -188,7 +188,7 @@ def _graph_time(torch, fn, steps=100):
     return e0.elapsed_time(e1) * 1e-3 / steps
 
 
-def other_conv_rows(torch, B, I):
+def other_conv_rows(torch, B, I, tune=True):
     """1-D, 3-D and transposed 2-D convolution (the rest of the paper's operator set), fp16, synthetic shapes."""
     rows = []
 
@@ -207,13 +207,17 @@ def other_conv_rows(torch, B, I):
     # conv3d: 1 x 10 x 16 x 16 x 128 -> 64, 3x3x3
     N, D, H, W, C, K = 1, 10, 16, 16, 128, 64
     x, w, y = dev((N, D, H, W, C), 7010), dev((K, 3, 3, 3, C), 7011), B.empty_out((N, D, H, W, K), "f16")
+    if tune:
+        B.tir_tune_conv3d(x, w, y, N, D, H, W, C, K, 3, 3, 3, (1, 1, 1), (1, 1, 1), (1, 1, 1), 1, "f16", "f16", reps=10)
     sec = _graph_time(torch, lambda st: B.tir_conv3d(x, w, y, N, D, H, W, C, K, 3, 3, 3, (1, 1, 1), (1, 1, 1), (1, 1, 1), 1, "f16", "f16", stream=st))
-    row("c3d_10x16x16x128_k3_f16", "general convolution decode (depth axis)", sec, 2.0 * N * D * H * W * K * 27 * C, 2.0 * (N * D * H * W * (C + K) + K * 27 * C))
+    row("c3d_10x16x16x128_k3_f16", B.tir_conv3d_variant(N, D, H, W, C, K, 3, 3, 3, (1, 1, 1), (1, 1, 1), (1, 1, 1), 1, "f16", "f16"), sec, 2.0 * N * D * H * W * K * 27 * C, 2.0 * (N * D * H * W * (C + K) + K * 27 * C))
     # transposed conv2d: 16 x 28 x 28 x 64 -> 56 x 56 x 64, 4x4, stride 2 (FLOPs of the taps that exist, not of the gather's zeros)
     N, H, W, C, K = 16, 28, 28, 64, 64
     x, w, y = dev((N, H, W, C), 7020), dev((K, 4, 4, C), 7021), B.empty_out((N, 56, 56, K), "f16")
+    if tune:
+        B.tir_tune_conv2d_transpose(x, w, y, N, H, W, C, K, 4, 4, (2, 2), (1, 1), (1, 1), (0, 0), 1, "f16", "f16", reps=10)
     sec = _graph_time(torch, lambda st: B.tir_conv2d_transpose(x, w, y, N, H, W, C, K, 4, 4, (2, 2), (1, 1), (1, 1), (0, 0), 1, "f16", "f16", stream=st))
-    row("t2d_28x28x64_k4s2_f16", "general convolution decode (transposed, gather form)", sec, 2.0 * N * H * W * K * 16 * C, 2.0 * (N * H * W * C + K * 16 * C + N * 56 * 56 * K))
+    row("t2d_28x28x64_k4s2_f16", B.tir_conv2d_transpose_variant(N, H, W, C, K, 4, 4, (2, 2), (1, 1), (1, 1), (0, 0), 1, "f16", "f16"), sec, 2.0 * N * H * W * K * 16 * C, 2.0 * (N * H * W * C + K * 16 * C + N * 56 * 56 * K))
     return rows
 
 
@@ -306,7 +310,7 @@ def main():
                               "gbs": round(o.min_bytes() * k / e_ / 1e9, 1), "cache": "hot"})
             del s
         operators.append(attention_row(torch, B, I))
-        operators.extend(other_conv_rows(torch, B, I))
+        operators.extend(other_conv_rows(torch, B, I, tune=not args.no_tune))
 
     out = {
         "metric": "TFLOP/s and % of MI355X MFMA peak per operator (fp16 GEMM, conv2d)",

@@ -177,6 +177,14 @@ const char* tir_gemm_variant(int64_t batch, int64_t M, int64_t N, int64_t K, int
 const char* tir_conv2d_variant(int64_t N, int64_t H, int64_t W, int64_t C, int64_t K, int64_t R, int64_t S,
                                int stride_h, int stride_w, int pad_h, int pad_w, int dil_h, int dil_w,
                                int groups, tir_dtype in, tir_dtype out);
+const char* tir_conv3d_variant(int64_t N, int64_t D, int64_t H, int64_t W, int64_t C, int64_t K, int64_t T, int64_t R,
+                               int64_t S, int stride_d, int stride_h, int stride_w, int pad_d, int pad_h, int pad_w,
+                               int dil_d, int dil_h, int dil_w, int groups, tir_dtype in, tir_dtype out);
+/* Likewise for tir_conv2d_transpose; a strided problem computed per output phase reports
+ * "<variant>/ph<stride_h>x<stride_w>" (see tir_conv2d_transpose). */
+const char* tir_conv2d_transpose_variant(int64_t N, int64_t H, int64_t W, int64_t C, int64_t K, int64_t R, int64_t S,
+                                         int stride_h, int stride_w, int pad_h, int pad_w, int dil_h, int dil_w,
+                                         int outpad_h, int outpad_w, int groups, tir_dtype in, tir_dtype out);
 
 /*
  * Choice of kernel variant by measurement (TensorIR paper sec. 4.4: candidates that differ only in the
@@ -209,6 +217,16 @@ tir_status tir_tune_conv2d(const void* x, const void* w, void* y, int64_t N, int
                            int64_t K, int64_t R, int64_t S, int stride_h, int stride_w, int pad_h, int pad_w,
                            int dil_h, int dil_w, int groups, tir_dtype in, tir_dtype out,
                            const tir_epilogue* ep, int reps, double* best_us, tir_stream stream);
+/* The same for tir_conv3d and tir_conv2d_transpose (arguments as for those entry points). */
+tir_status tir_tune_conv3d(const void* x, const void* w, void* y, int64_t N, int64_t D, int64_t H, int64_t W, int64_t C,
+                           int64_t K, int64_t T, int64_t R, int64_t S, int stride_d, int stride_h, int stride_w,
+                           int pad_d, int pad_h, int pad_w, int dil_d, int dil_h, int dil_w, int groups, tir_dtype in,
+                           tir_dtype out, const tir_epilogue* ep, int reps, double* best_us, tir_stream stream);
+tir_status tir_tune_conv2d_transpose(const void* x, const void* w, void* y, int64_t N, int64_t H, int64_t W, int64_t C,
+                                     int64_t K, int64_t R, int64_t S, int stride_h, int stride_w, int pad_h, int pad_w,
+                                     int dil_h, int dil_w, int outpad_h, int outpad_w, int groups, tir_dtype in,
+                                     tir_dtype out, const tir_epilogue* ep, int reps, double* best_us,
+                                     tir_stream stream);
 int tir_tune_count(void);                       /* number of records */
 void tir_tune_clear(void);                      /* forget every record */
 tir_status tir_tune_save(const char* path);     /* TIR_ERR_INVALID_ARG if the file cannot be written */
@@ -225,9 +243,16 @@ void tir_debug_force_tile(int bm, int bn);
 /* Force the first variant of the matching dtype / copy mode whose name contains name_part
  * ("" or NULL restores the automatic choice); tir_debug_variant_name enumerates the names. */
 void tir_debug_force_variant(const char* name_part);
+/* Make later calls split every tile's reduction over `slices` workgroups where the chosen variant, the
+ * reduction's length and the workspace allow it (0 or 1 restores the automatic choice, measured records
+ * are ignored meanwhile).  The variant queries report a split as "<variant>/z<slices>". */
+void tir_debug_force_ksplit(int slices);
 int tir_debug_variant_count(void);
 const char* tir_debug_variant_name(int i);
 void tir_debug_tile_of_block(int bid, int tiles_m, int tiles_n, int* tm, int* tn);
+/* Host copy of the kernels' division by a launch constant: m / d for d >= 1 and m < 2^31 through the
+ * multiply-and-shift constants the planner derives from d (used to decode output rows into pixels). */
+unsigned tir_debug_fastdiv(unsigned d, unsigned m);
 
 /*
  * Measurement aid: enqueue a register-only fp16 MFMA loop (no memory traffic) of `iters` x 16 MFMAs

@@ -21,7 +21,8 @@ EXPORTS = ["tir_gemm", "tir_batch_matmul", "tir_conv2d", "tir_last_error", "tir_
            "tir_debug_variant_name", "tir_debug_tile_of_block", "tir_probe_mfma_rate", "tir_version",
            "tir_tune_batch_matmul", "tir_tune_conv2d", "tir_tune_count", "tir_tune_clear", "tir_tune_save",
            "tir_tune_load", "tir_gemm_fused", "tir_batch_matmul_fused", "tir_conv2d_fused", "tir_attention",
-           "tir_conv1d", "tir_conv3d", "tir_conv2d_transpose"]
+           "tir_conv1d", "tir_conv3d", "tir_conv2d_transpose", "tir_debug_force_ksplit", "tir_debug_fastdiv",
+           "tir_conv2d_transpose_variant", "tir_conv3d_variant", "tir_tune_conv3d", "tir_tune_conv2d_transpose"]
 
 
 class Epilogue(ctypes.Structure):
@@ -70,10 +71,16 @@ def lib() -> ctypes.CDLL:
     L.tir_gemm_variant.restype = ctypes.c_char_p
     L.tir_conv2d_variant.argtypes = [i64] * 7 + [ci] * 7 + [ci, ci]
     L.tir_conv2d_variant.restype = ctypes.c_char_p
+    L.tir_conv2d_transpose_variant.argtypes = [i64] * 7 + [ci] * 9 + [ci, ci]
+    L.tir_conv2d_transpose_variant.restype = ctypes.c_char_p
     L.tir_debug_force_tile.argtypes = [ci, ci]
     L.tir_debug_force_tile.restype = None
     L.tir_debug_force_variant.argtypes = [ctypes.c_char_p]
     L.tir_debug_force_variant.restype = None
+    L.tir_debug_fastdiv.argtypes = [ctypes.c_uint, ctypes.c_uint]
+    L.tir_debug_fastdiv.restype = ctypes.c_uint
+    L.tir_debug_force_ksplit.argtypes = [ctypes.c_int]
+    L.tir_debug_force_ksplit.restype = None
     L.tir_debug_variant_count.restype = ci
     L.tir_debug_variant_name.argtypes = [ci]
     L.tir_debug_variant_name.restype = ctypes.c_char_p
@@ -102,6 +109,12 @@ def lib() -> ctypes.CDLL:
     L.tir_tune_batch_matmul.restype = ci
     L.tir_tune_conv2d.argtypes = [vp, vp, vp] + [i64] * 7 + [ci] * 7 + [ci, ci, pe, ci, pd, vp]
     L.tir_tune_conv2d.restype = ci
+    L.tir_tune_conv3d.argtypes = [vp, vp, vp] + [i64] * 9 + [ci] * 10 + [ci, ci, pe, ci, pd, vp]
+    L.tir_tune_conv3d.restype = ci
+    L.tir_tune_conv2d_transpose.argtypes = [vp, vp, vp] + [i64] * 7 + [ci] * 9 + [ci, ci, pe, ci, pd, vp]
+    L.tir_tune_conv2d_transpose.restype = ci
+    L.tir_conv3d_variant.argtypes = [i64] * 9 + [ci] * 10 + [ci, ci]
+    L.tir_conv3d_variant.restype = ctypes.c_char_p
     L.tir_tune_count.restype = ci
     L.tir_tune_clear.restype = None
     L.tir_tune_save.argtypes = [ctypes.c_char_p]
@@ -189,12 +202,25 @@ def tir_conv2d_variant(N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w, di
                                     _code(in_dtype), _code(out_dtype)).decode()
 
 
+def tir_conv2d_transpose_variant(N, H, W, C, K, R, S, stride, pad, dil, outpad, groups, in_dtype, out_dtype) -> str:
+    return lib().tir_conv2d_transpose_variant(N, H, W, C, K, R, S, *stride, *pad, *dil, *outpad, groups, _code(in_dtype),
+                                              _code(out_dtype)).decode()
+
+
 def tir_debug_force_tile(bm: int, bn: int) -> None:
     lib().tir_debug_force_tile(bm, bn)
 
 
 def tir_debug_force_variant(name_part: str) -> None:
     lib().tir_debug_force_variant((name_part or "").encode())
+
+
+def tir_debug_fastdiv(d: int, m: int) -> int:
+    return int(lib().tir_debug_fastdiv(d, m))
+
+
+def tir_debug_force_ksplit(slices: int) -> None:
+    lib().tir_debug_force_ksplit(int(slices))
 
 
 def tir_debug_variant_names():
@@ -289,6 +315,28 @@ def tir_tune_conv2d(x, w, y, N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad
                                  dil_h, dil_w, groups, _code(in_dtype), _code(out_dtype), _ep_arg(ep), int(reps),
                                  ctypes.byref(us), _stream(stream)))
     return us.value
+
+
+def tir_tune_conv3d(x, w, y, N, D, H, W, C, K, T, R, S, stride, pad, dil, groups, in_dtype, out_dtype, ep=None, reps=5,
+                    stream=None) -> float:
+    us = ctypes.c_double()
+    _check(lib().tir_tune_conv3d(_ptr(x), _ptr(w), _ptr(y), N, D, H, W, C, K, T, R, S, *stride, *pad, *dil, groups,
+                                 _code(in_dtype), _code(out_dtype), _ep_arg(ep), int(reps), ctypes.byref(us), _stream(stream)))
+    return us.value
+
+
+def tir_tune_conv2d_transpose(x, w, y, N, H, W, C, K, R, S, stride, pad, dil, outpad, groups, in_dtype, out_dtype, ep=None,
+                              reps=5, stream=None) -> float:
+    us = ctypes.c_double()
+    _check(lib().tir_tune_conv2d_transpose(_ptr(x), _ptr(w), _ptr(y), N, H, W, C, K, R, S, *stride, *pad, *dil, *outpad, groups,
+                                           _code(in_dtype), _code(out_dtype), _ep_arg(ep), int(reps), ctypes.byref(us),
+                                           _stream(stream)))
+    return us.value
+
+
+def tir_conv3d_variant(N, D, H, W, C, K, T, R, S, stride, pad, dil, groups, in_dtype, out_dtype) -> str:
+    return lib().tir_conv3d_variant(N, D, H, W, C, K, T, R, S, *stride, *pad, *dil, groups, _code(in_dtype),
+                                    _code(out_dtype)).decode()
 
 
 def tir_tune_count() -> int:

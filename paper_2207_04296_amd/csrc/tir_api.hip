@@ -9,6 +9,7 @@
 #include <map>
 #include <mutex>
 #include <tuple>
+#include <utility>
 
 #include "tir.h"
 #include "tir_launch.h"
@@ -79,7 +80,7 @@ static const Variant* depthwise_variant(int dt, int out) {
 }
 
 static thread_local char g_err[512] = "";
-static int g_force_bm = 0, g_force_bn = 0;
+static int g_force_bm = 0, g_force_bn = 0, g_force_ksplit = 0;
 static char g_force_name[64] = "";
 
 static tir_status fail(tir_status st, const char* fmt, ...) {
@@ -117,15 +118,47 @@ struct TuneKey {
                std::tie(o.kind, o.dt, o.out, o.amode, o.bmode, o.batch, o.M, o.N, o.K, o.geom);
     }
 };
+// A kernel variant plus the number of workgroups that share one tile's reduction (1 = no split).
+struct Choice {
+    const Variant* v;
+    int ksplit;
+};
+static const Choice kNoChoice = {nullptr, 1};
 static std::mutex g_tune_mu;
-static std::map<TuneKey, const Variant*> g_tuned;
-// set by the tuner around its trial launches on the calling thread: the variant to plan with
-static thread_local const Variant* g_trial = nullptr;
+static std::map<TuneKey, Choice> g_tuned;
+// set by the tuner around its trial launches on the calling thread: the choice to plan with
+static thread_local Choice g_trial = {nullptr, 1};
 
-static const Variant* tuned_lookup(const TuneKey& k) {
+static Choice tuned_lookup(const TuneKey& k) {
     std::lock_guard<std::mutex> lock(g_tune_mu);
     auto it = g_tuned.find(k);
-    return it == g_tuned.end() ? nullptr : it->second;
+    return it == g_tuned.end() ? kNoChoice : it->second;
+}
+
+// ------------------------------------------------------------------------------- split reduction
+// Workspace of the reduction split over workgroups: the slices' partial sums and one arrival counter
+// per output tile.  One fixed-size block per (device, stream), allocated at the first launch that
+// needs it and kept until the process ends: launches on one stream follow each other, so they can
+// share it; launches on different streams may overlap and get their own.
+static const int64_t kWsBytes = 32ll << 20;      // partial sums
+static const int64_t kWsTiles = 16384;           // counters
+struct Workspace {
+    void* partial;
+    unsigned* count;
+};
+static std::mutex g_ws_mu;
+static std::map<std::pair<int, hipStream_t>, Workspace> g_ws;
+
+// Can variant v reduce a problem of `tiles` output tiles per batch entry in ks slices?
+static bool split_fits(const Variant* v, int ks, int64_t batch, int64_t tiles, int64_t K) {
+    if (ks == 1) return true;
+    if (ks < 1 || ks > 64) return false;
+    if (v->amode != A_KMAJOR && v->amode != A_CONV && v->amode != A_CONVX) return false;      // the fast kernel only
+    const int64_t stages = (K * elem_size(v->dt) + v->rowb - 1) / v->rowb;
+    const int64_t per = (stages + ks - 1) / ks;
+    if ((ks - 1) * per >= stages) return false;       // a slice would be empty
+    if (batch > 65535 || batch * tiles > kWsTiles) return false;
+    return batch * tiles * ks * v->bm * v->bn * 4 <= kWsBytes;
 }
 
 static uint64_t hash_fields(const int64_t* f, int n) {
@@ -143,17 +176,31 @@ static uint64_t hash_fields(const int64_t* f, int n) {
 // saturating at the 256x256 tile).  Among equal tiles the ring depth is chosen by occupancy:
 // deep rings when one workgroup per CU must hide the global latency alone, shallow ones when
 // several workgroups share a CU (their LDS must fit side by side) or the reduction is short.
-static const Variant* pick(int dt, int out, int amode, int bmode, int64_t batch, int64_t M, int64_t N, int64_t K) {
-    const Variant* best = nullptr;
+//
+// A reduction much longer than the tile grid is wide (few tiles, many stages) is split over several
+// workgroups per tile, as many as fill the CUs once while each keeps at least eight stages.
+static Choice pick(int dt, int out, int amode, int bmode, int64_t batch, int64_t M, int64_t N, int64_t K) {
+    Choice best = kNoChoice;
     double best_score = -1.0;
     const int es = elem_size(dt);
     for (int i = 0; i < kNumVariants; ++i) {
         const Variant* v = &kVariants[i];
         if (v->dt != dt || v->out != out || v->amode != amode || v->bmode != bmode) continue;
-        if (g_force_name[0] && strstr(v->name, g_force_name)) return v;          // testing / tuning overrides
-        if (g_force_bm && v->bm == g_force_bm && v->bn == g_force_bn && v->kw == 1) return v;
+        const int64_t tiles_1 = ((M + v->bm - 1) / v->bm) * ((N + v->bn - 1) / v->bn);
+        const int forced_ks = (g_force_ksplit > 1 && split_fits(v, g_force_ksplit, batch, tiles_1, K)) ? g_force_ksplit : 1;
+        if (g_force_name[0] && strstr(v->name, g_force_name)) return Choice{v, forced_ks};          // testing / tuning overrides
+        if (g_force_bm && v->bm == g_force_bm && v->bn == g_force_bn && v->kw == 1) return Choice{v, forced_ks};
         const double tm = (double)((M + v->bm - 1) / v->bm), tn = (double)((N + v->bn - 1) / v->bn);
-        const double tiles = tm * tn * (double)batch;
+        int ks = forced_ks;
+        if (!g_force_ksplit) {
+            const int64_t stages = (K * es + v->rowb - 1) / v->rowb;
+            int64_t want = (int64_t)kCUs / (tiles_1 * batch);
+            if (want > stages / (8 * v->kw)) want = stages / (8 * v->kw);
+            if (want > 8) want = 8;
+            while (want > 1 && !split_fits(v, (int)want, batch, tiles_1, K)) --want;
+            if (want > 1) ks = (int)want;
+        }
+        const double tiles = tm * tn * (double)batch * ks;
         const double eff = ((double)M * (double)N) / (tm * v->bm * tn * v->bn);
         const double rounds = tiles <= kCUs ? 1.0 : (double)((int64_t)(tiles + kCUs - 1) / kCUs);
         const double fill = tiles / (rounds * kCUs);
@@ -175,8 +222,8 @@ static const Variant* pick(int dt, int out, int amode, int bmode, int64_t batch,
         if (tiles > kCUs && lds > 80 * 1024) depth -= 0.03;
         else if (tiles <= kCUs) depth += 0.01 * v->nstage;
         else depth += 0.005 * v->nstage;
-        score *= depth;
-        if (score > best_score) { best_score = score; best = v; }
+        score *= depth * (1.0 - 0.03 * (ks - 1));       // the partial sums' round trip
+        if (score > best_score) { best_score = score; best = Choice{v, ks}; }
     }
     return best;
 }
@@ -189,11 +236,11 @@ struct Plan {
 };
 
 // The variant a plan uses: the tuner's trial variant, else a measured record, else the scoring rule.
-static const Variant* choose(const TuneKey& key, int64_t batch, int64_t M, int64_t N, int64_t K) {
-    if (g_trial) return g_trial;
-    if (!g_force_name[0] && !g_force_bm) {
-        const Variant* t = tuned_lookup(key);
-        if (t) return t;
+static Choice choose(const TuneKey& key, int64_t batch, int64_t M, int64_t N, int64_t K) {
+    if (g_trial.v) return g_trial;
+    if (!g_force_name[0] && !g_force_bm && !g_force_ksplit) {
+        const Choice t = tuned_lookup(key);
+        if (t.v) return t;
     }
     return pick(key.dt, key.out, key.amode, key.bmode, batch, M, N, K);
 }
@@ -250,10 +297,12 @@ static tir_status plan_gemm(bool need_ptrs, const void* A, const void* B, void* 
 
     plan->key = TuneKey{0, in, out, amode, bmode, batch, M, N, K, 0};
     plan->patch_ok = false;
-    const Variant* v = choose(plan->key, batch, M, N, K);
+    const Choice ch = choose(plan->key, batch, M, N, K);
+    const Variant* v = ch.v;
     if (!v) return fail(TIR_ERR_UNSUPPORTED, "no kernel variant for this dtype / layout / forced tile");
     Params& p = plan->p;
     memset(&p, 0, sizeof p);
+    p.ksplit = split_fits(v, ch.ksplit, batch, ((M + v->bm - 1) / v->bm) * ((N + v->bn - 1) / v->bn), K) ? ch.ksplit : 1;
     p.A = A; p.B = B; p.C = C;
     p.M = (int)M; p.N = (int)N; p.K = (int)K;
     p.batch = (int)batch;
@@ -295,6 +344,7 @@ static tir_status plan_conv_geom(bool need_ptrs, const void* x, const void* w, v
     if (g.stride_d <= 0 || g.stride_h <= 0 || g.stride_w <= 0 || g.dil_d <= 0 || g.dil_h <= 0 || g.dil_w <= 0 || g.pad_d < 0 || g.pad_h < 0 || g.pad_w < 0)
         return fail(TIR_ERR_INVALID_ARG, "stride and dilation must be positive, padding non-negative");
     if (g.transposed && (g.outpad_h < 0 || g.outpad_w < 0)) return fail(TIR_ERR_INVALID_ARG, "output padding must be non-negative");
+    if (g.transposed && (g.stride_h > 16383 || g.stride_w > 16383)) return fail(TIR_ERR_UNSUPPORTED, "transposed convolution: stride beyond 16383");
     if (groups <= 0 || C % groups != 0 || K % groups != 0)
         return fail(TIR_ERR_INVALID_ARG, "groups=%d must divide C=%lld and K=%lld", groups, (long long)C, (long long)K);
     int64_t OD = 1, P, Q;
@@ -327,38 +377,52 @@ static tir_status plan_conv_geom(bool need_ptrs, const void* x, const void* w, v
         amode = plain2d ? A_CONV : A_CONVX;
         bmode = B_KMAJOR;
     }
+    // A strided transposed convolution multiplies mostly structural zeros when read as one gather (only every
+    // stride-th tap meets an input pixel).  Undilated, with whole stages per tap (one stage = 128 bytes of channels),
+    // it is computed per output phase instead: stride_h*stride_w stride-1 convolutions with a tap subset each, all
+    // in one launch of the 2-D kernels (a forced general-decode variant keeps the gather).
+    const int64_t phases = (int64_t)g.stride_h * g.stride_w;
+    const int64_t Pp = (P + g.stride_h - 1) / g.stride_h, Qp = (Q + g.stride_w - 1) / g.stride_w;      // pixel grid of one phase
+    const bool phased = g.transposed && amode == A_CONVX && phases > 1 && g.dil_h == 1 && g.dil_w == 1 && (Cg * es) % 128 == 0 &&
+                        groups * phases <= 65535 && N * P * Q * K * elem_size(out) < kMaxExtent && N * Pp * Qp <= kMaxExtent &&
+                        !(g_force_name[0] && (strstr(g_force_name, "convx") || strstr(g_force_name, "generic")));
+    if (phased) amode = A_CONV;
     // LDS-resident input patch: one pixel of one group is exactly one 128-byte LDS row, the input rows
     // that 256 consecutive output pixels touch (copied in passes of 64 pixels) fit beside the R*S filter slabs
     const int64_t span_out = (255 + Q - 1) / Q < P - 1 ? (255 + Q - 1) / Q : P - 1;   // output rows a tile can span, minus one
     const int64_t span_rows = span_out * g.stride_h + (R - 1) * g.dil_h + 1;
     const int64_t patch_w = (Q - 1) * g.stride_w + (S - 1) * g.dil_w + 1;
-    const bool patch_ok = amode == A_CONV && Cg * es == 128 && P * Q >= 128 && (span_rows * patch_w + 63) / 64 * 8192 + R * S * 8192 <= 160 * 1024 &&
+    const bool patch_ok = amode == A_CONV && !phased && Cg * es == 128 && P * Q >= 128 && (span_rows * patch_w + 63) / 64 * 8192 + R * S * 8192 <= 160 * 1024 &&
                           (K * 256 + Kg) * elem_size(out) < kMaxExtent;
     plan->patch_ok = patch_ok;
     // records are kept under the implicit-GEMM signature; a record (or a trial) may name either kernel family
     const int64_t geom[21] = {N, groups, D, H, W, T, R, S, g.stride_d, g.stride_h, g.stride_w, g.pad_d, g.pad_h, g.pad_w, g.dil_d, g.dil_h, g.dil_w,
                               g.transposed ? 1 : 0, g.transposed ? g.outpad_h : 0, g.transposed ? g.outpad_w : 0, 0};
     plan->key = TuneKey{1, in, out, amode, bmode, groups * N, OD * P * Q, Kg, Kd, hash_fields(geom, 21)};
-    const Variant* v = nullptr;
+    // the tile grid the variants are scored on: by phase, every phase is a batch entry of its own with a share of the taps
+    const int64_t sc_batch = phased ? groups * phases : groups, sc_M = phased ? N * Pp * Qp : Mg, sc_K = phased ? (Kd + phases - 1) / phases : Kd;
+    Choice ch = kNoChoice;
     // depth-wise (one input and one output channel per group): the direct kernel, unless a test forces a tile variant
     if (plain2d && Cg == 1 && Kg == 1 && C % vec == 0 && R * S <= kDwMaxTaps && aligned(x, 16) && aligned(w, 16) && aligned(y, 16) &&
-        N * H * W * C * es < kMaxExtent && Mg * K * elem_size(out) < kMaxExtent && !g_trial &&
+        N * H * W * C * es < kMaxExtent && Mg * K * elem_size(out) < kMaxExtent && !g_trial.v &&
         !g_force_name[0] && !g_force_bm)
-        v = depthwise_variant(in, out);
-    const bool depthwise = v != nullptr;
+        ch.v = depthwise_variant(in, out);
+    const bool depthwise = ch.v != nullptr;
     if (depthwise) amode = A_DEPTHWISE;
-    else if (g_trial) v = g_trial;
-    else if (!g_force_name[0] && !g_force_bm) v = tuned_lookup(plan->key);
-    if (v && v->amode == A_CONV_PATCH && !patch_ok) v = nullptr;
-    if (!v) {
-        const bool use_patch = patch_ok && (!g_force_name[0] || strstr(g_force_name, "patch"));
-        if (use_patch) v = pick(in, out, A_CONV_PATCH, bmode, groups * N, P * Q, Kg, Kd);
-        else v = pick(in, out, amode, bmode, groups, Mg, Kg, Kd);
+    else if (g_trial.v) ch = g_trial;
+    else if (!g_force_name[0] && !g_force_bm && !g_force_ksplit) ch = tuned_lookup(plan->key);
+    if (ch.v && ch.v->amode == A_CONV_PATCH && !patch_ok) ch = kNoChoice;
+    if (!ch.v) {
+        const bool use_patch = patch_ok && !g_force_ksplit && (!g_force_name[0] || strstr(g_force_name, "patch"));
+        if (use_patch) ch = pick(in, out, A_CONV_PATCH, bmode, groups * N, P * Q, Kg, Kd);
+        else ch = pick(in, out, amode, bmode, sc_batch, sc_M, Kg, sc_K);
     }
+    const Variant* v = ch.v;
     if (v && v->amode == A_CONV_PATCH) amode = A_CONV_PATCH;
     if (!v) return fail(TIR_ERR_UNSUPPORTED, "no kernel variant for this dtype / forced tile");
     Params& p = plan->p;
     memset(&p, 0, sizeof p);
+    p.ksplit = (!depthwise && !phased && split_fits(v, ch.ksplit, groups, ((Mg + v->bm - 1) / v->bm) * ((Kg + v->bn - 1) / v->bn), Kd)) ? ch.ksplit : 1;
     p.A = x; p.B = w; p.C = y;
     p.M = (int)Mg; p.N = (int)Kg; p.K = (int)Kd;
     p.batch = depthwise ? 1 : groups;                 // the depth-wise kernel covers every channel in one launch
@@ -381,7 +445,19 @@ static tir_status plan_conv_geom(bool need_ptrs, const void* x, const void* w, v
     p.D = (int)D; p.T = (int)T; p.OD = (int)OD;
     p.stride_d = g.stride_d; p.pad_d = g.pad_d; p.dil_d = g.dil_d;
     p.dil_h = g.dil_h; p.dil_w = g.dil_w;
-    if (g.transposed) {
+    if (phased) {
+        if (v->amode != A_CONV) return fail(TIR_ERR_UNSUPPORTED, "transposed convolution by phase needs a 2-D implicit-GEMM variant (got %s)", v->name);
+        p.M = (int)(N * Pp * Qp);
+        p.batch = (int)(groups * phases);
+        p.tiles_m = (int)((p.M + v->bm - 1) / v->bm);
+        p.P = (int)Pp; p.Q = (int)Qp; p.P_full = (int)P; p.Q_full = (int)Q;
+        p.phases_h = g.stride_h; p.phases_w = g.stride_w; p.t_pad_h = g.pad_h; p.t_pad_w = g.pad_w;
+        p.conv_groups = groups;
+        p.stride_h = 1; p.stride_w = 1; p.pad_h = 0; p.pad_w = 0;      // per phase, derived by the kernel
+        p.tap_sign = 1; p.up_h = 1; p.up_w = 1;
+        const FastDiv dpq = make_fastdiv((unsigned)(Pp * Qp)), dq = make_fastdiv((unsigned)Qp);
+        p.div_pq_magic = dpq.magic; p.div_pq_shift = dpq.shift; p.div_q_magic = dq.magic; p.div_q_shift = dq.shift;
+    } else if (g.transposed) {
         // gather form of the adjoint: output pixel oh reads input (oh + pad - r*dil) / stride where that is an integer
         p.stride_h = 1; p.stride_w = 1; p.pad_h = -g.pad_h; p.pad_w = -g.pad_w;
         p.tap_sign = -1; p.up_h = g.stride_h; p.up_w = g.stride_w;
@@ -400,8 +476,45 @@ static tir_status plan_conv(bool need_ptrs, const void* x, const void* w, void* 
     return plan_conv_geom(need_ptrs, x, w, y, g, in, out, ep, plan);
 }
 
+// Give a plan with a split reduction its workspace.  Allocation happens outside any stream capture (a capturing
+// stream that has no workspace yet runs the same variant without the split instead).
+static tir_status attach_workspace(Plan* plan, hipStream_t stream) {
+    if (!plan->v || plan->p.ksplit <= 1) return TIR_OK;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(TIR_ERR_LAUNCH, "hipGetDevice failed: %s", hipGetErrorString(e));
+    std::lock_guard<std::mutex> lock(g_ws_mu);
+    auto it = g_ws.find(std::make_pair(dev, stream));
+    if (it == g_ws.end()) {
+        hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+        if (stream && (hipStreamIsCapturing(stream, &cs) != hipSuccess || cs != hipStreamCaptureStatusNone)) {
+            (void)hipGetLastError();
+            plan->p.ksplit = 1;
+            return TIR_OK;
+        }
+        void* base = nullptr;
+        e = hipMalloc(&base, (size_t)(kWsBytes + kWsTiles * 4));
+        if (e == hipSuccess) e = hipMemset((char*)base + kWsBytes, 0, (size_t)(kWsTiles * 4));
+        if (e == hipSuccess) e = hipDeviceSynchronize();
+        if (e != hipSuccess) {
+            // no memory, or another thread captures in a mode that forbids allocation: run without the split
+            (void)hipGetLastError();
+            if (base) (void)hipFree(base);
+            plan->p.ksplit = 1;
+            return TIR_OK;
+        }
+        Workspace w = {base, (unsigned*)((char*)base + kWsBytes)};
+        it = g_ws.insert(std::make_pair(std::make_pair(dev, stream), w)).first;
+    }
+    plan->p.ws = it->second.partial;
+    plan->p.ws_count = it->second.count;
+    return TIR_OK;
+}
+
 static tir_status run(const Plan& plan, hipStream_t stream) {
     if (!plan.v) return TIR_OK;
+    if (plan.p.ksplit > 1 && (!plan.p.ws || !plan.p.ws_count || plan.p.batch > 65535))
+        return fail(TIR_ERR_LAUNCH, "split reduction planned without its workspace");
     // grid.y is limited to 65535: launch the batch in slices
     const int es = elem_size(plan.v->dt), os = elem_size(plan.v->out);
     const int total = plan.p.batch;
@@ -418,6 +531,12 @@ static tir_status run(const Plan& plan, hipStream_t stream) {
     return TIR_OK;
 }
 
+static tir_status launch(Plan& plan, hipStream_t stream) {
+    tir_status st = attach_workspace(&plan, stream);
+    if (st != TIR_OK) return st;
+    return run(plan, stream);
+}
+
 // ------------------------------------------------------------------------------- tuning by measurement
 static bool record_fits(const TuneKey& k, const Variant* v) {
     if (v->dt != k.dt || v->out != k.out) return false;
@@ -426,7 +545,7 @@ static bool record_fits(const TuneKey& k, const Variant* v) {
 }
 
 struct TrialGuard {
-    ~TrialGuard() { g_trial = nullptr; }
+    ~TrialGuard() { g_trial = kNoChoice; }
 };
 
 // Run every variant that can compute the problem `make_plan` describes, `reps` times each, and record
@@ -436,9 +555,9 @@ static tir_status tune_problem(MakePlan make_plan, int reps, hipStream_t stream,
     if (best_us) *best_us = 0.0;
     if (best_name) *best_name = "";
     if (reps <= 0 || reps > 1000) return fail(TIR_ERR_INVALID_ARG, "reps must be in [1, 1000]");
-    if (g_force_name[0] || g_force_bm) return fail(TIR_ERR_INVALID_ARG, "tuning while a variant or tile is forced");
+    if (g_force_name[0] || g_force_bm || g_force_ksplit) return fail(TIR_ERR_INVALID_ARG, "tuning while a variant or tile is forced");
     Plan base;
-    g_trial = nullptr;
+    g_trial = kNoChoice;
     tir_status st = make_plan(&base);
     if (st != TIR_OK) return st;
     if (!base.v) return TIR_OK;                       // zero-sized problem: nothing to measure
@@ -464,15 +583,26 @@ static tir_status tune_problem(MakePlan make_plan, int reps, hipStream_t stream,
         stream = own;
     }
     TrialGuard guard;
-    const Variant* best = nullptr;
+    Choice best = kNoChoice;
     float best_ms = 0.f;
-    for (int i = 0; i < kNumVariants && st == TIR_OK; ++i) {
-        const Variant* v = &kVariants[i];
+    // reduction splits tried per variant (where the variant, the workspace and the reduction's length allow
+    // them and the workgroups still fit two rounds of the CUs)
+    static const int kSplits[] = {1, 2, 3, 4, 6, 8};
+    for (int i = 0; i < kNumVariants * 6 && st == TIR_OK; ++i) {
+        const Variant* v = &kVariants[i / 6];
+        const int ks = kSplits[i % 6];
         if (!record_fits(base.key, v) || (v->amode == A_CONV_PATCH && !base.patch_ok)) continue;
-        g_trial = v;
+        g_trial = Choice{v, ks};
         Plan pl;
         st = make_plan(&pl);
+        if (st == TIR_OK) st = attach_workspace(&pl, stream);
         if (st != TIR_OK) break;
+        if (pl.p.ksplit != ks) continue;              // this split does not apply
+        if (ks > 1) {
+            const int64_t wgs = (int64_t)pl.p.tiles_m * pl.p.tiles_n * pl.p.batch * ks;
+            const int64_t stages = ((int64_t)pl.p.K * elem_size(v->dt) + v->rowb - 1) / v->rowb;
+            if (wgs > 2 * (int64_t)kCUs || stages / ks < 2) continue;
+        }
         // two launches first (a variant several times slower than the best so far is not worth `reps`
         // more), then the measured batch; every HIP call is checked, the first failure ends the tuning
         float ms = 0.f;
@@ -502,20 +632,20 @@ static tir_status tune_problem(MakePlan make_plan, int reps, hipStream_t stream,
         };
         st = timed(1);
         if (st != TIR_OK) break;
-        if (best && ms > 4.f * best_ms + 0.05f) continue;
+        if (best.v && ms > 4.f * best_ms + 0.05f) continue;
         st = timed(reps);
         if (st != TIR_OK) break;
-        if (!best || ms < best_ms) { best = v; best_ms = ms; }
+        if (!best.v || ms < best_ms) { best = Choice{v, ks}; best_ms = ms; }
     }
     (void)hipEventDestroy(e0);
     (void)hipEventDestroy(e1);
     if (own) (void)hipStreamDestroy(own);
     if (st != TIR_OK) return st;
-    if (best) {
+    if (best.v) {
         std::lock_guard<std::mutex> lock(g_tune_mu);
         g_tuned[base.key] = best;
         if (best_us) *best_us = (double)best_ms * 1e3;
-        if (best_name) *best_name = best->name;
+        if (best_name) *best_name = best.v->name;
     }
     return TIR_OK;
 }
@@ -532,7 +662,7 @@ tir_status tir_gemm_fused(const void* A, const void* B, void* C, int64_t M, int6
     Plan plan;
     tir_status st = plan_gemm(true, A, B, C, 1, M, N, K, 0, a_rs, a_cs, 0, b_rs, b_cs, 0, c_rs, c_cs, (int)in, (int)out, ep, &plan);
     if (st != TIR_OK) return st;
-    return run(plan, (hipStream_t)stream);
+    return launch(plan, (hipStream_t)stream);
 }
 
 tir_status tir_batch_matmul_fused(const void* A, const void* B, void* C, int64_t batch, int64_t M, int64_t N, int64_t K,
@@ -542,7 +672,7 @@ tir_status tir_batch_matmul_fused(const void* A, const void* B, void* C, int64_t
     Plan plan;
     tir_status st = plan_gemm(true, A, B, C, batch, M, N, K, a_bs, a_rs, a_cs, b_bs, b_rs, b_cs, c_bs, c_rs, c_cs, (int)in, (int)out, ep, &plan);
     if (st != TIR_OK) return st;
-    return run(plan, (hipStream_t)stream);
+    return launch(plan, (hipStream_t)stream);
 }
 
 tir_status tir_conv2d_fused(const void* x, const void* w, void* y, int64_t N, int64_t H, int64_t W, int64_t C, int64_t K,
@@ -551,7 +681,7 @@ tir_status tir_conv2d_fused(const void* x, const void* w, void* y, int64_t N, in
     Plan plan;
     tir_status st = plan_conv(true, x, w, y, N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, groups, (int)in, (int)out, ep, &plan);
     if (st != TIR_OK) return st;
-    return run(plan, (hipStream_t)stream);
+    return launch(plan, (hipStream_t)stream);
 }
 
 tir_status tir_gemm(const void* A, const void* B, void* C, int64_t M, int64_t N, int64_t K, int64_t a_rs,
@@ -575,12 +705,22 @@ tir_status tir_conv2d(const void* x, const void* w, void* y, int64_t N, int64_t 
 
 const char* tir_last_error(void) { return g_err; }
 
+// "<variant>" or "<variant>/z<slices>" for a plan with a split reduction
+static const char* plan_name(const Plan& plan) {
+    static thread_local char buf[160];
+    if (!plan.v) return "";
+    if (plan.p.phases_h) snprintf(buf, sizeof buf, "%s/ph%dx%d", plan.v->name, plan.p.phases_h, plan.p.phases_w);
+    else if (plan.p.ksplit > 1) snprintf(buf, sizeof buf, "%s/z%d", plan.v->name, plan.p.ksplit);
+    else return plan.v->name;
+    return buf;
+}
+
 const char* tir_gemm_variant(int64_t batch, int64_t M, int64_t N, int64_t K, int64_t a_rs, int64_t a_cs, int64_t b_rs,
                              int64_t b_cs, int64_t c_rs, int64_t c_cs, tir_dtype in, tir_dtype out) {
     Plan plan;
     // batch strides of dense operands, only their divisibility matters for the choice
     tir_status st = plan_gemm(false, nullptr, nullptr, nullptr, batch, M, N, K, M * K, a_rs, a_cs, K * N, b_rs, b_cs, M * N, c_rs, c_cs, (int)in, (int)out, out == TIR_I8 ? &kQueryRequant : nullptr, &plan);
-    return (st == TIR_OK && plan.v) ? plan.v->name : "";
+    return st == TIR_OK ? plan_name(plan) : "";
 }
 
 const char* tir_conv2d_variant(int64_t N, int64_t H, int64_t W, int64_t C, int64_t K, int64_t R, int64_t S,
@@ -588,13 +728,33 @@ const char* tir_conv2d_variant(int64_t N, int64_t H, int64_t W, int64_t C, int64
                                tir_dtype in, tir_dtype out) {
     Plan plan;
     tir_status st = plan_conv(false, nullptr, nullptr, nullptr, N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, groups, (int)in, (int)out, out == TIR_I8 ? &kQueryRequant : nullptr, &plan);
-    return (st == TIR_OK && plan.v) ? plan.v->name : "";
+    return st == TIR_OK ? plan_name(plan) : "";
+}
+
+const char* tir_conv3d_variant(int64_t N, int64_t D, int64_t H, int64_t W, int64_t C, int64_t K, int64_t T, int64_t R,
+                               int64_t S, int stride_d, int stride_h, int stride_w, int pad_d, int pad_h, int pad_w,
+                               int dil_d, int dil_h, int dil_w, int groups, tir_dtype in, tir_dtype out) {
+    const ConvGeom g = {N, D, H, W, C, K, T, R, S, stride_d, stride_h, stride_w, pad_d, pad_h, pad_w, dil_d, dil_h, dil_w, groups, false, 0, 0};
+    Plan plan;
+    tir_status st = plan_conv_geom(false, nullptr, nullptr, nullptr, g, (int)in, (int)out, out == TIR_I8 ? &kQueryRequant : nullptr, &plan);
+    return st == TIR_OK ? plan_name(plan) : "";
+}
+
+const char* tir_conv2d_transpose_variant(int64_t N, int64_t H, int64_t W, int64_t C, int64_t K, int64_t R, int64_t S,
+                                         int stride_h, int stride_w, int pad_h, int pad_w, int dil_h, int dil_w,
+                                         int outpad_h, int outpad_w, int groups, tir_dtype in, tir_dtype out) {
+    const ConvGeom g = {N, 1, H, W, C, K, 1, R, S, 1, stride_h, stride_w, 0, pad_h, pad_w, 1, dil_h, dil_w, groups, true, outpad_h, outpad_w};
+    Plan plan;
+    tir_status st = plan_conv_geom(false, nullptr, nullptr, nullptr, g, (int)in, (int)out, out == TIR_I8 ? &kQueryRequant : nullptr, &plan);
+    return st == TIR_OK ? plan_name(plan) : "";
 }
 
 void tir_debug_force_tile(int bm, int bn) {
     g_force_bm = bm;
     g_force_bn = bn;
 }
+
+void tir_debug_force_ksplit(int slices) { g_force_ksplit = slices > 1 ? slices : 0; }
 
 void tir_debug_force_variant(const char* name_part) {
     snprintf(g_force_name, sizeof g_force_name, "%s", name_part ? name_part : "");
@@ -605,6 +765,11 @@ int tir_debug_variant_count(void) { return kNumVariants; }
 const char* tir_debug_variant_name(int i) { return (i >= 0 && i < kNumVariants) ? kVariants[i].name : ""; }
 
 void tir_debug_tile_of_block(int bid, int tiles_m, int tiles_n, int* tm, int* tn) { tile_of_block(bid, tiles_m, tiles_n, tm, tn); }
+
+unsigned tir_debug_fastdiv(unsigned d, unsigned m) {
+    const FastDiv f = make_fastdiv(d);
+    return fastdiv(m, f.magic, f.shift);
+}
 
 tir_status tir_probe_mfma_rate(void* sink, int iters, int random_operands, double* flop, tir_stream stream) {
     if (!sink || iters <= 0) return fail(TIR_ERR_INVALID_ARG, "tir_probe_mfma_rate: sink is null or iters <= 0");
@@ -635,6 +800,25 @@ tir_status tir_tune_conv2d(const void* x, const void* w, void* y, int64_t N, int
     return tune_problem(make, reps, (hipStream_t)stream, best_us, nullptr);
 }
 
+tir_status tir_tune_conv3d(const void* x, const void* w, void* y, int64_t N, int64_t D, int64_t H, int64_t W, int64_t C,
+                           int64_t K, int64_t T, int64_t R, int64_t S, int stride_d, int stride_h, int stride_w,
+                           int pad_d, int pad_h, int pad_w, int dil_d, int dil_h, int dil_w, int groups, tir_dtype in,
+                           tir_dtype out, const tir_epilogue* ep, int reps, double* best_us, tir_stream stream) {
+    const ConvGeom g = {N, D, H, W, C, K, T, R, S, stride_d, stride_h, stride_w, pad_d, pad_h, pad_w, dil_d, dil_h, dil_w, groups, false, 0, 0};
+    auto make = [&](Plan* pl) { return plan_conv_geom(true, x, w, y, g, (int)in, (int)out, ep, pl); };
+    return tune_problem(make, reps, (hipStream_t)stream, best_us, nullptr);
+}
+
+tir_status tir_tune_conv2d_transpose(const void* x, const void* w, void* y, int64_t N, int64_t H, int64_t W, int64_t C,
+                                     int64_t K, int64_t R, int64_t S, int stride_h, int stride_w, int pad_h, int pad_w,
+                                     int dil_h, int dil_w, int outpad_h, int outpad_w, int groups, tir_dtype in,
+                                     tir_dtype out, const tir_epilogue* ep, int reps, double* best_us,
+                                     tir_stream stream) {
+    const ConvGeom g = {N, 1, H, W, C, K, 1, R, S, 1, stride_h, stride_w, 0, pad_h, pad_w, 1, dil_h, dil_w, groups, true, outpad_h, outpad_w};
+    auto make = [&](Plan* pl) { return plan_conv_geom(true, x, w, y, g, (int)in, (int)out, ep, pl); };
+    return tune_problem(make, reps, (hipStream_t)stream, best_us, nullptr);
+}
+
 int tir_tune_count(void) {
     std::lock_guard<std::mutex> lock(g_tune_mu);
     return (int)g_tuned.size();
@@ -653,8 +837,8 @@ tir_status tir_tune_save(const char* path) {
     fprintf(f, "tir-tune-records 1\n");
     for (const auto& kv : g_tuned) {
         const TuneKey& k = kv.first;
-        fprintf(f, "%d %d %d %d %d %lld %lld %lld %lld %llu %s\n", k.kind, k.dt, k.out, k.amode, k.bmode, (long long)k.batch,
-                (long long)k.M, (long long)k.N, (long long)k.K, (unsigned long long)k.geom, kv.second->name);
+        fprintf(f, "%d %d %d %d %d %lld %lld %lld %lld %llu %s %d\n", k.kind, k.dt, k.out, k.amode, k.bmode, (long long)k.batch,
+                (long long)k.M, (long long)k.N, (long long)k.K, (unsigned long long)k.geom, kv.second.v->name, kv.second.ksplit);
     }
     const bool ok = fclose(f) == 0;
     return ok ? TIR_OK : fail(TIR_ERR_INVALID_ARG, "writing %s failed", path);
@@ -676,14 +860,15 @@ tir_status tir_tune_load(const char* path) {
         long long b, m, n, kk;
         unsigned long long geom;
         char name[128];
-        if (sscanf(line, "%d %d %d %d %d %lld %lld %lld %lld %llu %127s", &k.kind, &k.dt, &k.out, &k.amode, &k.bmode, &b, &m, &n, &kk,
-                   &geom, name) != 11)
+        int ks = 1;                                     // last field: slices of a split reduction (absent = 1)
+        if (sscanf(line, "%d %d %d %d %d %lld %lld %lld %lld %llu %127s %d", &k.kind, &k.dt, &k.out, &k.amode, &k.bmode, &b, &m, &n, &kk,
+                   &geom, name, &ks) < 11 || ks < 1 || ks > 64)
             continue;                                   // malformed line: ignored
         k.batch = b; k.M = m; k.N = n; k.K = kk; k.geom = geom;
         // records of another build may name variants this one does not have, or that do not fit the key
         for (int i = 0; i < kNumVariants; ++i)
             if (strcmp(kVariants[i].name, name) == 0 && record_fits(k, &kVariants[i])) {
-                g_tuned[k] = &kVariants[i];
+                g_tuned[k] = Choice{&kVariants[i], ks};      // a split that does not fit the problem is dropped when planned
                 break;
             }
     }
@@ -723,7 +908,7 @@ tir_status tir_conv1d(const void* x, const void* w, void* y, int64_t N, int64_t 
     Plan plan;
     tir_status st = plan_conv(true, x, w, y, N, 1, L, C, K, 1, R, 1, stride, 0, pad, 1, dil, groups, (int)in, (int)out, ep, &plan);
     if (st != TIR_OK) return st;
-    return run(plan, (hipStream_t)stream);
+    return launch(plan, (hipStream_t)stream);
 }
 
 tir_status tir_conv3d(const void* x, const void* w, void* y, int64_t N, int64_t D, int64_t H, int64_t W, int64_t C,
@@ -734,7 +919,7 @@ tir_status tir_conv3d(const void* x, const void* w, void* y, int64_t N, int64_t 
     Plan plan;
     tir_status st = plan_conv_geom(true, x, w, y, g, (int)in, (int)out, ep, &plan);
     if (st != TIR_OK) return st;
-    return run(plan, (hipStream_t)stream);
+    return launch(plan, (hipStream_t)stream);
 }
 
 tir_status tir_conv2d_transpose(const void* x, const void* w, void* y, int64_t N, int64_t H, int64_t W, int64_t C,
@@ -745,7 +930,7 @@ tir_status tir_conv2d_transpose(const void* x, const void* w, void* y, int64_t N
     Plan plan;
     tir_status st = plan_conv_geom(true, x, w, y, g, (int)in, (int)out, ep, &plan);
     if (st != TIR_OK) return st;
-    return run(plan, (hipStream_t)stream);
+    return launch(plan, (hipStream_t)stream);
 }
 
 const char* tir_version(void) { return "0.1"; }

@@ -17,8 +17,10 @@ template <class C> hipError_t launch_cfg(const Params& p, hipStream_t stream) {
         hipLaunchKernelGGL((conv_patch_kernel<C::DT, C::OUT>), grid, dim3(512), 0, stream, p);
     } else if constexpr (C::AMODE == A_GENERIC || C::AMODE == A_CONV_GENERIC)
         hipLaunchKernelGGL(contract_staged_kernel<C>, grid, dim3(C::THREADS), 0, stream, p);
-    else
+    else {
+        grid.z = (unsigned)p.ksplit;
         hipLaunchKernelGGL(contract_direct_kernel<C>, grid, dim3(C::THREADS), 0, stream, p);
+    }
     return hipGetLastError();
 }
 

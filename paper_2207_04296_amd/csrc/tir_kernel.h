@@ -361,6 +361,47 @@ __device__ __forceinline__ void store_tile(const Params& p, long long bz, int m0
     }
 }
 
+// Epilogue of one output phase of a transposed convolution: row m of the tile is pixel (img, op, oq) of the
+// phase's grid, i.e. pixel (op*phases_h + ph, oq*phases_w + pw) of the output image.  Rows are decoded with
+// the host's division constants; rows past M and pixels past the output's edge (extents not divisible by the
+// phase count) are switched off.
+template <class C, class acc_t>
+__device__ __forceinline__ void store_tile_phase(const Params& p, long long bz, int m0, int n0, int wm, int wn, int lane,
+                                                 acc_t (&acc)[C::MI][C::NI],
+                                                 const typename std::conditional<std::is_same<acc_t, f32x16>::value, float, int>::type (&bias_r)[C::NI],
+                                                 int ph, int pw) {
+    typedef typename OutTraits<C::OUT>::type out_t;
+    constexpr int OS = (int)sizeof(out_t);
+    const int l31 = lane & 31, g = lane >> 5;
+    const int cols = p.N - n0 < C::BN ? p.N - n0 : C::BN;
+    const int PQ = p.P * p.Q;
+    const long long total = (long long)p.batch_imgs * p.P_full * p.Q_full * p.c_rs * OS;      // bytes of the whole output
+    const __amdgpu_buffer_rsrc_t rc = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)((out_t*)p.C + bz * p.c_bs + n0), 0, (int)(total - (bz * p.c_bs + n0) * OS), 0x00020000);
+#pragma unroll
+    for (int j = 0; j < C::NI; ++j) asm volatile("" ::"v"(bias_r[j]));
+#pragma unroll
+    for (int i = 0; i < C::MI; ++i) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const unsigned m = (unsigned)(m0 + wm * C::TM + i * 32 + 8 * (r >> 2) + 4 * g + (r & 3));
+            const unsigned img = fastdiv(m, p.div_pq_magic, p.div_pq_shift);
+            const unsigned rem = m - img * (unsigned)PQ;
+            const unsigned op = fastdiv(rem, p.div_q_magic, p.div_q_shift);
+            const unsigned oq = rem - op * (unsigned)p.Q;
+            const int oh = (int)op * p.phases_h + ph, ow = (int)oq * p.phases_w + pw;
+            const bool row_ok = (int)m < p.M && oh < p.P_full && ow < p.Q_full;
+            const unsigned pix = ((img * (unsigned)p.P_full + (unsigned)oh) * (unsigned)p.Q_full + (unsigned)ow) * (unsigned)(p.c_rs * OS);
+#pragma unroll
+            for (int j = 0; j < C::NI; ++j) {
+                const int col = wn * C::TN + j * 32 + l31;
+                const unsigned voff = (row_ok && col < cols) ? pix + (unsigned)(col * OS) : kOutOfRange;
+                store_value(finish_value<C::OUT>(consumer(acc[i][j][r], bias_r[j], p.relu), p.scale), rc, (int)voff, 0);
+            }
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 // Fast kernel: vector copy modes, global -> LDS without a register hop, NSTAGE-deep copy ring.
 //
@@ -398,13 +439,41 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
     int tm, tn;
     tile_of_block(blockIdx.x, p.tiles_m, p.tiles_n, &tm, &tn);
     const int m0 = tm * C::BM, n0 = tn * C::BN;
-    const long long bz = blockIdx.y;
+    long long bz = blockIdx.y;
+
+    // Transposed convolution by output phase: this grid.y entry is (phase, group).  The phase's pixels are a
+    // stride-1 convolution with every phases-th filter tap, taken backwards (cursor tap (fr, fs) is filter tap
+    // (f_r0 - phases_h*fr, f_s0 - phases_w*fs)); tap count, padding and with them K differ per phase.
+    int cS = p.S, cK = p.K, cpad_h = p.pad_h, cpad_w = p.pad_w;
+    int f_r0 = 0, f_s0 = 0, ph = 0, pw = 0;
+    bool phased = false;
+    if constexpr (C::AMODE == A_CONV) {
+        phased = p.phases_h != 0;
+        if (phased) {
+            const int phase = (int)bz / p.conv_groups;
+            bz -= (long long)phase * p.conv_groups;
+            ph = phase / p.phases_w;
+            pw = phase - ph * p.phases_w;
+            const int r0 = (ph + p.t_pad_h) % p.phases_h, s0 = (pw + p.t_pad_w) % p.phases_w;
+            const int cR = p.R > r0 ? (p.R - r0 + p.phases_h - 1) / p.phases_h : 0;
+            cS = p.S > s0 ? (p.S - s0 + p.phases_w - 1) / p.phases_w : 0;
+            cpad_h = (cR - 1) - (ph + p.t_pad_h - r0) / p.phases_h;
+            cpad_w = (cS - 1) - (pw + p.t_pad_w - s0) / p.phases_w;
+            f_r0 = r0 + p.phases_h * (cR - 1);
+            f_s0 = s0 + p.phases_w * (cS - 1);
+            cK = cR * cS * p.Cg;                          // 0 for a phase no tap reaches: its pixels get the empty sum
+        }
+    }
 
     const char* Ab = (const char*)p.A + bz * p.a_bs * ES;
     const char* Bb = (const char*)p.B + bz * p.b_bs * ES;
-    const int nh_all = (p.K + BK - 1) / BK;             // stages of the reduction
-    const int nh = (nh_all + C::KW - 1) / C::KW;         // ... per group (the last one may be empty for some groups)
-    const bool ktail = (p.K % BK) != 0;                 // last stage is partly beyond K
+    const int nh_all = (cK + BK - 1) / BK;              // stages of the reduction
+    // this workgroup's slice of them (grid.z slices of nh_slice consecutive stages; the host makes every slice non-empty)
+    const int nh_slice = (nh_all + p.ksplit - 1) / p.ksplit;
+    const int s_begin = (int)blockIdx.z * nh_slice;
+    const int s_end = s_begin + nh_slice < nh_all ? s_begin + nh_slice : nh_all;
+    const int nh = (s_end - s_begin + C::KW - 1) / C::KW;   // ... per group (the last one may be empty for some groups)
+    const bool ktail = (cK % BK) != 0;                  // last stage is partly beyond K
 
     // ------------------------------------------------------------ copy stage: A
     // LDS slot q = tid + i*THREADS is row q/RCH, physical 16-byte column q%RCH of the [BM][ROWB]
@@ -414,6 +483,7 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
     unsigned a_off[C::A_IT];
     int a_hw[C::A_IT];
     int a_dz[C::AMODE == A_CONVX ? C::A_IT : 1];       // general decode: first input depth of the row's output pixel
+    int a_res[C::AMODE == A_CONVX ? C::A_IT : 1];      // ... and the remainders of its tap-(0,0) coordinates modulo the up-sampling
     const char* a_base = Ab;
     long long a_bytes = 0;     // valid bytes from a_base (at k = 0)
     if constexpr (C::AMODE == A_KMAJOR) {
@@ -442,9 +512,14 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
                 ih0 = op * p.stride_h - p.pad_h;
                 iw0 = oq * p.stride_w - p.pad_w;
             }
+            // coordinate = up * quotient + remainder (floor division, once per row): tap offsets are uniform per
+            // stage, so whether a tap hits an input pixel is decided by adding remainders, without a division
+            const int qh = ih0 >= 0 ? ih0 / p.up_h : -((-ih0 + p.up_h - 1) / p.up_h);
+            const int qw = iw0 >= 0 ? iw0 / p.up_w : -((-iw0 + p.up_w - 1) / p.up_w);
             a_off[i] = (unsigned)img * (unsigned)(p.D * p.H * p.W);
             a_dz[i] = id0;
-            a_hw[i] = (ih0 << 16) | (iw0 & 0xffff);
+            a_hw[i] = (qh << 16) | (qw & 0xffff);
+            a_res[i] = ((ih0 - qh * p.up_h) << 16) | (iw0 - qw * p.up_w);
         }
     } else {
         // ReIndex: row m of A_t is output pixel (img, op, oq) = unfuse(m); keep the element offset of
@@ -459,8 +534,8 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
                 img = m / PQ;
                 const int rem = m - img * PQ;
                 const int op = rem / p.Q, oq = rem - op * p.Q;
-                ih0 = op * p.stride_h - p.pad_h;
-                iw0 = oq * p.stride_w - p.pad_w;
+                ih0 = op * p.stride_h - cpad_h;
+                iw0 = oq * p.stride_w - cpad_w;
             }
             a_off[i] = (((unsigned)img * (unsigned)p.H + (unsigned)ih0) * (unsigned)p.W + (unsigned)iw0) * (unsigned)p.Cin;
             a_hw[i] = (ih0 << 16) | (iw0 & 0xffff);
@@ -504,7 +579,7 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
         conv_cc += stages * BK;
         while (conv_cc >= p.Cg) {
             conv_cc -= p.Cg;
-            if (++conv_fs == p.S) {
+            if (++conv_fs == cS) {
                 conv_fs = 0;
                 ++conv_fr;
                 if constexpr (C::AMODE == A_CONVX) {
@@ -513,7 +588,7 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
             }
         }
     };
-    if (conv_uniform_tap && C::KW > 1) conv_advance(kgrp);
+    if (conv_uniform_tap) conv_advance(s_begin + kgrp);
     i32x4 ra, rb;
     unsigned a_voff[C::A_IT];
     char* lds_dst = ring;    // wave-uniform destination of this wave's first A chunk
@@ -522,9 +597,10 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
     // by one through copy_unit() so that they can be interleaved with MFMAs.
     auto copy_begin = [&](int slot_stage) {
         lds_dst = ring + (slot_stage % NSTAGE) * C::STAGE_BYTES + wave * 1024;
-        const int stage = slot_stage * C::KW + kgrp;       // stage of the whole reduction
+        const int stage = s_begin + slot_stage * C::KW + kgrp;       // stage of the whole reduction
         const int nh = nh_all;
-        const bool live = stage < nh;      // past the end: empty descriptors, the copies write zeros (they add nothing)
+        const int tap_fr = conv_fr, tap_fs = conv_fs, tap_cc = conv_cc;    // the stage's tap, before the cursor moves on
+        const bool live = stage < s_end;   // past the end: empty descriptors, the copies write zeros (they add nothing)
         if constexpr (C::AMODE == A_KMAJOR) {
             ra = make_rsrc(a_base + (long long)stage * ROWB, live ? a_bytes - (long long)stage * ROWB : 0);
             if (ktail && stage == nh - 1) {
@@ -558,21 +634,19 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
                 fs = rs - fr * p.S;
                 kv = kb < p.K;
             }
+            // tap offset = up * quotient + remainder too (scalar in the one-tap-per-stage case); the sum of the two
+            // remainders is 0 or up exactly when the tap lands on an input pixel
             const int dd = ft * p.dil_d, dh = p.tap_sign * fr * p.dil_h, dw = p.tap_sign * fs * p.dil_w;
-            const bool up = p.up_h > 1 || p.up_w > 1;
+            const int dqh = dh >= 0 ? dh / p.up_h : -((-dh + p.up_h - 1) / p.up_h), drh = dh - dqh * p.up_h;
+            const int dqw = dw >= 0 ? dw / p.up_w : -((-dw + p.up_w - 1) / p.up_w), drw = dw - dqw * p.up_w;
 #pragma unroll
             for (int i = 0; i < C::A_IT; ++i) {
                 const int idn = a_dz[i] + dd;
-                int ih = (a_hw[i] >> 16) + dh;
-                int iw = (int)(short)(a_hw[i] & 0xffff) + dw;
-                bool ok = kv && (unsigned)idn < (unsigned)p.D && ih >= 0 && iw >= 0;
-                if (up) {
-                    const int qh = ih / p.up_h, qw = iw / p.up_w;
-                    ok = ok && qh * p.up_h == ih && qw * p.up_w == iw;
-                    ih = qh;
-                    iw = qw;
-                }
-                ok = ok && ih < p.H && iw < p.W;
+                const int sh = (a_res[i] >> 16) + drh, sw = (a_res[i] & 0xffff) + drw;
+                const int ih = (a_hw[i] >> 16) + dqh + (sh == p.up_h ? 1 : 0);
+                const int iw = (int)(short)(a_hw[i] & 0xffff) + dqw + (sw == p.up_w ? 1 : 0);
+                const bool ok = kv && (unsigned)idn < (unsigned)p.D && (sh == 0 || sh == p.up_h) && (sw == 0 || sw == p.up_w) &&
+                                (unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W;
                 a_voff[i] = ok ? ((a_off[i] + (unsigned)((idn * p.H + ih) * p.W + iw)) * (unsigned)p.Cin + (unsigned)cc) * ES : kOutOfRange;
             }
         } else {
@@ -610,7 +684,10 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
             }
         }
         if constexpr (C::BMODE == B_KMAJOR) {
-            rb = make_rsrc(b_base + (long long)stage * ROWB, live ? b_bytes - (long long)stage * ROWB : 0);
+            // k offset of the stage inside a filter row: consecutive, or (by phase) that of the tap it stands for
+            const long long kb = phased ? (long long)(((f_r0 - p.phases_h * tap_fr) * p.S + (f_s0 - p.phases_w * tap_fs)) * p.Cg + tap_cc) * ES
+                                        : (long long)stage * ROWB;
+            rb = make_rsrc(b_base + kb, live ? b_bytes - kb : 0);
             if (ktail && stage == nh - 1) {
                 const bool kv = stage * BK + b_lc * VEC < p.K;
 #pragma unroll
@@ -732,6 +809,80 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
 #pragma unroll
                     for (int e = 0; e < 4; ++e) acc[i][j][r4 * 4 + e] += v[e];
                 }
+    }
+    if (p.ksplit > 1) {
+        // Reduction split over workgroups.  Every slice leaves its partial sums in the workspace (one
+        // 16-byte vector per lane and store: whole lines) and counts itself at the tile's counter; the
+        // slice that finds every other one already counted adds all partial sums - its own included,
+        // from memory, in slice order, so the rounding does not depend on the order of arrival - and
+        // finishes the tile.  Nobody waits for anybody.
+        // The slices of a tile run on different XCDs, whose L2s do not see each other's lines: the partial
+        // sums are written through to memory and read past the caches (system-scope stores and loads);
+        // a release / acquire fence pair would write back and invalidate a whole L2 per workgroup instead
+        // (measured: 50-100 us per launch).  The stores have left the L2 when their counter drains, which
+        // is before the workgroup's arrival is counted.
+        typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+        constexpr int SLICE_BYTES = C::BM * C::BN * 4;
+        constexpr int kSystemScope = 17;                         // sc0 | sc1
+        const long long tile_lin = bz * ((long long)p.tiles_m * p.tiles_n) + blockIdx.x;
+        const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(
+            (char*)p.ws + tile_lin * p.ksplit * SLICE_BYTES, 0, p.ksplit * SLICE_BYTES, 0x00020000);
+        const int lane_off = (wave * (C::MI * C::NI * 4 * 64) + lane) * 16;     // block (i, j), quarter r4: + ((i*NI + j)*4 + r4) * 1024
+#pragma unroll
+        for (int i = 0; i < C::MI; ++i)
+#pragma unroll
+            for (int j = 0; j < C::NI; ++j)
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    u32x4 v;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const acc_e t = acc[i][j][r4 * 4 + e];      // a copy: bit_cast applied to a vector element reads element 0
+                        v[e] = __builtin_bit_cast(unsigned, t);
+                    }
+                    __builtin_amdgcn_raw_buffer_store_b128(v, rw, lane_off + ((i * C::NI + j) * 4 + r4) * 1024,
+                                                           (int)blockIdx.z * SLICE_BYTES, kSystemScope);
+                }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");        // this wave's partial sums are in memory
+        __syncthreads();                                        // ... and every wave's
+        unsigned* const flag = (unsigned*)smem;                 // the rings are idle: every wave is past its last read
+        if (threadIdx.x == 0) *flag = __hip_atomic_fetch_add(p.ws_count + tile_lin, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        __syncthreads();
+        if (*flag != (unsigned)p.ksplit - 1u) return;
+        if (threadIdx.x == 0) __hip_atomic_store(p.ws_count + tile_lin, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);   // ready for the next launch
+#pragma unroll
+        for (int i = 0; i < C::MI; ++i)
+#pragma unroll
+            for (int j = 0; j < C::NI; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+        // G slices are requested together (a load from memory takes longer than adding a slice) and added in
+        // slice order; slices past the last one are switched off and add zeros
+        constexpr int G = C::MI * C::NI <= 2 ? 4 : 2;
+        for (int z0 = 0; z0 < p.ksplit; z0 += G) {
+            u32x4 part[G][C::MI * C::NI * 4];
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+#pragma unroll
+                for (int q = 0; q < C::MI * C::NI * 4; ++q)
+                    part[g][q] = __builtin_amdgcn_raw_buffer_load_b128(rw, z0 + g < p.ksplit ? lane_off + q * 1024 : (int)kOutOfRange,
+                                                                       (z0 + g) * SLICE_BYTES, kSystemScope);
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+#pragma unroll
+                for (int q = 0; q < C::MI * C::NI * 4; ++q)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const unsigned t = part[g][q][e];
+                        acc[q / (C::NI * 4)][(q / 4) % C::NI][(q % 4) * 4 + e] += __builtin_bit_cast(acc_e, t);
+                    }
+        }
+    }
+    if constexpr (C::AMODE == A_CONV) {
+        if (phased) {
+            store_tile_phase<C>(p, bz, m0, n0, wm, wn, lane, acc, bias_r, ph, pw);
+            return;
+        }
     }
     store_tile<C>(p, bz, m0, n0, wm, wn, lane, acc, bias_r);
 }

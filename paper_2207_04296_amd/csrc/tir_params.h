@@ -50,6 +50,20 @@ struct Params {
     long long bias_bs;   // bias elements between consecutive grid.y slices (conv groups: channels per group; batches: 0)
     int relu;
     float scale;         // int8 output only: code = clamp(rint(float(t) * scale), -128, 127)
+    // Transposed convolution by output phase (A_CONV variants; phases_h = 0: off).  The output pixels with
+    // (oh mod phases_h, ow mod phases_w) = (ph, pw) form a stride-1 convolution of the input with the filter taps
+    // r = r0 + phases_h*t, r0 = (ph + t_pad_h) mod phases_h (likewise in w): grid.y enumerates (phase, group), the
+    // kernel derives that phase's tap subset, padding and output pixels.  P, Q are then the extents of one phase's
+    // pixel grid (ceil(P_full / phases_h) ...), M = images * P * Q, R, S, K those of the whole filter.
+    int phases_h, phases_w, t_pad_h, t_pad_w, P_full, Q_full, conv_groups;
+    unsigned div_pq_magic, div_q_magic;      // m / (P*Q) and m / Q for m < 2^31: (m * magic) >> (32 + shift)
+    int div_pq_shift, div_q_shift;           // shift < 0: divisor 1
+    // reduction split over workgroups (fast kernels): ksplit slices (grid.z) reduce consecutive runs of stages
+    // of one output tile; each writes its partial sums to ws, the slice that arrives last at the tile's counter
+    // adds all of them in slice order (the sum does not depend on who is last) and runs the epilogue
+    int ksplit;          // 1: no split, ws and ws_count unused
+    void* ws;            // partial sums: [grid.y][tile][slice][BM*BN] accumulator elements (4 bytes each)
+    unsigned* ws_count;  // [grid.y][tile] arrival counters, zero between launches (the last slice resets its tile's)
 };
 
 // Number of XCDs (L2 domains) workgroups are dealt to round-robin by the dispatcher.
@@ -73,6 +87,29 @@ __host__ __device__ inline void tile_of_block(int bid, int tiles_m, int tiles_n,
     int in_group = logical - group * width;
     *tm = first_m + in_group % gsz;
     *tn = in_group / gsz;
+}
+
+// Exact unsigned division of m < 2^31 by a fixed d >= 1: the host picks s = ceil(log2 d) and
+// magic = floor(2^(31+s) / d) + 1 < 2^32, then m / d = (m * magic) >> (31 + s).  d = 1 is shift = -1.
+struct FastDiv {
+    unsigned magic;
+    int shift;      // applied to the high half of the product: s - 1
+};
+inline FastDiv make_fastdiv(unsigned d) {
+    FastDiv f = {0u, -1};
+    if (d <= 1) return f;
+    int s = 0;
+    while ((1ull << s) < d) ++s;
+    f.magic = (unsigned)(((1ull << (31 + s)) / d) + 1ull);
+    f.shift = s - 1;
+    return f;
+}
+__host__ __device__ inline unsigned fastdiv(unsigned m, unsigned magic, int shift) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    return shift < 0 ? m : __umulhi(m, magic) >> shift;
+#else
+    return shift < 0 ? m : (unsigned)(((unsigned long long)m * magic) >> 32) >> shift;
+#endif
 }
 
 constexpr int elem_size(int dt) { return dt == DT_I8 ? 1 : (dt == DT_F16 || dt == DT_BF16) ? 2 : 4; }

@@ -4,6 +4,7 @@ output tiles bijectively."""
 import re
 from pathlib import Path
 
+import numpy as np
 import pytest
 
 from paper_2207_04296_amd import binding as B
@@ -99,6 +100,18 @@ def test_block_to_tile_map_is_a_bijection(tiles):
     assert all(0 <= a < tm and 0 <= b < tn for a, b in seen)
 
 
+def test_division_by_launch_constants_is_exact():
+    """The kernels decode output rows with multiply-and-shift constants; exact for every dividend below 2^31."""
+    rng = np.random.default_rng(5)
+    divisors = [1, 2, 3, 5, 7, 28, 49, 56, 784, 3136, 12544, 65535, 65536, 65537, 2**30 - 1, 2**30, 2**30 + 1, 2**31 - 1]
+    divisors += [int(x) for x in rng.integers(1, 2**31, 40)]
+    for d in divisors:
+        edge = [0, 1, d - 1, d, d + 1, 2 * d - 1, 2 * d, 2**31 - 1, 2**31 - 2, (2**31 - 1) // d * d, (2**31 - 1) // d * d - 1]
+        for m in edge + [int(x) for x in rng.integers(0, 2**31, 200)]:
+            if 0 <= m < 2**31:
+                assert B.tir_debug_fastdiv(d, m) == m // d, (d, m)
+
+
 def test_variant_choice_reflects_layout():
     # row-major B is read N-major, a transposed B K-major; odd K falls back to the general kernel
     assert B.tir_gemm_variant(1, 4096, 4096, 4096, 4096, 1, 4096, 1, 4096, 1, "f16", "f32").endswith("ak_bn")
@@ -146,13 +159,53 @@ def test_tuning_records_load_save_and_steer_the_choice(tmp_path):
         out = tmp_path / "saved.txt"
         B.tir_tune_save(out)
         lines = out.read_text().splitlines()
-        assert lines[0] == "tir-tune-records 1" and lines[1:] == [f"0 0 3 0 1 1 512 512 512 0 {other}"]
+        assert lines[0] == "tir-tune-records 1" and lines[1:] == [f"0 0 3 0 1 1 512 512 512 0 {other} 1"]   # last field: reduction slices
         B.tir_tune_clear()
         assert B.tir_tune_count() == 0 and _gemm_variant_512() == default
         B.tir_tune_load(out)
         assert _gemm_variant_512() == other
     finally:
         B.tir_debug_force_variant("")
+        B.tir_tune_clear()
+
+
+def test_reduction_split_is_planned_only_where_it_fits(tmp_path):
+    """A reduction can be split over several workgroups per output tile ("<variant>/z<slices>"): only by the fast
+    kernels, only when every slice gets a stage, and the scoring rule asks for it when few tiles face a long K."""
+    def gemm(M, N, K, batch=1):
+        return B.tir_gemm_variant(batch, M, N, K, K, 1, 1, K, N, 1, "f16", "f32")
+    B.tir_tune_clear()
+    try:
+        assert "/z" not in gemm(4096, 4096, 4096)                     # the tiles fill the CUs: no split
+        auto = gemm(128, 128, 16384)
+        assert "/z" in auto and 2 <= int(auto.split("/z")[1]) <= 8    # 1-4 tiles, 256 stages
+        B.tir_debug_force_ksplit(4)
+        assert gemm(128, 128, 16384).endswith("/z4")
+        assert gemm(4096, 4096, 4096).endswith("/z4") is False       # workspace: 256 tiles x 4 slices x 256 KiB > 32 MiB
+        assert "/z" not in gemm(128, 128, 128)                        # two stages cannot feed four slices
+        assert gemm(128, 128, 256).endswith("/z4")                    # four stages can
+        assert "/z" not in gemm(100, 100, 4001)                       # odd K: the general kernel does not split
+        assert "/z" not in B.tir_conv2d_variant(1, 8, 8, 3, 8, 3, 3, 1, 1, 1, 1, 1, 1, 1, "f16", "f16")
+        conv = B.tir_conv2d_variant(2, 14, 14, 256, 64, 3, 3, 1, 1, 1, 1, 1, 1, 1, "f16", "f16")
+        assert conv.endswith("/z4") and "patch" not in conv
+        B.tir_debug_force_ksplit(0)
+        # a record carries the split; one that does not fit its problem is planned without it
+        name = "f16_f32_t64x64w2x2s3_ak_bk"
+        assert name in B.tir_debug_variant_names()
+        rec = tmp_path / "split.txt"
+        rec.write_text("tir-tune-records 1\n"
+                       f"0 0 3 0 0 1 128 128 16384 0 {name} 6\n"
+                       f"0 0 3 0 0 1 128 128 128 0 {name} 6\n"
+                       f"0 0 3 0 0 1 128 128 256 0 {name} 99\n")           # out of range: skipped
+        B.tir_tune_load(rec)
+        assert B.tir_tune_count() == 2
+        assert gemm(128, 128, 16384) == name + "/z6"
+        assert gemm(128, 128, 128) == name
+        out = tmp_path / "saved.txt"
+        B.tir_tune_save(out)
+        assert f"0 0 3 0 0 1 128 128 16384 0 {name} 6" in out.read_text().splitlines()
+    finally:
+        B.tir_debug_force_ksplit(0)
         B.tir_tune_clear()
 
 

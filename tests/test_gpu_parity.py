@@ -4,6 +4,7 @@ seeded inputs.  int8 -> int32 must be bit-exact; fp16 / bf16 within 2e-3*S + 1e-
 Sizes: the small cases span several workgroup tiles plus a ragged tail and finish in the oracle
 within seconds; the five benchmark configurations run at full size (the 4096^3 GEMM is checked on
 256 whole rows and 256 whole columns, each an exact oracle result, spread over every tile)."""
+import dataclasses
 import sys
 
 import numpy as np
@@ -346,7 +347,7 @@ def test_tuning_measures_records_and_keeps_results_correct(B, oracle, tmp_path):
             torch.cuda.synchronize()
             assert us > 0.0 and B.tir_tune_count() == n_rec
             name = PT.variant_name(B, wl)
-            assert name in names and name.startswith(f"{wl.dtype}_{wl.out}_")
+            assert name.split("/z")[0] in names and name.startswith(f"{wl.dtype}_{wl.out}_")
             chosen[wl.name] = name
             # the tuner's last trial left a valid result in c; a fresh call uses the record
             PT.assert_close(PT.gpu_to_f64(c), ref, S, f"{wl.name} after tuning")
@@ -616,6 +617,51 @@ def test_conv2d_transpose_matches_oracle(B, oracle, dtype, out):
         PT.assert_close(PT.gpu_to_f64(y), ref, S, "conv2d_transpose")
 
 
+@pytest.mark.parametrize("dtype,out", [("f16", "f16"), ("f16", "f32"), ("bf16", "f32"), ("i8", "i32"), ("i8", "i8")])
+def test_conv2d_transpose_by_output_phase(B, oracle, dtype, out):
+    """Strided, undilated transposed convolutions whose channel blocks fill whole stages run as stride_h*stride_w
+    stride-1 convolutions (one per output phase, with that phase's taps) in one launch; same bar, and the gather
+    form of the same problem (forced) must agree with the oracle as well."""
+    import torch
+    dist = "i" if dtype == "i8" else "n0.1"
+    cg = 128 if dtype == "i8" else 64
+    cases = [
+        # N, H, W, C, K, R, S, stride, pad, outpad, groups, bias, relu
+        (2, 14, 14, cg, 48, 4, 4, (2, 2), (1, 1), (0, 0), 1, False, False),        # the usual 2x up-sampling block: 4 phases of 2x2 taps
+        (1, 9, 11, 2 * cg, 40, 3, 3, (2, 2), (1, 1), (1, 1), 2, True, True),       # groups; phases with 2 and with 1 tap per axis
+        (2, 7, 8, cg, 32, 2, 5, (3, 2), (0, 2), (2, 0), 1, True, False),           # filter shorter than the stride: a phase without taps
+        (1, 6, 6, 2 * cg, 64, 5, 5, (2, 3), (2, 1), (1, 2), 1, False, True),       # two stages per tap; output extents not divisible
+        (1, 5, 7, cg, 16, 1, 1, (2, 2), (0, 0), (1, 1), 1, False, False),          # 1x1 filter: three of four phases are empty sums
+        (3, 1, 20, cg, 24, 1, 4, (1, 4), (0, 0), (0, 3), 1, True, False),          # a 1-D up-sampling by 4
+    ]
+    for (N, H, W, C, K, R, S_, stride, pad, outpad, groups, bias, relu) in cases:
+        scale = 1.0 / 700.0 if out == "i8" else 0.0
+        if out == "i8":
+            bias = True
+        name = B.tir_conv2d_transpose_variant(N, H, W, C, K, R, S_, stride, pad, (1, 1), outpad, groups, dtype, out)
+        _say(f"conv2d_transpose by phase {dtype}->{out} N={N} H={H} W={W} C={C} K={K} R={R} S={S_} s={stride} p={pad} op={outpad} g={groups} -> {name}")
+        assert name.endswith(f"/ph{stride[0]}x{stride[1]}"), name
+        xb = I.make_tensor(dtype, dist, 9930 + H, (N, H, W, C)); wb = I.make_tensor(dtype, dist, 9931 + K, (K, R, S_, C // groups))
+        ref, S = oracle.conv2d_transpose(dtype, xb, wb, stride, pad, (1, 1), outpad, groups)
+        bias_v = None
+        if bias or relu or scale:
+            if bias:
+                bias_v = (I.int8_uniform(9932 + K, K).astype(np.int32) * np.int32(64)) if dtype == "i8" else I.normal(9932 + K, K, 0.1).astype(np.float32)
+            ref, S = oracle.epilogue(ref, S, bias=bias_v, relu=relu, scale=scale)
+        xd, wd = B.to_device(xb, dtype), B.to_device(wb, dtype)
+        bias_d = None if bias_v is None else torch.from_numpy(bias_v).cuda()
+        ep = B.make_epilogue(bias_d, relu, scale)
+        try:
+            for force in ("", "convx"):
+                B.tir_debug_force_variant(force)
+                y = _gpu_out(B, ref.shape, out)
+                B.tir_conv2d_transpose(xd, wd, y, N, H, W, C, K, R, S_, stride, pad, (1, 1), outpad, groups, dtype, out, ep=ep)
+                torch.cuda.synchronize()
+                PT.assert_close(PT.gpu_to_f64(y), ref, S, f"conv2d_transpose {'by phase' if not force else 'as a gather'}")
+        finally:
+            B.tir_debug_force_variant("")
+
+
 # ------------------------------------------------------------------------------ depth-wise convolution
 DEPTHWISE_CASES = [
     # dtype, out, n, h, w, c, r, s, stride, pad, dil, bias, relu, scale
@@ -656,3 +702,80 @@ def test_batch_count_beyond_one_launch(B, oracle, K, bias):
     wl = I.Workload(f"bmm_many_k{K}", "bmm", "f16", "f32", "u", 9990 + K, batch=70001, M=16, N=16, K=K, trans_b=(K == 24), ep_bias=bias)
     _say(f"{wl.name} -> {PT.variant_name(B, wl)}")
     PT.check_workload(wl, oracle)
+
+
+# ------------------------------------------------------------------------------ reduction split over workgroups
+SPLIT_GEMMS = [
+    # batch, M, N, K, trans_b      few tiles, long K; ragged tiles; K tail inside the last slice (every K leaves no
+    # slice of 2, 3 or 8 empty, for 32-, 64- and 128-element stages)
+    (1, 64, 64, 4096, True),
+    (1, 96, 72, 1800, False),
+    (3, 130, 40, 3592, True),
+    (1, 33, 40, 1024, False),
+]
+
+
+@pytest.mark.parametrize("ks", [2, 3, 8])
+@pytest.mark.parametrize("dtype,out", [("f16", "f32"), ("f16", "f16"), ("bf16", "f32"), ("i8", "i32")])
+def test_reduction_split_over_workgroups(B, oracle, ks, dtype, out):
+    """ksplit workgroups per output tile, each reducing a run of stages; the last to arrive adds the partial sums in
+    slice order.  Same bar as the unsplit kernels; two launches in a row give bit-identical results (the sum does
+    not depend on the order of arrival, the tile counters are back at zero)."""
+    import torch
+    try:
+        for force in ("", "t64x64w2x2s3k2_"):
+            B.tir_debug_force_variant(force)
+            B.tir_debug_force_ksplit(ks)
+            for (batch, M, N, K, trans_b) in SPLIT_GEMMS:
+                if dtype == "i8":
+                    K = (K + 15) // 16 * 16
+                    N = (N + 15) // 16 * 16
+                kind = "bmm" if batch > 1 else "gemm"
+                wl = I.Workload(f"split{ks}_{kind}_{batch}x{M}x{N}x{K}_{dtype}_{out}_tb{int(trans_b)}", kind, dtype, out,
+                                "i" if dtype == "i8" else "u", 9700 + M + K, batch=batch, M=M, N=N, K=K, trans_b=trans_b)
+                name = PT.variant_name(B, wl)
+                _say(f"{wl.name} -> {name}")
+                assert name.endswith(f"/z{ks}"), name
+                a_bits, b_bits = wl.operands()
+                ref, S = PT.run_oracle(wl, a_bits, b_bits, oracle)
+                first = PT.run_gpu(wl, a_bits, b_bits)
+                PT.assert_close(first, ref, S, f"{wl.name} via {name}")
+                # other operands through the same workspace in between: a slice read from a stale cache line would show
+                wl2 = dataclasses.replace(wl, name=wl.name + "_other", seed=wl.seed + 1)
+                a2, b2 = wl2.operands()
+                ref2, S2 = PT.run_oracle(wl2, a2, b2, oracle)
+                PT.assert_close(PT.run_gpu(wl2, a2, b2), ref2, S2, f"{wl2.name} via {name}")
+                again = PT.run_gpu(wl, a_bits, b_bits)
+                assert np.array_equal(first, again), f"{wl.name}: two launches differ"
+    finally:
+        B.tir_debug_force_variant("")
+        B.tir_debug_force_ksplit(0)
+
+
+@pytest.mark.parametrize("dtype,out", [("f16", "f16"), ("i8", "i8")])
+def test_reduction_split_convolutions_with_consumer(B, oracle, dtype, out):
+    """Split reductions under the convolution decodes (2-D strided, grouped; 3-D) with the fused consumer applied by
+    the slice that finishes the tile."""
+    import torch
+    vec = 16 if dtype == "i8" else 8
+    dist = "i" if dtype == "i8" else "n0.1"
+    try:
+        B.tir_debug_force_ksplit(3)
+        wl = I.Workload(f"split_conv_{dtype}_{out}", "conv2d", dtype, out, dist, 9800, n=2, h=14, w=13, c=16 * vec, k=48, r=3, s=3,
+                        stride=(2, 1), pad=(1, 1), dil=(1, 1), groups=2, ep_bias=True, ep_relu=True,
+                        **({"ep_scale": 1.0 / 900.0} if out == "i8" else {}))
+        name = PT.variant_name(B, wl)
+        _say(f"{wl.name} -> {name}")
+        assert name.endswith("/z3"), name
+        PT.check_workload(wl, oracle)
+        if out != "i8":
+            N, D, H, W, C, K, T, R, S_ = 1, 5, 8, 8, 8 * vec, 40, 3, 3, 3
+            xb = I.make_tensor(dtype, dist, 9810, (N, D, H, W, C)); wb = I.make_tensor(dtype, dist, 9811, (K, T, R, S_, C))
+            ref, S = oracle.conv3d(dtype, xb, wb, (1, 1, 1), (1, 1, 1), (1, 1, 1), 1)
+            y = _gpu_out(B, ref.shape, out)
+            _say("split conv3d")
+            B.tir_conv3d(B.to_device(xb, dtype), B.to_device(wb, dtype), y, N, D, H, W, C, K, T, R, S_, (1, 1, 1), (1, 1, 1), (1, 1, 1), 1, dtype, out)
+            torch.cuda.synchronize()
+            PT.assert_close(PT.gpu_to_f64(y), ref, S, "split conv3d")
+    finally:
+        B.tir_debug_force_ksplit(0)
