@@ -177,7 +177,7 @@ static uint64_t hash_fields(const int64_t* f, int n) {
 // deep rings when one workgroup per CU must hide the global latency alone, shallow ones when
 // several workgroups share a CU (their LDS must fit side by side) or the reduction is short.
 //
-// A reduction much longer than the tile grid is wide (few tiles, many stages) is split over several
+// A reduction much longer than the tile grid is wide (few small tiles, many stages) is split over several
 // workgroups per tile, as many as fill the CUs once while each keeps at least eight stages.
 static Choice pick(int dt, int out, int amode, int bmode, int64_t batch, int64_t M, int64_t N, int64_t K) {
     Choice best = kNoChoice;
@@ -192,9 +192,11 @@ static Choice pick(int dt, int out, int amode, int bmode, int64_t batch, int64_t
         if (g_force_bm && v->bm == g_force_bm && v->bn == g_force_bn && v->kw == 1) return Choice{v, forced_ks};
         const double tm = (double)((M + v->bm - 1) / v->bm), tn = (double)((N + v->bn - 1) / v->bn);
         int ks = forced_ks;
-        if (!g_force_ksplit) {
+        // (the partial sums' trip through memory costs about 4 us for a 64x64 tile and grows with the tile: it pays
+        // only for small tiles whose wave groups face two dozen stages or more)
+        if (!g_force_ksplit && v->bm * v->bn <= 64 * 64) {
             const int64_t stages = (K * es + v->rowb - 1) / v->rowb;
-            int64_t want = (int64_t)kCUs / (tiles_1 * batch);
+            int64_t want = stages / v->kw >= 24 ? (int64_t)kCUs / (tiles_1 * batch) : 1;
             if (want > stages / (8 * v->kw)) want = stages / (8 * v->kw);
             if (want > 8) want = 8;
             while (want > 1 && !split_fits(v, (int)want, batch, tiles_1, K)) --want;
@@ -569,7 +571,9 @@ static tir_status tune_problem(MakePlan make_plan, int reps, hipStream_t stream,
         (void)hipEventDestroy(e0);
         return fail(TIR_ERR_LAUNCH, "hipEventCreate failed: %s", hipGetErrorString(ce));
     }
-    // the legacy default stream cannot be captured: trials then run on a stream of their own
+    // the legacy default stream cannot be captured: trials then run on a stream of their own (which borrows the
+    // caller's stream's workspace: everything queued there has finished, and the trials finish before the call returns)
+    const hipStream_t caller_stream = stream;
     hipStream_t own = nullptr;
     if (!stream) {
         ce = hipStreamCreateWithFlags(&own, hipStreamNonBlocking);
@@ -595,7 +599,7 @@ static tir_status tune_problem(MakePlan make_plan, int reps, hipStream_t stream,
         g_trial = Choice{v, ks};
         Plan pl;
         st = make_plan(&pl);
-        if (st == TIR_OK) st = attach_workspace(&pl, stream);
+        if (st == TIR_OK) st = attach_workspace(&pl, caller_stream);
         if (st != TIR_OK) break;
         if (pl.p.ksplit != ks) continue;              // this split does not apply
         if (ks > 1) {
