@@ -306,4 +306,13 @@ def test_conv1d_conv3d_and_transposed_conv_validate_on_the_host():
     assert ct(s=(0, 1)) == B.TIR_ERR_INVALID_ARG
     assert ct(H=1, W=1, R=1, S=1, p=(1, 1), op=(0, 0), s=(1, 1)) == B.TIR_ERR_INVALID_ARG   # extent (1-1)*1 - 2 + 0 + 0 + 1 < 1
     assert ct(K=15, groups=2) == B.TIR_ERR_INVALID_ARG
+    assert ct(H=1, s=(20000, 1), op=(0, 0)) == B.TIR_ERR_UNSUPPORTED    # the kernels keep remainders modulo the stride in 16 bits
     assert ct(N=0) == B.TIR_OK
+    # by output phase: only undilated, strided, whole 128-byte channel blocks; the queries report how a problem would run
+    q = lambda C, s, d, dt="f16": B.tir_conv2d_transpose_variant(2, 8, 8, C, 32, 4, 4, s, (1, 1), d, (0, 0), 1, dt, dt if dt != "i8" else "i32")
+    assert q(64, (2, 2), (1, 1)).endswith("_conv/ph2x2")
+    assert q(128, (1, 3), (1, 1)).endswith("_conv/ph1x3")
+    assert q(128, (2, 2), (1, 1), "i8").endswith("_conv/ph2x2") and "ph" not in q(64, (2, 2), (1, 1), "i8")
+    assert "convx" in q(64, (2, 2), (2, 1)) and "convx" in q(32, (2, 2), (1, 1)) and "convx" in q(64, (1, 1), (1, 1))
+    assert B.tir_conv3d_variant(1, 10, 16, 16, 128, 64, 3, 3, 3, (1, 1, 1), (1, 1, 1), (1, 1, 1), 1, "f16", "f16").endswith("_convx/z6")
+    assert B.tir_conv3d_variant(1, 0, 16, 16, 128, 64, 3, 3, 3, (1, 1, 1), (1, 1, 1), (1, 1, 1), 1, "f16", "f16") == ""

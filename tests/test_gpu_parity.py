@@ -44,6 +44,32 @@ def test_config_full_size(B, oracle, name):
     _say(f"{name} max err/tol {ratio:.3g}")
 
 
+@pytest.mark.parametrize("name", FULL + list(I.FUSED_WORKLOADS))
+def test_config_full_size_in_the_measured_launch_configuration(B, oracle, name):
+    """bench.py tunes each workload (tir_tune_*) before it times it: the variant the records then select - which
+    may differ from the scoring rule's - must meet the same bar at full size."""
+    import torch
+    wl = I.WORKLOADS.get(name) or I.FUSED_WORKLOADS[name]
+    a_bits, b_bits = wl.operands()
+    a, b = B.to_device(a_bits, wl.dtype), B.to_device(b_bits, wl.dtype)
+    c = B.empty_out(B.out_shape(wl), wl.out)
+    bias = B.bias_to_device(wl)
+    B.tir_tune_clear()
+    try:
+        us = B.tune_workload(wl, a, b, c, bias, reps=5)
+        name_tuned = PT.variant_name(B, wl)
+        _say(f"{name}: tuned to {name_tuned} ({us:.2f} us)")
+        assert us > 0.0 and B.tir_tune_count() == 1
+        ref, S = PT.run_oracle(wl, a_bits, b_bits, oracle)
+        c.fill_(float("nan") if c.dtype.is_floating_point else -77)
+        B.run_workload(wl, a, b, c, bias)
+        torch.cuda.synchronize()
+        ratio = PT.assert_close(PT.gpu_to_f64(c), ref, S, f"{name} via {name_tuned}")
+        _say(f"{name} max err/tol {ratio:.3g}")
+    finally:
+        B.tir_tune_clear()
+
+
 @pytest.mark.parametrize("name", list(I.FUSED_WORKLOADS) + list(I.MORE_WORKLOADS))
 def test_config_full_size_with_fused_consumer(B, oracle, name):
     """The benchmark operators with a consumer fused behind the tensorized block: bias + ReLU, down-cast
