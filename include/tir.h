@@ -12,8 +12,15 @@
  *                       mapped onto Eq. 1 by ReIndex + fuse: x = fuse(n,h,w), y = co, k = fuse(rh,rw,rc))
  *
  * Common conventions
- *   - Every pointer is a DEVICE pointer owned by the caller.  The library never allocates, frees,
- *     copies to the host or synchronises; each call enqueues kernels on `stream` and returns.
+ *   - Every pointer is a DEVICE pointer owned by the caller.  The library never copies to the host or
+ *     synchronises; each call enqueues kernels on `stream` and returns.  It allocates in one case only: a
+ *     reduction that is split over several workgroups per output tile (few small tiles facing a long K; the
+ *     variant queries report it as "<variant>/z<slices>") keeps partial sums and arrival counters in a
+ *     workspace of 32 MiB + 64 KiB per (device, stream), allocated with hipMalloc on the first such launch
+ *     (which also synchronises the device once) and kept until the process ends.  Launches on one stream
+ *     share it in stream order; a stream under capture that has no workspace yet runs the same kernel
+ *     without the split.  The result does not depend on the split's timing: the partial sums are added in a
+ *     fixed order.
  *   - The output is fully overwritten (reduction init is 0; there is no alpha / beta), and must not
  *     overlap an input.
  *   - Inputs F16 / BF16 accumulate in fp32; input I8 accumulates in int32 (wrap-around on overflow,
@@ -132,6 +139,10 @@ tir_status tir_conv2d_fused(const void* x, const void* w, void* y, int64_t N, in
  *     columns that receive no or fewer contributions).  Every input pixel (ih, iw) adds
  *     x[n,ih,iw,g*C/groups + c] * w[k,r,s,c] to y[n, ih*stride_h - pad_h + r*dil_h, iw*stride_w - pad_w + s*dil_w, k]
  *     (targets outside y are dropped).  Computed as a gather: no atomics, the result is deterministic.
+ *     Strided, undilated problems whose C/groups channels fill whole 128-byte blocks are computed per
+ *     output phase (oh mod stride_h, ow mod stride_w): stride_h*stride_w stride-1 convolutions with the
+ *     taps each phase can reach, in one launch (variant query: "<variant>/ph<stride_h>x<stride_w>");
+ *     strides above 16383 are TIR_ERR_UNSUPPORTED.
  */
 tir_status tir_conv1d(const void* x, const void* w, void* y, int64_t N, int64_t L, int64_t C, int64_t K, int64_t R,
                       int stride, int pad, int dil, int groups, tir_dtype in, tir_dtype out, const tir_epilogue* ep,
