@@ -805,3 +805,61 @@ def test_reduction_split_convolutions_with_consumer(B, oracle, dtype, out):
             PT.assert_close(PT.gpu_to_f64(y), ref, S, "split conv3d")
     finally:
         B.tir_debug_force_ksplit(0)
+
+
+# ------------------------------------------------------------------------------ maximum sizes
+def test_gemm_operands_beyond_two_gib(B, oracle):
+    """A and C of more than 2^31 bytes each (M = 2^24 + 33 rows): base pointers advance in 64 bits, only offsets
+    inside one tile are 32-bit.  A repeats a seeded block of 999 983 rows (a count that does not divide 2^31
+    bytes, so an address that wrapped would land on other data); sampled rows - the first, those around the
+    2^31-byte line, the last - match the oracle, every row was written, and rows one block apart are bitwise equal."""
+    import torch
+    R0, K, N = 999_983, 64, 32
+    M = (1 << 24) + 33
+    a_block = I.make_tensor("f16", "u", 9950, (R0, K))
+    b_bits = I.make_tensor("f16", "u", 9951, (K, N))
+    blk = B.to_device(a_block, "f16")
+    reps = (M + R0 - 1) // R0
+    a = blk.repeat(reps, 1)[:M].contiguous()
+    assert a.numel() * 2 > (1 << 31)
+    b = B.to_device(b_bits, "f16")
+    c = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda:0")
+    assert c.numel() * 4 > (1 << 31)
+    _say(f"gemm {M}x{N}x{K}: {B.tir_gemm_variant(1, M, N, K, K, 1, N, 1, N, 1, 'f16', 'f32')}")
+    B.tir_gemm(a, b, c, M, N, K, K, 1, N, 1, N, 1, "f16", "f32")
+    torch.cuda.synchronize()
+    assert not bool(torch.isnan(c).any()), "rows left unwritten"
+    assert bool(torch.equal(c[: M - R0], c[R0:])), "rows one block apart differ: some tile read or wrote the wrong rows"
+    rng = np.random.default_rng(7)
+    rows = np.unique(np.concatenate([np.arange(0, 64), np.arange((1 << 24) - 64, M), rng.integers(0, M, 256)]))
+    ref, S = oracle.gemm("f16", np.ascontiguousarray(a_block[rows % R0]), b_bits, len(rows), N, K, K, 1, N, 1)
+    got = c[torch.from_numpy(rows).cuda()].cpu().numpy().astype(np.float64)
+    PT.assert_close(got, ref, S, "gemm beyond 2 GiB, sampled rows")
+
+
+def test_conv_input_just_below_the_32_bit_limit(B, oracle):
+    """The fast convolution kernels keep byte offsets into x in 32 bits and the planner gives inputs of 2^31 bytes
+    and more to the element-wise kernel: an input of 2^31 - 4 MiB bytes (16 x 511 x 512 x 256 fp16) is the
+    largest class they run.  Every image is the
+    seeded first image rotated by a different odd element count; the last image - the highest addresses - is
+    checked in full against the oracle, and image 0 too."""
+    import torch
+    N, H, W, C, K = 16, 511, 512, 256, 16
+    assert N * H * W * C * 2 < (1 << 31) <= N * (H + 1) * W * C * 2
+    img = I.make_tensor("f16", "u", 9960, (H * W * C,))
+    w_bits = I.make_tensor("f16", "n0.1", 9961, (K, 3, 3, C))
+    shifts = [n * 1_000_003 for n in range(N)]
+    x0 = B.to_device(img, "f16")
+    x = torch.stack([torch.roll(x0, s) for s in shifts]).view(N, H, W, C).contiguous()
+    wd = B.to_device(w_bits, "f16")
+    y = torch.full((N, H, W, K), float("nan"), dtype=torch.float16, device="cuda:0")
+    _say(f"conv {N}x{H}x{W}x{C}->{K}: {B.tir_conv2d_variant(N, H, W, C, K, 3, 3, 1, 1, 1, 1, 1, 1, 1, 'f16', 'f16')}")
+    B.tir_conv2d(x, wd, y, N, H, W, C, K, 3, 3, 1, 1, 1, 1, 1, 1, 1, "f16", "f16")
+    torch.cuda.synchronize()
+    assert not bool(torch.isnan(y).any())
+    for n in (0, N - 1):
+        xb = np.roll(img, shifts[n]).reshape(1, H, W, C)
+        ref, S = oracle.conv2d("f16", xb, w_bits, (1, 1), (1, 1), (1, 1), 1)
+        PT.assert_close(PT.gpu_to_f64(y[n:n + 1]), ref, S, f"conv near the 32-bit limit, image {n}")
+    # one more image row reaches 2^31 bytes: planned on the element-wise kernel with 64-bit addresses (query only)
+    assert B.tir_conv2d_variant(N, H + 1, W, C, K, 3, 3, 1, 1, 1, 1, 1, 1, 1, "f16", "f16").endswith("conv_generic")
