@@ -202,6 +202,8 @@ def other_conv_rows(torch, B, I, tune=True):
     # conv1d: 16 x 4096 x 128 -> 128, 9 taps
     N, L, C, K, R = 16, 4096, 128, 128, 9
     x, w, y = dev((N, L, C), 7000), dev((K, R, C), 7001), B.empty_out((N, L, K), "f16")
+    if tune:      # a 1-D convolution is planned as the 2-D one on an image of height 1: same record
+        B.tir_tune_conv2d(x, w, y, N, 1, L, C, K, 1, R, 1, 1, 0, 4, 1, 1, 1, "f16", "f16", reps=10)
     sec = _graph_time(torch, lambda st: B.tir_conv1d(x, w, y, N, L, C, K, R, 1, 4, 1, 1, "f16", "f16", stream=st))
     row("c1d_16x4096x128_k9_f16", B.tir_conv2d_variant(N, 1, L, C, K, 1, R, 1, 1, 0, 4, 1, 1, 1, "f16", "f16"), sec, 2.0 * N * L * K * R * C, 2.0 * (N * L * C + K * R * C + N * L * K))
     # conv3d: 1 x 10 x 16 x 16 x 128 -> 64, 3x3x3

@@ -48,8 +48,8 @@ __global__ void __launch_bounds__(256) mfma_probe_kernel(float* sink, int iters,
 }
 
 // ------------------------------------------------------------------------------- variant table
-#define TIR_ROW(name, DT, OUT, BM, BN, WM, WN, AM, BMO, RB, NS, KW) \
-    {name, DT, OUT, BM, BN, WM, WN, AM, BMO, RB, NS, KW, &launch_cfg<Cfg<DT, OUT, BM, BN, WM, WN, AM, BMO, RB, NS, KW>>},
+#define TIR_ROW(name, DT, OUT, BM, BN, WM, WN, AM, BMO, RB, NS, KW, CW) \
+    {name, DT, OUT, BM, BN, WM, WN, AM, BMO, RB, NS, KW, CW, &launch_cfg<Cfg<DT, OUT, BM, BN, WM, WN, AM, BMO, RB, NS, KW, CW>>},
 #define V0 TIR_ROW
 #define V1 TIR_ROW
 #define V2 TIR_ROW
@@ -64,12 +64,12 @@ static const int kNumVariants = (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 // The depth-wise kernel is not a tile variant: one entry per dtype pair, filled on first use.
 static const Variant* depthwise_variant(int dt, int out) {
     static Variant table[6] = {
-        {"f16_f16_depthwise", DT_F16, DT_F16, 0, 0, 0, 0, A_DEPTHWISE, B_GENERIC, 0, 0, 1, nullptr},
-        {"f16_f32_depthwise", DT_F16, DT_F32, 0, 0, 0, 0, A_DEPTHWISE, B_GENERIC, 0, 0, 1, nullptr},
-        {"bf16_bf16_depthwise", DT_BF16, DT_BF16, 0, 0, 0, 0, A_DEPTHWISE, B_GENERIC, 0, 0, 1, nullptr},
-        {"bf16_f32_depthwise", DT_BF16, DT_F32, 0, 0, 0, 0, A_DEPTHWISE, B_GENERIC, 0, 0, 1, nullptr},
-        {"i8_i32_depthwise", DT_I8, DT_I32, 0, 0, 0, 0, A_DEPTHWISE, B_GENERIC, 0, 0, 1, nullptr},
-        {"i8_i8_depthwise", DT_I8, DT_I8, 0, 0, 0, 0, A_DEPTHWISE, B_GENERIC, 0, 0, 1, nullptr},
+        {"f16_f16_depthwise", DT_F16, DT_F16, 0, 0, 0, 0, A_DEPTHWISE, B_GENERIC, 0, 0, 1, 0, nullptr},
+        {"f16_f32_depthwise", DT_F16, DT_F32, 0, 0, 0, 0, A_DEPTHWISE, B_GENERIC, 0, 0, 1, 0, nullptr},
+        {"bf16_bf16_depthwise", DT_BF16, DT_BF16, 0, 0, 0, 0, A_DEPTHWISE, B_GENERIC, 0, 0, 1, 0, nullptr},
+        {"bf16_f32_depthwise", DT_BF16, DT_F32, 0, 0, 0, 0, A_DEPTHWISE, B_GENERIC, 0, 0, 1, 0, nullptr},
+        {"i8_i32_depthwise", DT_I8, DT_I32, 0, 0, 0, 0, A_DEPTHWISE, B_GENERIC, 0, 0, 1, 0, nullptr},
+        {"i8_i8_depthwise", DT_I8, DT_I8, 0, 0, 0, 0, A_DEPTHWISE, B_GENERIC, 0, 0, 1, 0, nullptr},
     };
     for (Variant& v : table)
         if (v.dt == dt && v.out == out) {
@@ -189,7 +189,7 @@ static Choice pick(int dt, int out, int amode, int bmode, int64_t batch, int64_t
         const int64_t tiles_1 = ((M + v->bm - 1) / v->bm) * ((N + v->bn - 1) / v->bn);
         const int forced_ks = (g_force_ksplit > 1 && split_fits(v, g_force_ksplit, batch, tiles_1, K)) ? g_force_ksplit : 1;
         if (g_force_name[0] && strstr(v->name, g_force_name)) return Choice{v, forced_ks};          // testing / tuning overrides
-        if (g_force_bm && v->bm == g_force_bm && v->bn == g_force_bn && v->kw == 1) return Choice{v, forced_ks};
+        if (g_force_bm && v->bm == g_force_bm && v->bn == g_force_bn && v->kw == 1 && v->cw == 0) return Choice{v, forced_ks};
         const double tm = (double)((M + v->bm - 1) / v->bm), tn = (double)((N + v->bn - 1) / v->bn);
         int ks = forced_ks;
         // (the partial sums' trip through memory costs about 4 us for a 64x64 tile and grows with the tile: it pays
@@ -220,6 +220,9 @@ static Choice pick(int dt, int out, int amode, int bmode, int64_t batch, int64_t
             if (tiles > kCUs || nslab < 4 * v->kw || v->bm * v->bn > 64 * 64) continue;
             depth += 0.05;
         }
+        // copy waves pay off once a stage is worth the extra waves: measured -8 .. -17 % on 128x128 and larger
+        // tiles of mid-size GEMMs, a loss on the narrow ones
+        if (v->cw) depth += (v->bm * v->bn >= 128 * 128 && nslab >= 8) ? 0.04 : -0.04;
         if (nslab < v->nstage) depth -= 0.02 * (v->nstage - (int)nslab);
         if (tiles > kCUs && lds > 80 * 1024) depth -= 0.03;
         else if (tiles <= kCUs) depth += 0.01 * v->nstage;

@@ -24,8 +24,8 @@ template <class C> hipError_t launch_cfg(const Params& p, hipStream_t stream) {
     return hipGetLastError();
 }
 
-#define TIR_DEFINE(name, DT, OUT, BM, BN, WM, WN, AM, BMO, RB, NS, KW) \
-    template hipError_t launch_cfg<Cfg<DT, OUT, BM, BN, WM, WN, AM, BMO, RB, NS, KW>>(const Params&, hipStream_t);
+#define TIR_DEFINE(name, DT, OUT, BM, BN, WM, WN, AM, BMO, RB, NS, KW, CW) \
+    template hipError_t launch_cfg<Cfg<DT, OUT, BM, BN, WM, WN, AM, BMO, RB, NS, KW, CW>>(const Params&, hipStream_t);
 #define TIR_SKIP(...)
 
 #if TIR_UNIT == 0

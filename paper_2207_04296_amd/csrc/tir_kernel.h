@@ -427,12 +427,15 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
     __shared__ __attribute__((aligned(1024))) char smem[C::LDS_BYTES];
     prefetch_args(p);
 
-    // reduction group kgrp owns the stages s with s % KW == kgrp; inside the group, thread tid of SUB
+    // reduction group kgrp owns the stages s with s % KW == kgrp; inside the group, thread tid of SUB.
+    // With copy waves (CW > 0) the waves past the multiplying ones only copy: thread tid of CT, wave `wave` of CW.
+    constexpr bool SPEC = C::CW > 0;
     const int lane = threadIdx.x & 63;
     const int wave_wg = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const bool copier = SPEC && wave_wg >= C::WM * C::WN;        // wave-uniform
     const int kgrp = C::KW == 1 ? 0 : wave_wg / (C::WM * C::WN);
-    const int wave = wave_wg - kgrp * (C::WM * C::WN);
-    const int tid = (int)threadIdx.x - kgrp * C::SUB;
+    const int wave = wave_wg - (copier ? C::WM * C::WN : kgrp * (C::WM * C::WN));
+    const int tid = (int)threadIdx.x - (copier ? C::SUB : kgrp * C::SUB);
     const int wm = wave / C::WN, wn = wave % C::WN;
     char* const ring = smem + kgrp * C::RING_BYTES;
 
@@ -699,9 +702,37 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
     };
     // u-th copy instruction of the prepared stage (u < L): A chunks first, then B chunks.
     auto copy_unit = [&](int u) {
-        if (u < C::A_IT) load_to_lds(ra, lds_dst + u * C::SUB * 16, a_voff[u]);
-        else load_to_lds(rb, lds_dst + C::A_BYTES + (u - C::A_IT) * C::SUB * 16, b_off[u - C::A_IT]);
+        if (u < C::A_IT) load_to_lds(ra, lds_dst + u * C::CT * 16, a_voff[u]);
+        else load_to_lds(rb, lds_dst + C::A_BYTES + (u - C::A_IT) * C::CT * 16, b_off[u - C::A_IT]);
     };
+
+    // ------------------------------------------------------------ copy waves
+    // A wave's LDS reads do not return while a global->LDS load the same wave issued earlier is still in
+    // flight: a wave that both copies and multiplies exposes one memory latency per stage, whatever the
+    // ring's depth.  Copy waves keep that wait away from the multiplying waves.  Both roles meet at one
+    // barrier per stage: the copy waves arrive when the next stage has landed, the multiplying waves when
+    // they have read the current one (whose slot the copy waves refill right after).
+    if constexpr (SPEC) {
+        if (copier) {
+            if (nh > 0) {
+#pragma unroll
+                for (int st = 0; st < NSTAGE - 1; ++st) {
+                    copy_begin(st);
+#pragma unroll
+                    for (int u = 0; u < L; ++u) copy_unit(u);
+                }
+                copy_barrier<(NSTAGE - 2) * L>();
+                for (int h = 0; h < nh; ++h) {
+                    copy_begin(h + NSTAGE - 1);
+#pragma unroll
+                    for (int u = 0; u < L; ++u) copy_unit(u);
+                    copy_barrier<(NSTAGE - 2) * L>();
+                }
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // empty copies past the end: drain before the LDS is released
+            }
+            return;
+        }
+    }
 
     // ------------------------------------------------------------ MFMA stage
     const Frag<C> frag(lane, wm, wn);
@@ -742,28 +773,31 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
 
     if (nh > 0) {
         // prologue: fill NSTAGE-1 slots, wait for stage 0
+        if constexpr (!SPEC) {
 #pragma unroll
-        for (int st = 0; st < NSTAGE - 1; ++st) {
-            copy_begin(st);
+            for (int st = 0; st < NSTAGE - 1; ++st) {
+                copy_begin(st);
 #pragma unroll
-            for (int u = 0; u < L; ++u) copy_unit(u);
+                for (int u = 0; u < L; ++u) copy_unit(u);
+            }
         }
         copy_barrier<(NSTAGE - 2) * L>();
         frag.read_a(ring, 0, af[0]);
         frag.read_b(ring + C::A_BYTES, 0, bf[0]);
         TIR_FENCE();
 
-        constexpr int VPK = (L + KSTEPS - 2) / (KSTEPS - 1);     // copy units per k-step of part (1)
+        constexpr int LM = SPEC ? 0 : L;                           // copy units the multiplying waves issue per stage
+        constexpr int VPK = (LM + KSTEPS - 2) / (KSTEPS - 1);     // ... per k-step of part (1)
         for (int h = 0; h < nh; ++h) {
             const char* sa = ring + (h % NSTAGE) * C::STAGE_BYTES;
             const char* sb = sa + C::A_BYTES;
             const char* na = ring + ((h + 1) % NSTAGE) * C::STAGE_BYTES;
-            copy_begin(h + NSTAGE - 1);
+            if constexpr (!SPEC) copy_begin(h + NSTAGE - 1);
             TIR_FENCE();
 #pragma unroll
             for (int kk = 0; kk < KSTEPS - 1; ++kk) {
                 const int v0 = kk * VPK;
-                const int nv = v0 + VPK <= L ? VPK : (L > v0 ? L - v0 : 0);
+                const int nv = v0 + VPK <= LM ? VPK : (LM > v0 ? LM - v0 : 0);
                 kstep(kk & 1, sa, sb, kk + 1, v0, nv);
             }
             // this wave's copy of stage h+1 has landed; after the barrier everybody's has, and
@@ -856,26 +890,29 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
             for (int j = 0; j < C::NI; ++j)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
-        // G slices are requested together (a load from memory takes longer than adding a slice) and added in
-        // slice order; slices past the last one are switched off and add zeros
-        constexpr int G = C::MI * C::NI <= 2 ? 4 : 2;
+        // G slices of one 32x32 block are requested together (a load from memory takes longer than adding a
+        // slice) and added in slice order; slices past the last one are switched off and add zeros
+        constexpr int G = 4;
         for (int z0 = 0; z0 < p.ksplit; z0 += G) {
-            u32x4 part[G][C::MI * C::NI * 4];
 #pragma unroll
-            for (int g = 0; g < G; ++g)
+            for (int blk = 0; blk < C::MI * C::NI; ++blk) {
+                u32x4 part[G][4];
 #pragma unroll
-                for (int q = 0; q < C::MI * C::NI * 4; ++q)
-                    part[g][q] = __builtin_amdgcn_raw_buffer_load_b128(rw, z0 + g < p.ksplit ? lane_off + q * 1024 : (int)kOutOfRange,
-                                                                       (z0 + g) * SLICE_BYTES, kSystemScope);
+                for (int g = 0; g < G; ++g)
 #pragma unroll
-            for (int g = 0; g < G; ++g)
+                    for (int r4 = 0; r4 < 4; ++r4)
+                        part[g][r4] = __builtin_amdgcn_raw_buffer_load_b128(rw, z0 + g < p.ksplit ? lane_off + (blk * 4 + r4) * 1024 : (int)kOutOfRange,
+                                                                            (z0 + g) * SLICE_BYTES, kSystemScope);
 #pragma unroll
-                for (int q = 0; q < C::MI * C::NI * 4; ++q)
+                for (int g = 0; g < G; ++g)
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const unsigned t = part[g][q][e];
-                        acc[q / (C::NI * 4)][(q / 4) % C::NI][(q % 4) * 4 + e] += __builtin_bit_cast(acc_e, t);
-                    }
+                    for (int r4 = 0; r4 < 4; ++r4)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const unsigned t = part[g][r4][e];
+                            acc[blk / C::NI][blk % C::NI][r4 * 4 + e] += __builtin_bit_cast(acc_e, t);
+                        }
+            }
         }
     }
     if constexpr (C::AMODE == A_CONV) {

@@ -12,7 +12,7 @@ typedef hipError_t (*launch_fn)(const Params&, hipStream_t);
 
 struct Variant {
     const char* name;
-    int dt, out, bm, bn, wm, wn, amode, bmode, rowb, nstage, kw;
+    int dt, out, bm, bn, wm, wn, amode, bmode, rowb, nstage, kw, cw;
     launch_fn fn;
 };
 

@@ -117,13 +117,15 @@ constexpr int elem_size(int dt) { return dt == DT_I8 ? 1 : (dt == DT_F16 || dt =
 // Compile-time shape of one kernel variant: BM x BN workgroup tile, WM x WN waves, ROWB bytes of k
 // per LDS row and stage (128 or 64), NSTAGE LDS stages in the copy ring, KW reduction groups: KW
 // sets of WM x WN waves share the output tile, group g reduces the stages s with s % KW == g through
-// a ring of its own, and the partial sums are added through LDS before the store.
-template <int DT_, int OUT_, int BM_, int BN_, int WM_, int WN_, int AMODE_, int BMODE_, int ROWB_ = 128, int NSTAGE_ = 2, int KW_ = 1>
+// a ring of its own, and the partial sums are added through LDS before the store.  CW > 0 adds CW
+// waves that do nothing but the global->LDS copy (the multiplying waves then issue none).
+template <int DT_, int OUT_, int BM_, int BN_, int WM_, int WN_, int AMODE_, int BMODE_, int ROWB_ = 128, int NSTAGE_ = 2, int KW_ = 1, int CW_ = 0>
 struct Cfg {
     static constexpr int DT = DT_, OUT = OUT_, BM = BM_, BN = BN_, WM = WM_, WN = WN_;
-    static constexpr int AMODE = AMODE_, BMODE = BMODE_, ROWB = ROWB_, NSTAGE = NSTAGE_, KW = KW_;
-    static constexpr int SUB = WM * WN * 64;      // threads of one reduction group (they share the copy of a stage)
-    static constexpr int THREADS = SUB * KW;
+    static constexpr int AMODE = AMODE_, BMODE = BMODE_, ROWB = ROWB_, NSTAGE = NSTAGE_, KW = KW_, CW = CW_;
+    static constexpr int SUB = WM * WN * 64;      // threads of one reduction group
+    static constexpr int CT = CW ? CW * 64 : SUB; // threads that share the copy of a stage
+    static constexpr int THREADS = SUB * KW + CW * 64;
     static constexpr int ES = elem_size(DT);
     static constexpr int VEC = 16 / ES;        // elements per 16-byte vector
     static constexpr int BK = ROWB / ES;       // elements of k per stage
@@ -135,24 +137,24 @@ struct Cfg {
     static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
     static constexpr int RING_BYTES = NSTAGE * STAGE_BYTES;   // one reduction group's ring
     static constexpr int LDS_BYTES = KW * RING_BYTES;
-    static constexpr int A_IT = BM * RCH / SUB;   // 16-byte chunks per thread per stage
-    static constexpr int B_IT = BN * RCH / SUB;
-    static constexpr int K_RSTEP = SUB / RCH;         // K-major rows covered by one pass of the group
+    static constexpr int A_IT = BM * RCH / CT;    // 16-byte chunks per copying thread per stage
+    static constexpr int B_IT = BN * RCH / CT;
+    static constexpr int K_RSTEP = CT / RCH;          // K-major rows covered by one pass of the copying threads
     // N-major B tile in LDS: BK k-rows of BN*ES bytes
     static constexpr int BROW = BN * ES;
     static constexpr int B_RC = BROW / 16;          // 16-byte chunks per k-row
-    static constexpr int N_RSTEP = SUB / B_RC;      // k-rows covered by one pass of the group
+    static constexpr int N_RSTEP = CT / B_RC;       // k-rows covered by one pass of the copying threads
     static constexpr int SEG = (ES == 2) ? 64 : 32; // bytes one half-wave reads per k-row on the transposing read
     static constexpr int WIN = BROW < 256 ? BROW : 256;
     static constexpr int NSEG = WIN / SEG > 0 ? WIN / SEG : 1;
     static constexpr int RPW = 256 / WIN;
     static_assert(ROWB == 128 || ROWB == 64, "");
     static_assert(TM % 32 == 0 && TN % 32 == 0, "wave tile must be a multiple of the 32x32 MFMA block");
-    static_assert((BM * RCH) % SUB == 0 && (BN * RCH) % SUB == 0, "copy must divide evenly");
+    static_assert((BM * RCH) % CT == 0 && (BN * RCH) % CT == 0, "copy must divide evenly");
     static_assert(K_RSTEP % 16 == 0, "the K-major swizzle must repeat with the copy's row step");
-    static_assert(BMODE != B_NMAJOR || (SUB % B_RC == 0 && BROW >= SEG), "N-major copy shape");
+    static_assert(BMODE != B_NMAJOR || (CT % B_RC == 0 && BROW >= SEG), "N-major copy shape");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of one CU");
-    static_assert(KW >= 1 && KW <= 2 && THREADS <= 1024, "");
+    static_assert(KW >= 1 && KW <= 2 && THREADS <= 1024 && (CW == 0 || KW == 1), "");
     static_assert((KW - 1) * BM * BN * 4 <= LDS_BYTES, "the partial sums of the other groups must fit the rings");
 };
 
