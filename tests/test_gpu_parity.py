@@ -749,7 +749,7 @@ def test_reduction_split_over_workgroups(B, oracle, ks, dtype, out):
     not depend on the order of arrival, the tile counters are back at zero)."""
     import torch
     try:
-        for force in ("", "t64x64w2x2s3k2_"):
+        for force in ("", "t64x64w2x2s3k2_", "t64x64w2x2s3c4_"):      # plain, two reduction groups, copy waves
             B.tir_debug_force_variant(force)
             B.tir_debug_force_ksplit(ks)
             for (batch, M, N, K, trans_b) in SPLIT_GEMMS:
