@@ -179,13 +179,13 @@ static uint64_t hash_fields(const int64_t* f, int n) {
 //
 // A reduction much longer than the tile grid is wide (few small tiles, many stages) is split over several
 // workgroups per tile, as many as fill the CUs once while each keeps at least eight stages.
-static Choice pick(int dt, int out, int amode, int bmode, int64_t batch, int64_t M, int64_t N, int64_t K) {
+static Choice pick(int dt, int out, int amode, int bmode, int64_t batch, int64_t M, int64_t N, int64_t K, int max_rowb = 256) {
     Choice best = kNoChoice;
     double best_score = -1.0;
     const int es = elem_size(dt);
     for (int i = 0; i < kNumVariants; ++i) {
         const Variant* v = &kVariants[i];
-        if (v->dt != dt || v->out != out || v->amode != amode || v->bmode != bmode) continue;
+        if (v->dt != dt || v->out != out || v->amode != amode || v->bmode != bmode || v->rowb > max_rowb) continue;
         const int64_t tiles_1 = ((M + v->bm - 1) / v->bm) * ((N + v->bn - 1) / v->bn);
         const int forced_ks = (g_force_ksplit > 1 && split_fits(v, g_force_ksplit, batch, tiles_1, K)) ? g_force_ksplit : 1;
         if (g_force_name[0] && strstr(v->name, g_force_name)) return Choice{v, forced_ks};          // testing / tuning overrides
@@ -222,7 +222,9 @@ static Choice pick(int dt, int out, int amode, int bmode, int64_t batch, int64_t
         }
         // copy waves pay off once a stage is worth the extra waves: measured -8 .. -17 % on 128x128 and larger
         // tiles of mid-size GEMMs, a loss on the narrow ones
-        if (v->cw) depth += (v->bm * v->bn >= 128 * 128 && nslab >= 8) ? 0.04 : -0.04;
+        // (and -13 % on a 64x64-tile convolution with 18 stages once the stages are 256 bytes)
+        if (v->cw) depth += ((v->bm * v->bn >= 128 * 128 && nslab >= 8) ? 0.04 : (v->rowb == 256 && tiles <= kCUs && nslab >= 8) ? 0.07 : -0.04);
+        else if (v->rowb == 256) depth -= 0.04;
         if (nslab < v->nstage) depth -= 0.02 * (v->nstage - (int)nslab);
         if (tiles > kCUs && lds > 80 * 1024) depth -= 0.03;
         else if (tiles <= kCUs) depth += 0.01 * v->nstage;
@@ -231,6 +233,11 @@ static Choice pick(int dt, int out, int amode, int bmode, int64_t batch, int64_t
         if (score > best_score) { best_score = score; best = Choice{v, ks}; }
     }
     return best;
+}
+
+// by phase, a stage must hold channels of one tap
+static bool tuned_or_trial_mismatch(const Variant* v, int64_t group_channel_bytes) {
+    return v->amode == A_CONV && group_channel_bytes % v->rowb != 0 && !g_trial.v;
 }
 
 struct Plan {
@@ -420,8 +427,9 @@ static tir_status plan_conv_geom(bool need_ptrs, const void* x, const void* w, v
     if (!ch.v) {
         const bool use_patch = patch_ok && !g_force_ksplit && (!g_force_name[0] || strstr(g_force_name, "patch"));
         if (use_patch) ch = pick(in, out, A_CONV_PATCH, bmode, groups * N, P * Q, Kg, Kd);
-        else ch = pick(in, out, amode, bmode, sc_batch, sc_M, Kg, sc_K);
+        else ch = pick(in, out, amode, bmode, sc_batch, sc_M, Kg, sc_K, phased ? (int)(Cg * es >= 256 && (Cg * es) % 256 == 0 ? 256 : 128) : 256);
     }
+    if (phased && ch.v && tuned_or_trial_mismatch(ch.v, Cg * es)) ch = pick(in, out, amode, bmode, sc_batch, sc_M, Kg, sc_K, 128);
     const Variant* v = ch.v;
     if (v && v->amode == A_CONV_PATCH) amode = A_CONV_PATCH;
     if (!v) return fail(TIR_ERR_UNSUPPORTED, "no kernel variant for this dtype / forced tile");
@@ -451,7 +459,8 @@ static tir_status plan_conv_geom(bool need_ptrs, const void* x, const void* w, v
     p.stride_d = g.stride_d; p.pad_d = g.pad_d; p.dil_d = g.dil_d;
     p.dil_h = g.dil_h; p.dil_w = g.dil_w;
     if (phased) {
-        if (v->amode != A_CONV) return fail(TIR_ERR_UNSUPPORTED, "transposed convolution by phase needs a 2-D implicit-GEMM variant (got %s)", v->name);
+        if (v->amode != A_CONV || (Cg * es) % v->rowb != 0)
+            return fail(TIR_ERR_UNSUPPORTED, "transposed convolution by phase needs a 2-D implicit-GEMM variant whose stages hold one tap (got %s)", v->name);
         p.M = (int)(N * Pp * Qp);
         p.batch = (int)(groups * phases);
         p.tiles_m = (int)((p.M + v->bm - 1) / v->bm);
@@ -602,6 +611,7 @@ static tir_status tune_problem(MakePlan make_plan, int reps, hipStream_t stream,
         g_trial = Choice{v, ks};
         Plan pl;
         st = make_plan(&pl);
+        if (st == TIR_ERR_UNSUPPORTED) { st = TIR_OK; continue; }      // this variant cannot run the problem
         if (st == TIR_OK) st = attach_workspace(&pl, caller_stream);
         if (st != TIR_OK) break;
         if (pl.p.ksplit != ks) continue;              // this split does not apply

@@ -13,8 +13,8 @@
 //   - accumulators start at zero (reduction init) and the epilogue converts and stores them
 //     straight from registers.
 //
-// One LDS stage holds ROWB = 64 or 128 bytes of k per row (e.g. 32 or 64 fp16 values) = 2 or 4 MFMA
-// k-steps; the stages form a ring that the copy stage fills NSTAGE-1 stages ahead of the MFMAs.
+// One LDS stage holds ROWB = 64, 128 or 256 bytes of k per row (e.g. 32, 64 or 128 fp16 values) = 2, 4 or 8
+// MFMA k-steps; the stages form a ring that the copy stage fills NSTAGE-1 stages ahead of the MFMAs.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <type_traits>
@@ -139,10 +139,10 @@ __device__ __forceinline__ void store_block(const ACC& a, bool fused, E bias, in
 
 // K-major LDS tile: [rows][ROWB bytes], 16-byte columns XOR-swizzled by the row so that the 16
 // rows one ds_read_b128 phase touches at a fixed logical column fall on all 64 banks exactly once
-// (ROWB 128: column ^ (row/2 mod 8); ROWB 64: column ^ (row/4 mod 4)).  The XOR is its own inverse,
+// (ROWB 256: column ^ (row mod 16); ROWB 128: column ^ (row/2 mod 8); ROWB 64: column ^ (row/4 mod 4)).  The XOR is its own inverse,
 // so the copy stage uses the same expression to find which logical column a physical slot holds.
 template <int ROWB> __device__ __forceinline__ int kmajor_swz(int row) {
-    return ROWB == 128 ? ((row >> 1) & 7) : ((row >> 2) & 3);
+    return ROWB == 256 ? (row & 15) : ROWB == 128 ? ((row >> 1) & 7) : ((row >> 2) & 3);
 }
 template <int ROWB> __device__ __forceinline__ int kmajor_off(int row, int chunk) {
     return row * ROWB + ((chunk ^ kmajor_swz<ROWB>(row)) << 4);
@@ -166,6 +166,19 @@ __device__ __forceinline__ i32x4 make_rsrc(const void* base, long long bytes) {
     r[0] = __builtin_amdgcn_readfirstlane((int)(unsigned)a);
     r[1] = __builtin_amdgcn_readfirstlane((int)((unsigned)(a >> 32) & 0xffffu));
     r[2] = __builtin_amdgcn_readfirstlane((int)n);
+    r[3] = 0x00020000;
+    return r;
+}
+
+// The same for a byte count the host has already bounded by 2^31 - 1 (every K-major and convolution operand):
+// the 64-bit clamp above compiles to vector compares of uniform values whose results travel back to the scalar
+// unit, twice per descriptor and stage.
+__device__ __forceinline__ i32x4 make_rsrc32(const void* base, unsigned bytes) {
+    const unsigned long long a = (unsigned long long)base;
+    i32x4 r;
+    r[0] = __builtin_amdgcn_readfirstlane((int)(unsigned)a);
+    r[1] = __builtin_amdgcn_readfirstlane((int)((unsigned)(a >> 32) & 0xffffu));
+    r[2] = __builtin_amdgcn_readfirstlane((int)bytes);
     r[3] = 0x00020000;
     return r;
 }
@@ -605,7 +618,7 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
         const int tap_fr = conv_fr, tap_fs = conv_fs, tap_cc = conv_cc;    // the stage's tap, before the cursor moves on
         const bool live = stage < s_end;   // past the end: empty descriptors, the copies write zeros (they add nothing)
         if constexpr (C::AMODE == A_KMAJOR) {
-            ra = make_rsrc(a_base + (long long)stage * ROWB, live ? a_bytes - (long long)stage * ROWB : 0);
+            ra = make_rsrc32(a_base + (long long)stage * ROWB, live ? (unsigned)a_bytes - (unsigned)stage * ROWB : 0u);
             if (ktail && stage == nh - 1) {
                 // K tail: the bytes between K and the row stride are not zero, switch those lanes off
                 const bool kv = stage * BK + a_lc * VEC < p.K;
@@ -617,7 +630,7 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
         } else if constexpr (C::AMODE == A_CONVX) {
             // fuse(rt, rh, rw, rc) -> (rt, rh, rw, rc), per lane; taps step by tap_sign, and with up > 1 only
             // coordinates divisible by it are input pixels (the transposed convolution read as a gather)
-            ra = make_rsrc(Ab, live ? a_bytes : 0);
+            ra = make_rsrc32(Ab, live ? (unsigned)a_bytes : 0u);
             int ft, fr, fs, cc;
             bool kv;
             if (conv_uniform_tap) {
@@ -654,7 +667,7 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
             }
         } else {
             // fuse(rh, rw, rc) -> (rh, rw, rc); a 16-byte vector never straddles a tap (Cg % VEC == 0)
-            ra = make_rsrc(Ab, live ? a_bytes : 0);
+            ra = make_rsrc32(Ab, live ? (unsigned)a_bytes : 0u);
             if (conv_uniform_tap) {
                 // Cg is a multiple of the stage's k extent: the whole stage belongs to one tap, so the tap
                 // decode is scalar and advances incrementally (stages are prepared in order)
@@ -690,7 +703,7 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
             // k offset of the stage inside a filter row: consecutive, or (by phase) that of the tap it stands for
             const long long kb = phased ? (long long)(((f_r0 - p.phases_h * tap_fr) * p.S + (f_s0 - p.phases_w * tap_fs)) * p.Cg + tap_cc) * ES
                                         : (long long)stage * ROWB;
-            rb = make_rsrc(b_base + kb, live ? b_bytes - kb : 0);
+            rb = make_rsrc32(b_base + kb, live ? (unsigned)b_bytes - (unsigned)kb : 0u);
             if (ktail && stage == nh - 1) {
                 const bool kv = stage * BK + b_lc * VEC < p.K;
 #pragma unroll

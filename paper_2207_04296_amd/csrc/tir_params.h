@@ -148,7 +148,7 @@ struct Cfg {
     static constexpr int WIN = BROW < 256 ? BROW : 256;
     static constexpr int NSEG = WIN / SEG > 0 ? WIN / SEG : 1;
     static constexpr int RPW = 256 / WIN;
-    static_assert(ROWB == 128 || ROWB == 64, "");
+    static_assert(ROWB == 256 || ROWB == 128 || ROWB == 64, "");
     static_assert(TM % 32 == 0 && TN % 32 == 0, "wave tile must be a multiple of the 32x32 MFMA block");
     static_assert((BM * RCH) % CT == 0 && (BN * RCH) % CT == 0, "copy must divide evenly");
     static_assert(K_RSTEP % 16 == 0, "the K-major swizzle must repeat with the copy's row step");
