@@ -304,7 +304,7 @@ static tir_status plan_gemm(bool need_ptrs, const void* A, const void* B, void* 
     if (b_rs == 1 && k_vec && b_cs % vec == 0 && b_bs % vec == 0 && aligned(B, 16) && (b_cs >= K || N == 1) &&
         (b_cs * 256 + K) * es < kMaxExtent) bmode = B_KMAJOR;
     else if (b_cs == 1 && N % vec == 0 && b_rs % vec == 0 && b_bs % vec == 0 && aligned(B, 16) && b_rs >= N &&
-             (b_rs * 128 + N) * es < kMaxExtent) bmode = B_NMAJOR;
+             (b_rs * 256 + N) * es < kMaxExtent) bmode = B_NMAJOR;
     if (amode == A_GENERIC || bmode == B_GENERIC) { amode = A_GENERIC; bmode = B_GENERIC; }
 
     plan->key = TuneKey{0, in, out, amode, bmode, batch, M, N, K, 0};

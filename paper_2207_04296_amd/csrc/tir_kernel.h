@@ -710,7 +710,11 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
                 for (int i = 0; i < C::B_IT; ++i) b_off[i] = kv ? b_off[i] : kOutOfRange;
             }
         } else {
-            rb = make_rsrc(b_base + stage * b_step, live ? b_bytes - stage * b_step : 0);
+            // a stage reads BK k-rows: the descriptor covers exactly those (32-bit size, bounded by the host for
+            // 128 rows), or what is left of B in the last stage, so that rows past K stay out of range
+            const unsigned b_window = (unsigned)(((long long)(BK - 1) * p.b_rs + (p.N - n0)) * ES);
+            const unsigned b_left = (stage + 1) * BK <= p.K ? b_window : (unsigned)(b_bytes - stage * b_step);
+            rb = make_rsrc32(b_base + stage * b_step, live ? b_left : 0u);
         }
     };
     // u-th copy instruction of the prepared stage (u < L): A chunks first, then B chunks.
