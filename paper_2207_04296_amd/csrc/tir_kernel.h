@@ -1008,7 +1008,7 @@ __global__ void __launch_bounds__(512) conv_patch_kernel(const Params p) {
     // the copy waves' share: one half each is fastest, 7.8 vs 8.45 us on the 56x56x64 benchmark convolution).
     const int nsplit = (nit + 1) / 2;
     auto copy_patch = [&](int first, int last) {
-        const i32x4 rx = make_rsrc((const char*)p.A, (long long)p.batch_imgs * p.H * p.W * p.Cin * ES);
+        const i32x4 rx = make_rsrc32((const char*)p.A, (unsigned)((long long)p.batch_imgs * p.H * p.W * p.Cin * ES));      // < 2^31: the host checks
         const unsigned gofs = (unsigned)(grp * p.Cg * ES);
         const int pc = tid & 7;
         int px = first * 32 + (tid >> 3);
@@ -1041,7 +1041,7 @@ __global__ void __launch_bounds__(512) conv_patch_kernel(const Params p) {
             w_off[j] = n < ncols ? (unsigned)(n * (int)Kd * ES) + lc * 16 : kOutOfRange;
         }
         auto issue_slab = [&](int t) {
-            const i32x4 rw = make_rsrc(wbase + (long long)t * p.Cg * ES, ((long long)(ncols - 1) * Kd + p.Cg) * ES);
+            const i32x4 rw = make_rsrc32(wbase + (long long)t * p.Cg * ES, (unsigned)(((long long)(ncols - 1) * Kd + p.Cg) * ES));
             char* dst = s_filt + t * SLAB + cw * 1024;
             load_to_lds(rw, dst, w_off[0]);
             load_to_lds(rw, dst + 4096, w_off[1]);
