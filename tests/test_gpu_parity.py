@@ -291,8 +291,13 @@ def test_every_variant_on_ragged_problems(B, oracle, dtype, out):
         "_conv": I.Workload("v_conv", "conv2d", dtype, out, "i" if dtype == "i8" else "n0.1", 8300, n=2, h=13, w=11,
                             c=4 * vec, k=80, r=3, s=3, stride=(1, 1), pad=(1, 1), dil=(1, 1), groups=2),
     }
+    # the convolution again with channel blocks that fill whole stages (128 or 256 bytes per tap and group): the copy
+    # stage then decodes one tap per stage with its scalar cursor instead of per lane
+    problems["_conv "] = I.Workload("v_conv_wide", "conv2d", dtype, out, "i" if dtype == "i8" else "n0.1", 8400, n=2, h=9, w=10,
+                                    c=32 * vec, k=80, r=3, s=2, stride=(2, 1), pad=(1, 2), dil=(1, 2), groups=2)
     try:
         for suffix, wl in problems.items():
+            suffix = suffix.strip()
             a_bits, b_bits = wl.operands()
             ref, S = PT.run_oracle(wl, a_bits, b_bits, oracle)
             if out == "bf16":       # rounding to bf16 costs up to 2^-8 |c| on top of the accumulation bound
