@@ -23,7 +23,13 @@ template <int DT, int OUT> static hipError_t launch_dw(const Params& p, hipStrea
     constexpr int VEC = 16 / elem_size(DT);
     constexpr int PP = 256 / (kDwChannels / VEC);
     dim3 grid((unsigned)((p.M + kDwPixPerThread * PP - 1) / (kDwPixPerThread * PP)), (unsigned)((p.Cin + kDwChannels - 1) / kDwChannels));
-    if (p.R == 3 && p.S == 3) hipLaunchKernelGGL((depthwise_kernel<DT, OUT, true>), grid, dim3(256), 0, stream, p);
+    if (p.R == 3 && p.S == 3 && p.dil_w == 1 && (p.stride_w == 1 || p.stride_w == 2) && p.Q >= kDwBlockPix) {
+        // four adjacent pixels per thread
+        const long long groups = (long long)p.batch_imgs * p.P * ((p.Q + kDwBlockPix - 1) / kDwBlockPix);
+        grid.x = (unsigned)((groups + PP - 1) / PP);
+        if (p.stride_w == 1) hipLaunchKernelGGL((depthwise3x3_blocked_kernel<DT, OUT, 1>), grid, dim3(256), 0, stream, p);
+        else hipLaunchKernelGGL((depthwise3x3_blocked_kernel<DT, OUT, 2>), grid, dim3(256), 0, stream, p);
+    } else if (p.R == 3 && p.S == 3) hipLaunchKernelGGL((depthwise_kernel<DT, OUT, true>), grid, dim3(256), 0, stream, p);
     else hipLaunchKernelGGL((depthwise_kernel<DT, OUT, false>), grid, dim3(256), 0, stream, p);
     return hipGetLastError();
 }
