@@ -653,8 +653,11 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
             // tap offset = up * quotient + remainder too (scalar in the one-tap-per-stage case); the sum of the two
             // remainders is 0 or up exactly when the tap lands on an input pixel
             const int dd = ft * p.dil_d, dh = p.tap_sign * fr * p.dil_h, dw = p.tap_sign * fs * p.dil_w;
-            const int dqh = dh >= 0 ? dh / p.up_h : -((-dh + p.up_h - 1) / p.up_h), drh = dh - dqh * p.up_h;
-            const int dqw = dw >= 0 ? dw / p.up_w : -((-dw + p.up_w - 1) / p.up_w), drw = dw - dqw * p.up_w;
+            int dqh = dh, drh = 0, dqw = dw, drw = 0;
+            if (p.up_h != 1 || p.up_w != 1) {       // (uniform; a 3-D convolution never divides)
+                dqh = dh >= 0 ? dh / p.up_h : -((-dh + p.up_h - 1) / p.up_h); drh = dh - dqh * p.up_h;
+                dqw = dw >= 0 ? dw / p.up_w : -((-dw + p.up_w - 1) / p.up_w); drw = dw - dqw * p.up_w;
+            }
 #pragma unroll
             for (int i = 0; i < C::A_IT; ++i) {
                 const int idn = a_dz[i] + dd;
