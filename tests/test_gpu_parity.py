@@ -868,3 +868,39 @@ def test_conv_input_just_below_the_32_bit_limit(B, oracle):
         PT.assert_close(PT.gpu_to_f64(y[n:n + 1]), ref, S, f"conv near the 32-bit limit, image {n}")
     # one more image row reaches 2^31 bytes: planned on the element-wise kernel with 64-bit addresses (query only)
     assert B.tir_conv2d_variant(N, H + 1, W, C, K, 3, 3, 1, 1, 1, 1, 1, 1, 1, "f16", "f16").endswith("conv_generic")
+
+
+def test_split_reduction_under_graph_capture(B, oracle):
+    """A split reduction needs the library's workspace, which cannot be allocated while a stream is captured: a
+    capture on a stream that has none yet runs the same variant unsplit; once an eager call has allocated it, the
+    captured launches split, and every replay (with eager work of the library in between) gives the oracle's result
+    - the tile counters are back at zero after each launch, nothing in the graph clears them."""
+    import torch
+    dtype, out = "f16", "f16"
+    N, D, H, W, C, K = 1, 6, 8, 8, 128, 40          # few tiles, 54 stages: planned as a split reduction
+    xb = I.make_tensor(dtype, "n0.1", 9970, (N, D, H, W, C)); wb = I.make_tensor(dtype, "n0.1", 9971, (K, 3, 3, 3, C))
+    ref, S = oracle.conv3d(dtype, xb, wb, (1, 1, 1), (1, 1, 1), (1, 1, 1), 1)
+    name = B.tir_conv3d_variant(N, D, H, W, C, K, 3, 3, 3, (1, 1, 1), (1, 1, 1), (1, 1, 1), 1, dtype, out)
+    _say(f"conv3d planned as {name}")
+    assert "/z" in name
+    x, w = B.to_device(xb, dtype), B.to_device(wb, dtype)
+    call = lambda y, st: B.tir_conv3d(x, w, y, N, D, H, W, C, K, 3, 3, 3, (1, 1, 1), (1, 1, 1), (1, 1, 1), 1, dtype, out, stream=st.cuda_stream)
+    for warm in (False, True):
+        st = torch.cuda.Stream()                    # a fresh stream: no workspace yet
+        y = _gpu_out(B, ref.shape, out)
+        other = _gpu_out(B, ref.shape, out)
+        with torch.cuda.stream(st):
+            if warm:
+                call(other, st)                     # eager: allocates this stream's workspace
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=st):
+                call(y, st)
+            for rep in range(3):
+                y.fill_(float("nan"))
+                g.replay()
+                torch.cuda.synchronize()
+                PT.assert_close(PT.gpu_to_f64(y), ref, S, f"conv3d graph replay {rep} ({'split' if warm else 'unsplit'} in the graph)")
+                call(other, st)                     # eager work of the library between the replays
+                torch.cuda.synchronize()
+                PT.assert_close(PT.gpu_to_f64(other), ref, S, "conv3d eager between replays")
