@@ -204,7 +204,8 @@ const char* tir_conv2d_transpose_variant(int64_t N, int64_t H, int64_t W, int64_
  *
  * tir_tune_batch_matmul / tir_tune_conv2d take the arguments of tir_batch_matmul_fused / tir_conv2d_fused
  * (batch = 1 with zero batch strides tunes tir_gemm; ep may be NULL), launch every compiled variant that computes this problem
- * `reps` times on `stream`, and record the fastest under the problem's signature (dtypes, copy
+ * - and, where few tiles face a long reduction, the same variant with the reduction split over 2, 3, 4, 6 or 8
+ * workgroups per tile - `reps` times on `stream`, and record the fastest under the problem's signature (dtypes, copy
  * modes implied by strides and alignment, extents, convolution geometry).  Later calls of the
  * operator entry points with the same signature use the recorded variant instead of the built-in
  * scoring rule.  Unlike every other call these BLOCK until the trial launches have finished, create
@@ -216,7 +217,7 @@ const char* tir_conv2d_transpose_variant(int64_t N, int64_t H, int64_t W, int64_
  * reps must be in [1, 1000].
  *
  * Records are process-wide and thread-safe.  tir_tune_save writes them as text (one record per line,
- * variant by name), tir_tune_load merges a file into the table; lines naming a variant this build
+ * variant by name, then the number of reduction slices), tir_tune_load merges a file into the table; lines naming a variant this build
  * does not have, or one that cannot compute the recorded signature, are skipped.
  */
 tir_status tir_tune_batch_matmul(const void* A, const void* B, void* C, int64_t batch, int64_t M, int64_t N,
