@@ -1110,8 +1110,9 @@ __global__ void __launch_bounds__(512) conv_patch_kernel(const Params p) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");          // this wave's patch copies (and its bias) have landed
     __builtin_amdgcn_s_barrier();                 // barrier 0: patch, slabs 0 and 1 are in LDS
     asm volatile("" ::: "memory");
+    constexpr int LOOK = 2;      // k-steps of lookahead (1, 2 and 3 measure alike: the loop is bound by LDS bandwidth, not latency)
 #pragma unroll
-    for (int kk = 0; kk < 2; ++kk)
+    for (int kk = 0; kk < LOOK; ++kk)
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             af[kk][i] = read_a(0, kk, i);
@@ -1135,9 +1136,9 @@ __global__ void __launch_bounds__(512) conv_patch_kernel(const Params p) {
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
             // two k-steps ahead: same tap for kk < 2, the next tap's first k-steps otherwise
-            const int rk = (kk + 2) & 3;
-            const int rpx = kk < 2 ? tap_px : next_px;
-            const int rt = kk < 2 ? t : next_t;
+            const int rk = (kk + LOOK) & 3;
+            const int rpx = kk < 4 - LOOK ? tap_px : next_px;
+            const int rt = kk < 4 - LOOK ? t : next_t;
             acc[0][0] = InTraits<DT>::mfma(af[kk][0], bf[kk][0], acc[0][0]);
             TIR_FENCE();
             af[rk][0] = read_a(rpx, rk, 0);
