@@ -248,8 +248,8 @@ def cpu_baseline(wl):
 def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on exactly one GPU (every output tile is independent; see DESIGN.md "
-              "for how the path would shard). Run with --gpus 1.", file=sys.stderr)
+        print("bench.py: this build runs on exactly one GPU (every output tile is independent: rows, batches and "
+              "convolution groups would be sharded over GPUs without communication). Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
     sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
     import torch
