@@ -20,7 +20,8 @@
  *     (which also synchronises the device once) and kept until the process ends.  Launches on one stream
  *     share it in stream order; a stream under capture that has no workspace yet runs the same kernel
  *     without the split.  The result does not depend on the split's timing: the partial sums are added in a
- *     fixed order.
+ *     fixed order.  A caller that wants no allocation inside the library hands it a buffer of its own
+ *     first (tir_set_workspace); then the library allocates nothing on that stream, captured or not.
  *   - The output is fully overwritten (reduction init is 0; there is no alpha / beta), and must not
  *     overlap an input.
  *   - Inputs F16 / BF16 accumulate in fp32; input I8 accumulates in int32 (wrap-around on overflow,
@@ -175,6 +176,24 @@ tir_status tir_attention(const void* Q, const void* K, const void* V, void* O, i
 /* Message for the calling thread's last failed call ("" if none).  Never NULL; valid until the
  * thread's next failing call. */
 const char* tir_last_error(void);
+
+/*
+ * Caller-provided workspace for split reductions (for callers that must not let the library allocate:
+ * code under stream capture, serving loops with a fixed memory plan).
+ * tir_workspace_bytes: size the buffer must have (partial sums, then the arrival counters).
+ * tir_set_workspace: from now on, launches on `stream` of the CURRENT device keep their partial sums in
+ * `ws` (device memory, 256-byte aligned, at least tir_workspace_bytes() bytes, owned by the caller).  The
+ * call enqueues one small kernel on `stream` that zeroes the counters (a kernel, not a memset, so the
+ * call may be captured) and returns; every launch leaves them zero again.  The buffer must stay
+ * allocated until the work enqueued on `stream` has finished and a later tir_set_workspace has replaced
+ * it; ws = NULL goes back to the library's own block (allocated on demand as described at the top).  Two
+ * streams that may run at the same time need two buffers: launches that share one race.  Tuning calls
+ * use the workspace of the stream they are given.
+ * Errors: TIR_ERR_INVALID_ARG (buffer too small), TIR_ERR_ALIGNMENT, TIR_ERR_LAUNCH; the previous
+ * workspace stays in place then.
+ */
+uint64_t tir_workspace_bytes(void);
+tir_status tir_set_workspace(tir_stream stream, void* ws, uint64_t bytes);
 
 /*
  * Name of the kernel variant the next identical call would launch (for profiling harnesses), e.g.

@@ -22,7 +22,8 @@ EXPORTS = ["tir_gemm", "tir_batch_matmul", "tir_conv2d", "tir_last_error", "tir_
            "tir_tune_batch_matmul", "tir_tune_conv2d", "tir_tune_count", "tir_tune_clear", "tir_tune_save",
            "tir_tune_load", "tir_gemm_fused", "tir_batch_matmul_fused", "tir_conv2d_fused", "tir_attention",
            "tir_conv1d", "tir_conv3d", "tir_conv2d_transpose", "tir_debug_force_ksplit", "tir_debug_fastdiv",
-           "tir_conv2d_transpose_variant", "tir_conv3d_variant", "tir_tune_conv3d", "tir_tune_conv2d_transpose"]
+           "tir_conv2d_transpose_variant", "tir_conv3d_variant", "tir_tune_conv3d", "tir_tune_conv2d_transpose",
+           "tir_workspace_bytes", "tir_set_workspace"]
 
 
 class Epilogue(ctypes.Structure):
@@ -115,6 +116,9 @@ def lib() -> ctypes.CDLL:
     L.tir_tune_conv2d_transpose.restype = ci
     L.tir_conv3d_variant.argtypes = [i64] * 9 + [ci] * 10 + [ci, ci]
     L.tir_conv3d_variant.restype = ctypes.c_char_p
+    L.tir_workspace_bytes.restype = ctypes.c_uint64
+    L.tir_set_workspace.argtypes = [vp, vp, ctypes.c_uint64]
+    L.tir_set_workspace.restype = ci
     L.tir_tune_count.restype = ci
     L.tir_tune_clear.restype = None
     L.tir_tune_save.argtypes = [ctypes.c_char_p]
@@ -221,6 +225,22 @@ def tir_debug_fastdiv(d: int, m: int) -> int:
 
 def tir_debug_force_ksplit(slices: int) -> None:
     lib().tir_debug_force_ksplit(int(slices))
+
+
+def tir_workspace_bytes() -> int:
+    return int(lib().tir_workspace_bytes())
+
+
+def tir_set_workspace_status(ws, nbytes: int, stream=0) -> int:
+    """Raw call returning the status code (the size and alignment checks need no GPU)."""
+    return lib().tir_set_workspace(stream or None, _ptr(ws) or None, int(nbytes))
+
+
+def tir_set_workspace(ws, stream=None) -> None:
+    """Hand the library a caller-owned uint8 device tensor for the split reductions launched on `stream`
+    (None as `ws`: back to the library's own block).  The caller keeps the tensor alive."""
+    nbytes = 0 if ws is None else ws.numel() * ws.element_size()
+    _check(lib().tir_set_workspace(_stream(stream) or None, _ptr(ws) or None, nbytes))
 
 
 def tir_debug_variant_names():

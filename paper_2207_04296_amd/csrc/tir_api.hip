@@ -145,9 +145,16 @@ static const int64_t kWsTiles = 16384;           // counters
 struct Workspace {
     void* partial;
     unsigned* count;
+    void* owned;         // the library's own allocation for this key, if any (kept while a caller's buffer stands in)
 };
 static std::mutex g_ws_mu;
 static std::map<std::pair<int, hipStream_t>, Workspace> g_ws;
+
+// Arrival counters start at zero; every launch leaves them at zero again (the last workgroup of a tile resets its counter).
+__global__ void __launch_bounds__(256) clear_counters_kernel(unsigned* count, int n) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < n) count[i] = 0;
+}
 
 // Can variant v reduce a problem of `tiles` output tiles per batch entry in ks slices?
 static bool split_fits(const Variant* v, int ks, int64_t batch, int64_t tiles, int64_t K) {
@@ -517,7 +524,7 @@ static tir_status attach_workspace(Plan* plan, hipStream_t stream) {
             plan->p.ksplit = 1;
             return TIR_OK;
         }
-        Workspace w = {base, (unsigned*)((char*)base + kWsBytes)};
+        Workspace w = {base, (unsigned*)((char*)base + kWsBytes), base};
         it = g_ws.insert(std::make_pair(std::make_pair(dev, stream), w)).first;
     }
     plan->p.ws = it->second.partial;
@@ -769,6 +776,48 @@ const char* tir_conv2d_transpose_variant(int64_t N, int64_t H, int64_t W, int64_
 void tir_debug_force_tile(int bm, int bn) {
     g_force_bm = bm;
     g_force_bn = bn;
+}
+
+uint64_t tir_workspace_bytes(void) { return (uint64_t)(kWsBytes + kWsTiles * 4); }
+
+tir_status tir_set_workspace(tir_stream stream_, void* ws, uint64_t bytes) {
+    hipStream_t stream = (hipStream_t)stream_;
+    if (ws) {
+        if (bytes < tir_workspace_bytes())
+            return fail(TIR_ERR_INVALID_ARG, "workspace of %llu bytes, tir_workspace_bytes() = %llu are needed", (unsigned long long)bytes,
+                        (unsigned long long)tir_workspace_bytes());
+        if ((uintptr_t)ws & 255) return fail(TIR_ERR_ALIGNMENT, "workspace not aligned to 256 bytes");
+    }
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(TIR_ERR_LAUNCH, "hipGetDevice failed: %s", hipGetErrorString(e));
+    std::lock_guard<std::mutex> lock(g_ws_mu);
+    const std::pair<int, hipStream_t> key(dev, stream);
+    auto it = g_ws.find(key);
+    if (!ws) {
+        // back to the library's own block (its counters are zero whenever no launch is in flight), or to none
+        if (it != g_ws.end()) {
+            if (it->second.owned) {
+                it->second.partial = it->second.owned;
+                it->second.count = (unsigned*)((char*)it->second.owned + kWsBytes);
+            } else {
+                g_ws.erase(it);
+            }
+        }
+        return TIR_OK;
+    }
+    unsigned* count = (unsigned*)((char*)ws + kWsBytes);
+    hipLaunchKernelGGL(clear_counters_kernel, dim3((unsigned)(kWsTiles / 256)), dim3(256), 0, stream, count, (int)kWsTiles);
+    e = hipGetLastError();
+    if (e != hipSuccess) return fail(TIR_ERR_LAUNCH, "clearing the workspace counters failed: %s", hipGetErrorString(e));
+    if (it == g_ws.end()) {
+        Workspace w = {ws, count, nullptr};
+        g_ws.insert(std::make_pair(key, w));
+    } else {
+        it->second.partial = ws;
+        it->second.count = count;
+    }
+    return TIR_OK;
 }
 
 void tir_debug_force_ksplit(int slices) { g_force_ksplit = slices > 1 ? slices : 0; }

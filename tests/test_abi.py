@@ -209,6 +209,15 @@ def test_reduction_split_is_planned_only_where_it_fits(tmp_path):
         B.tir_tune_clear()
 
 
+def test_caller_workspace_arguments_are_checked():
+    """tir_set_workspace rejects a buffer that is too small or not 256-byte aligned before it touches the device."""
+    need = B.tir_workspace_bytes()
+    assert need == (32 << 20) + 16384 * 4
+    assert B.tir_set_workspace_status(FAKE, need - 1) == B.TIR_ERR_INVALID_ARG
+    assert "tir_workspace_bytes" in B.last_error()
+    assert B.tir_set_workspace_status(FAKE + 16, need) == B.TIR_ERR_ALIGNMENT
+
+
 def test_tuning_record_files_are_validated(tmp_path):
     bad = tmp_path / "bad.txt"
     bad.write_text("something else\n")

@@ -904,3 +904,74 @@ def test_split_reduction_under_graph_capture(B, oracle):
                 call(other, st)                     # eager work of the library between the replays
                 torch.cuda.synchronize()
                 PT.assert_close(PT.gpu_to_f64(other), ref, S, "conv3d eager between replays")
+
+
+def test_caller_provided_workspace(B, oracle):
+    """With a caller's buffer registered for a stream the library allocates nothing there: a capture on a fresh stream
+    splits at once (the partial sums land in the caller's buffer, the arrival counters are zero again after every
+    replay), a second, smaller problem reuses the buffer, and tir_set_workspace(None) goes back to the library's own."""
+    import torch
+    dtype, out = "f16", "f16"
+    N, D, H, W, C, K = 1, 6, 8, 8, 128, 40          # few tiles, 54 stages: planned as a split reduction
+    xb = I.make_tensor(dtype, "n0.1", 9980, (N, D, H, W, C)); wb = I.make_tensor(dtype, "n0.1", 9981, (K, 3, 3, 3, C))
+    ref, S = oracle.conv3d(dtype, xb, wb, (1, 1, 1), (1, 1, 1), (1, 1, 1), 1)
+    name = B.tir_conv3d_variant(N, D, H, W, C, K, 3, 3, 3, (1, 1, 1), (1, 1, 1), (1, 1, 1), 1, dtype, out)
+    _say(f"conv3d planned as {name}")
+    assert "/z" in name
+    x, w = B.to_device(xb, dtype), B.to_device(wb, dtype)
+    need = B.tir_workspace_bytes()
+    partial_bytes = need - 16384 * 4
+    ws = torch.full((need,), 0xAB, dtype=torch.uint8, device="cuda:0")
+    assert ws.data_ptr() % 256 == 0
+    # argument errors leave everything as it was (the pointers are real and large enough: nothing depends on the rejection)
+    spare = torch.empty(need + 256, dtype=torch.uint8, device="cuda:0")
+    assert B.tir_set_workspace_status(spare, need - 1) == B.TIR_ERR_INVALID_ARG
+    assert B.tir_set_workspace_status(spare.data_ptr() + 16, need) == B.TIR_ERR_ALIGNMENT
+    st = torch.cuda.Stream()                        # a fresh stream: the library has no workspace for it
+    y = _gpu_out(B, ref.shape, out)
+    try:
+        with torch.cuda.stream(st):
+            _say("register the workspace, capture")
+            B.tir_set_workspace(ws, stream=st)
+            torch.cuda.synchronize()
+            assert int(ws[partial_bytes:].max()) == 0, "counters not cleared"
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=st):
+                B.tir_conv3d(x, w, y, N, D, H, W, C, K, 3, 3, 3, (1, 1, 1), (1, 1, 1), (1, 1, 1), 1, dtype, out, stream=st.cuda_stream)
+            for rep in range(3):
+                y.fill_(float("nan"))
+                ws[:partial_bytes].fill_(0xAB)
+                torch.cuda.synchronize()
+                g.replay()
+                torch.cuda.synchronize()
+                PT.assert_close(PT.gpu_to_f64(y), ref, S, f"conv3d, caller's workspace, replay {rep}")
+                assert int((ws[:65536] != 0xAB).sum()) > 0, "the partial sums did not go to the caller's buffer"
+                assert int(ws[partial_bytes:].max()) == 0, "counters not back at zero"
+            # a smaller problem next, eager, through the same buffer
+            B.tir_debug_force_ksplit(2)
+            wl = I.Workload("ws_gemm_96x80x1024", "gemm", "f16", "f32", "u", 9985, M=96, N=80, K=1024)
+            assert PT.variant_name(B, wl).endswith("/z2")
+            a_bits, b_bits = wl.operands()
+            gref, gS = PT.run_oracle(wl, a_bits, b_bits, oracle)
+            a, b = B.to_device(a_bits, "f16"), B.to_device(b_bits, "f16")
+            c = _gpu_out(B, gref.shape, "f32")
+            _say("split GEMM through the caller's workspace")
+            ws[:partial_bytes].fill_(0xAB)
+            B.run_workload(wl, a, b, c, stream=st)
+            torch.cuda.synchronize()
+            PT.assert_close(PT.gpu_to_f64(c), gref, gS, "split GEMM, caller's workspace")
+            assert int((ws[:65536] != 0xAB).sum()) > 0
+            assert int(ws[partial_bytes:].max()) == 0
+            # back to the library's own block: the caller's buffer stays untouched
+            _say("back to the library's workspace")
+            B.tir_set_workspace(None, stream=st)
+            ws[:partial_bytes].fill_(0xAB)
+            c.zero_()
+            B.run_workload(wl, a, b, c, stream=st)
+            torch.cuda.synchronize()
+            PT.assert_close(PT.gpu_to_f64(c), gref, gS, "split GEMM, library's workspace")
+            assert int((ws[:65536] != 0xAB).sum()) == 0
+    finally:
+        B.tir_debug_force_ksplit(0)
+        torch.cuda.synchronize()
+        B.tir_set_workspace(None, stream=st)
