@@ -985,7 +985,10 @@ __global__ void __launch_bounds__(512) conv_patch_kernel(const Params p) {
     const int l31 = lane & 31, g = lane >> 5;
 
     // workgroup -> (image, pixel tile, channel tile); group = blockIdx.y
-    const int bid = blockIdx.x;
+    // Workgroups go to the 8 L2 domains round-robin by launch index: give each domain a run of consecutive tiles,
+    // so that the input rows two neighbouring pixel tiles share (the halo) are fetched into one L2 once.
+    const int xq = gridDim.x >> 3, xr = gridDim.x & 7, xf = blockIdx.x & 7;
+    const int bid = xf * xq + (xf < xr ? xf : xr) + (blockIdx.x >> 3);
     const int nt = bid % p.tiles_n;
     const int rest = bid / p.tiles_n;
     const int tix = rest % p.tiles_m;           // tiles_m = pixel tiles per image here
