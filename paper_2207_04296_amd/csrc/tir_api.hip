@@ -168,6 +168,31 @@ static bool split_fits(const Variant* v, int ks, int64_t batch, int64_t tiles, i
     return batch * tiles * ks * v->bm * v->bn * 4 <= kWsBytes;
 }
 
+// The kernels divide by these launch constants through multiply-and-shift (see Params).
+static void set_divisors(Params& p) {
+    auto put = [](unsigned d, unsigned* magic, int* shift) {
+        const FastDiv f = make_fastdiv(d < 1 ? 1u : d);
+        *magic = f.magic;
+        *shift = f.shift;
+    };
+    put((unsigned)(kGroupM * p.tiles_n), &p.div_gw_magic, &p.div_gw_shift);
+    put((unsigned)p.tiles_n, &p.div_tn_magic, &p.div_tn_shift);
+    put((unsigned)p.tiles_m, &p.div_tm_magic, &p.div_tm_shift);
+    put((unsigned)p.PW, &p.div_pw_magic, &p.div_pw_shift);
+    put((unsigned)p.Q, &p.div_q_magic, &p.div_q_shift);
+    put((unsigned)(p.P * p.Q), &p.div_pq_magic, &p.div_pq_shift);
+    put((unsigned)(p.OD < 1 ? 1 : p.OD) * (unsigned)(p.P * p.Q), &p.div_opq_magic, &p.div_opq_shift);
+    put((unsigned)p.Cg, &p.div_cg_magic, &p.div_cg_shift);
+    put((unsigned)p.S, &p.div_s_magic, &p.div_s_shift);
+    put((unsigned)(p.R * p.S), &p.div_rs_magic, &p.div_rs_shift);
+    put((unsigned)p.conv_groups, &p.div_grp_magic, &p.div_grp_shift);
+    put((unsigned)p.phases_h, &p.div_phh_magic, &p.div_phh_shift);
+    put((unsigned)p.phases_w, &p.div_phw_magic, &p.div_phw_shift);
+    const unsigned qg = (unsigned)((p.Q + kDwBlockPix - 1) / kDwBlockPix);
+    put(qg, &p.div_dwq_magic, &p.div_dwq_shift);
+    put((unsigned)p.P * qg, &p.div_dwpq_magic, &p.div_dwpq_shift);
+}
+
 static uint64_t hash_fields(const int64_t* f, int n) {
     // the fields of a convolution's geometry do not fit 64 bits side by side: mix them instead (FNV-1a)
     uint64_t h = 1469598103934665603ull;
@@ -332,6 +357,7 @@ static tir_status plan_gemm(bool need_ptrs, const void* A, const void* B, void* 
     p.a_rs = a_rs; p.a_cs = a_cs; p.b_rs = b_rs; p.b_cs = b_cs; p.c_rs = c_rs; p.c_cs = c_cs;
     p.c_fast = (c_cs == 1 && (c_rs >= N || M == 1) && (c_rs * 256 + N) * elem_size(out) < kMaxExtent) ? 1 : 0;
     if (ep) { p.bias = ep->bias; p.bias_bs = 0; p.relu = ep->relu != 0; p.scale = ep->scale; }
+    set_divisors(p);
     plan->v = v;
     return TIR_OK;
 }
@@ -476,8 +502,6 @@ static tir_status plan_conv_geom(bool need_ptrs, const void* x, const void* w, v
         p.conv_groups = groups;
         p.stride_h = 1; p.stride_w = 1; p.pad_h = 0; p.pad_w = 0;      // per phase, derived by the kernel
         p.tap_sign = 1; p.up_h = 1; p.up_w = 1;
-        const FastDiv dpq = make_fastdiv((unsigned)(Pp * Qp)), dq = make_fastdiv((unsigned)Qp);
-        p.div_pq_magic = dpq.magic; p.div_pq_shift = dpq.shift; p.div_q_magic = dq.magic; p.div_q_shift = dq.shift;
     } else if (g.transposed) {
         // gather form of the adjoint: output pixel oh reads input (oh + pad - r*dil) / stride where that is an integer
         p.stride_h = 1; p.stride_w = 1; p.pad_h = -g.pad_h; p.pad_w = -g.pad_w;
@@ -486,6 +510,7 @@ static tir_status plan_conv_geom(bool need_ptrs, const void* x, const void* w, v
         p.stride_h = g.stride_h; p.stride_w = g.stride_w; p.pad_h = g.pad_h; p.pad_w = g.pad_w;
         p.tap_sign = 1; p.up_h = 1; p.up_w = 1;
     }
+    set_divisors(p);
     plan->v = v;
     return TIR_OK;
 }
@@ -830,7 +855,10 @@ int tir_debug_variant_count(void) { return kNumVariants; }
 
 const char* tir_debug_variant_name(int i) { return (i >= 0 && i < kNumVariants) ? kVariants[i].name : ""; }
 
-void tir_debug_tile_of_block(int bid, int tiles_m, int tiles_n, int* tm, int* tn) { tile_of_block(bid, tiles_m, tiles_n, tm, tn); }
+void tir_debug_tile_of_block(int bid, int tiles_m, int tiles_n, int* tm, int* tn) {
+    const FastDiv gw = make_fastdiv((unsigned)(kGroupM * tiles_n));
+    tile_of_block(bid, tiles_m, tiles_n, gw.magic, gw.shift, tm, tn);
+}
 
 unsigned tir_debug_fastdiv(unsigned d, unsigned m) {
     const FastDiv f = make_fastdiv(d);
@@ -962,6 +990,8 @@ tir_status tir_attention(const void* Q, const void* K, const void* V, void* O, i
     p.Q = Q; p.K = K; p.V = V; p.O = O;
     p.M = (int)M; p.N = (int)N; p.batch = (int)batch; p.tiles_m = (int)tiles_m;
     p.scale_log2e = scale * 1.44269504088896340736f;
+    const FastDiv dtm = make_fastdiv((unsigned)tiles_m);
+    p.div_tm_magic = dtm.magic; p.div_tm_shift = dtm.shift;
     hipError_t e = fn(p, (hipStream_t)stream);
     if (e != hipSuccess) return fail(TIR_ERR_LAUNCH, "attention launch failed: %s", hipGetErrorString(e));
     return TIR_OK;

@@ -24,6 +24,8 @@ struct AttnParams {
     int M, N, batch;
     int tiles_m;     // ceil(M / 128)
     float scale_log2e;   // scale * log2(e): the softmax runs in base 2
+    unsigned div_tm_magic;   // workgroup id / tiles_m as multiply-and-shift (make_fastdiv)
+    int div_tm_shift;
 };
 
 template <int DT> struct PackP;
@@ -69,8 +71,8 @@ __global__ void __launch_bounds__(256) attention_kernel(const AttnParams p) {
     const int l31 = lane & 31, g = lane >> 5;
     const int blk = lane >> 4, s16 = lane & 15;
 
-    const int tm = blockIdx.x % p.tiles_m;
-    const long long b = blockIdx.x / p.tiles_m;
+    const long long b = fastdiv(blockIdx.x, p.div_tm_magic, p.div_tm_shift);
+    const int tm = (int)blockIdx.x - (int)b * p.tiles_m;
     const int m0 = tm * 128;
     const int rows_q = p.M - m0 < 128 ? p.M - m0 : 128;
     const int nchunk = (p.N + 127) / 128;

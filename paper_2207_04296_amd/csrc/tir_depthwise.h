@@ -103,8 +103,8 @@ __global__ void __launch_bounds__(256) depthwise_kernel(const Params p) {
     for (int j = 0; j < NPIX; ++j) {
         const int m = (bx * NPIX + j) * PP + pl;
         if (m >= p.M) break;
-        const int img = m / PQ, rem = m - img * PQ;
-        const int op = rem / p.Q, oq = rem - op * p.Q;
+        const int img = (int)fastdiv((unsigned)m, p.div_pq_magic, p.div_pq_shift), rem = m - img * PQ;
+        const int op = (int)fastdiv((unsigned)rem, p.div_q_magic, p.div_q_shift), oq = rem - op * p.Q;
         const int ih0 = op * p.stride_h - p.pad_h, iw0 = oq * p.stride_w - p.pad_w;
         const int pix0 = (img * p.H + ih0) * p.W + iw0;              // may be "negative": only used when the tap is valid
         acc_e acc[VEC];
@@ -151,7 +151,6 @@ __global__ void __launch_bounds__(256) depthwise_kernel(const Params p) {
 // once (18 vectors for 4 pixels at stride 1 instead of 36) and all requested before the first multiply; row and
 // column validity are decided once per row / column, so a tap's address costs three vector instructions instead
 // of a dozen.  The one-pixel kernel above spent twice as many instructions on addresses as on multiply-adds.
-constexpr int kDwBlockPix = 4;      // measured 2, 4, 8: 8.5 / 7.2 / 6.9 us at stride 1 (16x56x56x128 fp16), 7.1 / 6.2 / 9.8 us at stride 2 (int8)
 template <int DT, int OUT, int SW>
 __global__ void __launch_bounds__(256) depthwise3x3_blocked_kernel(const Params p) {
     typedef typename DwIn<DT>::acc_e acc_e;
@@ -184,8 +183,8 @@ __global__ void __launch_bounds__(256) depthwise3x3_blocked_kernel(const Params 
     const int QG = (p.Q + NP - 1) / NP;              // pixel groups per output row
     const int gidx = bx * PP + pl;
     if (gidx >= p.batch_imgs * p.P * QG) return;
-    const int img = gidx / (p.P * QG), rem = gidx - img * (p.P * QG);
-    const int op = rem / QG, oq0 = (rem - op * QG) * NP;
+    const int img = (int)fastdiv((unsigned)gidx, p.div_dwpq_magic, p.div_dwpq_shift), rem = gidx - img * (p.P * QG);
+    const int op = (int)fastdiv((unsigned)rem, p.div_dwq_magic, p.div_dwq_shift), oq0 = (rem - op * QG) * NP;
     const int ih0 = op * p.stride_h - p.pad_h, iw0 = oq0 * SW - p.pad_w;
 
     const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void*)p.A, 0, (int)((long long)p.batch_imgs * p.H * p.W * p.Cin * ES), 0x00020000);

@@ -453,7 +453,7 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
     char* const ring = smem + kgrp * C::RING_BYTES;
 
     int tm, tn;
-    tile_of_block(blockIdx.x, p.tiles_m, p.tiles_n, &tm, &tn);
+    tile_of_block(blockIdx.x, p.tiles_m, p.tiles_n, p.div_gw_magic, p.div_gw_shift, &tm, &tn);
     const int m0 = tm * C::BM, n0 = tn * C::BN;
     long long bz = blockIdx.y;
 
@@ -466,15 +466,18 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
     if constexpr (C::AMODE == A_CONV) {
         phased = p.phases_h != 0;
         if (phased) {
-            const int phase = (int)bz / p.conv_groups;
+            auto div_h = [&](int v) { return (int)fastdiv((unsigned)v, p.div_phh_magic, p.div_phh_shift); };    // v >= 0
+            auto div_w = [&](int v) { return (int)fastdiv((unsigned)v, p.div_phw_magic, p.div_phw_shift); };
+            const int phase = (int)fastdiv((unsigned)bz, p.div_grp_magic, p.div_grp_shift);
             bz -= (long long)phase * p.conv_groups;
-            ph = phase / p.phases_w;
+            ph = div_w(phase);
             pw = phase - ph * p.phases_w;
-            const int r0 = (ph + p.t_pad_h) % p.phases_h, s0 = (pw + p.t_pad_w) % p.phases_w;
-            const int cR = p.R > r0 ? (p.R - r0 + p.phases_h - 1) / p.phases_h : 0;
-            cS = p.S > s0 ? (p.S - s0 + p.phases_w - 1) / p.phases_w : 0;
-            cpad_h = (cR - 1) - (ph + p.t_pad_h - r0) / p.phases_h;
-            cpad_w = (cS - 1) - (pw + p.t_pad_w - s0) / p.phases_w;
+            const int qh = div_h(ph + p.t_pad_h), qw = div_w(pw + p.t_pad_w);
+            const int r0 = ph + p.t_pad_h - qh * p.phases_h, s0 = pw + p.t_pad_w - qw * p.phases_w;
+            const int cR = p.R > r0 ? div_h(p.R - r0 + p.phases_h - 1) : 0;
+            cS = p.S > s0 ? div_w(p.S - s0 + p.phases_w - 1) : 0;
+            cpad_h = (cR - 1) - qh;       // (ph + t_pad_h - r0) / phases_h
+            cpad_w = (cS - 1) - qw;
             f_r0 = r0 + p.phases_h * (cR - 1);
             f_s0 = s0 + p.phases_w * (cS - 1);
             cK = cR * cS * p.Cg;                          // 0 for a phase no tap reaches: its pixels get the empty sum
@@ -485,7 +488,7 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
     const char* Bb = (const char*)p.B + bz * p.b_bs * ES;
     const int nh_all = (cK + BK - 1) / BK;              // stages of the reduction
     // this workgroup's slice of them (grid.z slices of nh_slice consecutive stages; the host makes every slice non-empty)
-    const int nh_slice = (nh_all + p.ksplit - 1) / p.ksplit;
+    const int nh_slice = p.ksplit > 1 ? (nh_all + p.ksplit - 1) / p.ksplit : nh_all;
     const int s_begin = (int)blockIdx.z * nh_slice;
     const int s_end = s_begin + nh_slice < nh_all ? s_begin + nh_slice : nh_all;
     const int nh = (s_end - s_begin + C::KW - 1) / C::KW;   // ... per group (the last one may be empty for some groups)
@@ -514,24 +517,27 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
         // ReIndex with a depth axis: row m of A_t is output pixel (img, od, op, oq) = unfuse(m); keep the
         // pixel index of the image's first pixel and the (possibly up-sampled) coordinates of tap (0,0,0)
         const int PQ = p.P * p.Q, OPQ = p.OD * PQ;
-        a_bytes = ((long long)p.M / OPQ) * p.D * p.H * p.W * p.Cin * ES - bz * p.a_bs * ES;
+        a_bytes = (long long)p.batch_imgs * p.D * p.H * p.W * p.Cin * ES - bz * p.a_bs * ES;
 #pragma unroll
         for (int i = 0; i < C::A_IT; ++i) {
             const int m = m0 + a_r0 + i * C::K_RSTEP;
             int id0 = 0, ih0 = -30000, iw0 = 0, img = 0;
             if (m < p.M) {
-                img = m / OPQ;
+                img = (int)fastdiv((unsigned)m, p.div_opq_magic, p.div_opq_shift);
                 const int rem = m - img * OPQ;
-                const int od = rem / PQ, rem2 = rem - od * PQ;
-                const int op = rem2 / p.Q, oq = rem2 - op * p.Q;
+                const int od = (int)fastdiv((unsigned)rem, p.div_pq_magic, p.div_pq_shift), rem2 = rem - od * PQ;
+                const int op = (int)fastdiv((unsigned)rem2, p.div_q_magic, p.div_q_shift), oq = rem2 - op * p.Q;
                 id0 = od * p.stride_d - p.pad_d;
                 ih0 = op * p.stride_h - p.pad_h;
                 iw0 = oq * p.stride_w - p.pad_w;
             }
             // coordinate = up * quotient + remainder (floor division, once per row): tap offsets are uniform per
             // stage, so whether a tap hits an input pixel is decided by adding remainders, without a division
-            const int qh = ih0 >= 0 ? ih0 / p.up_h : -((-ih0 + p.up_h - 1) / p.up_h);
-            const int qw = iw0 >= 0 ? iw0 / p.up_w : -((-iw0 + p.up_w - 1) / p.up_w);
+            int qh = ih0, qw = iw0;
+            if (p.up_h != 1 || p.up_w != 1) {       // (uniform; a 3-D convolution never divides)
+                qh = ih0 >= 0 ? ih0 / p.up_h : -((-ih0 + p.up_h - 1) / p.up_h);
+                qw = iw0 >= 0 ? iw0 / p.up_w : -((-iw0 + p.up_w - 1) / p.up_w);
+            }
             a_off[i] = (unsigned)img * (unsigned)(p.D * p.H * p.W);
             a_dz[i] = id0;
             a_hw[i] = (qh << 16) | (qw & 0xffff);
@@ -540,16 +546,16 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
     } else {
         // ReIndex: row m of A_t is output pixel (img, op, oq) = unfuse(m); keep the element offset of
         // its top-left input pixel and that pixel's coordinates.
-        a_bytes = ((long long)p.M / (p.P * p.Q)) * p.H * p.W * p.Cin * ES - bz * p.a_bs * ES;
+        a_bytes = (long long)p.batch_imgs * p.H * p.W * p.Cin * ES - bz * p.a_bs * ES;
         const int PQ = p.P * p.Q;
 #pragma unroll
         for (int i = 0; i < C::A_IT; ++i) {
             const int m = m0 + a_r0 + i * C::K_RSTEP;
             int ih0 = -30000, iw0 = 0, img = 0;
             if (m < p.M) {
-                img = m / PQ;
+                img = (int)fastdiv((unsigned)m, p.div_pq_magic, p.div_pq_shift);
                 const int rem = m - img * PQ;
-                const int op = rem / p.Q, oq = rem - op * p.Q;
+                const int op = (int)fastdiv((unsigned)rem, p.div_q_magic, p.div_q_shift), oq = rem - op * p.Q;
                 ih0 = op * p.stride_h - cpad_h;
                 iw0 = oq * p.stride_w - cpad_w;
             }
@@ -641,12 +647,12 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
                 conv_advance(C::KW);
             } else {
                 const int kb = stage * BK + a_lc * VEC;
-                const int tap = kb / p.Cg;
+                const int tap = (int)fastdiv((unsigned)kb, p.div_cg_magic, p.div_cg_shift);
                 cc = kb - tap * p.Cg;
                 const int RS = p.R * p.S;
-                ft = tap / RS;
+                ft = (int)fastdiv((unsigned)tap, p.div_rs_magic, p.div_rs_shift);
                 const int rs = tap - ft * RS;
-                fr = rs / p.S;
+                fr = (int)fastdiv((unsigned)rs, p.div_s_magic, p.div_s_shift);
                 fs = rs - fr * p.S;
                 kv = kb < p.K;
             }
@@ -687,9 +693,9 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
                 conv_advance(C::KW);
             } else {
                 const int kb = stage * BK + a_lc * VEC;
-                const int tap = kb / p.Cg;
+                const int tap = (int)fastdiv((unsigned)kb, p.div_cg_magic, p.div_cg_shift);
                 const int cc = kb - tap * p.Cg;
-                const int fr = tap / p.S, fs = tap - fr * p.S;
+                const int fr = (int)fastdiv((unsigned)tap, p.div_s_magic, p.div_s_shift), fs = tap - fr * p.S;
                 const int dh = fr * p.dil_h, dw = fs * p.dil_w;
                 const unsigned delta = (unsigned)((dh * p.W + dw) * p.Cin + cc);
                 const bool kv = kb < p.K;
@@ -989,10 +995,10 @@ __global__ void __launch_bounds__(512) conv_patch_kernel(const Params p) {
     // so that the input rows two neighbouring pixel tiles share (the halo) are fetched into one L2 once.
     const int xq = gridDim.x >> 3, xr = gridDim.x & 7, xf = blockIdx.x & 7;
     const int bid = xf * xq + (xf < xr ? xf : xr) + (blockIdx.x >> 3);
-    const int nt = bid % p.tiles_n;
-    const int rest = bid / p.tiles_n;
-    const int tix = rest % p.tiles_m;           // tiles_m = pixel tiles per image here
-    const int img = rest / p.tiles_m;
+    const int rest = (int)fastdiv((unsigned)bid, p.div_tn_magic, p.div_tn_shift);
+    const int nt = bid - rest * p.tiles_n;
+    const int img = (int)fastdiv((unsigned)rest, p.div_tm_magic, p.div_tm_shift);
+    const int tix = rest - img * p.tiles_m;     // tiles_m = pixel tiles per image here
     const int grp = blockIdx.y;
     const int PQ = p.P * p.Q;
     const int m_first = tix * 256;
@@ -1002,7 +1008,7 @@ __global__ void __launch_bounds__(512) conv_patch_kernel(const Params p) {
     const int RS = p.R * p.S;
 
     // patch geometry: output rows p_a..p_b of this image, input rows ih_base .. ih_base + nrows - 1
-    const int p_a = m_first / p.Q, p_b = (m_first + m_cnt - 1) / p.Q;
+    const int p_a = (int)fastdiv((unsigned)m_first, p.div_q_magic, p.div_q_shift), p_b = (int)fastdiv((unsigned)(m_first + m_cnt - 1), p.div_q_magic, p.div_q_shift);
     const int ih_base = p_a * p.stride_h - p.pad_h;
     const int nrows = (p_b - p_a) * p.stride_h + (p.R - 1) * p.dil_h + 1;
     const int PW = p.PW;                        // (Q-1)*s_w + (S-1)*d_w + 1 patch columns, first is iw = -pad_w
@@ -1018,8 +1024,8 @@ __global__ void __launch_bounds__(512) conv_patch_kernel(const Params p) {
         const unsigned gofs = (unsigned)(grp * p.Cg * ES);
         const int pc = tid & 7;
         int px = first * 32 + (tid >> 3);
-        int pr = px / PW, pcx = px - pr * PW;
-        const int d_r = 32 / PW, d_c = 32 - d_r * PW;
+        int pr = (int)fastdiv((unsigned)px, p.div_pw_magic, p.div_pw_shift), pcx = px - pr * PW;
+        const int d_r = (int)fastdiv(32u, p.div_pw_magic, p.div_pw_shift), d_c = 32 - d_r * PW;
         for (int it = first; it < last; ++it) {
             const int lc = pc ^ kmajor_swz<128>(px);
             const int ih = ih_base + pr, iw = pcx - p.pad_w;
@@ -1077,7 +1083,7 @@ __global__ void __launch_bounds__(512) conv_patch_kernel(const Params p) {
         int m = cw * 64 + i * 32 + l31;
         if (m >= m_cnt) m = m_cnt - 1;                         // rows past the tile re-read its last pixel; never stored
         const int mm = m_first + m;
-        const int op = mm / p.Q, oq = mm - op * p.Q;
+        const int op = (int)fastdiv((unsigned)mm, p.div_q_magic, p.div_q_shift), oq = mm - op * p.Q;
         base_px[i] = (op - p_a) * p.stride_h * PW + oq * p.stride_w;
     }
     const int swn = kmajor_swz<128>(l31);
@@ -1200,7 +1206,7 @@ __global__ void __launch_bounds__(C::THREADS) contract_staged_kernel(const Param
     const int wm = wave / C::WN, wn = wave % C::WN;
 
     int tm, tn;
-    tile_of_block(blockIdx.x, p.tiles_m, p.tiles_n, &tm, &tn);
+    tile_of_block(blockIdx.x, p.tiles_m, p.tiles_n, p.div_gw_magic, p.div_gw_shift, &tm, &tn);
     const int m0 = tm * C::BM, n0 = tn * C::BN;
     const long long bz = blockIdx.y;
 

@@ -56,8 +56,22 @@ struct Params {
     // kernel derives that phase's tap subset, padding and output pixels.  P, Q are then the extents of one phase's
     // pixel grid (ceil(P_full / phases_h) ...), M = images * P * Q, R, S, K those of the whole filter.
     int phases_h, phases_w, t_pad_h, t_pad_w, P_full, Q_full, conv_groups;
-    unsigned div_pq_magic, div_q_magic;      // m / (P*Q) and m / Q for m < 2^31: (m * magic) >> (32 + shift)
-    int div_pq_shift, div_q_shift;           // shift < 0: divisor 1
+    // Divisions by launch constants as multiply-and-shift (make_fastdiv; m < 2^31; shift < 0: divisor 1).  A runtime
+    // integer division is a chain of ~25 dependent instructions, and the kernels' first copy waits for several.
+    unsigned div_pq_magic, div_q_magic;      // m / (P*Q) and m / Q: output row -> (image, row, column)
+    int div_pq_shift, div_q_shift;
+    unsigned div_opq_magic;                  // m / (OD*P*Q): with a depth axis
+    int div_opq_shift;
+    unsigned div_gw_magic;                   // id / (kGroupM * tiles_n): the workgroup -> tile map
+    int div_gw_shift;
+    unsigned div_tn_magic, div_tm_magic, div_pw_magic;     // patch kernel: id / tiles_n, id / tiles_m, pixel / PW
+    int div_tn_shift, div_tm_shift, div_pw_shift;
+    unsigned div_cg_magic, div_s_magic, div_rs_magic;      // k / Cg, tap / S, tap / (R*S): per-lane tap decode when a stage spans taps
+    int div_cg_shift, div_s_shift, div_rs_shift;
+    unsigned div_grp_magic, div_phh_magic, div_phw_magic;  // by phase: / conv_groups, / phases_h, / phases_w
+    int div_grp_shift, div_phh_shift, div_phw_shift;
+    unsigned div_dwq_magic, div_dwpq_magic;                // depth-wise, pixel blocks: / ceil(Q / kDwBlockPix), / (P * that)
+    int div_dwq_shift, div_dwpq_shift;
     // reduction split over workgroups (fast kernels): ksplit slices (grid.z) reduce consecutive runs of stages
     // of one output tile; each writes its partial sums to ws, the slice that arrives last at the tile's counter
     // adds all of them in slice order (the sum does not depend on who is last) and runs the epilogue
@@ -65,29 +79,6 @@ struct Params {
     void* ws;            // partial sums: [grid.y][tile][slice][BM*BN] accumulator elements (4 bytes each)
     unsigned* ws_count;  // [grid.y][tile] arrival counters, zero between launches (the last slice resets its tile's)
 };
-
-// Number of XCDs (L2 domains) workgroups are dealt to round-robin by the dispatcher.
-constexpr int kXcds = 8;
-// Tile rows walked together before moving to the next tile column (L2 reuse of the B tile).
-constexpr int kGroupM = 4;
-
-// Map a linear workgroup id to an output tile.  Consecutive hardware ids land on different XCDs,
-// so ids are first regrouped such that each XCD owns a contiguous run of logical tiles (its L2
-// then sees few distinct A/B panels), and logical tiles walk kGroupM tile-rows at a time.
-// The map is a bijection from [0, tiles_m*tiles_n) onto the tile grid.
-__host__ __device__ inline void tile_of_block(int bid, int tiles_m, int tiles_n, int* tm, int* tn) {
-    int nb = tiles_m * tiles_n;
-    int nb8 = nb - nb % kXcds;
-    int logical = bid;
-    if (bid < nb8) logical = (bid % kXcds) * (nb8 / kXcds) + bid / kXcds;
-    int width = kGroupM * tiles_n;
-    int group = logical / width;
-    int first_m = group * kGroupM;
-    int gsz = tiles_m - first_m < kGroupM ? tiles_m - first_m : kGroupM;
-    int in_group = logical - group * width;
-    *tm = first_m + in_group % gsz;
-    *tn = in_group / gsz;
-}
 
 // Exact unsigned division of m < 2^31 by a fixed d >= 1: the host picks s = ceil(log2 d) and
 // magic = floor(2^(31+s) / d) + 1 < 2^32, then m / d = (m * magic) >> (31 + s).  d = 1 is shift = -1.
@@ -110,6 +101,38 @@ __host__ __device__ inline unsigned fastdiv(unsigned m, unsigned magic, int shif
 #else
     return shift < 0 ? m : (unsigned)(((unsigned long long)m * magic) >> 32) >> shift;
 #endif
+}
+
+// Adjacent output pixels one thread of the blocked depth-wise kernel owns.
+constexpr int kDwBlockPix = 4;      // measured 2, 4, 8: 8.5 / 7.2 / 6.9 us at stride 1 (16x56x56x128 fp16), 7.1 / 6.2 / 9.8 us at stride 2 (int8)
+
+// Number of XCDs (L2 domains) workgroups are dealt to round-robin by the dispatcher.
+constexpr int kXcds = 8;
+// Tile rows walked together before moving to the next tile column (L2 reuse of the B tile).
+constexpr int kGroupM = 4;
+
+// Map a linear workgroup id to an output tile.  Consecutive hardware ids land on different XCDs,
+// so ids are first regrouped such that each XCD owns a contiguous run of logical tiles (its L2
+// then sees few distinct A/B panels), and logical tiles walk kGroupM tile-rows at a time.
+// The map is a bijection from [0, tiles_m*tiles_n) onto the tile grid.
+// (gw_magic, gw_shift) = make_fastdiv(kGroupM * tiles_n).
+__host__ __device__ inline void tile_of_block(int bid, int tiles_m, int tiles_n, unsigned gw_magic, int gw_shift, int* tm, int* tn) {
+    int nb = tiles_m * tiles_n;
+    int nb8 = nb - nb % kXcds;
+    int logical = bid;
+    if (bid < nb8) logical = (bid % kXcds) * (nb8 / kXcds) + bid / kXcds;
+    int width = kGroupM * tiles_n;
+    int group = (int)fastdiv((unsigned)logical, gw_magic, gw_shift);
+    int first_m = group * kGroupM;
+    int in_group = logical - group * width;
+    if (tiles_m - first_m >= kGroupM) {
+        *tm = first_m + in_group % kGroupM;
+        *tn = in_group / kGroupM;
+    } else {
+        int gsz = tiles_m - first_m;      // last, shorter group of tile rows
+        *tm = first_m + in_group % gsz;
+        *tn = in_group / gsz;
+    }
 }
 
 constexpr int elem_size(int dt) { return dt == DT_I8 ? 1 : (dt == DT_F16 || dt == DT_BF16) ? 2 : 4; }
