@@ -92,7 +92,7 @@ __global__ void __launch_bounds__(256) depthwise_kernel(const Params p) {
     // range of pixels and finds the rows its neighbouring taps share in its own L2
     int bx = blockIdx.x;
     {
-        const int nb = gridDim.x, nb8 = nb - nb % kXcds;
+        const int nb = (p.M + NPIX * PP - 1) / (NPIX * PP), nb8 = nb - nb % kXcds;      // = gridDim.x (a hidden argument, fetched late)
         if (bx < nb8) bx = (bx % kXcds) * (nb8 / kXcds) + bx / kXcds;
     }
     // taps outside the image read through the descriptor's range check: zeros, and no branch around the load
@@ -163,6 +163,10 @@ __global__ void __launch_bounds__(256) depthwise3x3_blocked_kernel(const Params 
     constexpr int PP = 256 / CV;                     // pixel groups per workgroup
     constexpr int NP = kDwBlockPix, NC = (NP - 1) * SW + 3;
 
+    // every argument the kernel reads, fetched in one batch
+    asm volatile("" ::"s"(p.A), "s"(p.B), "s"(p.C), "s"(p.M), "s"(p.bias), "s"(p.relu), "s"(p.scale), "s"(p.batch_imgs), "s"(p.H), "s"(p.W), "s"(p.Cin),
+                 "s"(p.P), "s"(p.Q), "s"(p.stride_h), "s"(p.pad_h), "s"(p.pad_w), "s"(p.dil_h));
+    asm volatile("" ::"s"(p.div_dwq_magic), "s"(p.div_dwq_shift), "s"(p.div_dwpq_magic), "s"(p.div_dwpq_shift));
     const int tid = threadIdx.x;
     const int cv = tid % CV, pl = tid / CV;
     const int c0 = blockIdx.y * kDwChannels + cv * VEC;
@@ -175,12 +179,12 @@ __global__ void __launch_bounds__(256) depthwise3x3_blocked_kernel(const Params 
 #pragma unroll
     for (int e = 0; e < VEC; ++e) bias_r[e] = p.bias ? ((const acc_e*)p.bias)[c0 + e] : (acc_e)0;
 
+    const int QG = (p.Q + NP - 1) / NP;              // pixel groups per output row
     int bx = blockIdx.x;                             // each XCD owns a contiguous range of pixel groups (shared rows stay in its L2)
     {
-        const int nb = gridDim.x, nb8 = nb - nb % kXcds;
+        const int nb = (p.batch_imgs * p.P * QG + PP - 1) / PP, nb8 = nb - nb % kXcds;      // = gridDim.x (a hidden argument, fetched late)
         if (bx < nb8) bx = (bx % kXcds) * (nb8 / kXcds) + bx / kXcds;
     }
-    const int QG = (p.Q + NP - 1) / NP;              // pixel groups per output row
     const int gidx = bx * PP + pl;
     if (gidx >= p.batch_imgs * p.P * QG) return;
     const int img = (int)fastdiv((unsigned)gidx, p.div_dwpq_magic, p.div_dwpq_shift), rem = gidx - img * (p.P * QG);

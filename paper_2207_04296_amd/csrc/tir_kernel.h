@@ -201,10 +201,17 @@ __device__ __forceinline__ void load_to_lds(const i32x4& rsrc, const char* lds_b
 // Kernel arguments are fetched lazily, a few at a time, each fetch an exposed scalar-memory latency
 // of several hundred cycles.  Naming the fields a kernel needs before its first copy in one asm
 // statement makes the compiler fetch them in one batch at the very start.
-__device__ __forceinline__ void prefetch_args(const Params& p) {
-    asm volatile("" ::"s"(p.A), "s"(p.B), "s"(p.C), "s"(p.bias), "s"(p.M), "s"(p.N), "s"(p.K), "s"(p.tiles_m), "s"(p.tiles_n),
-                 "s"(p.c_fast), "s"(p.relu), "s"(p.scale));
-    asm volatile("" ::"s"(p.a_bs), "s"(p.b_bs), "s"(p.c_bs), "s"(p.a_rs), "s"(p.b_rs), "s"(p.b_cs), "s"(p.c_rs), "s"(p.c_cs), "s"(p.bias_bs));
+__device__ __forceinline__ void prefetch_args(const Params& p, bool conv) {
+    asm volatile("" ::"s"(p.A), "s"(p.B), "s"(p.C), "s"(p.M), "s"(p.N), "s"(p.K), "s"(p.tiles_m), "s"(p.tiles_n),
+                 "s"(p.c_fast), "s"(p.ksplit), "s"(p.div_gw_magic), "s"(p.div_gw_shift));
+    asm volatile("" ::"s"(p.a_bs), "s"(p.b_bs), "s"(p.c_bs), "s"(p.a_rs), "s"(p.b_rs), "s"(p.b_cs), "s"(p.c_rs), "s"(p.c_cs), "s"(p.bias_bs),
+                 "s"(p.bias), "s"(p.relu), "s"(p.scale), "s"(p.ws), "s"(p.batch_imgs));
+    if (conv) {
+        asm volatile("" ::"s"(p.H), "s"(p.W), "s"(p.Cin), "s"(p.Cg), "s"(p.P), "s"(p.Q), "s"(p.S), "s"(p.stride_h), "s"(p.stride_w), "s"(p.pad_h),
+                     "s"(p.pad_w), "s"(p.dil_h), "s"(p.dil_w));
+        asm volatile("" ::"s"(p.div_pq_magic), "s"(p.div_q_magic), "s"(p.div_pq_shift), "s"(p.div_q_shift), "s"(p.div_cg_magic), "s"(p.div_s_magic),
+                     "s"(p.div_cg_shift), "s"(p.div_s_shift), "s"(p.phases_h));
+    }
 }
 
 // Workgroup barrier that also publishes this wave's global->LDS copies (counted by vmcnt; all but
@@ -450,7 +457,7 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
     static_assert(KSTEPS % 2 == 0, "fragment sets alternate per k-step and must line up per stage");
 
     __shared__ __attribute__((aligned(1024))) char smem[C::LDS_BYTES];
-    prefetch_args(p);
+    prefetch_args(p, C::AMODE != A_KMAJOR);
 
     // reduction group kgrp owns the stages s with s % KW == kgrp; inside the group, thread tid of SUB.
     // With copy waves (CW > 0) the waves past the multiplying ones only copy: thread tid of CT, wave `wave` of CW.
@@ -563,15 +570,13 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
 #pragma unroll
         for (int i = 0; i < C::A_IT; ++i) {
             const int m = m0 + a_r0 + i * C::K_RSTEP;
-            int ih0 = -30000, iw0 = 0, img = 0;
-            if (m < p.M) {
-                img = (int)fastdiv((unsigned)m, p.div_pq_magic, p.div_pq_shift);
-                const int rem = m - img * PQ;
-                const int op = (int)fastdiv((unsigned)rem, p.div_q_magic, p.div_q_shift), oq = rem - op * p.Q;
-                ih0 = op * p.stride_h - cpad_h;
-                iw0 = oq * p.stride_w - cpad_w;
-            }
-            a_off[i] = (((unsigned)img * (unsigned)p.H + (unsigned)ih0) * (unsigned)p.W + (unsigned)iw0) * (unsigned)p.Cin;
+            // (decoded for rows past M too - the arithmetic is total - and then moved out of the image: no branch)
+            const int img = (int)fastdiv((unsigned)m, p.div_pq_magic, p.div_pq_shift);
+            const int rem = m - img * PQ;
+            const int op = (int)fastdiv((unsigned)rem, p.div_q_magic, p.div_q_shift), oq = rem - op * p.Q;
+            const int ih0 = m < p.M ? op * p.stride_h - cpad_h : -30000;
+            const int iw0 = oq * p.stride_w - cpad_w;
+            a_off[i] = (((unsigned)img * (unsigned)p.H + (unsigned)ih0) * (unsigned)p.W + (unsigned)iw0) * (unsigned)(p.Cin * ES);    // bytes, modulo 2^32
             a_hw[i] = (ih0 << 16) | (iw0 & 0xffff);
         }
     }
@@ -625,6 +630,15 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
     if (conv_uniform_tap) conv_advance(s_begin + kgrp);
     i32x4 ra, rb;
     unsigned a_voff[C::A_IT];
+    // Is tap offset d (rows in the high half, columns in the low half) of the packed pixel coordinates hw inside the
+    // image?  Both 16-bit sums at once: a coordinate is inside iff clamping it to the last row / column (unsigned, so
+    // negative ones are huge) leaves it unchanged.  The host keeps every coordinate within (-2^15, 2^16).
+    typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+    const u16x2 hw_last = {(unsigned short)(p.W - 1), (unsigned short)(p.H - 1)};
+    auto inside = [&](int hw, u16x2 d) -> bool {
+        const u16x2 c = __builtin_bit_cast(u16x2, hw) + d;
+        return __builtin_bit_cast(unsigned, __builtin_elementwise_min(c, hw_last)) == __builtin_bit_cast(unsigned, c);
+    };
     char* lds_dst = ring;    // wave-uniform destination of this wave's first A chunk
 
     // Prepare the copy of `stage` (descriptors, predicates); the loads themselves are issued one
@@ -693,15 +707,11 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
                 // Cg is a multiple of the stage's k extent: the whole stage belongs to one tap, so the tap
                 // decode is scalar and advances incrementally (stages are prepared in order)
                 const int dh = conv_fr * p.dil_h, dw = conv_fs * p.dil_w;
-                const unsigned delta = (unsigned)((dh * p.W + dw) * p.Cin + conv_cc + a_lc * VEC);
-                const bool kv = live;       // K = R*S*Cg is a multiple of the stage extent here
+                const unsigned delta = (unsigned)(((dh * p.W + dw) * p.Cin + conv_cc) * ES) + a_lc * 16;
+                // not live: the descriptor is empty (K = R*S*Cg is a multiple of the stage extent here)
+                const u16x2 d_hw = {(unsigned short)dw, (unsigned short)dh};
 #pragma unroll
-                for (int i = 0; i < C::A_IT; ++i) {
-                    const int ih = (a_hw[i] >> 16) + dh;
-                    const int iw = (int)(short)(a_hw[i] & 0xffff) + dw;
-                    const bool ok = kv && (unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W;
-                    a_voff[i] = ok ? (a_off[i] + delta) * ES : kOutOfRange;
-                }
+                for (int i = 0; i < C::A_IT; ++i) a_voff[i] = inside(a_hw[i], d_hw) ? a_off[i] + delta : kOutOfRange;
                 conv_advance(C::KW);
             } else {
                 const int kb = stage * BK + a_lc * VEC;
@@ -709,15 +719,11 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
                 const int cc = kb - tap * p.Cg;
                 const int fr = (int)fastdiv((unsigned)tap, p.div_s_magic, p.div_s_shift), fs = tap - fr * p.S;
                 const int dh = fr * p.dil_h, dw = fs * p.dil_w;
-                const unsigned delta = (unsigned)((dh * p.W + dw) * p.Cin + cc);
+                const unsigned delta = (unsigned)(((dh * p.W + dw) * p.Cin + cc) * ES);
                 const bool kv = kb < p.K;
+                const u16x2 d_hw = {(unsigned short)dw, (unsigned short)dh};
 #pragma unroll
-                for (int i = 0; i < C::A_IT; ++i) {
-                    const int ih = (a_hw[i] >> 16) + dh;
-                    const int iw = (int)(short)(a_hw[i] & 0xffff) + dw;
-                    const bool ok = kv && (unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W;
-                    a_voff[i] = ok ? (a_off[i] + delta) * ES : kOutOfRange;
-                }
+                for (int i = 0; i < C::A_IT; ++i) a_voff[i] = (kv && inside(a_hw[i], d_hw)) ? a_off[i] + delta : kOutOfRange;
             }
         }
         if constexpr (C::BMODE == B_KMAJOR) {
@@ -988,6 +994,13 @@ __global__ void __launch_bounds__(512) conv_patch_kernel(const Params p) {
     constexpr int SLAB = 64 * 128;              // one filter tap: 64 output channels x 128 B
 
     __shared__ __attribute__((aligned(1024))) char smem[160 * 1024];
+    // every argument the kernel reads, fetched in one batch (see prefetch_args)
+    asm volatile("" ::"s"(p.A), "s"(p.B), "s"(p.C), "s"(p.N), "s"(p.K), "s"(p.tiles_m), "s"(p.tiles_n), "s"(p.c_rs), "s"(p.bias), "s"(p.bias_bs),
+                 "s"(p.relu), "s"(p.scale), "s"(p.batch_imgs), "s"(p.PW));
+    asm volatile("" ::"s"(p.H), "s"(p.W), "s"(p.Cin), "s"(p.Cg), "s"(p.P), "s"(p.Q), "s"(p.R), "s"(p.S), "s"(p.stride_h), "s"(p.stride_w), "s"(p.pad_h),
+                 "s"(p.pad_w), "s"(p.dil_h), "s"(p.dil_w));
+    asm volatile("" ::"s"(p.div_q_magic), "s"(p.div_q_shift), "s"(p.div_tn_magic), "s"(p.div_tn_shift), "s"(p.div_tm_magic), "s"(p.div_tm_shift),
+                 "s"(p.div_pw_magic), "s"(p.div_pw_shift));
     char* const s_filt = smem;                  // R*S slabs, then the patch (the host checked that both fit)
     char* const s_patch = smem + p.R * p.S * SLAB;
 
@@ -1005,7 +1018,8 @@ __global__ void __launch_bounds__(512) conv_patch_kernel(const Params p) {
     // workgroup -> (image, pixel tile, channel tile); group = blockIdx.y
     // Workgroups go to the 8 L2 domains round-robin by launch index: give each domain a run of consecutive tiles,
     // so that the input rows two neighbouring pixel tiles share (the halo) are fetched into one L2 once.
-    const int xq = gridDim.x >> 3, xr = gridDim.x & 7, xf = blockIdx.x & 7;
+    const int nwg = p.batch_imgs * p.tiles_m * p.tiles_n;       // = gridDim.x, without the late fetch of a hidden argument
+    const int xq = nwg >> 3, xr = nwg & 7, xf = blockIdx.x & 7;
     const int bid = xf * xq + (xf < xr ? xf : xr) + (blockIdx.x >> 3);
     const int rest = (int)fastdiv((unsigned)bid, p.div_tn_magic, p.div_tn_shift);
     const int nt = bid - rest * p.tiles_n;

@@ -1,6 +1,7 @@
 // Kernel parameter block and small host/device helpers shared by the host dispatcher and the
 // gfx950 kernels.  Nothing here is visible across the C ABI.
 #pragma once
+#include <cstddef>
 #include <stdint.h>
 
 namespace tir {
@@ -24,7 +25,11 @@ enum : int {
     B_GENERIC = 2   // any strides, element-wise loads
 };
 
+// Kernel arguments.  The block is fetched through the scalar cache 64 bytes at a time and a kernel's first copy waits
+// for every field it needs, so what all kernels read sits in the first three lines and the convolution-only fields
+// follow (the kernels name their fields up front, which makes the compiler fetch them in one batch).
 struct Params {
+    // ---- line 0
     const void* A;
     const void* B;
     void* C;
@@ -32,74 +37,79 @@ struct Params {
     int batch;        // number of independent contractions (grid.y)
     int tiles_m, tiles_n;
     int c_fast;       // C has unit column stride, disjoint rows and 31-bit tile offsets: buffer-store epilogue
+    // reduction split over workgroups (fast kernels): ksplit slices (grid.z) reduce consecutive runs of stages
+    // of one output tile; each writes its partial sums to ws, the slice that arrives last at the tile's counter
+    // adds all of them in slice order (the sum does not depend on who is last) and runs the epilogue
+    int ksplit;          // 1: no split, ws and ws_count unused
+    // Divisions by launch constants as multiply-and-shift (make_fastdiv; m < 2^31).  A runtime
+    // integer division is a chain of ~25 dependent instructions, and the kernels' first copy waits for several.
+    unsigned div_gw_magic;                   // id / (kGroupM * tiles_n): the workgroup -> tile map
+    int div_gw_shift;
+    // ---- line 1
     long long a_bs, b_bs, c_bs;                 // per-batch offsets, in elements
-    long long a_rs, a_cs, b_rs, b_cs, c_rs, c_cs;  // element strides; for conv: a_* unused
-    // convolution geometry (A_CONV*): x is [n][H][W][Cin], one group reads Cg channels
-    int H, W, Cin, Cg, P, Q, R, S;
-    int stride_h, stride_w, pad_h, pad_w, dil_h, dil_w;
-    // general convolution decode (A_CONVX, A_CONV_GENERIC); a plain 2-D convolution has D = T = OD = 1, stride_d = dil_d = 1,
-    // pad_d = 0, tap_sign = 1, up_h = up_w = 1.  Input coordinate of output pixel (o, p, q) and tap (t, r, s):
-    //   depth  o*stride_d - pad_d + t*dil_d
-    //   height (p*stride_h - pad_h + tap_sign*r*dil_h) / up_h   if divisible by up_h, else the tap reads zero; width alike
-    int D, T, OD, stride_d, pad_d, dil_d;
-    int tap_sign, up_h, up_w;
-    int PW;           // patch kernel: columns of the LDS-resident input patch
-    int batch_imgs;   // patch kernel: images in x (for the descriptor)
+    long long a_rs, a_cs, b_rs, b_cs, c_rs;     // element strides; for conv: a_* unused
+    // ---- line 2
+    long long c_cs;
     // fused consumer: out = cvt(relu(acc + bias[column])); bias is fp32 (float inputs) or int32 (int8 inputs)
     const void* bias;    // null: no bias
     long long bias_bs;   // bias elements between consecutive grid.y slices (conv groups: channels per group; batches: 0)
     int relu;
     float scale;         // int8 output only: code = clamp(rint(float(t) * scale), -128, 127)
+    void* ws;            // partial sums: [grid.y][tile][slice][BM*BN] accumulator elements (4 bytes each)
+    unsigned* ws_count;  // [grid.y][tile] arrival counters, zero between launches (the last slice resets its tile's)
+    int batch_imgs;   // convolutions: images in x (for the descriptor)
+    int PW;           // patch kernel: columns of the LDS-resident input patch
+    // ---- convolution geometry (A_CONV*): x is [n][H][W][Cin], one group reads Cg channels
+    int H, W, Cin, Cg, P, Q, R, S;
+    int stride_h, stride_w, pad_h, pad_w, dil_h, dil_w;
+    unsigned div_pq_magic, div_q_magic;      // m / (P*Q) and m / Q: output row -> (image, row, column)
+    int div_pq_shift, div_q_shift;
+    unsigned div_cg_magic, div_s_magic, div_rs_magic;      // k / Cg, tap / S, tap / (R*S): per-lane tap decode when a stage spans taps
+    int div_cg_shift, div_s_shift, div_rs_shift;
+    unsigned div_tn_magic, div_tm_magic, div_pw_magic;     // patch kernel: id / tiles_n, id / tiles_m, pixel / PW
+    int div_tn_shift, div_tm_shift, div_pw_shift;
     // Transposed convolution by output phase (A_CONV variants; phases_h = 0: off).  The output pixels with
     // (oh mod phases_h, ow mod phases_w) = (ph, pw) form a stride-1 convolution of the input with the filter taps
     // r = r0 + phases_h*t, r0 = (ph + t_pad_h) mod phases_h (likewise in w): grid.y enumerates (phase, group), the
     // kernel derives that phase's tap subset, padding and output pixels.  P, Q are then the extents of one phase's
     // pixel grid (ceil(P_full / phases_h) ...), M = images * P * Q, R, S, K those of the whole filter.
     int phases_h, phases_w, t_pad_h, t_pad_w, P_full, Q_full, conv_groups;
-    // Divisions by launch constants as multiply-and-shift (make_fastdiv; m < 2^31; shift < 0: divisor 1).  A runtime
-    // integer division is a chain of ~25 dependent instructions, and the kernels' first copy waits for several.
-    unsigned div_pq_magic, div_q_magic;      // m / (P*Q) and m / Q: output row -> (image, row, column)
-    int div_pq_shift, div_q_shift;
-    unsigned div_opq_magic;                  // m / (OD*P*Q): with a depth axis
-    int div_opq_shift;
-    unsigned div_gw_magic;                   // id / (kGroupM * tiles_n): the workgroup -> tile map
-    int div_gw_shift;
-    unsigned div_tn_magic, div_tm_magic, div_pw_magic;     // patch kernel: id / tiles_n, id / tiles_m, pixel / PW
-    int div_tn_shift, div_tm_shift, div_pw_shift;
-    unsigned div_cg_magic, div_s_magic, div_rs_magic;      // k / Cg, tap / S, tap / (R*S): per-lane tap decode when a stage spans taps
-    int div_cg_shift, div_s_shift, div_rs_shift;
     unsigned div_grp_magic, div_phh_magic, div_phw_magic;  // by phase: / conv_groups, / phases_h, / phases_w
     int div_grp_shift, div_phh_shift, div_phw_shift;
+    // general convolution decode (A_CONVX, A_CONV_GENERIC); a plain 2-D convolution has D = T = OD = 1, stride_d = dil_d = 1,
+    // pad_d = 0, tap_sign = 1, up_h = up_w = 1.  Input coordinate of output pixel (o, p, q) and tap (t, r, s):
+    //   depth  o*stride_d - pad_d + t*dil_d
+    //   height (p*stride_h - pad_h + tap_sign*r*dil_h) / up_h   if divisible by up_h, else the tap reads zero; width alike
+    int D, T, OD, stride_d, pad_d, dil_d;
+    int tap_sign, up_h, up_w;
+    unsigned div_opq_magic;                  // m / (OD*P*Q): with a depth axis
+    int div_opq_shift;
     unsigned div_dwq_magic, div_dwpq_magic;                // depth-wise, pixel blocks: / ceil(Q / kDwBlockPix), / (P * that)
     int div_dwq_shift, div_dwpq_shift;
-    // reduction split over workgroups (fast kernels): ksplit slices (grid.z) reduce consecutive runs of stages
-    // of one output tile; each writes its partial sums to ws, the slice that arrives last at the tile's counter
-    // adds all of them in slice order (the sum does not depend on who is last) and runs the epilogue
-    int ksplit;          // 1: no split, ws and ws_count unused
-    void* ws;            // partial sums: [grid.y][tile][slice][BM*BN] accumulator elements (4 bytes each)
-    unsigned* ws_count;  // [grid.y][tile] arrival counters, zero between launches (the last slice resets its tile's)
 };
+static_assert(offsetof(Params, a_bs) == 64 && offsetof(Params, c_cs) == 128 && offsetof(Params, H) == 184, "the lines described above");
 
-// Exact unsigned division of m < 2^31 by a fixed d >= 1: the host picks s = ceil(log2 d) and
-// magic = floor(2^(31+s) / d) + 1 < 2^32, then m / d = (m * magic) >> (31 + s).  d = 1 is shift = -1.
+// Exact unsigned division of m < 2^31 by a fixed d >= 1 without a branch or a special case: with s = ceil(log2 d)
+// and magic = floor(2^32 * (2^s - d) / d) + 1 < 2^32,  m / d = (mulhi(m, magic) + m) >> s  (the round-up method of
+// Granlund and Montgomery; m < 2^31 keeps the sum inside 32 bits).  d = 1 gives magic 0, shift 0.
 struct FastDiv {
     unsigned magic;
-    int shift;      // applied to the high half of the product: s - 1
+    int shift;
 };
 inline FastDiv make_fastdiv(unsigned d) {
-    FastDiv f = {0u, -1};
+    FastDiv f = {0u, 0};
     if (d <= 1) return f;
     int s = 0;
     while ((1ull << s) < d) ++s;
-    f.magic = (unsigned)(((1ull << (31 + s)) / d) + 1ull);
-    f.shift = s - 1;
+    f.magic = (unsigned)(((1ull << (32 + s)) / d) + 1ull - (1ull << 32));
+    f.shift = s;
     return f;
 }
 __host__ __device__ inline unsigned fastdiv(unsigned m, unsigned magic, int shift) {
 #if defined(__HIP_DEVICE_COMPILE__)
-    return shift < 0 ? m : __umulhi(m, magic) >> shift;
+    return (__umulhi(m, magic) + m) >> shift;
 #else
-    return shift < 0 ? m : (unsigned)(((unsigned long long)m * magic) >> 32) >> shift;
+    return ((unsigned)(((unsigned long long)m * magic) >> 32) + m) >> shift;
 #endif
 }
 
@@ -125,14 +135,14 @@ __host__ __device__ inline void tile_of_block(int bid, int tiles_m, int tiles_n,
     int group = (int)fastdiv((unsigned)logical, gw_magic, gw_shift);
     int first_m = group * kGroupM;
     int in_group = logical - group * width;
-    if (tiles_m - first_m >= kGroupM) {
-        *tm = first_m + in_group % kGroupM;
-        *tn = in_group / kGroupM;
-    } else {
-        int gsz = tiles_m - first_m;      // last, shorter group of tile rows
-        *tm = first_m + in_group % gsz;
-        *tn = in_group / gsz;
-    }
+    // tile rows in this group: kGroupM, fewer in the last one; the division by 1 .. 4 as constants of fastdiv
+    int gsz = tiles_m - first_m < kGroupM ? tiles_m - first_m : kGroupM;
+    static_assert(kGroupM == 4, "the constants below are those of 1, 2, 3 and 4");
+    unsigned g_magic = gsz == 3 ? 0x55555556u : (gsz == 1 ? 0u : 1u);
+    int g_shift = gsz >= 3 ? 2 : gsz - 1;
+    int q = (int)fastdiv((unsigned)in_group, g_magic, g_shift);
+    *tm = first_m + in_group - q * gsz;
+    *tn = q;
 }
 
 constexpr int elem_size(int dt) { return dt == DT_I8 ? 1 : (dt == DT_F16 || dt == DT_BF16) ? 2 : 4; }
