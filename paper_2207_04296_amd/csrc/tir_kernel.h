@@ -628,6 +628,21 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
         }
     };
     if (conv_uniform_tap) conv_advance(s_begin + kgrp);
+    // One stage ahead, branch-free (Cg is a multiple of the stage's k extent: at most one tap boundary per stage).
+    auto conv_step = [&]() {
+        conv_cc += BK;
+        const bool tap_end = conv_cc >= p.Cg;
+        conv_cc = tap_end ? 0 : conv_cc;
+        conv_fs += tap_end ? 1 : 0;
+        const bool row_end = conv_fs == cS;
+        conv_fs = row_end ? 0 : conv_fs;
+        conv_fr += row_end ? 1 : 0;
+        if constexpr (C::AMODE == A_CONVX) {
+            const bool plane_end = conv_fr == p.R;
+            conv_fr = plane_end ? 0 : conv_fr;
+            conv_ft += plane_end ? 1 : 0;
+        }
+    };
     i32x4 ra, rb;
     unsigned a_voff[C::A_IT];
     // Is tap offset d (rows in the high half, columns in the low half) of the packed pixel coordinates hw inside the
@@ -640,12 +655,16 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
         return __builtin_bit_cast(unsigned, __builtin_elementwise_min(c, hw_last)) == __builtin_bit_cast(unsigned, c);
     };
     char* lds_dst = ring;    // wave-uniform destination of this wave's first A chunk
+    int c_slot = 0;          // ring slot and reduction stage of the next copy_begin (stages are prepared in order)
+    int c_stage = s_begin + kgrp;
 
     // Prepare the copy of `stage` (descriptors, predicates); the loads themselves are issued one
     // by one through copy_unit() so that they can be interleaved with MFMAs.
-    auto copy_begin = [&](int slot_stage) {
-        lds_dst = ring + (slot_stage % NSTAGE) * C::STAGE_BYTES + wave * 1024;
-        const int stage = s_begin + slot_stage * C::KW + kgrp;       // stage of the whole reduction
+    auto copy_begin = [&](int) {
+        lds_dst = ring + c_slot * C::STAGE_BYTES + wave * 1024;
+        const int stage = c_stage;                                   // stage of the whole reduction
+        c_slot = c_slot + 1 == NSTAGE ? 0 : c_slot + 1;
+        c_stage += C::KW;
         const int nh = nh_all;
         const int tap_fr = conv_fr, tap_fs = conv_fs, tap_cc = conv_cc;    // the stage's tap, before the cursor moves on
         const bool live = stage < s_end;   // past the end: empty descriptors, the copies write zeros (they add nothing)
@@ -670,7 +689,8 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
                 ft = conv_ft; fr = conv_fr; fs = conv_fs;
                 cc = conv_cc + a_lc * VEC;
                 kv = live;
-                conv_advance(C::KW);
+#pragma unroll
+                for (int kw = 0; kw < C::KW; ++kw) conv_step();
             } else {
                 const int kb = stage * BK + a_lc * VEC;
                 const int tap = (int)fastdiv((unsigned)kb, p.div_cg_magic, p.div_cg_shift);
@@ -712,7 +732,8 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
                 const u16x2 d_hw = {(unsigned short)dw, (unsigned short)dh};
 #pragma unroll
                 for (int i = 0; i < C::A_IT; ++i) a_voff[i] = inside(a_hw[i], d_hw) ? a_off[i] + delta : kOutOfRange;
-                conv_advance(C::KW);
+#pragma unroll
+                for (int kw = 0; kw < C::KW; ++kw) conv_step();
             } else {
                 const int kb = stage * BK + a_lc * VEC;
                 const int tap = (int)fastdiv((unsigned)kb, p.div_cg_magic, p.div_cg_shift);
@@ -728,8 +749,10 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
         }
         if constexpr (C::BMODE == B_KMAJOR) {
             // k offset of the stage inside a filter row: consecutive, or (by phase) that of the tap it stands for
-            const long long kb = phased ? (long long)(((f_r0 - p.phases_h * tap_fr) * p.S + (f_s0 - p.phases_w * tap_fs)) * p.Cg + tap_cc) * ES
-                                        : (long long)stage * ROWB;
+            long long kb = (long long)stage * ROWB;
+            if constexpr (C::AMODE == A_CONV) {
+                if (phased) kb = (long long)(((f_r0 - p.phases_h * tap_fr) * p.S + (f_s0 - p.phases_w * tap_fs)) * p.Cg + tap_cc) * ES;
+            }
             rb = make_rsrc32(b_base + kb, live ? (unsigned)b_bytes - (unsigned)kb : 0u);
             if (ktail && stage == nh - 1) {
                 const bool kv = stage * BK + b_lc * VEC < p.K;
@@ -833,10 +856,12 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
 
         constexpr int LM = SPEC ? 0 : L;                           // copy units the multiplying waves issue per stage
         constexpr int VPK = (LM + KSTEPS - 2) / (KSTEPS - 1);     // ... per k-step of part (1)
+        int r_off = 0;                                             // byte offset of stage h's ring slot (h % NSTAGE, without the division)
         for (int h = 0; h < nh; ++h) {
-            const char* sa = ring + (h % NSTAGE) * C::STAGE_BYTES;
+            const char* sa = ring + r_off;
             const char* sb = sa + C::A_BYTES;
-            const char* na = ring + ((h + 1) % NSTAGE) * C::STAGE_BYTES;
+            r_off = r_off + C::STAGE_BYTES == NSTAGE * C::STAGE_BYTES ? 0 : r_off + C::STAGE_BYTES;
+            const char* na = ring + r_off;
             if constexpr (!SPEC) copy_begin(h + NSTAGE - 1);
             TIR_FENCE();
 #pragma unroll
