@@ -27,13 +27,39 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-u
 
 
 def _compile(args):
+    """Compile one unit.  The compiler reports every kernel's register and scratch use (-Rpass-analysis): a kernel
+    that spills to scratch memory fails the build - a spill in a cold branch still makes every launch of the kernel
+    carry a scratch allocation, and one in a main loop costs far more than the tile shape it came with can gain."""
     src, obj, extra = args
-    cmd = [HIPCC, *FLAGS, *extra, "-c", str(src), "-o", str(obj)]
+    cmd = [HIPCC, *FLAGS, "-Rpass-analysis=kernel-resource-usage", *extra, "-c", str(src), "-o", str(obj)]
     r = subprocess.run(cmd, capture_output=True, text=True)
-    err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
+    lines = r.stderr.splitlines()
     if r.returncode != 0:
+        err = "\n".join(l for l in lines if "packed-fp32-ops" not in l and "remark:" not in l)
         raise RuntimeError(f"hipcc failed: {' '.join(cmd)}\n{err}")
-    return err
+    spilling, name = [], "?"
+    for l in lines:
+        if "remark: Function Name:" in l:
+            name = l.split("Function Name:")[1].split("[-Rpass")[0].strip()
+        elif "ScratchSize [bytes/lane]:" in l:
+            n = int(l.split("ScratchSize [bytes/lane]:")[1].split("[")[0])
+            if n > 0:
+                spilling.append(f"{name}: {n} bytes of scratch per lane")
+    if spilling:
+        raise RuntimeError(f"{src.name} {' '.join(extra)}: kernels spill registers to scratch memory:\n  " + "\n  ".join(sorted(set(spilling))))
+    # what is left to show: real warnings (the remarks and their source excerpts are dropped)
+    keep, skip = [], 0
+    for l in lines:
+        if "remark:" in l:
+            skip = 2            # the remark's source line and caret line follow
+            continue
+        if skip and (l.lstrip().startswith(("|", "^")) or "|" in l[:8]):
+            skip -= 1
+            continue
+        skip = 0
+        if "packed-fp32-ops" not in l and not l.startswith("In file included from") and "remarks generated" not in l:
+            keep.append(l)
+    return "\n".join(keep)
 
 
 def sources():

@@ -161,6 +161,7 @@ static bool split_fits(const Variant* v, int ks, int64_t batch, int64_t tiles, i
     if (ks == 1) return true;
     if (ks < 1 || ks > 64) return false;
     if (v->amode != A_KMAJOR && v->amode != A_CONV && v->amode != A_CONVX) return false;      // the fast kernel only
+    if (v->bm * v->bn > kSplitMaxTile) return false;
     const int64_t stages = (K * elem_size(v->dt) + v->rowb - 1) / v->rowb;
     const int64_t per = (stages + ks - 1) / ks;
     if ((ks - 1) * per >= stages) return false;       // a slice would be empty

@@ -914,7 +914,9 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
                     for (int e = 0; e < 4; ++e) acc[i][j][r4 * 4 + e] += v[e];
                 }
     }
-    if (p.ksplit > 1) {
+    // (Tiles above 128x128 have no split: their partial sums would be 256 KiB and more per slice, and the code below
+    // would push the big tiles' register allocation into scratch memory.  The host plans accordingly.)
+    if (C::BM * C::BN <= kSplitMaxTile && p.ksplit > 1) {
         // Reduction split over workgroups.  Every slice leaves its partial sums in the workspace (one
         // 16-byte vector per lane and store: whole lines) and counts itself at the tile's counter; the
         // slice that finds every other one already counted adds all partial sums - its own included,
@@ -962,7 +964,7 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
                 for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
         // G slices of one 32x32 block are requested together (a load from memory takes longer than adding a
         // slice) and added in slice order; slices past the last one are switched off and add zeros
-        constexpr int G = 4;
+        constexpr int G = C::MI * C::NI >= 4 ? 2 : 4;      // (four at a time would push the 64x64 wave tiles' registers into scratch)
         for (int z0 = 0; z0 < p.ksplit; z0 += G) {
 #pragma unroll
             for (int blk = 0; blk < C::MI * C::NI; ++blk) {

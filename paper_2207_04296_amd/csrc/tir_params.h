@@ -116,6 +116,9 @@ __host__ __device__ inline unsigned fastdiv(unsigned m, unsigned magic, int shif
 // Adjacent output pixels one thread of the blocked depth-wise kernel owns.
 constexpr int kDwBlockPix = 4;      // measured 2, 4, 8: 8.5 / 7.2 / 6.9 us at stride 1 (16x56x56x128 fp16), 7.1 / 6.2 / 9.8 us at stride 2 (int8)
 
+// Largest workgroup tile (rows x columns) whose reduction may be split over workgroups.
+constexpr int kSplitMaxTile = 128 * 128;
+
 // Number of XCDs (L2 domains) workgroups are dealt to round-robin by the dispatcher.
 constexpr int kXcds = 8;
 // Tile rows walked together before moving to the next tile column (L2 reuse of the B tile).
