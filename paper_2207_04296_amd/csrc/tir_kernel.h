@@ -660,7 +660,7 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
 
     // Prepare the copy of `stage` (descriptors, predicates); the loads themselves are issued one
     // by one through copy_unit() so that they can be interleaved with MFMAs.
-    auto copy_begin = [&](int) {
+    auto copy_begin = [&](int) __attribute__((always_inline)) {
         lds_dst = ring + c_slot * C::STAGE_BYTES + wave * 1024;
         const int stage = c_stage;                                   // stage of the whole reduction
         c_slot = c_slot + 1 == NSTAGE ? 0 : c_slot + 1;
@@ -768,7 +768,7 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
         }
     };
     // u-th copy instruction of the prepared stage (u < L): A chunks first, then B chunks.
-    auto copy_unit = [&](int u) {
+    auto copy_unit = [&](int u) __attribute__((always_inline)) {
         if (u < C::A_IT) load_to_lds(ra, lds_dst + u * C::CT * 16, a_voff[u]);
         else load_to_lds(rb, lds_dst + C::A_BYTES + (u - C::A_IT) * C::CT * 16, b_off[u - C::A_IT]);
     };
@@ -783,20 +783,27 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
     if constexpr (SPEC) {
         if (copier) {
             if (nh > 0) {
+                // (stages past the last one are not copied: see the multiplying waves' loop below)
 #pragma unroll
                 for (int st = 0; st < NSTAGE - 1; ++st) {
-                    copy_begin(st);
+                    if (st < nh) {
+                        copy_begin(st);
 #pragma unroll
-                    for (int u = 0; u < L; ++u) copy_unit(u);
+                        for (int u = 0; u < L; ++u) copy_unit(u);
+                    }
                 }
-                copy_barrier<(NSTAGE - 2) * L>();
+                if (nh >= NSTAGE - 1) copy_barrier<(NSTAGE - 2) * L>();
+                else copy_barrier<0>();
                 for (int h = 0; h < nh; ++h) {
-                    copy_begin(h + NSTAGE - 1);
+                    if (h + NSTAGE - 1 < nh) {
+                        copy_begin(h + NSTAGE - 1);
 #pragma unroll
-                    for (int u = 0; u < L; ++u) copy_unit(u);
-                    copy_barrier<(NSTAGE - 2) * L>();
+                        for (int u = 0; u < L; ++u) copy_unit(u);
+                        copy_barrier<(NSTAGE - 2) * L>();
+                    } else {
+                        copy_barrier<0>();
+                    }
                 }
-                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // empty copies past the end: drain before the LDS is released
             }
             return;
         }
@@ -821,7 +828,7 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
     // One k-step: the MI*NI MFMAs on fragment set `set`, interleaved with `nside` units of side
     // work: first the fragment reads of (ra_s, rb_s, rk) into the other set, then copy units
     // [v0, v0 + nv).
-    auto kstep = [&](int set, const char* ra_s, const char* rb_s, int rk, int v0, int nv) {
+    auto kstep = [&](int set, const char* ra_s, const char* rb_s, int rk, int v0, int nv) __attribute__((always_inline)) {
         constexpr int NM = C::MI * C::NI;
         constexpr int NR = C::MI + C::NI;
         const int nside = NR + nv;
@@ -844,12 +851,15 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
         if constexpr (!SPEC) {
 #pragma unroll
             for (int st = 0; st < NSTAGE - 1; ++st) {
-                copy_begin(st);
+                if (st < nh) {
+                    copy_begin(st);
 #pragma unroll
-                for (int u = 0; u < L; ++u) copy_unit(u);
+                    for (int u = 0; u < L; ++u) copy_unit(u);
+                }
             }
         }
-        copy_barrier<(NSTAGE - 2) * L>();
+        if (nh >= NSTAGE - 1) copy_barrier<(NSTAGE - 2) * L>();
+        else copy_barrier<0>();
         frag.read_a(ring, 0, af[0]);
         frag.read_b(ring + C::A_BYTES, 0, bf[0]);
         TIR_FENCE();
@@ -857,26 +867,33 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
         constexpr int LM = SPEC ? 0 : L;                           // copy units the multiplying waves issue per stage
         constexpr int VPK = (LM + KSTEPS - 2) / (KSTEPS - 1);     // ... per k-step of part (1)
         int r_off = 0;                                             // byte offset of stage h's ring slot (h % NSTAGE, without the division)
-        for (int h = 0; h < nh; ++h) {
+        // One iteration of the loop described above; COPY: stage h+NSTAGE-1 exists and is copied meanwhile.  The last
+        // NSTAGE-1 iterations have nothing left to copy (a copy instruction costs its wave ~60 cycles even when its
+        // descriptor is empty, and short reductions are mostly tail): they wait for everything still in flight.
+        auto iteration = [&](int h, auto copy_flag) __attribute__((always_inline)) {
+            constexpr bool COPY = decltype(copy_flag)::value;
+            constexpr int LC = COPY ? LM : 0;
             const char* sa = ring + r_off;
             const char* sb = sa + C::A_BYTES;
             r_off = r_off + C::STAGE_BYTES == NSTAGE * C::STAGE_BYTES ? 0 : r_off + C::STAGE_BYTES;
             const char* na = ring + r_off;
-            if constexpr (!SPEC) copy_begin(h + NSTAGE - 1);
+            if constexpr (!SPEC && COPY) copy_begin(h + NSTAGE - 1);
             TIR_FENCE();
 #pragma unroll
             for (int kk = 0; kk < KSTEPS - 1; ++kk) {
                 const int v0 = kk * VPK;
-                const int nv = v0 + VPK <= LM ? VPK : (LM > v0 ? LM - v0 : 0);
+                const int nv = v0 + VPK <= LC ? VPK : (LC > v0 ? LC - v0 : 0);
                 kstep(kk & 1, sa, sb, kk + 1, v0, nv);
             }
             // this wave's copy of stage h+1 has landed; after the barrier everybody's has, and
             // every wave is done reading stage h-1's slot ... and stage h (its last fragments are in registers)
-            copy_barrier<(NSTAGE - 2) * L>();
+            copy_barrier<COPY ? (NSTAGE - 2) * L : 0>();
             kstep((KSTEPS - 1) & 1, na, na + C::A_BYTES, 0, 0, 0);
-        }
-        // the ring still has copies in flight (empty ones past the end): drain before the LDS is released
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        };
+        int h = 0;
+        for (; h + NSTAGE - 1 < nh; ++h) iteration(h, std::true_type());
+        for (; h < nh; ++h) iteration(h, std::false_type());
+        // (nothing is in flight any more: the last iterations waited for every copy)
     }
 
     if constexpr (C::KW > 1) {
