@@ -193,6 +193,7 @@ __global__ void __launch_bounds__(256) depthwise3x3_blocked_kernel(const Params 
 
     const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void*)p.A, 0, (int)((long long)p.batch_imgs * p.H * p.W * p.Cin * ES), 0x00020000);
     const __amdgpu_buffer_rsrc_t ry = __builtin_amdgcn_make_buffer_rsrc(p.C, 0, (int)((long long)p.M * p.Cin * (int)sizeof(out_t)), 0x00020000);
+    const int cstep = p.Cin * ES;                    // bytes from one input column to the next
     bool col_ok[NC];
 #pragma unroll
     for (int c = 0; c < NC; ++c) col_ok[c] = (unsigned)(iw0 + c) < (unsigned)p.W;
@@ -201,10 +202,11 @@ __global__ void __launch_bounds__(256) depthwise3x3_blocked_kernel(const Params 
     for (int r = 0; r < 3; ++r) {
         const int ih = ih0 + r * p.dil_h;
         const bool row_ok = (unsigned)ih < (unsigned)p.H;
-        const int row_off = (((img * p.H + ih) * p.W + iw0) * p.Cin + c0) * ES;     // only used where the tap is inside the image
+        int row_off = (((img * p.H + ih) * p.W + iw0) * p.Cin + c0) * ES;           // only used where the tap is inside the image
+        asm volatile("" : "+v"(row_off));      // (kept as one value: re-associated with the column, every load's address became a multiply)
 #pragma unroll
         for (int c = 0; c < NC; ++c)
-            v[r][c] = __builtin_amdgcn_raw_buffer_load_b128(rx, (row_ok && col_ok[c]) ? row_off + c * p.Cin * ES : (int)kOutOfRange, 0, 0);
+            v[r][c] = __builtin_amdgcn_raw_buffer_load_b128(rx, (row_ok && col_ok[c]) ? row_off + c * cstep : (int)kOutOfRange, 0, 0);
     }
     const int out_pix0 = (img * p.P + op) * p.Q + oq0;
 #pragma unroll
