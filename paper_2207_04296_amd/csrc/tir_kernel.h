@@ -443,6 +443,10 @@ __device__ __forceinline__ void store_tile_phase(const Params& p, long long bz, 
 //       h-1, which every wave finished reading before the previous barrier);
 //   (2) waits until this wave's copy of stage h+1 has landed and joins the workgroup barrier;
 //   (3) multiplies the last k-step of stage h while requesting the first fragments of stage h+1.
+// The last NSTAGE-1 iterations have no stage left to copy and skip that part of (1).
+// A wave issues one instruction per ~4 cycles whatever its kind, and at one or two waves per SIMD all of
+// them are exposed: slots and stages advance by counters (no h % NSTAGE), divisions by launch constants
+// are multiply-and-shift, and nothing is recomputed per stage that a counter can carry.
 // With one wave per SIMD nothing else hides latency, so MFMAs and side work (LDS reads, copy
 // issue) are interleaved one by one in program order and scheduling fences keep that order.
 // ---------------------------------------------------------------------------------------------
@@ -658,9 +662,10 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
     int c_slot = 0;          // ring slot and reduction stage of the next copy_begin (stages are prepared in order)
     int c_stage = s_begin + kgrp;
 
-    // Prepare the copy of `stage` (descriptors, predicates); the loads themselves are issued one
-    // by one through copy_unit() so that they can be interleaved with MFMAs.
-    auto copy_begin = [&](int) __attribute__((always_inline)) {
+    // Prepare the copy of the next stage (descriptors, predicates) - stages are prepared strictly in order, the
+    // counters above say which one is next; the loads themselves are issued one by one through copy_unit() so
+    // that they can be interleaved with MFMAs.
+    auto copy_begin = [&]() __attribute__((always_inline)) {
         lds_dst = ring + c_slot * C::STAGE_BYTES + wave * 1024;
         const int stage = c_stage;                                   // stage of the whole reduction
         c_slot = c_slot + 1 == NSTAGE ? 0 : c_slot + 1;
@@ -787,7 +792,7 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
 #pragma unroll
                 for (int st = 0; st < NSTAGE - 1; ++st) {
                     if (st < nh) {
-                        copy_begin(st);
+                        copy_begin();
 #pragma unroll
                         for (int u = 0; u < L; ++u) copy_unit(u);
                     }
@@ -796,7 +801,7 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
                 else copy_barrier<0>();
                 for (int h = 0; h < nh; ++h) {
                     if (h + NSTAGE - 1 < nh) {
-                        copy_begin(h + NSTAGE - 1);
+                        copy_begin();
 #pragma unroll
                         for (int u = 0; u < L; ++u) copy_unit(u);
                         copy_barrier<(NSTAGE - 2) * L>();
@@ -852,7 +857,7 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
 #pragma unroll
             for (int st = 0; st < NSTAGE - 1; ++st) {
                 if (st < nh) {
-                    copy_begin(st);
+                    copy_begin();
 #pragma unroll
                     for (int u = 0; u < L; ++u) copy_unit(u);
                 }
@@ -877,7 +882,7 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
             const char* sb = sa + C::A_BYTES;
             r_off = r_off + C::STAGE_BYTES == NSTAGE * C::STAGE_BYTES ? 0 : r_off + C::STAGE_BYTES;
             const char* na = ring + r_off;
-            if constexpr (!SPEC && COPY) copy_begin(h + NSTAGE - 1);
+            if constexpr (!SPEC && COPY) copy_begin();
             TIR_FENCE();
 #pragma unroll
             for (int kk = 0; kk < KSTEPS - 1; ++kk) {
