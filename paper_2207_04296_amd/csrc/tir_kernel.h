@@ -97,9 +97,11 @@ template <> struct OutTraits<DT_I8> {
 // For int8 output the int32 sum is scaled in binary32 and rounded to the nearest code, ties to even
 // (v_rndne_f32), then saturated.
 template <class E> __device__ __forceinline__ E consumer(E acc, E bias, int relu) {
-    E t = acc + bias;
-    if (relu) t = t < (E)0 ? (E)0 : t;
-    return t;
+    // ReLU as a clamp from below at a uniform floor (0, or the lowest value = no clamp): add, compare, select per value,
+    // with nothing uniform left inside the per-value code.  A NaN fails the comparison and stays a NaN.
+    const E floor = relu ? (E)0 : (std::is_same<E, float>::value ? (E)(-__builtin_inff()) : (E)(-2147483647 - 1));
+    const E t = acc + bias;
+    return t < floor ? floor : t;
 }
 template <int OUT, class E> __device__ __forceinline__ typename OutTraits<OUT>::type finish_value(E t, float scale) {
     if constexpr (OUT == DT_I8) {
