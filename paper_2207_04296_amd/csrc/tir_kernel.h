@@ -107,8 +107,7 @@ template <int OUT, class E> __device__ __forceinline__ typename OutTraits<OUT>::
     if constexpr (OUT == DT_I8) {
         float f = (float)t * scale;
         f = __builtin_rintf(f);
-        f = f < -128.0f ? -128.0f : f;
-        f = f > 127.0f ? 127.0f : f;
+        f = __builtin_amdgcn_fmed3f(f, -128.0f, 127.0f);       // saturate: the median of the value and the two limits, one instruction
         return (signed char)(int)f;
     } else {
         return OutTraits<OUT>::cvt(t);
