@@ -38,7 +38,9 @@ template <> struct PackP<DT_F16> {
 };
 template <> struct PackP<DT_BF16> {
     static __device__ __forceinline__ unsigned two(float a, float b) {
-        return (unsigned)OutTraits<DT_BF16>::cvt(a) | ((unsigned)OutTraits<DT_BF16>::cvt(b) << 16);
+        typedef __bf16 b2 __attribute__((ext_vector_type(2)));
+        b2 v = {(__bf16)a, (__bf16)b};          // one v_cvt_pk_bf16_f32
+        return __builtin_bit_cast(unsigned, v);
     }
 };
 

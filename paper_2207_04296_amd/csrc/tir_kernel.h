@@ -82,10 +82,7 @@ template <> struct OutTraits<DT_F16> {
 template <> struct OutTraits<DT_BF16> {
     typedef unsigned short type;
     static __device__ __forceinline__ unsigned short cvt(float v) {
-        unsigned int u = __float_as_uint(v);
-        if ((u & 0x7fffffffu) > 0x7f800000u) return (unsigned short)((u >> 16) | 0x40u);  // quiet NaN
-        u += 0x7fffu + ((u >> 16) & 1u);
-        return (unsigned short)(u >> 16);
+        return __builtin_bit_cast(unsigned short, (__bf16)v);      // gfx950 converts in hardware (v_cvt_pk_bf16_f32: nearest even, quiet NaN)
     }
 };
 
