@@ -870,6 +870,27 @@ def test_conv_input_just_below_the_32_bit_limit(B, oracle):
     assert B.tir_conv2d_variant(N, H + 1, W, C, K, 3, 3, 1, 1, 1, 1, 1, 1, 1, "f16", "f16").endswith("conv_generic")
 
 
+@pytest.mark.parametrize("case", [
+    # (dtype, out, n, h, w, c, k, r, s, stride, pad, dil)
+    ("f16", "f16", 1, 16383, 9, 8, 16, 3, 3, (1, 1), (4000, 1), (4000, 1)),        # tallest image, tap rows 4000 apart, narrow channels
+    ("f16", "f32", 1, 16383, 5, 64, 8, 3, 3, (2, 1), (4000, 2), (4000, 2)),        # ... one tap per stage, strided
+    ("f16", "f16", 1, 3, 16383, 8, 16, 3, 3, (1, 1), (1, 7000), (1, 3500)),        # widest image, 7000 columns of padding each side
+    ("i8", "i32", 1, 16383, 6, 16, 32, 2, 3, (1, 1), (3800, 0), (8191, 1)),        # the largest dilated span the planner accepts
+    ("i8", "i32", 2, 7000, 4, 16, 16, 3, 1, (1, 1), (8191, 0), (2, 1)),            # ... and the largest padding (output rows up to 31 569 - 8191)
+])
+def test_conv_coordinates_at_the_16_bit_limits(B, oracle, case):
+    """The copy stage keeps a pixel's coordinates packed in 16 bits each and tests tap offsets with packed unsigned
+    arithmetic: the largest extents, paddings and dilated spans the planner accepts put coordinates between -8191 and
+    ~32000 on both sides of every comparison."""
+    dtype, out, n, h, w, c, k, r, s_, stride, pad, dil = case
+    wl = I.Workload(f"conv_limits_{dtype}_{h}x{w}x{c}", "conv2d", dtype, out, "i" if dtype == "i8" else "n0.1", 9990 + h + w, n=n, h=h, w=w, c=c,
+                    k=k, r=r, s=s_, stride=stride, pad=pad, dil=dil, groups=1)
+    name = PT.variant_name(B, wl)
+    _say(f"{wl.name} -> {name}")
+    assert name.endswith("_conv"), name                 # the implicit-GEMM kernel, not the element-wise fallback
+    PT.check_workload(wl, oracle)
+
+
 def test_split_reduction_under_graph_capture(B, oracle):
     """A split reduction needs the library's workspace, which cannot be allocated while a stream is captured: a
     capture on a stream that has none yet runs the same variant unsplit; once an eager call has allocated it, the
