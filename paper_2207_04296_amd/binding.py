@@ -23,7 +23,7 @@ EXPORTS = ["tir_gemm", "tir_batch_matmul", "tir_conv2d", "tir_last_error", "tir_
            "tir_tune_load", "tir_gemm_fused", "tir_batch_matmul_fused", "tir_conv2d_fused", "tir_attention",
            "tir_conv1d", "tir_conv3d", "tir_conv2d_transpose", "tir_debug_force_ksplit", "tir_debug_fastdiv",
            "tir_conv2d_transpose_variant", "tir_conv3d_variant", "tir_tune_conv3d", "tir_tune_conv2d_transpose",
-           "tir_workspace_bytes", "tir_set_workspace"]
+           "tir_workspace_bytes", "tir_set_workspace", "tir_set_output_policy"]
 
 
 class Epilogue(ctypes.Structure):
@@ -119,6 +119,8 @@ def lib() -> ctypes.CDLL:
     L.tir_workspace_bytes.restype = ctypes.c_uint64
     L.tir_set_workspace.argtypes = [vp, vp, ctypes.c_uint64]
     L.tir_set_workspace.restype = ci
+    L.tir_set_output_policy.argtypes = [ci]
+    L.tir_set_output_policy.restype = ci
     L.tir_tune_count.restype = ci
     L.tir_tune_clear.restype = None
     L.tir_tune_save.argtypes = [ctypes.c_char_p]
@@ -225,6 +227,14 @@ def tir_debug_fastdiv(d: int, m: int) -> int:
 
 def tir_debug_force_ksplit(slices: int) -> None:
     lib().tir_debug_force_ksplit(int(slices))
+
+
+TIR_OUTPUT_CACHED, TIR_OUTPUT_STREAMING = 0, 1
+
+
+def tir_set_output_policy(policy: int) -> None:
+    """TIR_OUTPUT_CACHED (default) or TIR_OUTPUT_STREAMING: how later calls write their outputs (see tir.h)."""
+    _check(lib().tir_set_output_policy(int(policy)))
 
 
 def tir_workspace_bytes() -> int:

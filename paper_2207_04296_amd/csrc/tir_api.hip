@@ -170,12 +170,15 @@ static bool split_fits(const Variant* v, int ks, int64_t batch, int64_t tiles, i
 }
 
 // The kernels divide by these launch constants through multiply-and-shift (see Params).
+static int g_store_nt = 0;       // tir_set_output_policy: 1 = outputs are written with non-temporal stores
+
 static void set_divisors(Params& p) {
     auto put = [](unsigned d, unsigned* magic, int* shift) {
         const FastDiv f = make_fastdiv(d < 1 ? 1u : d);
         *magic = f.magic;
         *shift = f.shift;
     };
+    p.store_nt = g_store_nt;
     put((unsigned)(kGroupM * p.tiles_n), &p.div_gw_magic, &p.div_gw_shift);
     put((unsigned)p.tiles_n, &p.div_tn_magic, &p.div_tn_shift);
     put((unsigned)p.tiles_m, &p.div_tm_magic, &p.div_tm_shift);
@@ -804,6 +807,12 @@ void tir_debug_force_tile(int bm, int bn) {
     g_force_bn = bn;
 }
 
+tir_status tir_set_output_policy(tir_output_policy policy) {
+    if (policy != TIR_OUTPUT_CACHED && policy != TIR_OUTPUT_STREAMING) return fail(TIR_ERR_INVALID_ARG, "unknown output policy %d", (int)policy);
+    g_store_nt = policy == TIR_OUTPUT_STREAMING ? 1 : 0;
+    return TIR_OK;
+}
+
 uint64_t tir_workspace_bytes(void) { return (uint64_t)(kWsBytes + kWsTiles * 4); }
 
 tir_status tir_set_workspace(tir_stream stream_, void* ws, uint64_t bytes) {
@@ -991,6 +1000,7 @@ tir_status tir_attention(const void* Q, const void* K, const void* V, void* O, i
     p.Q = Q; p.K = K; p.V = V; p.O = O;
     p.M = (int)M; p.N = (int)N; p.batch = (int)batch; p.tiles_m = (int)tiles_m;
     p.scale_log2e = scale * 1.44269504088896340736f;
+    p.store_nt = g_store_nt;
     const FastDiv dtm = make_fastdiv((unsigned)tiles_m);
     p.div_tm_magic = dtm.magic; p.div_tm_shift = dtm.shift;
     hipError_t e = fn(p, (hipStream_t)stream);

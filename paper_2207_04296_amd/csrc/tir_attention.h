@@ -26,6 +26,7 @@ struct AttnParams {
     float scale_log2e;   // scale * log2(e): the softmax runs in base 2
     unsigned div_tm_magic;   // workgroup id / tiles_m as multiply-and-shift (make_fastdiv)
     int div_tm_shift;
+    int store_nt;            // the output is not read again soon: non-temporal stores (see TIR_STORE_AUX_STREAM)
 };
 
 template <int DT> struct PackP;
@@ -251,7 +252,8 @@ __global__ void __launch_bounds__(256) attention_kernel(const AttnParams p) {
             const int row = q / ORC, pc = q % ORC;
             typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
             const u32x4 v = *(const u32x4*)(s_o + row * ORB + ((pc * 16) ^ ((row & 7) << 4)));
-            __builtin_amdgcn_raw_buffer_store_b128(v, ro, row * ORB + pc * 16, 0, TIR_STORE_AUX);   // rows past M: outside the descriptor
+            if (p.store_nt) __builtin_amdgcn_raw_buffer_store_b128(v, ro, row * ORB + pc * 16, 0, TIR_STORE_AUX_STREAM);
+            else __builtin_amdgcn_raw_buffer_store_b128(v, ro, row * ORB + pc * 16, 0, TIR_STORE_AUX);   // rows past M: outside the descriptor
         }
     }
 }

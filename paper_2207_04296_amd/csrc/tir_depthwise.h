@@ -142,7 +142,8 @@ __global__ void __launch_bounds__(256) depthwise_kernel(const Params p) {
         const int obyte = (m * p.Cin + c0) * (int)sizeof(out_t);     // < 2^31: checked by the host
 #pragma unroll
         for (int b = 0; b < OB; b += 16)
-            __builtin_amdgcn_raw_buffer_store_b128(*(const u32x4*)((const char*)o + b), ry, obyte + b, 0, TIR_STORE_AUX);   // write-through, like every epilogue
+            if (p.store_nt) __builtin_amdgcn_raw_buffer_store_b128(*(const u32x4*)((const char*)o + b), ry, obyte + b, 0, TIR_STORE_AUX_STREAM);
+            else __builtin_amdgcn_raw_buffer_store_b128(*(const u32x4*)((const char*)o + b), ry, obyte + b, 0, TIR_STORE_AUX);   // write-through, like every epilogue
     }
 }
 
@@ -165,7 +166,7 @@ __global__ void __launch_bounds__(256) depthwise3x3_blocked_kernel(const Params 
 
     // every argument the kernel reads, fetched in one batch
     asm volatile("" ::"s"(p.A), "s"(p.B), "s"(p.C), "s"(p.M), "s"(p.bias), "s"(p.relu), "s"(p.scale), "s"(p.batch_imgs), "s"(p.H), "s"(p.W), "s"(p.Cin),
-                 "s"(p.P), "s"(p.Q), "s"(p.stride_h), "s"(p.pad_h), "s"(p.pad_w), "s"(p.dil_h));
+                 "s"(p.P), "s"(p.Q), "s"(p.stride_h), "s"(p.pad_h), "s"(p.pad_w), "s"(p.dil_h), "s"(p.store_nt));
     asm volatile("" ::"s"(p.div_dwq_magic), "s"(p.div_dwq_shift), "s"(p.div_dwpq_magic), "s"(p.div_dwpq_shift));
     const int tid = threadIdx.x;
     const int cv = tid % CV, pl = tid / CV;
@@ -227,7 +228,8 @@ __global__ void __launch_bounds__(256) depthwise3x3_blocked_kernel(const Params 
         const int obyte = oq0 + j < p.Q ? ((out_pix0 + j) * p.Cin + c0) * (int)sizeof(out_t) : (int)kOutOfRange;      // < 2^31: checked by the host
 #pragma unroll
         for (int b = 0; b < OB; b += 16)
-            __builtin_amdgcn_raw_buffer_store_b128(*(const u32x4*)((const char*)o + b), ry, obyte + b, 0, TIR_STORE_AUX);
+            if (p.store_nt) __builtin_amdgcn_raw_buffer_store_b128(*(const u32x4*)((const char*)o + b), ry, obyte + b, 0, TIR_STORE_AUX_STREAM);
+            else __builtin_amdgcn_raw_buffer_store_b128(*(const u32x4*)((const char*)o + b), ry, obyte + b, 0, TIR_STORE_AUX);
     }
 }
 

@@ -59,6 +59,8 @@ struct Params {
     unsigned* ws_count;  // [grid.y][tile] arrival counters, zero between launches (the last slice resets its tile's)
     int batch_imgs;   // convolutions: images in x (for the descriptor)
     int PW;           // patch kernel: columns of the LDS-resident input patch
+    int store_nt;     // the caller does not read the output again soon: non-temporal epilogue stores (see TIR_STORE_AUX_STREAM)
+    int reserved0;
     // ---- convolution geometry (A_CONV*): x is [n][H][W][Cin], one group reads Cg channels
     int H, W, Cin, Cg, P, Q, R, S;
     int stride_h, stride_w, pad_h, pad_w, dil_h, dil_w;
@@ -87,7 +89,7 @@ struct Params {
     unsigned div_dwq_magic, div_dwpq_magic;                // depth-wise, pixel blocks: / ceil(Q / kDwBlockPix), / (P * that)
     int div_dwq_shift, div_dwpq_shift;
 };
-static_assert(offsetof(Params, a_bs) == 64 && offsetof(Params, c_cs) == 128 && offsetof(Params, H) == 184, "the lines described above");
+static_assert(offsetof(Params, a_bs) == 64 && offsetof(Params, c_cs) == 128 && offsetof(Params, H) == 192, "the lines described above");
 
 // Exact unsigned division of m < 2^31 by a fixed d >= 1 without a branch or a special case: with s = ceil(log2 d)
 // and magic = floor(2^32 * (2^s - d) / d) + 1 < 2^32,  m / d = (mulhi(m, magic) + m) >> s  (the round-up method of

@@ -209,6 +209,12 @@ def test_reduction_split_is_planned_only_where_it_fits(tmp_path):
         B.tir_tune_clear()
 
 
+def test_output_policy_argument_is_checked():
+    assert B.lib().tir_set_output_policy(7) == B.TIR_ERR_INVALID_ARG
+    B.tir_set_output_policy(B.TIR_OUTPUT_STREAMING)
+    B.tir_set_output_policy(B.TIR_OUTPUT_CACHED)
+
+
 def test_caller_workspace_arguments_are_checked():
     """tir_set_workspace rejects a buffer that is too small or not 256-byte aligned before it touches the device."""
     need = B.tir_workspace_bytes()

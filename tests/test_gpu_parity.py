@@ -891,6 +891,46 @@ def test_conv_coordinates_at_the_16_bit_limits(B, oracle, case):
     PT.check_workload(wl, oracle)
 
 
+def test_streaming_output_policy_gives_the_same_results(B, oracle):
+    """TIR_OUTPUT_STREAMING only changes the cache policy bits of the epilogue's stores: every kind of epilogue (the
+    tile stores of the GEMM and convolution kernels, fused consumers, int8 codes, the patch kernel, the phase decode,
+    the split reduction, depth-wise, attention) gives bit-identical outputs under both policies, and the oracle's."""
+    import torch
+    names = ["c1_gemm128_f16", "c2a_conv56x64_f16", "c3b_bmm_pv_f16", "c5b_conv_g8d2_i8"]
+    wls = ([I.WORKLOADS[n] for n in names] + [I.FUSED_WORKLOADS[n] for n in ("c2a_conv56x64_f16_bias_relu", "c5b_conv_g8d2_i8_relu_requant")] +
+           [I.MORE_WORKLOADS["dep_conv112x32s2_i8_requant"]])
+    try:
+        for wl in wls:
+            a_bits, b_bits = wl.operands()
+            B.tir_set_output_policy(B.TIR_OUTPUT_CACHED)
+            cached = PT.run_gpu(wl, a_bits, b_bits)
+            B.tir_set_output_policy(B.TIR_OUTPUT_STREAMING)
+            _say(f"streaming stores: {wl.name}")
+            streamed = PT.run_gpu(wl, a_bits, b_bits)
+            assert np.array_equal(cached, streamed), wl.name
+            ref, S = PT.run_oracle(wl, a_bits, b_bits, oracle)
+            PT.assert_close(streamed, ref, S, wl.name + " (streaming stores)")
+        # transposed convolution by phase, conv3d as a split reduction, attention
+        B.tir_set_output_policy(B.TIR_OUTPUT_STREAMING)
+        N, H, W, C, K = 2, 9, 10, 64, 48
+        xb = I.make_tensor("f16", "n0.1", 9991, (N, H, W, C)); wb = I.make_tensor("f16", "n0.1", 9992, (K, 4, 4, C))
+        ref, S = oracle.conv2d_transpose("f16", xb, wb, (2, 2), (1, 1), (1, 1), (0, 0), 1)
+        y = _gpu_out(B, ref.shape, "f16")
+        _say("streaming stores: transposed convolution by phase")
+        B.tir_conv2d_transpose(B.to_device(xb, "f16"), B.to_device(wb, "f16"), y, N, H, W, C, K, 4, 4, (2, 2), (1, 1), (1, 1), (0, 0), 1, "f16", "f16")
+        torch.cuda.synchronize()
+        PT.assert_close(PT.gpu_to_f64(y), ref, S, "transposed convolution (streaming stores)")
+        xb = I.make_tensor("f16", "n0.1", 9993, (1, 6, 8, 8, 128)); wb = I.make_tensor("f16", "n0.1", 9994, (40, 3, 3, 3, 128))
+        ref, S = oracle.conv3d("f16", xb, wb, (1, 1, 1), (1, 1, 1), (1, 1, 1), 1)
+        y = _gpu_out(B, ref.shape, "f16")
+        _say("streaming stores: conv3d (split reduction)")
+        B.tir_conv3d(B.to_device(xb, "f16"), B.to_device(wb, "f16"), y, 1, 6, 8, 8, 128, 40, 3, 3, 3, (1, 1, 1), (1, 1, 1), (1, 1, 1), 1, "f16", "f16")
+        torch.cuda.synchronize()
+        PT.assert_close(PT.gpu_to_f64(y), ref, S, "conv3d (streaming stores)")
+    finally:
+        B.tir_set_output_policy(B.TIR_OUTPUT_CACHED)
+
+
 def test_split_reduction_under_graph_capture(B, oracle):
     """A split reduction needs the library's workspace, which cannot be allocated while a stream is captured: a
     capture on a stream that has none yet runs the same variant unsplit; once an eager call has allocated it, the
