@@ -35,7 +35,7 @@ CACHE_BYTES = 256e6 + 8 * 4e6     # memory-side cache + the eight L2s
 # HBM bytes per launch of the headline kernel from rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled
 # by the same counters on a copy kernel of known size; see profiles/.  None until measured.
 MEASURED_TRAFFIC_BYTES = {
-    "c2a_conv56x64_f16": 7164058 + 6422528,      # FETCH_SIZE 3499.3 KiB x 1.9993, WRITE_SIZE 6272 KiB x 1.0
+    "c2a_conv56x64_f16": 7192720 + 6422528,      # FETCH_SIZE 3513.3 KiB x 1.9993, WRITE_SIZE 6272 KiB x 1.0
     "c4a_gemm4096_f16": 201415700 + 67108864,    # FETCH_SIZE 98382 KiB x 1.9993, WRITE_SIZE 65536 KiB x 1.0
 }
 
