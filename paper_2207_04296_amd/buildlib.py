@@ -26,6 +26,9 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-u
          f"-I{INCLUDE}", f"-I{CSRC}"]
 
 
+ALLOW_SCRATCH = False      # instrumented experiment builds may set this; the product build never does
+
+
 def _compile(args):
     """Compile one unit.  The compiler reports every kernel's register and scratch use (-Rpass-analysis): a kernel
     that spills to scratch memory fails the build - a spill in a cold branch still makes every launch of the kernel
@@ -45,7 +48,7 @@ def _compile(args):
             n = int(l.split("ScratchSize [bytes/lane]:")[1].split("[")[0])
             if n > 0:
                 spilling.append(f"{name}: {n} bytes of scratch per lane")
-    if spilling:
+    if spilling and not ALLOW_SCRATCH:
         raise RuntimeError(f"{src.name} {' '.join(extra)}: kernels spill registers to scratch memory:\n  " + "\n  ".join(sorted(set(spilling))))
     # what is left to show: real warnings (the remarks and their source excerpts are dropped)
     keep, skip = [], 0
