@@ -931,6 +931,39 @@ def test_streaming_output_policy_gives_the_same_results(B, oracle):
         B.tir_set_output_policy(B.TIR_OUTPUT_CACHED)
 
 
+@pytest.mark.parametrize("policy", ["cached", "streaming"])
+def test_consumer_reads_what_the_producer_wrote(B, oracle, policy):
+    """Two convolutions back to back on one stream, the second reading the first one's output, with no host
+    synchronisation in between - under both output policies, and with the intermediate buffer's old contents pulled
+    into the caches beforehand (a reader that saw stale lines would fail).  The second output is checked against the
+    oracle applied to the intermediate tensor the GPU produced."""
+    import torch
+    n, h, w, c = 4, 28, 28, 64
+    xb = I.make_tensor("f16", "n0.1", 9995, (n, h, w, c)); w1 = I.make_tensor("f16", "n0.1", 9996, (c, 3, 3, c)); w2 = I.make_tensor("f16", "n0.1", 9997, (c, 3, 3, c))
+    old = I.make_tensor("f16", "n0.1", 9998, (n, h, w, c))
+    x, f1, f2 = B.to_device(xb, "f16"), B.to_device(w1, "f16"), B.to_device(w2, "f16")
+    mid = B.to_device(old, "f16")                       # the intermediate buffer starts out holding other data
+    y = _gpu_out(B, (n, h, w, c), "f16"); scratch = _gpu_out(B, (n, h, w, c), "f16")
+    conv = lambda a, f, o: B.tir_conv2d(a, f, o, n, h, w, c, c, 3, 3, 1, 1, 1, 1, 1, 1, 1, "f16", "f16")
+    try:
+        B.tir_set_output_policy(B.TIR_OUTPUT_STREAMING if policy == "streaming" else B.TIR_OUTPUT_CACHED)
+        for rep in range(3):
+            _say(f"chain, {policy} outputs, round {rep}")
+            conv(mid, f2, scratch)                      # reads the old contents of `mid`: they are in the caches now
+            conv(x, f1, mid)                            # producer
+            conv(mid, f2, y)                            # consumer, right behind it
+            torch.cuda.synchronize()
+            mid_bits = mid.cpu().view(torch.int16).numpy().view(np.uint16).copy()
+            ref, S = oracle.conv2d("f16", mid_bits, w2, (1, 1), (1, 1), (1, 1), 1)
+            PT.assert_close(PT.gpu_to_f64(y), ref, S, f"consumer of a {policy} output, round {rep}")
+            ref1, S1 = oracle.conv2d("f16", xb, w1, (1, 1), (1, 1), (1, 1), 1)
+            PT.assert_close(PT.gpu_to_f64(mid), ref1, S1, f"producer, {policy} output, round {rep}")
+            mid.copy_(B.to_device(old, "f16"))          # next round starts from the old contents again
+            torch.cuda.synchronize()
+    finally:
+        B.tir_set_output_policy(B.TIR_OUTPUT_CACHED)
+
+
 def test_split_reduction_under_graph_capture(B, oracle):
     """A split reduction needs the library's workspace, which cannot be allocated while a stream is captured: a
     capture on a stream that has none yet runs the same variant unsplit; once an eager call has allocated it, the
