@@ -417,33 +417,45 @@ __device__ __forceinline__ void store_tile_phase(const Params& p, long long bz, 
         const int col = wn * C::TN + j * 32 + l31;
         col_off[j] = col < cols ? (unsigned)(col * OS) : kOutOfRange;
     }
+    // FUSED: a consumer is fused (else the accumulators go out with a conversion at most); STREAM: non-temporal stores.
+    auto emit = [&](auto fused_flag, auto stream_flag) __attribute__((always_inline)) {
+        constexpr bool FUSED = decltype(fused_flag)::value;
+        constexpr int AUX = decltype(stream_flag)::value ? TIR_STORE_AUX_STREAM : TIR_STORE_AUX;
 #pragma unroll
-    for (int i = 0; i < C::MI; ++i) {
-        // The 32 rows of block i are decoded once, row l31 by lane l31 (both half-waves alike); accumulator register r
-        // holds row 8*(r/4) + r%4 (+ 4 in the upper half-wave), whose offset comes over from the lane that decoded it.
-        // Decoding per register instead cost 16 divisions per lane and block: 4 us of this epilogue were address arithmetic.
-        const unsigned m = (unsigned)(m0 + wm * C::TM + i * 32 + l31);
-        const unsigned img = fastdiv(m, p.div_pq_magic, p.div_pq_shift);
-        const unsigned rem = m - img * (unsigned)PQ;
-        const unsigned op = fastdiv(rem, p.div_q_magic, p.div_q_shift);
-        const unsigned oq = rem - op * (unsigned)p.Q;
-        const int oh = (int)op * p.phases_h + ph, ow = (int)oq * p.phases_w + pw;
-        const bool row_ok = (int)m < p.M && oh < p.P_full && ow < p.Q_full;
-        // (< 2^31: the host bounds the output's bytes; an invalid row stays out of range whatever column is added)
-        const unsigned pixv = row_ok ? ((img * (unsigned)p.P_full + (unsigned)oh) * (unsigned)p.Q_full + (unsigned)ow) * (unsigned)(p.c_rs * OS) : kOutOfRange;
+        for (int i = 0; i < C::MI; ++i) {
+            // The 32 rows of block i are decoded once, row l31 by lane l31 (both half-waves alike); accumulator register r
+            // holds row 8*(r/4) + r%4 (+ 4 in the upper half-wave), whose offset comes over from the lane that decoded it.
+            // Decoding per register instead cost 16 divisions per lane and block: 4 us of this epilogue were address arithmetic.
+            const unsigned m = (unsigned)(m0 + wm * C::TM + i * 32 + l31);
+            const unsigned img = fastdiv(m, p.div_pq_magic, p.div_pq_shift);
+            const unsigned rem = m - img * (unsigned)PQ;
+            const unsigned op = fastdiv(rem, p.div_q_magic, p.div_q_shift);
+            const unsigned oq = rem - op * (unsigned)p.Q;
+            const int oh = (int)op * p.phases_h + ph, ow = (int)oq * p.phases_w + pw;
+            const bool row_ok = (int)m < p.M && oh < p.P_full && ow < p.Q_full;
+            // (< 2^31: the host bounds the output's bytes; an invalid row stays out of range whatever column is added)
+            const unsigned pixv = row_ok ? ((img * (unsigned)p.P_full + (unsigned)oh) * (unsigned)p.Q_full + (unsigned)ow) * (unsigned)(p.c_rs * OS) : kOutOfRange;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int row = 8 * (r >> 2) + (r & 3);
-            const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)pixv, row), hi = (unsigned)__builtin_amdgcn_readlane((int)pixv, row + 4);
-            const unsigned pix = g ? hi : lo;
+            for (int r = 0; r < 16; ++r) {
+                const int row = 8 * (r >> 2) + (r & 3);
+                const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)pixv, row), hi = (unsigned)__builtin_amdgcn_readlane((int)pixv, row + 4);
+                const unsigned pix = g ? hi : lo;
 #pragma unroll
-            for (int j = 0; j < C::NI; ++j) {
-                const unsigned voff = col_off[j] != kOutOfRange ? pix + col_off[j] : kOutOfRange;
-                const auto val = finish_value<C::OUT>(consumer(acc[i][j][r], bias_r[j], p.relu), p.scale);
-                if (p.store_nt) store_value<TIR_STORE_AUX_STREAM>(val, rc, (int)voff, 0);
-                else store_value(val, rc, (int)voff, 0);
+                for (int j = 0; j < C::NI; ++j) {
+                    const unsigned voff = col_off[j] != kOutOfRange ? pix + col_off[j] : kOutOfRange;
+                    const auto t = FUSED ? consumer(acc[i][j][r], bias_r[j], p.relu) : acc[i][j][r];
+                    store_value<AUX>(finish_value<C::OUT>(t, p.scale), rc, (int)voff, 0);
+                }
             }
         }
+    };
+    const bool fused = p.bias != nullptr || p.relu != 0;      // uniform, like the cache policy
+    if (fused) {
+        if (p.store_nt) emit(std::true_type(), std::true_type());
+        else emit(std::true_type(), std::false_type());
+    } else {
+        if (p.store_nt) emit(std::false_type(), std::true_type());
+        else emit(std::false_type(), std::false_type());
     }
 }
 
