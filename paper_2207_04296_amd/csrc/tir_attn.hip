@@ -19,7 +19,7 @@ attn_launch_fn attention_launcher(int dt, int out, int dh) {
     return nullptr;
 }
 
-template <int DT, int OUT> static hipError_t launch_dw(const Params& p, hipStream_t stream) {
+template <int DT, int OUT, bool STREAM> static void launch_dw_as(const Params& p, hipStream_t stream) {
     constexpr int VEC = 16 / elem_size(DT);
     constexpr int PP = 256 / (kDwChannels / VEC);
     dim3 grid((unsigned)((p.M + kDwPixPerThread * PP - 1) / (kDwPixPerThread * PP)), (unsigned)((p.Cin + kDwChannels - 1) / kDwChannels));
@@ -27,10 +27,15 @@ template <int DT, int OUT> static hipError_t launch_dw(const Params& p, hipStrea
         // four adjacent pixels per thread
         const long long groups = (long long)p.batch_imgs * p.P * ((p.Q + kDwBlockPix - 1) / kDwBlockPix);
         grid.x = (unsigned)((groups + PP - 1) / PP);
-        if (p.stride_w == 1) hipLaunchKernelGGL((depthwise3x3_blocked_kernel<DT, OUT, 1>), grid, dim3(256), 0, stream, p);
-        else hipLaunchKernelGGL((depthwise3x3_blocked_kernel<DT, OUT, 2>), grid, dim3(256), 0, stream, p);
-    } else if (p.R == 3 && p.S == 3) hipLaunchKernelGGL((depthwise_kernel<DT, OUT, true>), grid, dim3(256), 0, stream, p);
-    else hipLaunchKernelGGL((depthwise_kernel<DT, OUT, false>), grid, dim3(256), 0, stream, p);
+        if (p.stride_w == 1) hipLaunchKernelGGL((depthwise3x3_blocked_kernel<DT, OUT, 1, STREAM>), grid, dim3(256), 0, stream, p);
+        else hipLaunchKernelGGL((depthwise3x3_blocked_kernel<DT, OUT, 2, STREAM>), grid, dim3(256), 0, stream, p);
+    } else if (p.R == 3 && p.S == 3) hipLaunchKernelGGL((depthwise_kernel<DT, OUT, true, STREAM>), grid, dim3(256), 0, stream, p);
+    else hipLaunchKernelGGL((depthwise_kernel<DT, OUT, false, STREAM>), grid, dim3(256), 0, stream, p);
+}
+
+template <int DT, int OUT> static hipError_t launch_dw(const Params& p, hipStream_t stream) {
+    if (p.store_nt) launch_dw_as<DT, OUT, true>(p, stream);
+    else launch_dw_as<DT, OUT, false>(p, stream);
     return hipGetLastError();
 }
 
