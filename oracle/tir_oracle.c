@@ -33,8 +33,15 @@
  * cases; closed forms C = K and C = K*i*j; the fused consumers against hand-worked values (ties,
  * saturation, signs) and against the same arithmetic carried out in numpy's float32 / int64; the
  * attention head against closed forms (uniform attention, one dominant key, a single key), key
- * permutation invariance, shift invariance of the softmax, and scipy's softmax between two matmuls.
- * No function in this file is "parity unpinned".
+ * permutation invariance, shift invariance of the softmax, and scipy's softmax between two matmuls;
+ * conv1d against numpy.correlate and the 2-D operator at height 1; conv3d against its reduction to
+ * conv2d, a sum over depth taps (float and int8), a per-element gather at full int8 range and torch's
+ * fp64 routine; the transposed convolution (written here as a scatter) against a per-element gather
+ * (float and int8), the adjoint identity with conv2d (float and int8) and torch's fp64 routine; the
+ * side output S of every operator against the same operator applied to |x|, |w|, bit for bit.
+ * Each multiply-add line below (float and int8 branch of every function) and each S line is covered:
+ * doubling a product or tripling an S term in any of them turns a pin red.  No function in this file
+ * is "parity unpinned".
  */
 #include <math.h>
 #include <stdint.h>

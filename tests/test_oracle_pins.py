@@ -611,3 +611,147 @@ def test_conv2d_transpose_matches_torch_fp64_library(oracle, case):
             if 0 <= oh < yd.shape[1] and 0 <= ow < yd.shape[2]:
                 assert np.array_equal(yd[0, oh, ow, g * Kg:(g + 1) * Kg], _dec16(wb)[g * Kg:(g + 1) * Kg, r, s, 1 % Cg])
     assert np.count_nonzero(yd) <= R * S_ * Kg
+
+
+# ------------------------------------------------------------------------------ int8 branches and S of the later convolution forms
+def _brute_conv3d(x, w, stride, pad, dil, groups):
+    """Per-output-element gather for the 3-D convolution (definition of sec. 5.1's C3D with the readings of
+    the 2-D operator), on decoded values; index lists are built per element, nothing is shared with the oracle's loops."""
+    N, D, H, W, C = x.shape
+    K, T, R, S_, Cg = w.shape
+    Kg = K // groups
+    ext = [(i + 2 * p - d * (f - 1) - 1) // s + 1 for i, f, s, p, d in zip((D, H, W), (T, R, S_), stride, pad, dil)]
+    y = np.zeros((N, *ext, K), dtype=x.dtype)
+    for n, o, p, q, k in itertools.product(range(N), range(ext[0]), range(ext[1]), range(ext[2]), range(K)):
+        g = k // Kg
+        terms = []
+        for t, r, s in itertools.product(range(T), range(R), range(S_)):
+            i_d, ih, iw = (o * stride[0] - pad[0] + t * dil[0], p * stride[1] - pad[1] + r * dil[1], q * stride[2] - pad[2] + s * dil[2])
+            if 0 <= i_d < D and 0 <= ih < H and 0 <= iw < W:
+                terms.append(np.dot(x[n, i_d, ih, iw, g * Cg:(g + 1) * Cg], w[k, t, r, s]))
+        y[n, o, p, q, k] = sum(terms)
+    return y
+
+
+def _brute_conv2d_transpose_gather(x, w, stride, pad, dil, outpad, groups):
+    """The transposed convolution read as a GATHER (the oracle writes the scatter): output pixel (oh, ow) collects
+    x[(oh + pad - r*dil) / stride] * w[r] for the taps where the division is exact and the quotient is an input pixel."""
+    N, H, W, C = x.shape
+    K, R, S_, Cg = w.shape
+    Kg = K // groups
+    P = (H - 1) * stride[0] - 2 * pad[0] + dil[0] * (R - 1) + outpad[0] + 1
+    Q = (W - 1) * stride[1] - 2 * pad[1] + dil[1] * (S_ - 1) + outpad[1] + 1
+    y = np.zeros((N, P, Q, K), dtype=x.dtype)
+    for n, oh, ow, k in itertools.product(range(N), range(P), range(Q), range(K)):
+        g = k // Kg
+        acc = 0
+        for r, s in itertools.product(range(R), range(S_)):
+            nh, nw = oh + pad[0] - r * dil[0], ow + pad[1] - s * dil[1]
+            if nh % stride[0] or nw % stride[1]:
+                continue
+            ih, iw = nh // stride[0], nw // stride[1]
+            if 0 <= ih < H and 0 <= iw < W:
+                acc = acc + np.dot(x[n, ih, iw, g * Cg:(g + 1) * Cg], w[k, r, s])
+        y[n, oh, ow, k] = acc
+    return y
+
+
+_C3D_CASES = [((1, 1, 1), (0, 0, 0), (1, 1, 1), 1), ((2, 1, 2), (1, 0, 1), (1, 2, 1), 2), ((1, 2, 1), (1, 1, 2), (2, 1, 1), 4)]
+_T2D_CASES = [((1, 1), (0, 0), (1, 1), (0, 0), 1), ((2, 2), (1, 1), (1, 1), (1, 0), 2), ((3, 2), (0, 2), (2, 1), (2, 1), 1), ((2, 3), (2, 0), (1, 2), (0, 2), 4)]
+
+
+@pytest.mark.parametrize("case", _C3D_CASES)
+def test_conv3d_int8_matches_brute_force_gather(oracle, case):
+    """The int8 branch of the 3-D convolution has its own multiply-add line: full-range int8 data (so that a doubled
+    or dropped product, a sign-extension slip or a narrow accumulator shows) against the per-element gather."""
+    stride, pad, dil, groups = case
+    rng = np.random.default_rng(101)
+    x = rng.integers(-127, 128, size=(2, 4, 5, 4, 4)).astype(np.int8)
+    w = rng.integers(-127, 128, size=(4, 2, 3, 2, 4 // groups)).astype(np.int8)
+    y, S = oracle.conv3d("i8", x, w, stride, pad, dil, groups)
+    assert S is None and y.dtype == np.int64
+    assert np.array_equal(y, _brute_conv3d(x.astype(np.int64), w.astype(np.int64), stride, pad, dil, groups))
+
+
+def test_conv3d_int8_is_a_sum_over_depth_taps_of_int8_conv2d(oracle):
+    rng = np.random.default_rng(102)
+    N, D, H, W, C, K, T, R, S_ = 1, 6, 5, 6, 8, 4, 3, 3, 2
+    sd, pd, dd = 1, 1, 2
+    x = rng.integers(-127, 128, size=(N, D, H, W, C)).astype(np.int8)
+    w = rng.integers(-127, 128, size=(K, T, R, S_, C // 2)).astype(np.int8)
+    y, _ = oracle.conv3d("i8", x, w, (sd, 2, 1), (pd, 1, 1), (dd, 1, 1), 2)
+    OD = oracle.conv_out_extent(D, T, sd, pd, dd)
+    assert y.shape[1] == OD
+    for o in range(OD):
+        acc = 0
+        for t in range(T):
+            i_d = o * sd - pd + t * dd
+            if 0 <= i_d < D:
+                acc = acc + oracle.conv2d("i8", np.ascontiguousarray(x[:, i_d]), np.ascontiguousarray(w[:, t]), (2, 1), (1, 1), (1, 1), 2)[0]
+        assert np.array_equal(y[:, o], acc)
+    # 127 * 127 * (taps * channels) must survive: the accumulator is wider than 16 and 32 bits of products
+    xm = np.full((1, 3, 3, 3, 64), 127, dtype=np.int8); wm = np.full((1, 3, 3, 3, 64), -127, dtype=np.int8)
+    ym, _ = oracle.conv3d("i8", xm, wm, (1, 1, 1), (0, 0, 0), (1, 1, 1), 1)
+    assert ym.shape == (1, 1, 1, 1, 1) and int(ym[0, 0, 0, 0, 0]) == -127 * 127 * 27 * 64
+
+
+@pytest.mark.parametrize("case", _T2D_CASES)
+@pytest.mark.parametrize("dtype", ["i8", "f16"])
+def test_conv2d_transpose_matches_brute_force_gather(oracle, case, dtype):
+    """Scatter (oracle) against gather (here), int8 at full range and binary16 small integers (both exact)."""
+    stride, pad, dil, outpad, groups = case
+    rng = np.random.default_rng(103)
+    N, H, W, C, K, R, S_ = 2, 4, 5, 4, 8, 3, 2
+    if dtype == "i8":
+        xb = rng.integers(-127, 128, size=(N, H, W, C)).astype(np.int8); wb = rng.integers(-127, 128, size=(K, R, S_, C // groups)).astype(np.int8)
+        xv, wv = xb.astype(np.int64), wb.astype(np.int64)
+    else:
+        xb = _smallint_bits(rng, (N, H, W, C)); wb = _smallint_bits(rng, (K, R, S_, C // groups))
+        xv, wv = _dec16(xb), _dec16(wb)
+    y, S = oracle.conv2d_transpose(dtype, xb, wb, stride, pad, dil, outpad, groups)
+    assert np.array_equal(y, _brute_conv2d_transpose_gather(xv, wv, stride, pad, dil, outpad, groups))
+    if dtype != "i8":
+        # S is the same operator applied to the absolute values: exactly, on this data
+        assert np.array_equal(S, _brute_conv2d_transpose_gather(np.abs(xv), np.abs(wv), stride, pad, dil, outpad, groups))
+
+
+def test_conv2d_transpose_int8_is_the_adjoint_of_int8_conv2d(oracle):
+    """<conv2d(x, w), y> == <x, conv2d_transpose(y, w^T)> in exact integer arithmetic at full int8 range."""
+    rng = np.random.default_rng(104)
+    for (stride, pad, dil, groups, H, W) in [((1, 1), (0, 0), (1, 1), 1, 5, 6), ((2, 2), (1, 1), (1, 1), 2, 8, 7), ((3, 2), (1, 0), (1, 2), 1, 9, 8)]:
+        N, C, K, R, S_ = 2, 4, 6, 3, 2
+        Cg, Kg = C // groups, K // groups
+        xb = rng.integers(-127, 128, size=(N, H, W, C)).astype(np.int8); wb = rng.integers(-127, 128, size=(K, R, S_, Cg)).astype(np.int8)
+        fwd, _ = oracle.conv2d("i8", xb, wb, stride, pad, dil, groups)
+        P, Q = fwd.shape[1:3]
+        yb = rng.integers(-127, 128, size=(N, P, Q, K)).astype(np.int8)
+        wT = np.ascontiguousarray(wb.reshape(groups, Kg, R, S_, Cg).transpose(0, 4, 2, 3, 1)).reshape(C, R, S_, Kg)
+        outpad = ((H + 2 * pad[0] - dil[0] * (R - 1) - 1) % stride[0], (W + 2 * pad[1] - dil[1] * (S_ - 1) - 1) % stride[1])
+        back, _ = oracle.conv2d_transpose("i8", yb, wT, stride, pad, dil, outpad, groups)
+        assert back.shape == (N, H, W, C)
+        assert int(np.sum(fwd * yb.astype(np.int64))) == int(np.sum(xb.astype(np.int64) * back))
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_S_of_every_convolution_form_is_the_operator_on_absolute_values(oracle, dtype):
+    """The tolerance of every floating parity test is expressed in S = sum |x*w| over the operator's terms.  |x*w| =
+    |x|*|w|, so S(x, w) must equal y(|x|, |w|), term by term in the same order: bit-identical."""
+    def absbits(b):
+        return (b & np.uint16(0x7fff)).astype(np.uint16)      # clearing the sign bit of binary16 / bfloat16 is |.|
+    x2 = I.make_tensor(dtype, "u", 501, (2, 6, 7, 4)); w2 = I.make_tensor(dtype, "u", 502, (6, 3, 2, 2))
+    y, S = oracle.conv2d(dtype, x2, w2, (2, 1), (1, 1), (1, 2), 2)
+    assert np.array_equal(S, oracle.conv2d(dtype, absbits(x2), absbits(w2), (2, 1), (1, 1), (1, 2), 2)[0]) and np.any(S != np.abs(y))
+    x1 = I.make_tensor(dtype, "u", 503, (2, 19, 4)); w1 = I.make_tensor(dtype, "u", 504, (6, 3, 2))
+    y, S = oracle.conv1d(dtype, x1, w1, 2, 1, 2, 2)
+    assert np.array_equal(S, oracle.conv1d(dtype, absbits(x1), absbits(w1), 2, 1, 2, 2)[0]) and np.any(S != np.abs(y))
+    x3 = I.make_tensor(dtype, "u", 505, (1, 4, 5, 6, 4)); w3 = I.make_tensor(dtype, "u", 506, (4, 2, 3, 2, 2))
+    y, S = oracle.conv3d(dtype, x3, w3, (1, 2, 1), (1, 1, 0), (2, 1, 1), 2)
+    assert np.array_equal(S, oracle.conv3d(dtype, absbits(x3), absbits(w3), (1, 2, 1), (1, 1, 0), (2, 1, 1), 2)[0]) and np.any(S != np.abs(y))
+    for (stride, pad, dil, outpad, groups) in _T2D_CASES:
+        xt = I.make_tensor(dtype, "u", 507, (2, 4, 5, 4)); wt = I.make_tensor(dtype, "u", 508, (8, 3, 2, 4 // groups))
+        y, S = oracle.conv2d_transpose(dtype, xt, wt, stride, pad, dil, outpad, groups)
+        assert np.array_equal(S, oracle.conv2d_transpose(dtype, absbits(xt), absbits(wt), stride, pad, dil, outpad, groups)[0])
+        assert np.any(S != np.abs(y))
+    A = I.make_tensor(dtype, "u", 509, (7, 9)); Bm = I.make_tensor(dtype, "u", 510, (9, 5))
+    C_, S = oracle.gemm(dtype, A, Bm, 7, 5, 9, 9, 1, 5, 1)
+    assert np.array_equal(S, oracle.gemm(dtype, absbits(A), absbits(Bm), 7, 5, 9, 9, 1, 5, 1)[0])
