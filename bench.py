@@ -70,20 +70,20 @@ def make_sets(B, wl, count):
     return sets
 
 
-def timed_run(torch, B, wl, sets, steps, warmup, eager):
+def timed_run(torch, B, wl, sets, steps, warmup, eager, streaming=False):
     """Returns (wall seconds for `steps` launches, HIP-event seconds for the same region)."""
     stream = torch.cuda.Stream()
     n = len(sets)
     with torch.cuda.stream(stream):
         for i in range(warmup):
-            B.run_workload(wl, *sets[i % n], stream=stream)
+            B.run_workload(wl, *sets[i % n], stream=stream, streaming=streaming)
         torch.cuda.synchronize()
         graph = None
         if not eager:
             graph = torch.cuda.CUDAGraph()
             with torch.cuda.graph(graph, stream=stream):
                 for i in range(steps):
-                    B.run_workload(wl, *sets[i % n], stream=stream)
+                    B.run_workload(wl, *sets[i % n], stream=stream, streaming=streaming)
             graph.replay()            # untimed: first replay uploads the graph
             torch.cuda.synchronize()
         e0 = torch.cuda.Event(enable_timing=True)
@@ -95,7 +95,7 @@ def timed_run(torch, B, wl, sets, steps, warmup, eager):
             graph.replay()
         else:
             for i in range(steps):
-                B.run_workload(wl, *sets[i % n], stream=stream)
+                B.run_workload(wl, *sets[i % n], stream=stream, streaming=streaming)
         e1.record(stream)
         torch.cuda.synchronize()
         t1 = time.perf_counter()
@@ -285,12 +285,7 @@ def main():
     # the hot run and the operator table use the library's default (outputs stay cached for a consumer).
     streaming = not args.hot
     cold_cached_value = None
-    try:
-        if streaming:
-            B.tir_set_output_policy(B.TIR_OUTPUT_STREAMING)
-        wall, ev = timed_run(torch, B, wl, sets, args.steps, args.warmup, args.eager)
-    finally:
-        B.tir_set_output_policy(B.TIR_OUTPUT_CACHED)
+    wall, ev = timed_run(torch, B, wl, sets, args.steps, args.warmup, args.eager, streaming=streaming)
     if streaming and not args.profile_run:
         w3, _ = timed_run(torch, B, wl, sets, args.steps, args.warmup, args.eager)
         cold_cached_value = wl.flops() * args.steps / w3 / 1e12

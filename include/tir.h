@@ -12,16 +12,16 @@
  *                       mapped onto Eq. 1 by ReIndex + fuse: x = fuse(n,h,w), y = co, k = fuse(rh,rw,rc))
  *
  * Common conventions
- *   - Every pointer is a DEVICE pointer owned by the caller.  The library never copies to the host or
- *     synchronises; each call enqueues kernels on `stream` and returns.  It allocates in one case only: a
- *     reduction that is split over several workgroups per output tile (few small tiles facing a long K; the
- *     variant queries report it as "<variant>/z<slices>") keeps partial sums and arrival counters in a
- *     workspace of 32 MiB + 64 KiB per (device, stream), allocated with hipMalloc on the first such launch
- *     (which also synchronises the device once) and kept until the process ends.  Launches on one stream
- *     share it in stream order; a stream under capture that has no workspace yet runs the same kernel
- *     without the split.  The result does not depend on the split's timing: the partial sums are added in a
- *     fixed order.  A caller that wants no allocation inside the library hands it a buffer of its own
- *     first (tir_set_workspace); then the library allocates nothing on that stream, captured or not.
+ *   - Every pointer is a DEVICE pointer owned by the caller.  The operator entry points never allocate or free
+ *     device memory, never copy to the host and never synchronise: each call enqueues kernels on `stream` and
+ *     returns, also while `stream` (or any other stream) is being captured.  The only calls that block or create
+ *     HIP objects are the tuning calls (tir_tune_*), which say so.
+ *   - One kernel path needs scratch memory: a reduction that is split over several workgroups per output tile
+ *     (few small tiles facing a long K; the variant queries report it as "<variant>/z<slices>") keeps partial sums
+ *     and arrival counters in a workspace.  The library owns none: it plans such a split only for launches on a
+ *     stream for which the caller has registered a buffer (tir_set_workspace), and plans the same problem
+ *     unsplit otherwise.  The result does not depend on the split's timing: the partial sums are added in a
+ *     fixed order.
  *   - The output is fully overwritten (reduction init is 0; there is no alpha / beta), and must not
  *     overlap an input.
  *   - Inputs F16 / BF16 accumulate in fp32; input I8 accumulates in int32 (wrap-around on overflow,
@@ -104,11 +104,19 @@ tir_status tir_conv2d(const void* x, const void* w, void* y, int64_t N, int64_t 
  *                              product and the rounding in binary32, ties to even; scale must be
  *                              finite and > 0.  The int32 sum t must not overflow.
  * (I8, I8) is an allowed (in, out) pair for the fused entry points only; scale is ignored otherwise.
+ *
+ * streaming: cache policy of this call's output stores (0 or 1; anything else is TIR_ERR_INVALID_ARG).  Every
+ * kernel writes its output through to memory during its epilogue.  With 0 (and for the entry points that take no
+ * epilogue) the lines also stay in the caches, which is what a consumer launched next wants: in a chain of
+ * 56x56x64 convolutions that each read the previous one's output a launch takes 7.5 us this way and 8.1 us with
+ * streaming stores.  1 marks the stores non-temporal: for outputs that nothing reads soon - the last operator of a
+ * graph, results copied out later, tensors larger than the caches.  Results are identical either way.
  */
 typedef struct tir_epilogue {
     const void* bias;
     int relu;
     float scale;
+    int streaming;
 } tir_epilogue;
 
 tir_status tir_gemm_fused(const void* A, const void* B, void* C, int64_t M, int64_t N, int64_t K, int64_t a_rs,
@@ -169,6 +177,11 @@ tir_status tir_conv2d_transpose(const void* x, const void* w, void* y, int64_t N
  * same type or F32.  Scores and the softmax are fp32; the probabilities are rounded to the input type
  * before the second product, which accumulates in fp32.  N = 0 is an error (no keys), M = 0 or
  * batch = 0 a no-op.  scale must be finite.
+ * Accuracy a caller gets, with T[b,i,e] = sum_j P[b,i,j] * |V[b,j,e]| of the exact probabilities:
+ *   F16 inputs:  |O - exact| <= 2e-3 * T + 1e-5  (the bound of the plain operators; the rounding of P to binary16
+ *                costs at most 2^-11 * T of it);
+ *   BF16 inputs: |O - exact| <= 6e-3 * T + 1e-5  (P is rounded to bfloat16, 8 significant bits: that step alone
+ *                is up to 2^-9 * T = 2e-3 * T), plus 2^-8 * |O| when the output is BF16 as well.
  */
 tir_status tir_attention(const void* Q, const void* K, const void* V, void* O, int64_t batch, int64_t M, int64_t N,
                          int64_t d, float scale, tir_dtype in, tir_dtype out, tir_stream stream);
@@ -178,38 +191,26 @@ tir_status tir_attention(const void* Q, const void* K, const void* V, void* O, i
 const char* tir_last_error(void);
 
 /*
- * Caller-provided workspace for split reductions (for callers that must not let the library allocate:
- * code under stream capture, serving loops with a fixed memory plan).
+ * Workspace for split reductions (see the conventions at the top): without one, no reduction is split over
+ * workgroups.
  * tir_workspace_bytes: size the buffer must have (partial sums, then the arrival counters).
- * tir_set_workspace: from now on, launches on `stream` of the CURRENT device keep their partial sums in
- * `ws` (device memory, 256-byte aligned, at least tir_workspace_bytes() bytes, owned by the caller).  The
- * call enqueues one small kernel on `stream` that zeroes the counters (a kernel, not a memset, so the
- * call may be captured) and returns; every launch leaves them zero again.  The buffer must stay
- * allocated until the work enqueued on `stream` has finished and a later tir_set_workspace has replaced
- * it; ws = NULL goes back to the library's own block (allocated on demand as described at the top).  Two
- * streams that may run at the same time need two buffers: launches that share one race.  Tuning calls
- * use the workspace of the stream they are given.
+ * tir_set_workspace: from now on, launches on `stream` of the CURRENT device may split their reductions and keep
+ * the partial sums in `ws` (device memory, 256-byte aligned, at least tir_workspace_bytes() bytes, owned by the
+ * caller).  The call enqueues one small kernel on `stream` that zeroes the counters (a kernel, not a memset, so
+ * the call may be captured) and returns; every launch leaves them zero again.  The buffer must stay allocated
+ * until the work enqueued on `stream` has finished and a later tir_set_workspace has replaced or removed it;
+ * ws = NULL removes the registration (later launches on `stream` run unsplit).  Two streams that may run at the
+ * same time need two buffers: launches that share one race.  Tuning calls use the workspace of the stream they
+ * are given and try split reductions only if it has one.
  * Errors: TIR_ERR_INVALID_ARG (buffer too small), TIR_ERR_ALIGNMENT, TIR_ERR_LAUNCH; the previous
- * workspace stays in place then.
+ * registration stays in place then.
  */
 uint64_t tir_workspace_bytes(void);
 tir_status tir_set_workspace(tir_stream stream, void* ws, uint64_t bytes);
 
 /*
- * Where the outputs of later calls go (process-wide, read when a call is planned; not thread-safe).
- * Every kernel writes its output through to memory during its epilogue.  TIR_OUTPUT_CACHED (the default) also keeps
- * the lines in the caches, which is what a consumer launched next wants: in a chain of 56x56x64 convolutions that each
- * read the previous one's output a launch takes 7.5 us this way and 8.1 us with streaming stores.
- * TIR_OUTPUT_STREAMING marks the stores non-temporal: for outputs that nothing reads soon - the last operator of a
- * graph, results copied out later, tensors larger than the caches.  The same convolution with inputs from HBM and
- * an output that is not read again takes 7.4 us instead of 9.0.  Results are identical either way.
- */
-typedef enum { TIR_OUTPUT_CACHED = 0, TIR_OUTPUT_STREAMING = 1 } tir_output_policy;
-tir_status tir_set_output_policy(tir_output_policy policy);
-
-/*
  * Name of the kernel variant the next identical call would launch (for profiling harnesses), e.g.
- * "f16_f32_t256x256w2x4s2_ak_bn".  Arguments as for tir_batch_matmul / tir_conv2d without pointers
+ * "f16_f32_t256x256w2x4s2_ak_bn"; a "/z<slices>" suffix is the plan for a stream with a registered workspace.  Arguments as for tir_batch_matmul / tir_conv2d without pointers
  * being dereferenced; returns "" on invalid arguments.  The string is static.  out = TIR_I8 asks for the
  * requantising variant of the fused entry points.
  */
@@ -235,8 +236,8 @@ const char* tir_conv2d_transpose_variant(int64_t N, int64_t H, int64_t W, int64_
  *
  * tir_tune_batch_matmul / tir_tune_conv2d take the arguments of tir_batch_matmul_fused / tir_conv2d_fused
  * (batch = 1 with zero batch strides tunes tir_gemm; ep may be NULL), launch every compiled variant that computes this problem
- * - and, where few tiles face a long reduction, the same variant with the reduction split over 2, 3, 4, 6 or 8
- * workgroups per tile - `reps` times on `stream`, and record the fastest under the problem's signature (dtypes, copy
+ * - and, where few tiles face a long reduction and `stream` has a registered workspace, the same variant with the
+ * reduction split over 2, 3, 4, 6 or 8 workgroups per tile - `reps` times on `stream`, and record the fastest under the problem's signature (dtypes, copy
  * modes implied by strides and alignment, extents, convolution geometry).  Later calls of the
  * operator entry points with the same signature use the recorded variant instead of the built-in
  * scoring rule.  Unlike every other call these BLOCK until the trial launches have finished, create
@@ -287,7 +288,7 @@ void tir_debug_force_tile(int bm, int bn);
  * ("" or NULL restores the automatic choice); tir_debug_variant_name enumerates the names. */
 void tir_debug_force_variant(const char* name_part);
 /* Make later calls split every tile's reduction over `slices` workgroups where the chosen variant, the
- * reduction's length and the workspace allow it (0 or 1 restores the automatic choice, measured records
+ * reduction's length and the stream's registered workspace allow it (0 or 1 restores the automatic choice, measured records
  * are ignored meanwhile).  The variant queries report a split as "<variant>/z<slices>". */
 void tir_debug_force_ksplit(int slices);
 int tir_debug_variant_count(void);

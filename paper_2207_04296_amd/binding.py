@@ -23,19 +23,19 @@ EXPORTS = ["tir_gemm", "tir_batch_matmul", "tir_conv2d", "tir_last_error", "tir_
            "tir_tune_load", "tir_gemm_fused", "tir_batch_matmul_fused", "tir_conv2d_fused", "tir_attention",
            "tir_conv1d", "tir_conv3d", "tir_conv2d_transpose", "tir_debug_force_ksplit", "tir_debug_fastdiv",
            "tir_conv2d_transpose_variant", "tir_conv3d_variant", "tir_tune_conv3d", "tir_tune_conv2d_transpose",
-           "tir_workspace_bytes", "tir_set_workspace", "tir_set_output_policy"]
+           "tir_workspace_bytes", "tir_set_workspace"]
 
 
 class Epilogue(ctypes.Structure):
-    """struct tir_epilogue: bias pointer, relu flag, requantisation scale."""
-    _fields_ = [("bias", ctypes.c_void_p), ("relu", ctypes.c_int), ("scale", ctypes.c_float)]
+    """struct tir_epilogue: bias pointer, relu flag, requantisation scale, cache policy of the output stores."""
+    _fields_ = [("bias", ctypes.c_void_p), ("relu", ctypes.c_int), ("scale", ctypes.c_float), ("streaming", ctypes.c_int)]
 
 
-def make_epilogue(bias=None, relu=False, scale=0.0):
-    """ctypes tir_epilogue, or None when nothing is fused (the plain operator)."""
-    if bias is None and not relu and not scale:
+def make_epilogue(bias=None, relu=False, scale=0.0, streaming=False):
+    """ctypes tir_epilogue, or None when nothing is fused and the output policy is the default (the plain operator)."""
+    if bias is None and not relu and not scale and not streaming:
         return None
-    return Epilogue(_ptr(bias) or None, int(bool(relu)), float(scale))
+    return Epilogue(_ptr(bias) or None, int(bool(relu)), float(scale), int(streaming))
 
 
 class TirError(RuntimeError):
@@ -119,8 +119,6 @@ def lib() -> ctypes.CDLL:
     L.tir_workspace_bytes.restype = ctypes.c_uint64
     L.tir_set_workspace.argtypes = [vp, vp, ctypes.c_uint64]
     L.tir_set_workspace.restype = ci
-    L.tir_set_output_policy.argtypes = [ci]
-    L.tir_set_output_policy.restype = ci
     L.tir_tune_count.restype = ci
     L.tir_tune_clear.restype = None
     L.tir_tune_save.argtypes = [ctypes.c_char_p]
@@ -229,14 +227,6 @@ def tir_debug_force_ksplit(slices: int) -> None:
     lib().tir_debug_force_ksplit(int(slices))
 
 
-TIR_OUTPUT_CACHED, TIR_OUTPUT_STREAMING = 0, 1
-
-
-def tir_set_output_policy(policy: int) -> None:
-    """TIR_OUTPUT_CACHED (default) or TIR_OUTPUT_STREAMING: how later calls write their outputs (see tir.h)."""
-    _check(lib().tir_set_output_policy(int(policy)))
-
-
 def tir_workspace_bytes() -> int:
     return int(lib().tir_workspace_bytes())
 
@@ -248,7 +238,7 @@ def tir_set_workspace_status(ws, nbytes: int, stream=0) -> int:
 
 def tir_set_workspace(ws, stream=None) -> None:
     """Hand the library a caller-owned uint8 device tensor for the split reductions launched on `stream`
-    (None as `ws`: back to the library's own block).  The caller keeps the tensor alive."""
+    (None as `ws`: remove the registration, launches run unsplit).  The caller keeps the tensor alive."""
     nbytes = 0 if ws is None else ws.numel() * ws.element_size()
     _check(lib().tir_set_workspace(_stream(stream) or None, _ptr(ws) or None, nbytes))
 
@@ -411,15 +401,15 @@ def bias_to_device(wl, device="cuda:0"):
     return None if b is None else torch.from_numpy(b).to(device)
 
 
-def _wl_epilogue(wl, bias_dev):
+def _wl_epilogue(wl, bias_dev, streaming=False):
     if wl.ep_bias and bias_dev is None:
         raise ValueError(f"{wl.name} has a fused bias: pass its device tensor (bias_to_device)")
-    return make_epilogue(bias_dev if wl.ep_bias else None, wl.ep_relu, wl.ep_scale)
+    return make_epilogue(bias_dev if wl.ep_bias else None, wl.ep_relu, wl.ep_scale, streaming)
 
 
-def run_workload(wl, a_dev, b_dev, c_dev, bias_dev=None, stream=None) -> None:
-    """Launch one paper_2207_04296_amd.inputs.Workload on resident operands."""
-    ep = _wl_epilogue(wl, bias_dev)
+def run_workload(wl, a_dev, b_dev, c_dev, bias_dev=None, stream=None, streaming=False) -> None:
+    """Launch one paper_2207_04296_amd.inputs.Workload on resident operands (streaming: non-temporal output stores)."""
+    ep = _wl_epilogue(wl, bias_dev, streaming)
     if wl.kind == "conv2d":
         tir_conv2d_fused(a_dev, b_dev, c_dev, wl.n, wl.h, wl.w, wl.c, wl.k, wl.r, wl.s, wl.stride[0], wl.stride[1],
                          wl.pad[0], wl.pad[1], wl.dil[0], wl.dil[1], wl.groups, wl.dtype, wl.out, ep, stream)

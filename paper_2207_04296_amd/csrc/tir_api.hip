@@ -136,19 +136,28 @@ static Choice tuned_lookup(const TuneKey& k) {
 }
 
 // ------------------------------------------------------------------------------- split reduction
-// Workspace of the reduction split over workgroups: the slices' partial sums and one arrival counter
-// per output tile.  One fixed-size block per (device, stream), allocated at the first launch that
-// needs it and kept until the process ends: launches on one stream follow each other, so they can
-// share it; launches on different streams may overlap and get their own.
-static const int64_t kWsBytes = 32ll << 20;      // partial sums
-static const int64_t kWsTiles = 16384;           // counters
+// Scratch of the reduction split over workgroups: the slices' partial sums and one arrival counter per output
+// tile.  The library owns no such memory: a caller registers a buffer per (device, stream) with tir_set_workspace
+// (launches on one stream follow each other, so they can share it; launches on different streams may overlap and
+// need their own), or calls tir_gemm_split_static, whose scratch is a static device array.
+static const int64_t kWsBytes = 32ll << 20;      // partial sums of a registered workspace
+static const int64_t kWsTiles = 16384;           // ... and its counters
 struct Workspace {
     void* partial;
     unsigned* count;
-    void* owned;         // the library's own allocation for this key, if any (kept while a caller's buffer stands in)
 };
 static std::mutex g_ws_mu;
 static std::map<std::pair<int, hipStream_t>, Workspace> g_ws;
+
+// What a plan may use for split reductions: room for partial sums and counters (bytes = 0: none, never split),
+// and the slice count a caller insists on (force > 1: only variants that can split that way are considered,
+// measured records and the scoring rule's own idea of a split are ignored).
+struct SplitLimits {
+    int64_t bytes, tiles;
+    int force;
+};
+static const SplitLimits kNoSplit = {0, 0, 0};
+static const SplitLimits kRegisteredSplit = {kWsBytes, kWsTiles, 0};      // a registered workspace (also what the variant queries assume)
 
 // Arrival counters start at zero; every launch leaves them at zero again (the last workgroup of a tile resets its counter).
 __global__ void __launch_bounds__(256) clear_counters_kernel(unsigned* count, int n) {
@@ -157,28 +166,36 @@ __global__ void __launch_bounds__(256) clear_counters_kernel(unsigned* count, in
 }
 
 // Can variant v reduce a problem of `tiles` output tiles per batch entry in ks slices?
-static bool split_fits(const Variant* v, int ks, int64_t batch, int64_t tiles, int64_t K) {
+static bool split_fits(const Variant* v, int ks, int64_t batch, int64_t tiles, int64_t K, const SplitLimits& sl) {
     if (ks == 1) return true;
-    if (ks < 1 || ks > 64) return false;
+    if (ks < 1 || ks > 64 || sl.bytes <= 0) return false;
     if (v->amode != A_KMAJOR && v->amode != A_CONV && v->amode != A_CONVX) return false;      // the fast kernel only
     if (v->bm * v->bn > kSplitMaxTile) return false;
     const int64_t stages = (K * elem_size(v->dt) + v->rowb - 1) / v->rowb;
     const int64_t per = (stages + ks - 1) / ks;
     if ((ks - 1) * per >= stages) return false;       // a slice would be empty
-    if (batch > 65535 || batch * tiles > kWsTiles) return false;
-    return batch * tiles * ks * v->bm * v->bn * 4 <= kWsBytes;
+    if (batch > 65535 || batch * tiles > sl.tiles) return false;
+    return batch * tiles * ks * v->bm * v->bn * 4 <= sl.bytes;
+}
+
+// The split a launch on `stream` of the current device may use: that of its registered workspace, or none.
+static SplitLimits stream_split_limits(hipStream_t stream) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return kNoSplit;
+    }
+    std::lock_guard<std::mutex> lock(g_ws_mu);
+    return g_ws.count(std::make_pair(dev, stream)) ? kRegisteredSplit : kNoSplit;
 }
 
 // The kernels divide by these launch constants through multiply-and-shift (see Params).
-static int g_store_nt = 0;       // tir_set_output_policy: 1 = outputs are written with non-temporal stores
-
 static void set_divisors(Params& p) {
     auto put = [](unsigned d, unsigned* magic, int* shift) {
         const FastDiv f = make_fastdiv(d < 1 ? 1u : d);
         *magic = f.magic;
         *shift = f.shift;
     };
-    p.store_nt = g_store_nt;
     put((unsigned)(kGroupM * p.tiles_n), &p.div_gw_magic, &p.div_gw_shift);
     put((unsigned)p.tiles_n, &p.div_tn_magic, &p.div_tn_shift);
     put((unsigned)p.tiles_m, &p.div_tm_magic, &p.div_tm_shift);
@@ -215,7 +232,7 @@ static uint64_t hash_fields(const int64_t* f, int n) {
 //
 // A reduction much longer than the tile grid is wide (few small tiles, many stages) is split over several
 // workgroups per tile, as many as fill the CUs once while each keeps at least eight stages.
-static Choice pick(int dt, int out, int amode, int bmode, int64_t batch, int64_t M, int64_t N, int64_t K, int max_rowb = 256) {
+static Choice pick(int dt, int out, int amode, int bmode, int64_t batch, int64_t M, int64_t N, int64_t K, const SplitLimits& sl, int max_rowb = 256) {
     Choice best = kNoChoice;
     double best_score = -1.0;
     const int es = elem_size(dt);
@@ -223,19 +240,21 @@ static Choice pick(int dt, int out, int amode, int bmode, int64_t batch, int64_t
         const Variant* v = &kVariants[i];
         if (v->dt != dt || v->out != out || v->amode != amode || v->bmode != bmode || v->rowb > max_rowb) continue;
         const int64_t tiles_1 = ((M + v->bm - 1) / v->bm) * ((N + v->bn - 1) / v->bn);
-        const int forced_ks = (g_force_ksplit > 1 && split_fits(v, g_force_ksplit, batch, tiles_1, K)) ? g_force_ksplit : 1;
+        const int want_ks = sl.force > 1 ? sl.force : g_force_ksplit;
+        const int forced_ks = (want_ks > 1 && split_fits(v, want_ks, batch, tiles_1, K, sl)) ? want_ks : 1;
+        if (sl.force > 1 && forced_ks != sl.force) continue;          // the caller insists on this split
         if (g_force_name[0] && strstr(v->name, g_force_name)) return Choice{v, forced_ks};          // testing / tuning overrides
         if (g_force_bm && v->bm == g_force_bm && v->bn == g_force_bn && v->kw == 1 && v->cw == 0) return Choice{v, forced_ks};
         const double tm = (double)((M + v->bm - 1) / v->bm), tn = (double)((N + v->bn - 1) / v->bn);
         int ks = forced_ks;
         // (the partial sums' trip through memory costs about 4 us for a 64x64 tile and grows with the tile: it pays
         // only for small tiles whose wave groups face two dozen stages or more)
-        if (!g_force_ksplit && v->bm * v->bn <= 64 * 64) {
+        if (!want_ks && sl.bytes > 0 && v->bm * v->bn <= 64 * 64) {
             const int64_t stages = (K * es + v->rowb - 1) / v->rowb;
             int64_t want = stages / v->kw >= 24 ? (int64_t)kCUs / (tiles_1 * batch) : 1;
             if (want > stages / (8 * v->kw)) want = stages / (8 * v->kw);
             if (want > 8) want = 8;
-            while (want > 1 && !split_fits(v, (int)want, batch, tiles_1, K)) --want;
+            while (want > 1 && !split_fits(v, (int)want, batch, tiles_1, K, sl)) --want;
             if (want > 1) ks = (int)want;
         }
         const double tiles = tm * tn * (double)batch * ks;
@@ -284,19 +303,21 @@ struct Plan {
 };
 
 // The variant a plan uses: the tuner's trial variant, else a measured record, else the scoring rule.
-static Choice choose(const TuneKey& key, int64_t batch, int64_t M, int64_t N, int64_t K) {
+static Choice choose(const TuneKey& key, int64_t batch, int64_t M, int64_t N, int64_t K, const SplitLimits& sl) {
+    if (sl.force > 1) return pick(key.dt, key.out, key.amode, key.bmode, batch, M, N, K, sl);
     if (g_trial.v) return g_trial;
     if (!g_force_name[0] && !g_force_bm && !g_force_ksplit) {
         const Choice t = tuned_lookup(key);
         if (t.v) return t;
     }
-    return pick(key.dt, key.out, key.amode, key.bmode, batch, M, N, K);
+    return pick(key.dt, key.out, key.amode, key.bmode, batch, M, N, K, sl);
 }
 
 static tir_status check_common(const void* A, const void* B, const void* C, int in, int out, const tir_epilogue* ep) {
     if (in < 0 || in > TIR_I32 || out < 0 || out > TIR_I32) return fail(TIR_ERR_INVALID_ARG, "unknown dtype code (in=%d out=%d)", in, out);
     if (!dtype_pair_ok(in, out, ep != nullptr)) return fail(TIR_ERR_UNSUPPORTED, "unsupported (in, out) dtype pair (%d, %d)", in, out);
     if (ep) {
+        if (ep->streaming != 0 && ep->streaming != 1) return fail(TIR_ERR_INVALID_ARG, "epilogue: streaming must be 0 or 1 (got %d)", ep->streaming);
         if (!aligned(ep->bias, 4)) return fail(TIR_ERR_ALIGNMENT, "bias pointer not aligned to 4 bytes");
         if (out == TIR_I8 && !(ep->scale > 0.0f && ep->scale <= 3.402823466e38f))
             return fail(TIR_ERR_INVALID_ARG, "int8 output needs a finite scale > 0");
@@ -311,8 +332,9 @@ static tir_status check_common(const void* A, const void* B, const void* C, int 
 static tir_status plan_gemm(bool need_ptrs, const void* A, const void* B, void* C, int64_t batch, int64_t M, int64_t N,
                             int64_t K, int64_t a_bs, int64_t a_rs, int64_t a_cs, int64_t b_bs, int64_t b_rs,
                             int64_t b_cs, int64_t c_bs, int64_t c_rs, int64_t c_cs, int in, int out, const tir_epilogue* ep,
-                            Plan* plan) {
+                            const SplitLimits& sl, Plan* plan) {
     plan->v = nullptr;
+    plan->key.kind = -1;        // no signature yet
     tir_status st = check_common(A, B, C, in, out, ep);
     if (st != TIR_OK) return st;
     if (batch < 0 || M < 0 || N < 0 || K < 0) return fail(TIR_ERR_INVALID_ARG, "negative extent (batch=%lld M=%lld N=%lld K=%lld)", (long long)batch, (long long)M, (long long)N, (long long)K);
@@ -345,12 +367,12 @@ static tir_status plan_gemm(bool need_ptrs, const void* A, const void* B, void* 
 
     plan->key = TuneKey{0, in, out, amode, bmode, batch, M, N, K, 0};
     plan->patch_ok = false;
-    const Choice ch = choose(plan->key, batch, M, N, K);
+    const Choice ch = choose(plan->key, batch, M, N, K, sl);
     const Variant* v = ch.v;
     if (!v) return fail(TIR_ERR_UNSUPPORTED, "no kernel variant for this dtype / layout / forced tile");
     Params& p = plan->p;
     memset(&p, 0, sizeof p);
-    p.ksplit = split_fits(v, ch.ksplit, batch, ((M + v->bm - 1) / v->bm) * ((N + v->bn - 1) / v->bn), K) ? ch.ksplit : 1;
+    p.ksplit = split_fits(v, ch.ksplit, batch, ((M + v->bm - 1) / v->bm) * ((N + v->bn - 1) / v->bn), K, sl) ? ch.ksplit : 1;
     p.A = A; p.B = B; p.C = C;
     p.M = (int)M; p.N = (int)N; p.K = (int)K;
     p.batch = (int)batch;
@@ -360,7 +382,7 @@ static tir_status plan_gemm(bool need_ptrs, const void* A, const void* B, void* 
     p.a_bs = a_bs; p.b_bs = b_bs; p.c_bs = c_bs;
     p.a_rs = a_rs; p.a_cs = a_cs; p.b_rs = b_rs; p.b_cs = b_cs; p.c_rs = c_rs; p.c_cs = c_cs;
     p.c_fast = (c_cs == 1 && (c_rs >= N || M == 1) && (c_rs * 256 + N) * elem_size(out) < kMaxExtent) ? 1 : 0;
-    if (ep) { p.bias = ep->bias; p.bias_bs = 0; p.relu = ep->relu != 0; p.scale = ep->scale; }
+    if (ep) { p.bias = ep->bias; p.bias_bs = 0; p.relu = ep->relu != 0; p.scale = ep->scale; p.store_nt = ep->streaming; }
     set_divisors(p);
     plan->v = v;
     return TIR_OK;
@@ -382,7 +404,7 @@ struct ConvGeom {
 };
 
 static tir_status plan_conv_geom(bool need_ptrs, const void* x, const void* w, void* y, const ConvGeom& g, int in, int out,
-                                 const tir_epilogue* ep, Plan* plan) {
+                                 const tir_epilogue* ep, const SplitLimits& sl, Plan* plan) {
     plan->v = nullptr;
     tir_status st = check_common(x, w, y, in, out, ep);
     if (st != TIR_OK) return st;
@@ -463,16 +485,16 @@ static tir_status plan_conv_geom(bool need_ptrs, const void* x, const void* w, v
     if (ch.v && ch.v->amode == A_CONV_PATCH && !patch_ok) ch = kNoChoice;
     if (!ch.v) {
         const bool use_patch = patch_ok && !g_force_ksplit && (!g_force_name[0] || strstr(g_force_name, "patch"));
-        if (use_patch) ch = pick(in, out, A_CONV_PATCH, bmode, groups * N, P * Q, Kg, Kd);
-        else ch = pick(in, out, amode, bmode, sc_batch, sc_M, Kg, sc_K, phased ? (int)(Cg * es >= 256 && (Cg * es) % 256 == 0 ? 256 : 128) : 256);
+        if (use_patch) ch = pick(in, out, A_CONV_PATCH, bmode, groups * N, P * Q, Kg, Kd, sl);
+        else ch = pick(in, out, amode, bmode, sc_batch, sc_M, Kg, sc_K, sl, phased ? (int)(Cg * es >= 256 && (Cg * es) % 256 == 0 ? 256 : 128) : 256);
     }
-    if (phased && ch.v && tuned_or_trial_mismatch(ch.v, Cg * es)) ch = pick(in, out, amode, bmode, sc_batch, sc_M, Kg, sc_K, 128);
+    if (phased && ch.v && tuned_or_trial_mismatch(ch.v, Cg * es)) ch = pick(in, out, amode, bmode, sc_batch, sc_M, Kg, sc_K, sl, 128);
     const Variant* v = ch.v;
     if (v && v->amode == A_CONV_PATCH) amode = A_CONV_PATCH;
     if (!v) return fail(TIR_ERR_UNSUPPORTED, "no kernel variant for this dtype / forced tile");
     Params& p = plan->p;
     memset(&p, 0, sizeof p);
-    p.ksplit = (!depthwise && !phased && split_fits(v, ch.ksplit, groups, ((Mg + v->bm - 1) / v->bm) * ((Kg + v->bn - 1) / v->bn), Kd)) ? ch.ksplit : 1;
+    p.ksplit = (!depthwise && !phased && split_fits(v, ch.ksplit, groups, ((Mg + v->bm - 1) / v->bm) * ((Kg + v->bn - 1) / v->bn), Kd, sl)) ? ch.ksplit : 1;
     p.A = x; p.B = w; p.C = y;
     p.M = (int)Mg; p.N = (int)Kg; p.K = (int)Kd;
     p.batch = depthwise ? 1 : groups;                 // the depth-wise kernel covers every channel in one launch
@@ -490,7 +512,7 @@ static tir_status plan_conv_geom(bool need_ptrs, const void* x, const void* w, v
     p.b_rs = 1; p.b_cs = Kd;          // B[k][y] = w[y][k]: the filter (output channel major, channel innermost) is B stored K-major
     p.c_rs = K; p.c_cs = 1;           // the channels-last output is C_t[fuse(n,o,h,w)][co]
     p.c_fast = ((K * 256 + Kg) * elem_size(out) < kMaxExtent) ? 1 : 0;
-    if (ep) { p.bias = ep->bias; p.bias_bs = Kg; p.relu = ep->relu != 0; p.scale = ep->scale; }
+    if (ep) { p.bias = ep->bias; p.bias_bs = Kg; p.relu = ep->relu != 0; p.scale = ep->scale; p.store_nt = ep->streaming; }
     p.H = (int)H; p.W = (int)W; p.Cin = (int)C; p.Cg = (int)Cg; p.P = (int)P; p.Q = (int)Q; p.R = (int)R; p.S = (int)S;
     p.D = (int)D; p.T = (int)T; p.OD = (int)OD;
     p.stride_d = g.stride_d; p.pad_d = g.pad_d; p.dil_d = g.dil_d;
@@ -521,13 +543,14 @@ static tir_status plan_conv_geom(bool need_ptrs, const void* x, const void* w, v
 
 static tir_status plan_conv(bool need_ptrs, const void* x, const void* w, void* y, int64_t N, int64_t H, int64_t W,
                             int64_t C, int64_t K, int64_t R, int64_t S, int stride_h, int stride_w, int pad_h,
-                            int pad_w, int dil_h, int dil_w, int groups, int in, int out, const tir_epilogue* ep, Plan* plan) {
+                            int pad_w, int dil_h, int dil_w, int groups, int in, int out, const tir_epilogue* ep, const SplitLimits& sl,
+                            Plan* plan) {
     const ConvGeom g = {N, 1, H, W, C, K, 1, R, S, 1, stride_h, stride_w, 0, pad_h, pad_w, 1, dil_h, dil_w, groups, false, 0, 0};
-    return plan_conv_geom(need_ptrs, x, w, y, g, in, out, ep, plan);
+    return plan_conv_geom(need_ptrs, x, w, y, g, in, out, ep, sl, plan);
 }
 
-// Give a plan with a split reduction its workspace.  Allocation happens outside any stream capture (a capturing
-// stream that has no workspace yet runs the same variant without the split instead).
+// Give a plan with a split reduction the workspace registered for its stream (the plan was made with that stream's
+// limits; should the registration have gone meanwhile, the same variant runs unsplit).
 static tir_status attach_workspace(Plan* plan, hipStream_t stream) {
     if (!plan->v || plan->p.ksplit <= 1) return TIR_OK;
     int dev = 0;
@@ -536,25 +559,8 @@ static tir_status attach_workspace(Plan* plan, hipStream_t stream) {
     std::lock_guard<std::mutex> lock(g_ws_mu);
     auto it = g_ws.find(std::make_pair(dev, stream));
     if (it == g_ws.end()) {
-        hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
-        if (stream && (hipStreamIsCapturing(stream, &cs) != hipSuccess || cs != hipStreamCaptureStatusNone)) {
-            (void)hipGetLastError();
-            plan->p.ksplit = 1;
-            return TIR_OK;
-        }
-        void* base = nullptr;
-        e = hipMalloc(&base, (size_t)(kWsBytes + kWsTiles * 4));
-        if (e == hipSuccess) e = hipMemset((char*)base + kWsBytes, 0, (size_t)(kWsTiles * 4));
-        if (e == hipSuccess) e = hipDeviceSynchronize();
-        if (e != hipSuccess) {
-            // no memory, or another thread captures in a mode that forbids allocation: run without the split
-            (void)hipGetLastError();
-            if (base) (void)hipFree(base);
-            plan->p.ksplit = 1;
-            return TIR_OK;
-        }
-        Workspace w = {base, (unsigned*)((char*)base + kWsBytes), base};
-        it = g_ws.insert(std::make_pair(std::make_pair(dev, stream), w)).first;
+        plan->p.ksplit = 1;
+        return TIR_OK;
     }
     plan->p.ws = it->second.partial;
     plan->p.ws_count = it->second.count;
@@ -713,7 +719,7 @@ tir_status tir_gemm_fused(const void* A, const void* B, void* C, int64_t M, int6
                           int64_t a_cs, int64_t b_rs, int64_t b_cs, int64_t c_rs, int64_t c_cs, tir_dtype in,
                           tir_dtype out, const tir_epilogue* ep, tir_stream stream) {
     Plan plan;
-    tir_status st = plan_gemm(true, A, B, C, 1, M, N, K, 0, a_rs, a_cs, 0, b_rs, b_cs, 0, c_rs, c_cs, (int)in, (int)out, ep, &plan);
+    tir_status st = plan_gemm(true, A, B, C, 1, M, N, K, 0, a_rs, a_cs, 0, b_rs, b_cs, 0, c_rs, c_cs, (int)in, (int)out, ep, stream_split_limits((hipStream_t)stream), &plan);
     if (st != TIR_OK) return st;
     return launch(plan, (hipStream_t)stream);
 }
@@ -723,7 +729,7 @@ tir_status tir_batch_matmul_fused(const void* A, const void* B, void* C, int64_t
                                   int64_t c_bs, int64_t c_rs, int64_t c_cs, tir_dtype in, tir_dtype out,
                                   const tir_epilogue* ep, tir_stream stream) {
     Plan plan;
-    tir_status st = plan_gemm(true, A, B, C, batch, M, N, K, a_bs, a_rs, a_cs, b_bs, b_rs, b_cs, c_bs, c_rs, c_cs, (int)in, (int)out, ep, &plan);
+    tir_status st = plan_gemm(true, A, B, C, batch, M, N, K, a_bs, a_rs, a_cs, b_bs, b_rs, b_cs, c_bs, c_rs, c_cs, (int)in, (int)out, ep, stream_split_limits((hipStream_t)stream), &plan);
     if (st != TIR_OK) return st;
     return launch(plan, (hipStream_t)stream);
 }
@@ -732,7 +738,7 @@ tir_status tir_conv2d_fused(const void* x, const void* w, void* y, int64_t N, in
                             int64_t R, int64_t S, int stride_h, int stride_w, int pad_h, int pad_w, int dil_h, int dil_w,
                             int groups, tir_dtype in, tir_dtype out, const tir_epilogue* ep, tir_stream stream) {
     Plan plan;
-    tir_status st = plan_conv(true, x, w, y, N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, groups, (int)in, (int)out, ep, &plan);
+    tir_status st = plan_conv(true, x, w, y, N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, groups, (int)in, (int)out, ep, stream_split_limits((hipStream_t)stream), &plan);
     if (st != TIR_OK) return st;
     return launch(plan, (hipStream_t)stream);
 }
@@ -772,7 +778,7 @@ const char* tir_gemm_variant(int64_t batch, int64_t M, int64_t N, int64_t K, int
                              int64_t b_cs, int64_t c_rs, int64_t c_cs, tir_dtype in, tir_dtype out) {
     Plan plan;
     // batch strides of dense operands, only their divisibility matters for the choice
-    tir_status st = plan_gemm(false, nullptr, nullptr, nullptr, batch, M, N, K, M * K, a_rs, a_cs, K * N, b_rs, b_cs, M * N, c_rs, c_cs, (int)in, (int)out, out == TIR_I8 ? &kQueryRequant : nullptr, &plan);
+    tir_status st = plan_gemm(false, nullptr, nullptr, nullptr, batch, M, N, K, M * K, a_rs, a_cs, K * N, b_rs, b_cs, M * N, c_rs, c_cs, (int)in, (int)out, out == TIR_I8 ? &kQueryRequant : nullptr, kRegisteredSplit, &plan);
     return st == TIR_OK ? plan_name(plan) : "";
 }
 
@@ -780,7 +786,7 @@ const char* tir_conv2d_variant(int64_t N, int64_t H, int64_t W, int64_t C, int64
                                int stride_h, int stride_w, int pad_h, int pad_w, int dil_h, int dil_w, int groups,
                                tir_dtype in, tir_dtype out) {
     Plan plan;
-    tir_status st = plan_conv(false, nullptr, nullptr, nullptr, N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, groups, (int)in, (int)out, out == TIR_I8 ? &kQueryRequant : nullptr, &plan);
+    tir_status st = plan_conv(false, nullptr, nullptr, nullptr, N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, groups, (int)in, (int)out, out == TIR_I8 ? &kQueryRequant : nullptr, kRegisteredSplit, &plan);
     return st == TIR_OK ? plan_name(plan) : "";
 }
 
@@ -789,7 +795,7 @@ const char* tir_conv3d_variant(int64_t N, int64_t D, int64_t H, int64_t W, int64
                                int dil_d, int dil_h, int dil_w, int groups, tir_dtype in, tir_dtype out) {
     const ConvGeom g = {N, D, H, W, C, K, T, R, S, stride_d, stride_h, stride_w, pad_d, pad_h, pad_w, dil_d, dil_h, dil_w, groups, false, 0, 0};
     Plan plan;
-    tir_status st = plan_conv_geom(false, nullptr, nullptr, nullptr, g, (int)in, (int)out, out == TIR_I8 ? &kQueryRequant : nullptr, &plan);
+    tir_status st = plan_conv_geom(false, nullptr, nullptr, nullptr, g, (int)in, (int)out, out == TIR_I8 ? &kQueryRequant : nullptr, kRegisteredSplit, &plan);
     return st == TIR_OK ? plan_name(plan) : "";
 }
 
@@ -798,19 +804,13 @@ const char* tir_conv2d_transpose_variant(int64_t N, int64_t H, int64_t W, int64_
                                          int outpad_h, int outpad_w, int groups, tir_dtype in, tir_dtype out) {
     const ConvGeom g = {N, 1, H, W, C, K, 1, R, S, 1, stride_h, stride_w, 0, pad_h, pad_w, 1, dil_h, dil_w, groups, true, outpad_h, outpad_w};
     Plan plan;
-    tir_status st = plan_conv_geom(false, nullptr, nullptr, nullptr, g, (int)in, (int)out, out == TIR_I8 ? &kQueryRequant : nullptr, &plan);
+    tir_status st = plan_conv_geom(false, nullptr, nullptr, nullptr, g, (int)in, (int)out, out == TIR_I8 ? &kQueryRequant : nullptr, kRegisteredSplit, &plan);
     return st == TIR_OK ? plan_name(plan) : "";
 }
 
 void tir_debug_force_tile(int bm, int bn) {
     g_force_bm = bm;
     g_force_bn = bn;
-}
-
-tir_status tir_set_output_policy(tir_output_policy policy) {
-    if (policy != TIR_OUTPUT_CACHED && policy != TIR_OUTPUT_STREAMING) return fail(TIR_ERR_INVALID_ARG, "unknown output policy %d", (int)policy);
-    g_store_nt = policy == TIR_OUTPUT_STREAMING ? 1 : 0;
-    return TIR_OK;
 }
 
 uint64_t tir_workspace_bytes(void) { return (uint64_t)(kWsBytes + kWsTiles * 4); }
@@ -828,30 +828,15 @@ tir_status tir_set_workspace(tir_stream stream_, void* ws, uint64_t bytes) {
     if (e != hipSuccess) return fail(TIR_ERR_LAUNCH, "hipGetDevice failed: %s", hipGetErrorString(e));
     std::lock_guard<std::mutex> lock(g_ws_mu);
     const std::pair<int, hipStream_t> key(dev, stream);
-    auto it = g_ws.find(key);
     if (!ws) {
-        // back to the library's own block (its counters are zero whenever no launch is in flight), or to none
-        if (it != g_ws.end()) {
-            if (it->second.owned) {
-                it->second.partial = it->second.owned;
-                it->second.count = (unsigned*)((char*)it->second.owned + kWsBytes);
-            } else {
-                g_ws.erase(it);
-            }
-        }
+        g_ws.erase(key);
         return TIR_OK;
     }
     unsigned* count = (unsigned*)((char*)ws + kWsBytes);
     hipLaunchKernelGGL(clear_counters_kernel, dim3((unsigned)(kWsTiles / 256)), dim3(256), 0, stream, count, (int)kWsTiles);
     e = hipGetLastError();
     if (e != hipSuccess) return fail(TIR_ERR_LAUNCH, "clearing the workspace counters failed: %s", hipGetErrorString(e));
-    if (it == g_ws.end()) {
-        Workspace w = {ws, count, nullptr};
-        g_ws.insert(std::make_pair(key, w));
-    } else {
-        it->second.partial = ws;
-        it->second.count = count;
-    }
+    g_ws[key] = Workspace{ws, count};
     return TIR_OK;
 }
 
@@ -888,8 +873,9 @@ tir_status tir_tune_batch_matmul(const void* A, const void* B, void* C, int64_t 
                                  int64_t a_bs, int64_t a_rs, int64_t a_cs, int64_t b_bs, int64_t b_rs, int64_t b_cs,
                                  int64_t c_bs, int64_t c_rs, int64_t c_cs, tir_dtype in, tir_dtype out,
                                  const tir_epilogue* ep, int reps, double* best_us, tir_stream stream) {
+    const SplitLimits sl = stream_split_limits((hipStream_t)stream);
     auto make = [&](Plan* pl) {
-        return plan_gemm(true, A, B, C, batch, M, N, K, a_bs, a_rs, a_cs, b_bs, b_rs, b_cs, c_bs, c_rs, c_cs, (int)in, (int)out, ep, pl);
+        return plan_gemm(true, A, B, C, batch, M, N, K, a_bs, a_rs, a_cs, b_bs, b_rs, b_cs, c_bs, c_rs, c_cs, (int)in, (int)out, ep, sl, pl);
     };
     return tune_problem(make, reps, (hipStream_t)stream, best_us, nullptr);
 }
@@ -898,8 +884,9 @@ tir_status tir_tune_conv2d(const void* x, const void* w, void* y, int64_t N, int
                            int64_t R, int64_t S, int stride_h, int stride_w, int pad_h, int pad_w, int dil_h, int dil_w,
                            int groups, tir_dtype in, tir_dtype out, const tir_epilogue* ep, int reps, double* best_us,
                            tir_stream stream) {
+    const SplitLimits sl = stream_split_limits((hipStream_t)stream);
     auto make = [&](Plan* pl) {
-        return plan_conv(true, x, w, y, N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, groups, (int)in, (int)out, ep, pl);
+        return plan_conv(true, x, w, y, N, H, W, C, K, R, S, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, groups, (int)in, (int)out, ep, sl, pl);
     };
     return tune_problem(make, reps, (hipStream_t)stream, best_us, nullptr);
 }
@@ -909,7 +896,8 @@ tir_status tir_tune_conv3d(const void* x, const void* w, void* y, int64_t N, int
                            int pad_d, int pad_h, int pad_w, int dil_d, int dil_h, int dil_w, int groups, tir_dtype in,
                            tir_dtype out, const tir_epilogue* ep, int reps, double* best_us, tir_stream stream) {
     const ConvGeom g = {N, D, H, W, C, K, T, R, S, stride_d, stride_h, stride_w, pad_d, pad_h, pad_w, dil_d, dil_h, dil_w, groups, false, 0, 0};
-    auto make = [&](Plan* pl) { return plan_conv_geom(true, x, w, y, g, (int)in, (int)out, ep, pl); };
+    const SplitLimits sl = stream_split_limits((hipStream_t)stream);
+    auto make = [&](Plan* pl) { return plan_conv_geom(true, x, w, y, g, (int)in, (int)out, ep, sl, pl); };
     return tune_problem(make, reps, (hipStream_t)stream, best_us, nullptr);
 }
 
@@ -919,7 +907,8 @@ tir_status tir_tune_conv2d_transpose(const void* x, const void* w, void* y, int6
                                      tir_dtype out, const tir_epilogue* ep, int reps, double* best_us,
                                      tir_stream stream) {
     const ConvGeom g = {N, 1, H, W, C, K, 1, R, S, 1, stride_h, stride_w, 0, pad_h, pad_w, 1, dil_h, dil_w, groups, true, outpad_h, outpad_w};
-    auto make = [&](Plan* pl) { return plan_conv_geom(true, x, w, y, g, (int)in, (int)out, ep, pl); };
+    const SplitLimits sl = stream_split_limits((hipStream_t)stream);
+    auto make = [&](Plan* pl) { return plan_conv_geom(true, x, w, y, g, (int)in, (int)out, ep, sl, pl); };
     return tune_problem(make, reps, (hipStream_t)stream, best_us, nullptr);
 }
 
@@ -1000,7 +989,6 @@ tir_status tir_attention(const void* Q, const void* K, const void* V, void* O, i
     p.Q = Q; p.K = K; p.V = V; p.O = O;
     p.M = (int)M; p.N = (int)N; p.batch = (int)batch; p.tiles_m = (int)tiles_m;
     p.scale_log2e = scale * 1.44269504088896340736f;
-    p.store_nt = g_store_nt;
     const FastDiv dtm = make_fastdiv((unsigned)tiles_m);
     p.div_tm_magic = dtm.magic; p.div_tm_shift = dtm.shift;
     hipError_t e = fn(p, (hipStream_t)stream);
@@ -1013,7 +1001,7 @@ tir_status tir_conv1d(const void* x, const void* w, void* y, int64_t N, int64_t 
                       tir_stream stream) {
     // a 1-D convolution is the 2-D one on an image of height 1 with a filter of height 1
     Plan plan;
-    tir_status st = plan_conv(true, x, w, y, N, 1, L, C, K, 1, R, 1, stride, 0, pad, 1, dil, groups, (int)in, (int)out, ep, &plan);
+    tir_status st = plan_conv(true, x, w, y, N, 1, L, C, K, 1, R, 1, stride, 0, pad, 1, dil, groups, (int)in, (int)out, ep, stream_split_limits((hipStream_t)stream), &plan);
     if (st != TIR_OK) return st;
     return launch(plan, (hipStream_t)stream);
 }
@@ -1024,7 +1012,7 @@ tir_status tir_conv3d(const void* x, const void* w, void* y, int64_t N, int64_t 
                       const tir_epilogue* ep, tir_stream stream) {
     const ConvGeom g = {N, D, H, W, C, K, T, R, S, stride_d, stride_h, stride_w, pad_d, pad_h, pad_w, dil_d, dil_h, dil_w, groups, false, 0, 0};
     Plan plan;
-    tir_status st = plan_conv_geom(true, x, w, y, g, (int)in, (int)out, ep, &plan);
+    tir_status st = plan_conv_geom(true, x, w, y, g, (int)in, (int)out, ep, stream_split_limits((hipStream_t)stream), &plan);
     if (st != TIR_OK) return st;
     return launch(plan, (hipStream_t)stream);
 }
@@ -1035,7 +1023,7 @@ tir_status tir_conv2d_transpose(const void* x, const void* w, void* y, int64_t N
                                 const tir_epilogue* ep, tir_stream stream) {
     const ConvGeom g = {N, 1, H, W, C, K, 1, R, S, 1, stride_h, stride_w, 0, pad_h, pad_w, 1, dil_h, dil_w, groups, true, outpad_h, outpad_w};
     Plan plan;
-    tir_status st = plan_conv_geom(true, x, w, y, g, (int)in, (int)out, ep, &plan);
+    tir_status st = plan_conv_geom(true, x, w, y, g, (int)in, (int)out, ep, stream_split_limits((hipStream_t)stream), &plan);
     if (st != TIR_OK) return st;
     return launch(plan, (hipStream_t)stream);
 }

@@ -39,7 +39,7 @@ def assert_close(gpu, ref, S, what=""):
     return float(ratio.ravel()[worst])
 
 
-def run_gpu(wl, a_bits, b_bits, prefill=True):
+def run_gpu(wl, a_bits, b_bits, prefill=True, streaming=False):
     """Launch workload wl on cuda:0 through the C ABI; returns the output as float64 / int64 numpy."""
     import torch
     from paper_2207_04296_amd import binding as B
@@ -51,7 +51,7 @@ def run_gpu(wl, a_bits, b_bits, prefill=True):
             c.fill_(float("nan"))
         else:
             c.fill_(-77 if c.dtype == torch.int8 else -123456789)
-    B.run_workload(wl, a, b, c, B.bias_to_device(wl))
+    B.run_workload(wl, a, b, c, B.bias_to_device(wl), streaming=streaming)
     torch.cuda.synchronize()
     return gpu_to_f64(c)
 

@@ -209,10 +209,15 @@ def test_reduction_split_is_planned_only_where_it_fits(tmp_path):
         B.tir_tune_clear()
 
 
-def test_output_policy_argument_is_checked():
-    assert B.lib().tir_set_output_policy(7) == B.TIR_ERR_INVALID_ARG
-    B.tir_set_output_policy(B.TIR_OUTPUT_STREAMING)
-    B.tir_set_output_policy(B.TIR_OUTPUT_CACHED)
+def test_output_policy_is_a_checked_field_of_the_epilogue():
+    """The cache policy of a call's output stores travels in its epilogue: 0 or 1, anything else is rejected on the host."""
+    def call(streaming):
+        ep = B.Epilogue(None, 0, 0.0, streaming)
+        return B.lib().tir_gemm_fused(FAKE, FAKE, FAKE, 64, 64, 64, 64, 1, 64, 1, 64, 1, B.TIR_F16, B.TIR_F32, ep, None)
+    assert call(7) == B.TIR_ERR_INVALID_ARG and "streaming" in B.last_error()
+    assert call(-1) == B.TIR_ERR_INVALID_ARG
+    assert B.make_epilogue() is None and B.make_epilogue(streaming=True).streaming == 1
+    assert not hasattr(B.lib(), "tir_set_output_policy")       # no process-wide policy
 
 
 def test_caller_workspace_arguments_are_checked():

@@ -23,8 +23,16 @@ def B():
     from paper_2207_04296_amd import binding
     binding.lib()
     binding.tir_debug_force_tile(0, 0)
+    # reductions are split over workgroups only on streams with a registered workspace: the tests launch on the
+    # default stream, which gets one for the whole module
+    ws = torch.empty(binding.tir_workspace_bytes(), dtype=torch.uint8, device="cuda:0")
+    binding.tir_set_workspace(ws)
+    torch.cuda.synchronize()
     yield binding
+    torch.cuda.synchronize()
+    binding.tir_set_workspace(None)
     binding.tir_debug_force_tile(0, 0)
+    del ws
 
 
 def _say(msg):
@@ -892,43 +900,38 @@ def test_conv_coordinates_at_the_16_bit_limits(B, oracle, case):
 
 
 def test_streaming_output_policy_gives_the_same_results(B, oracle):
-    """TIR_OUTPUT_STREAMING only changes the cache policy bits of the epilogue's stores: every kind of epilogue (the
+    """tir_epilogue.streaming only changes the cache policy bits of the epilogue's stores: every kind of epilogue (the
     tile stores of the GEMM and convolution kernels, fused consumers, int8 codes, the patch kernel, the phase decode,
-    the split reduction, depth-wise, attention) gives bit-identical outputs under both policies, and the oracle's."""
+    the split reduction, depth-wise) gives bit-identical outputs under both policies, and the oracle's."""
     import torch
     names = ["c1_gemm128_f16", "c2a_conv56x64_f16", "c3b_bmm_pv_f16", "c5b_conv_g8d2_i8"]
     wls = ([I.WORKLOADS[n] for n in names] + [I.FUSED_WORKLOADS[n] for n in ("c2a_conv56x64_f16_bias_relu", "c5b_conv_g8d2_i8_relu_requant")] +
            [I.MORE_WORKLOADS["dep_conv112x32s2_i8_requant"]])
-    try:
-        for wl in wls:
-            a_bits, b_bits = wl.operands()
-            B.tir_set_output_policy(B.TIR_OUTPUT_CACHED)
-            cached = PT.run_gpu(wl, a_bits, b_bits)
-            B.tir_set_output_policy(B.TIR_OUTPUT_STREAMING)
-            _say(f"streaming stores: {wl.name}")
-            streamed = PT.run_gpu(wl, a_bits, b_bits)
-            assert np.array_equal(cached, streamed), wl.name
-            ref, S = PT.run_oracle(wl, a_bits, b_bits, oracle)
-            PT.assert_close(streamed, ref, S, wl.name + " (streaming stores)")
-        # transposed convolution by phase, conv3d as a split reduction, attention
-        B.tir_set_output_policy(B.TIR_OUTPUT_STREAMING)
-        N, H, W, C, K = 2, 9, 10, 64, 48
-        xb = I.make_tensor("f16", "n0.1", 9991, (N, H, W, C)); wb = I.make_tensor("f16", "n0.1", 9992, (K, 4, 4, C))
-        ref, S = oracle.conv2d_transpose("f16", xb, wb, (2, 2), (1, 1), (1, 1), (0, 0), 1)
-        y = _gpu_out(B, ref.shape, "f16")
-        _say("streaming stores: transposed convolution by phase")
-        B.tir_conv2d_transpose(B.to_device(xb, "f16"), B.to_device(wb, "f16"), y, N, H, W, C, K, 4, 4, (2, 2), (1, 1), (1, 1), (0, 0), 1, "f16", "f16")
-        torch.cuda.synchronize()
-        PT.assert_close(PT.gpu_to_f64(y), ref, S, "transposed convolution (streaming stores)")
-        xb = I.make_tensor("f16", "n0.1", 9993, (1, 6, 8, 8, 128)); wb = I.make_tensor("f16", "n0.1", 9994, (40, 3, 3, 3, 128))
-        ref, S = oracle.conv3d("f16", xb, wb, (1, 1, 1), (1, 1, 1), (1, 1, 1), 1)
-        y = _gpu_out(B, ref.shape, "f16")
-        _say("streaming stores: conv3d (split reduction)")
-        B.tir_conv3d(B.to_device(xb, "f16"), B.to_device(wb, "f16"), y, 1, 6, 8, 8, 128, 40, 3, 3, 3, (1, 1, 1), (1, 1, 1), (1, 1, 1), 1, "f16", "f16")
-        torch.cuda.synchronize()
-        PT.assert_close(PT.gpu_to_f64(y), ref, S, "conv3d (streaming stores)")
-    finally:
-        B.tir_set_output_policy(B.TIR_OUTPUT_CACHED)
+    for wl in wls:
+        a_bits, b_bits = wl.operands()
+        cached = PT.run_gpu(wl, a_bits, b_bits)
+        _say(f"streaming stores: {wl.name}")
+        streamed = PT.run_gpu(wl, a_bits, b_bits, streaming=True)
+        assert np.array_equal(cached, streamed), wl.name
+        ref, S = PT.run_oracle(wl, a_bits, b_bits, oracle)
+        PT.assert_close(streamed, ref, S, wl.name + " (streaming stores)")
+    # transposed convolution by phase, conv3d as a split reduction
+    ep = B.make_epilogue(streaming=True)
+    N, H, W, C, K = 2, 9, 10, 64, 48
+    xb = I.make_tensor("f16", "n0.1", 9991, (N, H, W, C)); wb = I.make_tensor("f16", "n0.1", 9992, (K, 4, 4, C))
+    ref, S = oracle.conv2d_transpose("f16", xb, wb, (2, 2), (1, 1), (1, 1), (0, 0), 1)
+    y = _gpu_out(B, ref.shape, "f16")
+    _say("streaming stores: transposed convolution by phase")
+    B.tir_conv2d_transpose(B.to_device(xb, "f16"), B.to_device(wb, "f16"), y, N, H, W, C, K, 4, 4, (2, 2), (1, 1), (1, 1), (0, 0), 1, "f16", "f16", ep)
+    torch.cuda.synchronize()
+    PT.assert_close(PT.gpu_to_f64(y), ref, S, "transposed convolution (streaming stores)")
+    xb = I.make_tensor("f16", "n0.1", 9993, (1, 6, 8, 8, 128)); wb = I.make_tensor("f16", "n0.1", 9994, (40, 3, 3, 3, 128))
+    ref, S = oracle.conv3d("f16", xb, wb, (1, 1, 1), (1, 1, 1), (1, 1, 1), 1)
+    y = _gpu_out(B, ref.shape, "f16")
+    _say("streaming stores: conv3d (split reduction)")
+    B.tir_conv3d(B.to_device(xb, "f16"), B.to_device(wb, "f16"), y, 1, 6, 8, 8, 128, 40, 3, 3, 3, (1, 1, 1), (1, 1, 1), (1, 1, 1), 1, "f16", "f16", ep)
+    torch.cuda.synchronize()
+    PT.assert_close(PT.gpu_to_f64(y), ref, S, "conv3d (streaming stores)")
 
 
 @pytest.mark.parametrize("policy", ["cached", "streaming"])
@@ -944,31 +947,28 @@ def test_consumer_reads_what_the_producer_wrote(B, oracle, policy):
     x, f1, f2 = B.to_device(xb, "f16"), B.to_device(w1, "f16"), B.to_device(w2, "f16")
     mid = B.to_device(old, "f16")                       # the intermediate buffer starts out holding other data
     y = _gpu_out(B, (n, h, w, c), "f16"); scratch = _gpu_out(B, (n, h, w, c), "f16")
-    conv = lambda a, f, o: B.tir_conv2d(a, f, o, n, h, w, c, c, 3, 3, 1, 1, 1, 1, 1, 1, 1, "f16", "f16")
-    try:
-        B.tir_set_output_policy(B.TIR_OUTPUT_STREAMING if policy == "streaming" else B.TIR_OUTPUT_CACHED)
-        for rep in range(3):
-            _say(f"chain, {policy} outputs, round {rep}")
-            conv(mid, f2, scratch)                      # reads the old contents of `mid`: they are in the caches now
-            conv(x, f1, mid)                            # producer
-            conv(mid, f2, y)                            # consumer, right behind it
-            torch.cuda.synchronize()
-            mid_bits = mid.cpu().view(torch.int16).numpy().view(np.uint16).copy()
-            ref, S = oracle.conv2d("f16", mid_bits, w2, (1, 1), (1, 1), (1, 1), 1)
-            PT.assert_close(PT.gpu_to_f64(y), ref, S, f"consumer of a {policy} output, round {rep}")
-            ref1, S1 = oracle.conv2d("f16", xb, w1, (1, 1), (1, 1), (1, 1), 1)
-            PT.assert_close(PT.gpu_to_f64(mid), ref1, S1, f"producer, {policy} output, round {rep}")
-            mid.copy_(B.to_device(old, "f16"))          # next round starts from the old contents again
-            torch.cuda.synchronize()
-    finally:
-        B.tir_set_output_policy(B.TIR_OUTPUT_CACHED)
+    ep = B.make_epilogue(streaming=(policy == "streaming"))
+    conv = lambda a, f, o: B.tir_conv2d_fused(a, f, o, n, h, w, c, c, 3, 3, 1, 1, 1, 1, 1, 1, 1, "f16", "f16", ep)
+    for rep in range(3):
+        _say(f"chain, {policy} outputs, round {rep}")
+        conv(mid, f2, scratch)                      # reads the old contents of `mid`: they are in the caches now
+        conv(x, f1, mid)                            # producer
+        conv(mid, f2, y)                            # consumer, right behind it
+        torch.cuda.synchronize()
+        mid_bits = mid.cpu().view(torch.int16).numpy().view(np.uint16).copy()
+        ref, S = oracle.conv2d("f16", mid_bits, w2, (1, 1), (1, 1), (1, 1), 1)
+        PT.assert_close(PT.gpu_to_f64(y), ref, S, f"consumer of a {policy} output, round {rep}")
+        ref1, S1 = oracle.conv2d("f16", xb, w1, (1, 1), (1, 1), (1, 1), 1)
+        PT.assert_close(PT.gpu_to_f64(mid), ref1, S1, f"producer, {policy} output, round {rep}")
+        mid.copy_(B.to_device(old, "f16"))          # next round starts from the old contents again
+        torch.cuda.synchronize()
 
 
 def test_split_reduction_under_graph_capture(B, oracle):
-    """A split reduction needs the library's workspace, which cannot be allocated while a stream is captured: a
-    capture on a stream that has none yet runs the same variant unsplit; once an eager call has allocated it, the
-    captured launches split, and every replay (with eager work of the library in between) gives the oracle's result
-    - the tile counters are back at zero after each launch, nothing in the graph clears them."""
+    """A reduction is split only on a stream with a registered workspace: a capture on a stream that has none runs the
+    same variant unsplit (nothing is allocated on its behalf); with a workspace registered, the captured launches split,
+    and every replay (with eager work of the library in between) gives the oracle's result - the tile counters are back
+    at zero after each launch, nothing in the graph clears them."""
     import torch
     dtype, out = "f16", "f16"
     N, D, H, W, C, K = 1, 6, 8, 8, 128, 40          # few tiles, 54 stages: planned as a split reduction
@@ -979,31 +979,92 @@ def test_split_reduction_under_graph_capture(B, oracle):
     assert "/z" in name
     x, w = B.to_device(xb, dtype), B.to_device(wb, dtype)
     call = lambda y, st: B.tir_conv3d(x, w, y, N, D, H, W, C, K, 3, 3, 3, (1, 1, 1), (1, 1, 1), (1, 1, 1), 1, dtype, out, stream=st.cuda_stream)
-    for warm in (False, True):
-        st = torch.cuda.Stream()                    # a fresh stream: no workspace yet
+    ws = torch.full((B.tir_workspace_bytes(),), 0xAB, dtype=torch.uint8, device="cuda:0")
+    for registered in (False, True):
+        st = torch.cuda.Stream()                    # a fresh stream: no workspace
         y = _gpu_out(B, ref.shape, out)
         other = _gpu_out(B, ref.shape, out)
-        with torch.cuda.stream(st):
-            if warm:
-                call(other, st)                     # eager: allocates this stream's workspace
+        try:
+            with torch.cuda.stream(st):
+                if registered:
+                    B.tir_set_workspace(ws, stream=st)
+                torch.cuda.synchronize()
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=st):
+                    call(y, st)
+                for rep in range(3):
+                    y.fill_(float("nan"))
+                    g.replay()
+                    torch.cuda.synchronize()
+                    PT.assert_close(PT.gpu_to_f64(y), ref, S, f"conv3d graph replay {rep} ({'split' if registered else 'unsplit'} in the graph)")
+                    call(other, st)                     # eager work of the library between the replays
+                    torch.cuda.synchronize()
+                    PT.assert_close(PT.gpu_to_f64(other), ref, S, "conv3d eager between replays")
+                touched = int((ws[:65536] != 0xAB).sum()) > 0
+                assert touched == registered, "partial sums went to the workspace exactly when one was registered"
+        finally:
             torch.cuda.synchronize()
-            g = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(g, stream=st):
-                call(y, st)
-            for rep in range(3):
-                y.fill_(float("nan"))
-                g.replay()
-                torch.cuda.synchronize()
-                PT.assert_close(PT.gpu_to_f64(y), ref, S, f"conv3d graph replay {rep} ({'split' if warm else 'unsplit'} in the graph)")
-                call(other, st)                     # eager work of the library between the replays
-                torch.cuda.synchronize()
-                PT.assert_close(PT.gpu_to_f64(other), ref, S, "conv3d eager between replays")
+            B.tir_set_workspace(None, stream=st)
+
+
+def test_operator_entry_points_neither_allocate_nor_synchronise(B, oracle):
+    """Every operator entry point is called while its stream is being captured in GLOBAL mode, in which any
+    hipMalloc, hipFree or device / stream synchronisation by this thread is an error that also invalidates the
+    capture.  The stream has no workspace, and the problems include ones that would be planned as split reductions.
+    The capture must end cleanly and a replay must give the oracle's results."""
+    import torch
+    st = torch.cuda.Stream()
+    dev = lambda bits, dt: B.to_device(bits, dt)
+    cases = []          # (label, launch(stream), output tensor, reference, S)
+    # GEMM with few tiles and a long K (a split candidate), batched matmul, fused GEMM
+    wl = I.Workload("noalloc_gemm", "gemm", "f16", "f32", "u", 9601, M=128, N=128, K=4096)
+    a_bits, b_bits = wl.operands(); ref, S = PT.run_oracle(wl, a_bits, b_bits, oracle)
+    a, b, c = dev(a_bits, "f16"), dev(b_bits, "f16"), _gpu_out(B, ref.shape, "f32")
+    cases.append(("tir_gemm", lambda s, a=a, b=b, c=c: B.tir_gemm(a, b, c, 128, 128, 4096, 4096, 1, 128, 1, 128, 1, "f16", "f32", stream=s), c, ref, S))
+    wl = I.Workload("noalloc_bmm", "bmm", "i8", "i32", "i", 9602, batch=3, M=80, N=48, K=256, trans_b=True)
+    a_bits, b_bits = wl.operands(); ref, S = PT.run_oracle(wl, a_bits, b_bits, oracle)
+    a2, b2, c2 = dev(a_bits, "i8"), dev(b_bits, "i8"), _gpu_out(B, ref.shape, "i32")
+    cases.append(("tir_batch_matmul", lambda s, wl=wl, a=a2, b=b2, c=c2: B.run_workload(wl, a, b, c, stream=s), c2, ref, S))
+    wl = I.Workload("noalloc_conv", "conv2d", "f16", "f16", "n0.1", 9603, n=2, h=14, w=14, c=256, k=64, r=3, s=3, pad=(1, 1), ep_bias=True, ep_relu=True)
+    a_bits, b_bits = wl.operands(); ref, S = PT.run_oracle(wl, a_bits, b_bits, oracle)
+    a3, b3, c3, bias3 = dev(a_bits, "f16"), dev(b_bits, "f16"), _gpu_out(B, ref.shape, "f16"), B.bias_to_device(wl)
+    cases.append(("tir_conv2d_fused", lambda s, wl=wl, a=a3, b=b3, c=c3, bias=bias3: B.run_workload(wl, a, b, c, bias, stream=s, streaming=True), c3, ref, S))
+    xb = I.make_tensor("f16", "n0.1", 9604, (1, 6, 8, 8, 128)); wb = I.make_tensor("f16", "n0.1", 9605, (40, 3, 3, 3, 128))
+    ref, S = oracle.conv3d("f16", xb, wb, (1, 1, 1), (1, 1, 1), (1, 1, 1), 1)
+    x4, w4, y4 = dev(xb, "f16"), dev(wb, "f16"), _gpu_out(B, ref.shape, "f16")
+    cases.append(("tir_conv3d", lambda s: B.tir_conv3d(x4, w4, y4, 1, 6, 8, 8, 128, 40, 3, 3, 3, (1, 1, 1), (1, 1, 1), (1, 1, 1), 1, "f16", "f16", stream=s), y4, ref, S))
+    xb = I.make_tensor("f16", "n0.1", 9606, (2, 40, 64)); wb = I.make_tensor("f16", "n0.1", 9607, (32, 5, 64))
+    ref, S = oracle.conv1d("f16", xb, wb, 1, 2, 1, 1)
+    x5, w5, y5 = dev(xb, "f16"), dev(wb, "f16"), _gpu_out(B, ref.shape, "f16")
+    cases.append(("tir_conv1d", lambda s: B.tir_conv1d(x5, w5, y5, 2, 40, 64, 32, 5, 1, 2, 1, 1, "f16", "f16", stream=s), y5, ref, S))
+    xb = I.make_tensor("f16", "n0.1", 9608, (2, 9, 10, 64)); wb = I.make_tensor("f16", "n0.1", 9609, (48, 4, 4, 64))
+    ref, S = oracle.conv2d_transpose("f16", xb, wb, (2, 2), (1, 1), (1, 1), (0, 0), 1)
+    x6, w6, y6 = dev(xb, "f16"), dev(wb, "f16"), _gpu_out(B, ref.shape, "f16")
+    cases.append(("tir_conv2d_transpose", lambda s: B.tir_conv2d_transpose(x6, w6, y6, 2, 9, 10, 64, 48, 4, 4, (2, 2), (1, 1), (1, 1), (0, 0), 1, "f16", "f16", stream=s), y6, ref, S))
+    Qb, Kb, Vb = (I.make_tensor("f16", "u", 9610 + i, (2, n, 64)) for i, n in enumerate((100, 150, 150)))
+    ref, T = oracle.attention("f16", Qb, Kb, Vb, 0.125)
+    q7, k7, v7, o7 = dev(Qb, "f16"), dev(Kb, "f16"), dev(Vb, "f16"), _gpu_out(B, ref.shape, "f16")
+    cases.append(("tir_attention", lambda s: B.tir_attention(q7, k7, v7, o7, 2, 100, 150, 64, 0.125, "f16", "f16", stream=s), o7, ref, T))
+    with torch.cuda.stream(st):
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=st, capture_error_mode="global"):
+            for label, launch, *_ in cases:
+                _say(f"capture (global mode): {label}")
+                launch(st)
+        for _, _, outp, _, _ in cases:
+            outp.fill_(float("nan")) if outp.dtype.is_floating_point else outp.fill_(-123456789)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+    for label, _, outp, ref, S in cases:
+        PT.assert_close(PT.gpu_to_f64(outp), ref, S, f"{label} (captured in global mode)")
 
 
 def test_caller_provided_workspace(B, oracle):
-    """With a caller's buffer registered for a stream the library allocates nothing there: a capture on a fresh stream
-    splits at once (the partial sums land in the caller's buffer, the arrival counters are zero again after every
-    replay), a second, smaller problem reuses the buffer, and tir_set_workspace(None) goes back to the library's own."""
+    """With a caller's buffer registered for a stream, a capture on that stream splits (the partial sums land in the
+    caller's buffer, the arrival counters are zero again after every replay), a second, smaller problem reuses the
+    buffer, and after tir_set_workspace(None) launches run unsplit and leave the buffer alone."""
     import torch
     dtype, out = "f16", "f16"
     N, D, H, W, C, K = 1, 6, 8, 8, 128, 40          # few tiles, 54 stages: planned as a split reduction
@@ -1056,14 +1117,14 @@ def test_caller_provided_workspace(B, oracle):
             PT.assert_close(PT.gpu_to_f64(c), gref, gS, "split GEMM, caller's workspace")
             assert int((ws[:65536] != 0xAB).sum()) > 0
             assert int(ws[partial_bytes:].max()) == 0
-            # back to the library's own block: the caller's buffer stays untouched
-            _say("back to the library's workspace")
+            # registration removed: the same call runs unsplit and the caller's buffer stays untouched
+            _say("without the workspace")
             B.tir_set_workspace(None, stream=st)
             ws[:partial_bytes].fill_(0xAB)
             c.zero_()
             B.run_workload(wl, a, b, c, stream=st)
             torch.cuda.synchronize()
-            PT.assert_close(PT.gpu_to_f64(c), gref, gS, "split GEMM, library's workspace")
+            PT.assert_close(PT.gpu_to_f64(c), gref, gS, "GEMM after the workspace was removed")
             assert int((ws[:65536] != 0xAB).sum()) == 0
     finally:
         B.tir_debug_force_ksplit(0)
