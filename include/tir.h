@@ -21,7 +21,7 @@
  *     and arrival counters in a workspace.  The library owns none: it plans such a split only for launches on a
  *     stream for which the caller has registered a buffer (tir_set_workspace), and plans the same problem
  *     unsplit otherwise.  The result does not depend on the split's timing: the partial sums are added in a
- *     fixed order.
+ *     fixed order.  tir_gemm_split_static is the variant for callers that cannot provide a buffer either.
  *   - The output is fully overwritten (reduction init is 0; there is no alpha / beta), and must not
  *     overlap an input.
  *   - Inputs F16 / BF16 accumulate in fp32; input I8 accumulates in int32 (wrap-around on overflow,
@@ -207,6 +207,30 @@ const char* tir_last_error(void);
  */
 uint64_t tir_workspace_bytes(void);
 tir_status tir_set_workspace(tir_stream stream, void* ws, uint64_t bytes);
+
+/*
+ * GEMM with the reduction split over `slices` workgroups per output tile, for callers that can neither let a
+ * library allocate nor hand it a buffer of their own: code under HIP graph capture, tight serving loops with a
+ * fixed memory plan, harnesses that forbid hipMalloc.  Arguments and result as tir_gemm_fused (ep may be NULL);
+ * the partial sums and arrival counters live in a static device array of the library, TIR_STATIC_SCRATCH_BYTES
+ * of partial sums and TIR_STATIC_SCRATCH_TILES counters per GPU, held from the first call on that GPU until the
+ * process ends.  The call allocates and frees nothing, does not synchronise, and enqueues on `stream` one small
+ * kernel that zeroes the counters it will use, then the GEMM.
+ *   slices: 2 .. 64, and at most the number of 128-byte stages of the reduction (K * element size / 128, rounded
+ *     up), such that no slice is empty.
+ *   Limits: the operands must qualify for the fast kernels (see "Strides" at the top; TIR_ERR_UNSUPPORTED
+ *     otherwise), the tile chosen is at most 128 x 128, and tiles * slices * tile rows * tile columns * 4 bytes
+ *     must fit TIR_STATIC_SCRATCH_BYTES and tiles must fit TIR_STATIC_SCRATCH_TILES: a problem beyond that is
+ *     TIR_ERR_INVALID_ARG with a message that states both numbers.  Zero-sized M or N is a no-op; K == 0 is
+ *     rejected (nothing to split).
+ *   Every call on one GPU shares that GPU's array, which keeps the last call's contents: calls that may overlap
+ *   on one GPU (two streams, two threads) race and must be serialised by the caller.  Calls on one stream are safe.
+ */
+#define TIR_STATIC_SCRATCH_BYTES (8u << 20)
+#define TIR_STATIC_SCRATCH_TILES 1024
+tir_status tir_gemm_split_static(const void* A, const void* B, void* C, int64_t M, int64_t N, int64_t K, int64_t a_rs,
+                                 int64_t a_cs, int64_t b_rs, int64_t b_cs, int64_t c_rs, int64_t c_cs, tir_dtype in,
+                                 tir_dtype out, const tir_epilogue* ep, int slices, tir_stream stream);
 
 /*
  * Name of the kernel variant the next identical call would launch (for profiling harnesses), e.g.

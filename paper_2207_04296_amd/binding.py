@@ -23,7 +23,7 @@ EXPORTS = ["tir_gemm", "tir_batch_matmul", "tir_conv2d", "tir_last_error", "tir_
            "tir_tune_load", "tir_gemm_fused", "tir_batch_matmul_fused", "tir_conv2d_fused", "tir_attention",
            "tir_conv1d", "tir_conv3d", "tir_conv2d_transpose", "tir_debug_force_ksplit", "tir_debug_fastdiv",
            "tir_conv2d_transpose_variant", "tir_conv3d_variant", "tir_tune_conv3d", "tir_tune_conv2d_transpose",
-           "tir_workspace_bytes", "tir_set_workspace"]
+           "tir_workspace_bytes", "tir_set_workspace", "tir_gemm_split_static"]
 
 
 class Epilogue(ctypes.Structure):
@@ -119,6 +119,8 @@ def lib() -> ctypes.CDLL:
     L.tir_workspace_bytes.restype = ctypes.c_uint64
     L.tir_set_workspace.argtypes = [vp, vp, ctypes.c_uint64]
     L.tir_set_workspace.restype = ci
+    L.tir_gemm_split_static.argtypes = [vp, vp, vp] + [i64] * 9 + [ci, ci, pe, ci, vp]
+    L.tir_gemm_split_static.restype = ci
     L.tir_tune_count.restype = ci
     L.tir_tune_clear.restype = None
     L.tir_tune_save.argtypes = [ctypes.c_char_p]
@@ -225,6 +227,20 @@ def tir_debug_fastdiv(d: int, m: int) -> int:
 
 def tir_debug_force_ksplit(slices: int) -> None:
     lib().tir_debug_force_ksplit(int(slices))
+
+
+TIR_STATIC_SCRATCH_BYTES, TIR_STATIC_SCRATCH_TILES = 8 << 20, 1024
+
+
+def tir_gemm_split_static_status(A, B, C, M, N, K, a_rs, a_cs, b_rs, b_cs, c_rs, c_cs, in_dtype, out_dtype, ep, slices, stream=0) -> int:
+    return lib().tir_gemm_split_static(_ptr(A), _ptr(B), _ptr(C), M, N, K, a_rs, a_cs, b_rs, b_cs, c_rs, c_cs, _code(in_dtype),
+                                       _code(out_dtype), _ep_arg(ep), int(slices), stream)
+
+
+def tir_gemm_split_static(A, B, C, M, N, K, a_rs, a_cs, b_rs, b_cs, c_rs, c_cs, in_dtype, out_dtype, ep=None, slices=2, stream=None) -> None:
+    """tir_gemm_fused with the reduction split `slices` ways over the library's static device scratch (allocates nothing)."""
+    _check(tir_gemm_split_static_status(A, B, C, M, N, K, a_rs, a_cs, b_rs, b_cs, c_rs, c_cs, in_dtype, out_dtype, ep, slices,
+                                        _stream(stream)))
 
 
 def tir_workspace_bytes() -> int:

@@ -1028,6 +1028,79 @@ tir_status tir_conv2d_transpose(const void* x, const void* w, void* y, int64_t N
     return launch(plan, (hipStream_t)stream);
 }
 
+// ------------------------------------------------------------------------------- split GEMM on static scratch
+}  // extern "C"
+
+namespace tir {
+// Partial sums, then arrival counters, of tir_gemm_split_static.  In host code this name is only a handle for
+// hipGetSymbolAddress: every use of the memory goes through the per-device address kept in g_static_ptr.
+static __device__ __align__(256) unsigned char scratch[TIR_STATIC_SCRATCH_BYTES + TIR_STATIC_SCRATCH_TILES * 4];
+static const int kMaxDevices = 64;
+static std::mutex g_static_mu;
+static void* g_static_ptr[kMaxDevices] = {};
+
+// Address of the current device's copy of `scratch` (looked up once per device).
+static tir_status static_scratch(void** out) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(TIR_ERR_LAUNCH, "hipGetDevice failed: %s", hipGetErrorString(e));
+    if (dev < 0 || dev >= kMaxDevices) return fail(TIR_ERR_UNSUPPORTED, "device index %d beyond %d", dev, kMaxDevices - 1);
+    std::lock_guard<std::mutex> lock(g_static_mu);
+    if (!g_static_ptr[dev]) {
+        void* ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr) {
+            (void)hipGetLastError();
+            return fail(TIR_ERR_LAUNCH, "hipGetSymbolAddress of the static scratch failed on device %d: %s", dev, hipGetErrorString(e));
+        }
+        g_static_ptr[dev] = ptr;
+    }
+    *out = g_static_ptr[dev];
+    return TIR_OK;
+}
+}  // namespace tir
+
+extern "C" {
+
+tir_status tir_gemm_split_static(const void* A, const void* B, void* C, int64_t M, int64_t N, int64_t K, int64_t a_rs,
+                                 int64_t a_cs, int64_t b_rs, int64_t b_cs, int64_t c_rs, int64_t c_cs, tir_dtype in,
+                                 tir_dtype out, const tir_epilogue* ep, int slices, tir_stream stream_) {
+    hipStream_t stream = (hipStream_t)stream_;
+    if (slices < 2 || slices > 64) return fail(TIR_ERR_INVALID_ARG, "tir_gemm_split_static: slices = %d, must be in [2, 64]", slices);
+    if (K == 0) return fail(TIR_ERR_INVALID_ARG, "tir_gemm_split_static: K = 0, there is no reduction to split");
+    const SplitLimits sl = {(int64_t)TIR_STATIC_SCRATCH_BYTES, (int64_t)TIR_STATIC_SCRATCH_TILES, slices};
+    Plan plan;
+    tir_status st = plan_gemm(true, A, B, C, 1, M, N, K, 0, a_rs, a_cs, 0, b_rs, b_cs, 0, c_rs, c_cs, (int)in, (int)out, ep, sl, &plan);
+    if (st == TIR_ERR_UNSUPPORTED && plan.key.kind == 0 && !plan.v) {
+        // no variant splits this problem `slices` ways inside the static scratch: say which limit it is
+        if (plan.key.amode != A_KMAJOR)
+            return fail(TIR_ERR_UNSUPPORTED, "tir_gemm_split_static: operand strides / alignment need the general kernel, which has no split reduction");
+        const SplitLimits any = {(int64_t)1 << 60, (int64_t)1 << 40, slices};
+        const Choice c = pick(plan.key.dt, plan.key.out, plan.key.amode, plan.key.bmode, 1, M, N, K, any);
+        if (c.v) {
+            const int64_t tiles = ((M + c.v->bm - 1) / c.v->bm) * ((N + c.v->bn - 1) / c.v->bn);
+            return fail(TIR_ERR_INVALID_ARG, "tir_gemm_split_static: %lld tiles x %d slices need %lld bytes of partial sums and %lld counters; the static scratch holds %u bytes and %d counters",
+                        (long long)tiles, slices, (long long)(tiles * slices * c.v->bm * c.v->bn * 4), (long long)tiles, (unsigned)TIR_STATIC_SCRATCH_BYTES, (int)TIR_STATIC_SCRATCH_TILES);
+        }
+        return fail(TIR_ERR_INVALID_ARG, "tir_gemm_split_static: a reduction of K = %lld cannot be cut into %d non-empty slices of whole stages", (long long)K, slices);
+    }
+    if (st != TIR_OK) return st;
+    if (!plan.v) return TIR_OK;                       // M or N is zero
+    if (plan.p.ksplit != slices) return fail(TIR_ERR_UNSUPPORTED, "tir_gemm_split_static: variant %s cannot split %d ways", plan.v->name, slices);
+    void* base = nullptr;
+    st = static_scratch(&base);
+    if (st != TIR_OK) return st;
+    plan.p.ws = base;
+    plan.p.ws_count = (unsigned*)((char*)base + TIR_STATIC_SCRATCH_BYTES);
+    // The array keeps whatever the last call left: the counters of the tiles this launch uses start at zero
+    // (a kernel, not a memset: the call may be captured into a graph).
+    const int ntiles = plan.p.tiles_m * plan.p.tiles_n;
+    hipLaunchKernelGGL(clear_counters_kernel, dim3((unsigned)((ntiles + 255) / 256)), dim3(256), 0, stream, plan.p.ws_count, ntiles);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(TIR_ERR_LAUNCH, "clearing the static scratch counters failed: %s", hipGetErrorString(e));
+    return run(plan, stream);
+}
+
 const char* tir_version(void) { return "0.1"; }
 
 }  // extern "C"

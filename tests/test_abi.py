@@ -220,6 +220,26 @@ def test_output_policy_is_a_checked_field_of_the_epilogue():
     assert not hasattr(B.lib(), "tir_set_output_policy")       # no process-wide policy
 
 
+def test_split_static_rejects_what_its_scratch_cannot_hold():
+    """tir_gemm_split_static checks slices, the copy mode and the size of its static scratch before any HIP call."""
+    def call(M=128, N=128, K=4096, slices=4, a_rs=None, in_dtype="f16", out_dtype="f32"):
+        return B.tir_gemm_split_static_status(FAKE, FAKE, FAKE, M, N, K, a_rs or K, 1, 1, K, N, 1, in_dtype, out_dtype, None, slices)
+    assert call(slices=1) == B.TIR_ERR_INVALID_ARG and "slices" in B.last_error()
+    assert call(slices=65) == B.TIR_ERR_INVALID_ARG
+    assert call(K=0) == B.TIR_ERR_INVALID_ARG
+    assert call(M=0) == B.TIR_OK                                              # nothing to do
+    assert call(K=4001, a_rs=4001) == B.TIR_ERR_UNSUPPORTED and "general kernel" in B.last_error()
+    assert call(K=128, slices=4) == B.TIR_ERR_INVALID_ARG and "non-empty slices" in B.last_error()     # two stages, four slices
+    # 4096 x 4096 outputs: at least 1024 tiles of 128 x 128 x 4 slices x 64 KiB = 256 MiB of partial sums
+    assert call(M=4096, N=4096, K=4096, slices=4) == B.TIR_ERR_INVALID_ARG
+    msg = B.last_error()
+    assert str(B.TIR_STATIC_SCRATCH_BYTES) in msg and str(B.TIR_STATIC_SCRATCH_TILES) in msg, msg
+    assert call(in_dtype="f16", out_dtype="i32") == B.TIR_ERR_UNSUPPORTED
+    header = (ROOT / "include" / "tir.h").read_text()
+    assert "#define TIR_STATIC_SCRATCH_BYTES (8u << 20)" in header and "#define TIR_STATIC_SCRATCH_TILES 1024" in header
+    assert (B.TIR_STATIC_SCRATCH_BYTES, B.TIR_STATIC_SCRATCH_TILES) == (8 << 20, 1024)
+
+
 def test_caller_workspace_arguments_are_checked():
     """tir_set_workspace rejects a buffer that is too small or not 256-byte aligned before it touches the device."""
     need = B.tir_workspace_bytes()
