@@ -1,63 +1,131 @@
 #!/usr/bin/env python3
 """Benchmark of the tensor-contraction hot path on one MI355X.
 
-    python bench.py --gpus 1 --steps K --warmup W [--workload NAME] [--hot] [--eager] [--no-operators]
+    python bench.py --gpus 1 --steps K --warmup W [--replays R] [--workload NAME] [--hot] [--no-operators]
 
 A step is one call of the C ABI for the headline workload (default: the fp16 NHWC conv2d
 16x56x56x64 -> 64, 3x3, stride 1, pad 1 with fp16 output), i.e. one pass of the whole path:
 fused-iterator decode, tile decomposition, global->LDS copy stage, MFMA accumulation, fused
 epilogue store.  Before the timed region the variants are measured once (tir_tune_*, the paper's
-search reduced to a table; --no-tune keeps the built-in scoring rule).  Operands are resident in
-device memory before the timed region.  By default the
-K steps rotate over enough distinct operand / output sets to exceed the 256 MB memory-side cache
-plus L2, so every step reads its inputs from HBM ("cold"); --hot reuses one set.  The K launches
-are captured in one HIP graph (the kernels are microseconds long, a Python launch loop would
-measure the host), replayed once inside the timed region; --eager launches them one by one.
+search reduced to a table; --no-tune keeps the built-in scoring rule, --records FILE loads kept
+records instead of measuring and writes them after measuring).  Operands are resident in device
+memory before the timed region.
 
-Prints ONE JSON line.  `value` = algorithmic TFLOP/s of the whole run (2*M*N*K of the fused GEMM
-view per step).  `roofline` prices the kernel against the dense fp16 MFMA peak; `cpu_baseline`
-times the CPU oracle on the same workload on this machine's host cores; `operators` lists every other
-benchmark configuration, plain and with a fused consumer (bias / ReLU / down-cast / int8
-requantisation), hot cache, for context.
+Timing protocol.  The K steps are captured in one HIP graph (the kernels are microseconds long, a
+Python launch loop would measure the host).  The timed region is one replay of that graph, bracketed
+by device synchronisations; it is repeated R times (default 31) and the MEDIAN replay is reported
+(minimum and maximum beside it), so the line does not hang on one sample of a fraction of a
+millisecond.  Cold mode (default): the K steps walk over enough distinct operand / output sets to
+exceed the 256 MB memory-side cache plus the L2s - the number of sets does not depend on K - and
+before every timed replay a 2 x 320 MB device copy (untimed) pushes whatever the previous replay
+left out of the caches, so every step reads its inputs from HBM whatever K is.  --hot reuses one
+set and skips the flush.  Outputs are written with the library's default (cached) policy; the same
+run with streaming output stores is reported beside it.
+
+Prints ONE JSON line.  `value` = algorithmic TFLOP/s of the median replay by the host clock
+(2*M*N*K of the fused GEMM view per step).  `roofline` prices the headline kernel against the roof
+that binds it (min of the MFMA peak and arithmetic intensity x 8 TB/s) with HIP-event times of the
+same replays; `roofline_gemm` is the same record for the 4096^3 fp16 GEMM; `cpu_baseline` times
+the CPU oracle on the same workload on this machine's host cores; `operators` lists every other
+benchmark configuration, plain and with a fused consumer, hot cache, and cold as well where the
+roofline that binds them is HBM.
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import statistics
 import sys
 import time
 
 PEAK_TFLOPS = {"f16": 2516.6, "bf16": 2516.6, "i8": 5033.2}   # 256 CU x 2.4 GHz x 4096 (8192) flop/clk/CU
 HBM_GBS = 8000.0
 CACHE_BYTES = 256e6 + 8 * 4e6     # memory-side cache + the eight L2s
+FLUSH_BYTES = 320 << 20           # source and destination of the flush copy, each larger than the caches
 
-# HBM bytes per launch of the headline kernel from rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled
-# by the same counters on a copy kernel of known size; see profiles/.  None until measured.
+# HBM-side bytes per launch from rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), each scaled by what the same counter
+# reads for a device copy of known size; produced by `python -m paper_2207_04296_amd.profile`, which prints the line
+# to paste here and writes the summary under profiles/.  Keyed by (workload, variant): a figure measured on another
+# variant than the one timed is not reported.
 MEASURED_TRAFFIC_BYTES = {
-    "c2a_conv56x64_f16": 7192720 + 6422528,      # FETCH_SIZE 3513.3 KiB x 1.9993, WRITE_SIZE 6272 KiB x 1.0
-    "c4a_gemm4096_f16": 201415700 + 67108864,    # FETCH_SIZE 98382 KiB x 1.9993, WRITE_SIZE 65536 KiB x 1.0
+    ("c2a_conv56x64_f16", "f16_f16_patch256x64_conv"): 7195362 + 6422528,
+    ("c4a_gemm4096_f16", "f16_f32_t256x128w4x2s3c4_ak_bn"): 268532434 + 67108864,
 }
 
 
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=480)
-    ap.add_argument("--warmup", type=int, default=48)
-    ap.add_argument("--workload", default="c2a_conv56x64_f16")
-    ap.add_argument("--hot", action="store_true", help="reuse one operand set (cache-resident inputs)")
-    ap.add_argument("--eager", action="store_true", help="launch step by step instead of one HIP graph")
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--replays", type=int, default=31, help="timed replays of the K-step graph; the median is reported")
+    ap.add_argument("--workload", default=None, help="headline workload (default c2a_conv56x64_f16); with --tune-only: tune just this one")
+    ap.add_argument("--hot", action="store_true", help="reuse one operand set (cache-resident inputs), no flush")
     ap.add_argument("--no-operators", action="store_true", help="skip the per-operator context table")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-tune", action="store_true",
                     help="use the built-in scoring rule instead of measuring the variants first (tir_tune_*)")
+    ap.add_argument("--records", default=None,
+                    help="file of kept tuning records: loaded instead of measuring if it exists, written after measuring otherwise")
+    ap.add_argument("--tune-only", action="store_true", help="measure the variants of every bench workload, write --records, exit")
     ap.add_argument("--profile-run", action="store_true",
-                    help="only the headline timed region (for rocprofv3): no tuning trials, hot rerun, operator table, probe or oracle")
+                    help="only the headline timed region (for rocprofv3): no tuning trials (use --records), hot rerun, "
+                         "operator table, probe or oracle; 2 replays")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="instead of the workload, run 8 device-to-device copies of 64 MiB (a plain copy kernel of "
                          "known size, to scale the FETCH_SIZE / WRITE_SIZE counters)")
     return ap.parse_args()
+
+
+class Harness:
+    """Device plumbing shared by every measurement: one stream, its split-reduction workspace, the flush buffers."""
+
+    def __init__(self, torch, B):
+        self.torch, self.B = torch, B
+        self.stream = torch.cuda.Stream()
+        # reductions are split over workgroups only on a stream with a registered workspace (tir_set_workspace)
+        self.ws = torch.empty(B.tir_workspace_bytes(), dtype=torch.uint8, device="cuda:0")
+        B.tir_set_workspace(self.ws, stream=self.stream)
+        self.flush_src = torch.ones(FLUSH_BYTES, dtype=torch.uint8, device="cuda:0")
+        self.flush_dst = torch.empty_like(self.flush_src)
+        torch.cuda.synchronize()
+
+    def flush(self):
+        """Push everything out of the L2s and the memory-side cache (enqueued on the harness stream)."""
+        self.flush_dst.copy_(self.flush_src)
+
+    def timed(self, launch, steps, warmup, replays, cold):
+        """launch(i, stream) enqueues step i.  Returns (wall seconds per replay, HIP-event seconds per replay), lists
+        of `replays` samples; one replay = `steps` launches from one HIP graph."""
+        torch = self.torch
+        with torch.cuda.stream(self.stream):
+            for i in range(warmup):
+                launch(i, self.stream)
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=self.stream):
+                for i in range(steps):
+                    launch(i, self.stream)
+            graph.replay()            # untimed: the first replay uploads the graph
+            torch.cuda.synchronize()
+            walls, events = [], []
+            for _ in range(replays):
+                if cold:
+                    self.flush()
+                e0 = torch.cuda.Event(enable_timing=True)
+                e1 = torch.cuda.Event(enable_timing=True)
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                e0.record(self.stream)
+                graph.replay()
+                e1.record(self.stream)
+                torch.cuda.synchronize()
+                t1 = time.perf_counter()
+                walls.append(t1 - t0)
+                events.append(e0.elapsed_time(e1) * 1e-3)
+            del graph
+        return walls, events
 
 
 def make_sets(B, wl, count):
@@ -70,36 +138,19 @@ def make_sets(B, wl, count):
     return sets
 
 
-def timed_run(torch, B, wl, sets, steps, warmup, eager, streaming=False):
-    """Returns (wall seconds for `steps` launches, HIP-event seconds for the same region)."""
-    stream = torch.cuda.Stream()
+def cold_set_count(wl):
+    """Distinct operand sets a cold run rotates over: 1.25 x the caches, whatever the step count."""
+    return max(2, int(CACHE_BYTES * 1.25 / wl.min_bytes()) + 1)
+
+
+def time_workload(H, wl, sets, steps, warmup, replays, cold, streaming=False):
     n = len(sets)
-    with torch.cuda.stream(stream):
-        for i in range(warmup):
-            B.run_workload(wl, *sets[i % n], stream=stream, streaming=streaming)
-        torch.cuda.synchronize()
-        graph = None
-        if not eager:
-            graph = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(graph, stream=stream):
-                for i in range(steps):
-                    B.run_workload(wl, *sets[i % n], stream=stream, streaming=streaming)
-            graph.replay()            # untimed: first replay uploads the graph
-            torch.cuda.synchronize()
-        e0 = torch.cuda.Event(enable_timing=True)
-        e1 = torch.cuda.Event(enable_timing=True)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        e0.record(stream)
-        if graph is not None:
-            graph.replay()
-        else:
-            for i in range(steps):
-                B.run_workload(wl, *sets[i % n], stream=stream, streaming=streaming)
-        e1.record(stream)
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-        return t1 - t0, e0.elapsed_time(e1) * 1e-3
+    return H.timed(lambda i, st: H.B.run_workload(wl, *sets[i % n], stream=st, streaming=streaming), steps, warmup, replays, cold)
+
+
+def stats(samples, scale=1.0):
+    return {"median": round(statistics.median(samples) * scale, 6), "min": round(min(samples) * scale, 6),
+            "max": round(max(samples) * scale, 6)}
 
 
 def variant_of(B, wl):
@@ -109,6 +160,38 @@ def variant_of(B, wl):
                                     wl.groups, wl.dtype, wl.out)
     b_rs, b_cs = (1, wl.K) if wl.trans_b else (wl.N, 1)
     return B.tir_gemm_variant(wl.batch, wl.M, wl.N, wl.K, wl.K, 1, b_rs, b_cs, wl.N, 1, wl.dtype, wl.out)
+
+
+def roof(dtype, flops, nbytes):
+    """The roof that binds: ("mfma" | "hbm", attainable TFLOP/s = min(peak, arithmetic intensity x 8 TB/s))."""
+    peak = PEAK_TFLOPS[dtype]
+    by_hbm = flops / nbytes * HBM_GBS / 1e3
+    return ("hbm", by_hbm) if by_hbm < peak else ("mfma", peak)
+
+
+def roofline_record(B, wl, event_s_per_launch, cache_note):
+    """Roofline object of one kernel: achieved / peak in the unit of the roof that binds it, both fractions beside."""
+    med = statistics.median(event_s_per_launch)
+    flops, nbytes = wl.flops(), wl.min_bytes()
+    bound, attain = roof(wl.dtype, flops, nbytes)
+    tf = flops / med / 1e12
+    gbs = nbytes / med / 1e9
+    variant = variant_of(B, wl)
+    traffic = MEASURED_TRAFFIC_BYTES.get((wl.name, variant))
+    rec = {"bound": bound}
+    if bound == "hbm":
+        rec.update({"achieved": round(gbs, 1), "peak": HBM_GBS, "unit": "GB/s", "frac": round(gbs / HBM_GBS, 4)})
+    else:
+        rec.update({"achieved": round(tf, 3), "peak": PEAK_TFLOPS[wl.dtype], "unit": "TFLOP/s", "frac": round(tf / PEAK_TFLOPS[wl.dtype], 4)})
+    rec.update({"traffic": traffic,
+                "traffic_source": None if traffic is None else "profiles/ (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, copy-calibrated), same variant",
+                "frac_mfma": round(tf / PEAK_TFLOPS[wl.dtype], 4), "frac_hbm": round(gbs / HBM_GBS, 4),
+                "achieved_tflops": round(tf, 3), "achieved_gbs": round(gbs, 1),
+                "attainable_tflops": round(attain, 1), "frac_attainable": round(tf / attain, 4),
+                "kernel": variant, "workload": wl.name, "cache": cache_note,
+                "avg_launch_us": round(med * 1e6, 3), "launch_us": stats(event_s_per_launch, 1e6),
+                "algorithmic_flop_per_launch": flops, "algorithmic_bytes_per_launch": nbytes})
+    return rec
 
 
 def mfma_ceiling(torch, B):
@@ -132,94 +215,66 @@ def mfma_ceiling(torch, B):
     return out
 
 
-def attention_row(torch, B, I):
+def op_row(name, variant, out, fused, dtype, sec, flops, nbytes, sec_cold=None):
+    tf = flops / sec / 1e12
+    bound, attain = roof(dtype, flops, nbytes)
+    row = {"workload": name, "variant": variant, "out": out, "fused": fused, "us": round(sec * 1e6, 3), "tflops": round(tf, 2),
+           "frac_mfma_peak": round(tf / PEAK_TFLOPS[dtype], 4), "bound": bound, "frac_attainable": round(tf / attain, 4),
+           "gbs": round(nbytes / sec / 1e9, 1), "cache": "hot"}
+    if sec_cold is not None:
+        row.update({"us_cold": round(sec_cold * 1e6, 3), "gbs_cold": round(nbytes / sec_cold / 1e9, 1),
+                    "frac_hbm_cold": round(nbytes / sec_cold / 1e9 / HBM_GBS, 4),
+                    "frac_attainable_cold": round(flops / sec_cold / 1e12 / attain, 4)})
+    return row
+
+
+def attention_row(H, I):
     """The two attention matmuls of configs[2] (QK^T, then PV) as ONE kernel with the softmax between them:
     192 heads of 128 x 128 x 64, fp16 in and out.  FLOPs count both matmuls; bytes Q, K, V and O once."""
+    B = H.B
     batch, M, N, d = 192, 128, 128, 64
-    q = B.to_device(I.make_tensor("f16", "u", 3000, (batch, M, d)), "f16")
-    k = B.to_device(I.make_tensor("f16", "u", 3001, (batch, N, d)), "f16")
-    v = B.to_device(I.make_tensor("f16", "u", 3101, (batch, N, d)), "f16")
-    o = B.empty_out((batch, M, d), "f16")
-    stream = torch.cuda.Stream()
-    steps = 200
-    with torch.cuda.stream(stream):
-        for _ in range(5):
-            B.tir_attention(q, k, v, o, batch, M, N, d, 0.125, "f16", "f16", stream=stream)
-        torch.cuda.synchronize()
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph, stream=stream):
-            for _ in range(steps):
-                B.tir_attention(q, k, v, o, batch, M, N, d, 0.125, "f16", "f16", stream=stream)
-        graph.replay()
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record(stream)
-        graph.replay()
-        e1.record(stream)
-        torch.cuda.synchronize()
-    sec = e0.elapsed_time(e1) * 1e-3 / steps
-    flops = 2.0 * batch * M * N * d * 2
     nbytes = 2.0 * batch * (M * d + 2 * N * d + M * d)
-    tf = flops / sec / 1e12
-    return {"workload": "c3_attention_f16 (QK^T, softmax, PV in one kernel)", "variant": "attention_kernel<f16,f16,64>",
-            "out": "f16", "fused": "softmax", "us": round(sec * 1e6, 3), "tflops": round(tf, 2),
-            "frac_mfma_peak": round(tf / PEAK_TFLOPS["f16"], 4),
-            "frac_attainable": round(tf / min(PEAK_TFLOPS["f16"], flops / nbytes * HBM_GBS / 1e3), 4),
-            "gbs": round(nbytes / sec / 1e9, 1), "cache": "hot"}
+
+    def make():
+        return (B.to_device(I.make_tensor("f16", "u", 3000, (batch, M, d)), "f16"), B.to_device(I.make_tensor("f16", "u", 3001, (batch, N, d)), "f16"),
+                B.to_device(I.make_tensor("f16", "u", 3101, (batch, N, d)), "f16"), B.empty_out((batch, M, d), "f16"))
+    sets = [make() for _ in range(max(2, int(CACHE_BYTES * 1.25 / nbytes) + 1))]
+    _, ev_cold = H.timed(lambda i, st: B.tir_attention(*sets[i % len(sets)], batch, M, N, d, 0.125, "f16", "f16", stream=st), 40, 5, 7, True)
+    _, ev = H.timed(lambda i, st: B.tir_attention(*sets[0], batch, M, N, d, 0.125, "f16", "f16", stream=st), 200, 5, 5, False)
+    return op_row("c3_attention_f16 (QK^T, softmax, PV in one kernel)", "attention_kernel<f16,f16,64>", "f16", "softmax", "f16",
+                  statistics.median(ev) / 200, 2.0 * batch * M * N * d * 2, nbytes, statistics.median(ev_cold) / 40)
 
 
-def _graph_time(torch, fn, steps=100):
-    stream = torch.cuda.Stream()
-    with torch.cuda.stream(stream):
-        for _ in range(5):
-            fn(stream)
-        torch.cuda.synchronize()
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph, stream=stream):
-            for _ in range(steps):
-                fn(stream)
-        graph.replay()
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record(stream)
-        graph.replay()
-        e1.record(stream)
-        torch.cuda.synchronize()
-    return e0.elapsed_time(e1) * 1e-3 / steps
-
-
-def other_conv_rows(torch, B, I, tune=True):
+def other_conv_rows(H, I, tune=True):
     """1-D, 3-D and transposed 2-D convolution (the rest of the paper's operator set), fp16, synthetic shapes."""
+    B = H.B
     rows = []
-
-    def row(name, variant, sec, flops, nbytes):
-        tf = flops / sec / 1e12
-        rows.append({"workload": name, "variant": variant, "out": "f16", "fused": "",
-                     "us": round(sec * 1e6, 3), "tflops": round(tf, 2), "frac_mfma_peak": round(tf / PEAK_TFLOPS["f16"], 4),
-                     "frac_attainable": round(tf / min(PEAK_TFLOPS["f16"], flops / nbytes * HBM_GBS / 1e3), 4),
-                     "gbs": round(nbytes / sec / 1e9, 1), "cache": "hot"})
     dev = lambda shape, seed: B.to_device(I.make_tensor("f16", "n0.1", seed, shape), "f16")
+    hot = lambda fn: statistics.median(H.timed(lambda i, st: fn(st), 100, 5, 5, False)[1]) / 100
     # conv1d: 16 x 4096 x 128 -> 128, 9 taps
     N, L, C, K, R = 16, 4096, 128, 128, 9
     x, w, y = dev((N, L, C), 7000), dev((K, R, C), 7001), B.empty_out((N, L, K), "f16")
     if tune:      # a 1-D convolution is planned as the 2-D one on an image of height 1: same record
-        B.tir_tune_conv2d(x, w, y, N, 1, L, C, K, 1, R, 1, 1, 0, 4, 1, 1, 1, "f16", "f16", reps=10)
-    sec = _graph_time(torch, lambda st: B.tir_conv1d(x, w, y, N, L, C, K, R, 1, 4, 1, 1, "f16", "f16", stream=st))
-    row("c1d_16x4096x128_k9_f16", B.tir_conv2d_variant(N, 1, L, C, K, 1, R, 1, 1, 0, 4, 1, 1, 1, "f16", "f16"), sec, 2.0 * N * L * K * R * C, 2.0 * (N * L * C + K * R * C + N * L * K))
+        B.tir_tune_conv2d(x, w, y, N, 1, L, C, K, 1, R, 1, 1, 0, 4, 1, 1, 1, "f16", "f16", reps=10, stream=H.stream)
+    sec = hot(lambda st: B.tir_conv1d(x, w, y, N, L, C, K, R, 1, 4, 1, 1, "f16", "f16", stream=st))
+    rows.append(op_row("c1d_16x4096x128_k9_f16", B.tir_conv2d_variant(N, 1, L, C, K, 1, R, 1, 1, 0, 4, 1, 1, 1, "f16", "f16"), "f16", "", "f16", sec,
+                       2.0 * N * L * K * R * C, 2.0 * (N * L * C + K * R * C + N * L * K)))
     # conv3d: 1 x 10 x 16 x 16 x 128 -> 64, 3x3x3
-    N, D, H, W, C, K = 1, 10, 16, 16, 128, 64
-    x, w, y = dev((N, D, H, W, C), 7010), dev((K, 3, 3, 3, C), 7011), B.empty_out((N, D, H, W, K), "f16")
+    N, D, Hh, W, C, K = 1, 10, 16, 16, 128, 64
+    x, w, y = dev((N, D, Hh, W, C), 7010), dev((K, 3, 3, 3, C), 7011), B.empty_out((N, D, Hh, W, K), "f16")
     if tune:
-        B.tir_tune_conv3d(x, w, y, N, D, H, W, C, K, 3, 3, 3, (1, 1, 1), (1, 1, 1), (1, 1, 1), 1, "f16", "f16", reps=10)
-    sec = _graph_time(torch, lambda st: B.tir_conv3d(x, w, y, N, D, H, W, C, K, 3, 3, 3, (1, 1, 1), (1, 1, 1), (1, 1, 1), 1, "f16", "f16", stream=st))
-    row("c3d_10x16x16x128_k3_f16", B.tir_conv3d_variant(N, D, H, W, C, K, 3, 3, 3, (1, 1, 1), (1, 1, 1), (1, 1, 1), 1, "f16", "f16"), sec, 2.0 * N * D * H * W * K * 27 * C, 2.0 * (N * D * H * W * (C + K) + K * 27 * C))
+        B.tir_tune_conv3d(x, w, y, N, D, Hh, W, C, K, 3, 3, 3, (1, 1, 1), (1, 1, 1), (1, 1, 1), 1, "f16", "f16", reps=10, stream=H.stream)
+    sec = hot(lambda st: B.tir_conv3d(x, w, y, N, D, Hh, W, C, K, 3, 3, 3, (1, 1, 1), (1, 1, 1), (1, 1, 1), 1, "f16", "f16", stream=st))
+    rows.append(op_row("c3d_10x16x16x128_k3_f16", B.tir_conv3d_variant(N, D, Hh, W, C, K, 3, 3, 3, (1, 1, 1), (1, 1, 1), (1, 1, 1), 1, "f16", "f16"), "f16", "",
+                       "f16", sec, 2.0 * N * D * Hh * W * K * 27 * C, 2.0 * (N * D * Hh * W * (C + K) + K * 27 * C)))
     # transposed conv2d: 16 x 28 x 28 x 64 -> 56 x 56 x 64, 4x4, stride 2 (FLOPs of the taps that exist, not of the gather's zeros)
-    N, H, W, C, K = 16, 28, 28, 64, 64
-    x, w, y = dev((N, H, W, C), 7020), dev((K, 4, 4, C), 7021), B.empty_out((N, 56, 56, K), "f16")
+    N, Hh, W, C, K = 16, 28, 28, 64, 64
+    x, w, y = dev((N, Hh, W, C), 7020), dev((K, 4, 4, C), 7021), B.empty_out((N, 56, 56, K), "f16")
     if tune:
-        B.tir_tune_conv2d_transpose(x, w, y, N, H, W, C, K, 4, 4, (2, 2), (1, 1), (1, 1), (0, 0), 1, "f16", "f16", reps=10)
-    sec = _graph_time(torch, lambda st: B.tir_conv2d_transpose(x, w, y, N, H, W, C, K, 4, 4, (2, 2), (1, 1), (1, 1), (0, 0), 1, "f16", "f16", stream=st))
-    row("t2d_28x28x64_k4s2_f16", B.tir_conv2d_transpose_variant(N, H, W, C, K, 4, 4, (2, 2), (1, 1), (1, 1), (0, 0), 1, "f16", "f16"), sec, 2.0 * N * H * W * K * 16 * C, 2.0 * (N * H * W * C + K * 16 * C + N * 56 * 56 * K))
+        B.tir_tune_conv2d_transpose(x, w, y, N, Hh, W, C, K, 4, 4, (2, 2), (1, 1), (1, 1), (0, 0), 1, "f16", "f16", reps=10, stream=H.stream)
+    sec = hot(lambda st: B.tir_conv2d_transpose(x, w, y, N, Hh, W, C, K, 4, 4, (2, 2), (1, 1), (1, 1), (0, 0), 1, "f16", "f16", stream=st))
+    rows.append(op_row("t2d_28x28x64_k4s2_f16", B.tir_conv2d_transpose_variant(N, Hh, W, C, K, 4, 4, (2, 2), (1, 1), (1, 1), (0, 0), 1, "f16", "f16"), "f16", "",
+                       "f16", sec, 2.0 * N * Hh * W * K * 16 * C, 2.0 * (N * Hh * W * C + K * 16 * C + N * 56 * 56 * K)))
     return rows
 
 
@@ -243,6 +298,10 @@ def cpu_baseline(wl):
         reps += 1
     return {"value": wl.flops() * reps / t / 1e12, "unit": "TFLOP/s", "cores": oracle.get_threads(),
             "kind": "oracle", "sample": f"{sample_note}, {reps} repetitions, fp64 direct loops incl. sum|a*b|"}
+
+
+def all_bench_workloads(I):
+    return list(I.WORKLOADS.items()) + list(I.FUSED_WORKLOADS.items()) + list(I.MORE_WORKLOADS.items())
 
 
 def main():
@@ -270,65 +329,99 @@ def main():
         print(json.dumps({"copy_calibration": {"bytes_read_per_dispatch": 64 << 20, "bytes_written_per_dispatch": 64 << 20,
                                                "dispatches": 8}}))
         return
-    if args.profile_run:
-        args.no_operators = args.no_cpu_baseline = args.no_tune = True
-    wl = I.WORKLOADS[args.workload]
+    H = Harness(torch, B)
+    have_records = bool(args.records) and os.path.exists(args.records)
+    if have_records:
+        B.tir_tune_load(args.records)
+    measure = not args.no_tune and not have_records and not args.profile_run     # run tir_tune_* before timing
+    selection = ("kept records (tir_tune_load)" if have_records else
+                 "measured (tir_tune_*, untimed, before the run)" if measure else "scoring rule")
 
-    per_set = wl.min_bytes()
-    nsets = 1 if args.hot else max(2, int(CACHE_BYTES * 1.25 / per_set) + 1)
-    nsets = min(nsets, max(1, args.steps))
+    if args.tune_only:
+        for name, o in all_bench_workloads(I):
+            if args.workload and name != args.workload:
+                continue
+            s = make_sets(B, o, 1)
+            B.tune_workload(o, *s[0], reps=5 if o.flops() > 4e10 else 10, stream=H.stream)
+            del s
+        if not args.workload:
+            other_conv_rows(H, I, tune=True)
+        if args.records:
+            B.tir_tune_save(args.records)
+        print(json.dumps({"tuned": B.tir_tune_count(), "records": args.records}))
+        return
+
+    wl = I.WORKLOADS[args.workload or "c2a_conv56x64_f16"]
+    steps, warmup = max(1, args.steps), max(0, args.warmup)
+    replays = 2 if args.profile_run else max(1, args.replays)
+    cold = not args.hot
+    nsets = cold_set_count(wl) if cold else 1
     sets = make_sets(B, wl, nsets)
-    if not args.no_tune:      # untimed: measure the variants once, like a deployment that keeps its records
-        B.tune_workload(wl, *sets[0], reps=10)
-    # Cold run: inputs come from HBM and nothing reads an output again before 27 other launches have gone by, which
-    # is what TIR_OUTPUT_STREAMING is for (see tir.h); the same run with cached outputs is reported next to it, and
-    # the hot run and the operator table use the library's default (outputs stay cached for a consumer).
-    streaming = not args.hot
-    cold_cached_value = None
-    wall, ev = timed_run(torch, B, wl, sets, args.steps, args.warmup, args.eager, streaming=streaming)
-    if streaming and not args.profile_run:
-        w3, _ = timed_run(torch, B, wl, sets, args.steps, args.warmup, args.eager)
-        cold_cached_value = wl.flops() * args.steps / w3 / 1e12
-    ms_per_step = wall * 1e3 / args.steps
-    value = wl.flops() * args.steps / wall / 1e12
-    peak = PEAK_TFLOPS[wl.dtype]
-    launch_s = ev / args.steps
-    achieved = wl.flops() / launch_s / 1e12
-    traffic = MEASURED_TRAFFIC_BYTES.get(wl.name)
+    if measure:               # untimed: measure the variants once, like a deployment that keeps its records
+        B.tune_workload(wl, *sets[0], reps=10, stream=H.stream)
 
-    hot_value = None
-    if not args.hot and not args.profile_run:
-        w2, _ = timed_run(torch, B, wl, sets[:1], args.steps, args.warmup, args.eager)
-        hot_value = wl.flops() * args.steps / w2 / 1e12
+    # headline: the library's default output policy (cached)
+    walls, events = time_workload(H, wl, sets, steps, warmup, replays, cold)
+    wall = statistics.median(walls)
+    ms_per_step = wall * 1e3 / steps
+    value = wl.flops() * steps / wall / 1e12
+    peak = PEAK_TFLOPS[wl.dtype]
+    cache_note = (f"cold (each replay walks {min(steps, nsets)} of {nsets} rotating operand sets = {nsets * wl.min_bytes() / 1e6:.0f} MB, "
+                  f"2 x {FLUSH_BYTES >> 20} MiB flush copy before every timed replay)") if cold else "hot (one operand set)"
+    roofline = roofline_record(B, wl, [e / steps for e in events], cache_note)
+
+    streaming_value = hot_value = None
+    if not args.profile_run:
+        if cold:
+            w3, _ = time_workload(H, wl, sets, steps, warmup, replays, True, streaming=True)
+            streaming_value = wl.flops() * steps / statistics.median(w3) / 1e12
+            w2, _ = time_workload(H, wl, sets[:1], steps, warmup, replays, False)
+            hot_value = wl.flops() * steps / statistics.median(w2) / 1e12
     del sets
 
+    roofline_gemm = None
+    if not args.profile_run and not args.no_operators and wl.name != "c4a_gemm4096_f16":
+        g = I.WORKLOADS["c4a_gemm4096_f16"]
+        gsets = make_sets(B, g, cold_set_count(g))
+        if measure:
+            B.tune_workload(g, *gsets[0], reps=5, stream=H.stream)
+        _, gev = time_workload(H, g, gsets, 12, 4, 9, True)
+        roofline_gemm = roofline_record(B, g, [e / 12 for e in gev],
+                                        f"cold ({len(gsets)} rotating operand sets, flush copy before every timed replay of 12 launches)")
+        del gsets
+
     operators = []
-    if not args.no_operators:
-        for name, o in list(I.WORKLOADS.items()) + list(I.FUSED_WORKLOADS.items()) + list(I.MORE_WORKLOADS.items()):
-            k = 20 if o.flops() > 4e10 else 200
+    if not args.no_operators and not args.profile_run:
+        for name, o in all_bench_workloads(I):
+            big = o.flops() > 4e10
+            k = 20 if big else 200
             s = make_sets(B, o, 1)
-            if not args.no_tune:
-                B.tune_workload(o, *s[0], reps=5 if o.flops() > 4e10 else 10)
-            w_, e_ = timed_run(torch, B, o, s, k, 5, args.eager)
-            tf = o.flops() * k / e_ / 1e12
-            attain = min(PEAK_TFLOPS[o.dtype], o.flops() / o.min_bytes() * HBM_GBS / 1e3)
-            operators.append({"workload": name, "variant": variant_of(B, o), "out": o.out,
-                              "fused": ("bias " if o.ep_bias else "") + ("relu " if o.ep_relu else "") + ("requant" if o.ep_scale else ""),
-                              "us": round(e_ / k * 1e6, 3),
-                              "tflops": round(tf, 2), "frac_mfma_peak": round(tf / PEAK_TFLOPS[o.dtype], 4),
-                              "frac_attainable": round(tf / attain, 4),
-                              "gbs": round(o.min_bytes() * k / e_ / 1e9, 1), "cache": "hot"})
+            if measure:
+                B.tune_workload(o, *s[0], reps=5 if big else 10, stream=H.stream)
+            _, e_ = time_workload(H, o, s, k, 5, 5, False)
+            sec_cold = None
+            if roof(o.dtype, o.flops(), o.min_bytes())[0] == "hbm":
+                # the roofline that binds this row is HBM bandwidth: only a cold run says anything about it
+                cs = s + make_sets(B, o, cold_set_count(o) - 1)
+                _, ec = time_workload(H, o, cs, 40, 5, 7, True)
+                sec_cold = statistics.median(ec) / 40
+                del cs
+            operators.append(op_row(name, variant_of(B, o), o.out,
+                                    ("bias " if o.ep_bias else "") + ("relu " if o.ep_relu else "") + ("requant" if o.ep_scale else ""),
+                                    o.dtype, statistics.median(e_) / k, o.flops(), o.min_bytes(), sec_cold))
             del s
-        operators.append(attention_row(torch, B, I))
-        operators.extend(other_conv_rows(torch, B, I, tune=not args.no_tune))
+        operators.append(attention_row(H, I))
+        operators.extend(other_conv_rows(H, I, tune=measure))
+    if measure and args.records:
+        B.tir_tune_save(args.records)
 
     out = {
         "metric": "TFLOP/s and % of MI355X MFMA peak per operator (fp16 GEMM, conv2d)",
         "value": round(value, 3),
         "unit": "TFLOP/s",
         "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
+        "steps": steps,
+        "warmup": warmup,
         "ms_per_step": round(ms_per_step, 6),
         "higher_is_better": True,
         "scaling": "weak",
@@ -336,23 +429,24 @@ def main():
         "dtype": {"f16": "f16", "bf16": "bf16", "i8": "i8"}[wl.dtype],
         "data": "synthetic (seeded; ResNet-50- / BERT-base-shaped operator instances)",
         "config": {"workload": wl.name, "kind": wl.kind, "gemm_view_bMNK": list(wl.gemm_view()),
-                   "out_dtype": wl.out, "variant": variant_of(B, wl),
-                   "launch": "hip_graph" if not args.eager else "eager",
-                   "selection": "scoring rule" if args.no_tune else "measured (tir_tune_*, untimed, before the run)",
-                   "cache": "hot (one operand set)" if args.hot else f"cold (rotating {nsets} operand sets)",
-                   "output_stores": "streaming (tir_set_output_policy: no launch reads an output again)" if streaming else "cached (library default)"},
+                   "out_dtype": wl.out, "variant": variant_of(B, wl), "launch": "hip_graph",
+                   "selection": selection, "cache": cache_note,
+                   "output_stores": "cached (library default)"},
+        "timing": {"replays": replays, "reported": "median replay; ms_per_step x steps = one replay",
+                   "wall_ms_per_replay": stats(walls, 1e3), "event_ms_per_replay": stats(events, 1e3)},
         "frac_mfma_peak": round(value / peak, 4),
+        "value_device_clock": round(wl.flops() * steps / statistics.median(events) / 1e12, 3),
         "value_hot_cache": None if hot_value is None else round(hot_value, 3),
-        "value_cold_cached_outputs": None if cold_cached_value is None else round(cold_cached_value, 3),
-        "roofline": {"bound": "mfma", "achieved": round(achieved, 3), "peak": peak, "unit": "TFLOP/s",
-                     "frac": round(achieved / peak, 4), "traffic": traffic,
-                     "kernel": variant_of(B, wl), "avg_launch_us": round(launch_s * 1e6, 3),
-                     "algorithmic_flop_per_launch": wl.flops(), "algorithmic_bytes_per_launch": wl.min_bytes()},
+        "value_cold_streaming_outputs": None if streaming_value is None else round(streaming_value, 3),
+        "roofline": roofline,
+        "roofline_gemm": roofline_gemm,
         "operators": operators,
         "mfma_sustained_tflops": None if args.profile_run else mfma_ceiling(torch, B),
     }
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not args.profile_run:
         out["cpu_baseline"] = cpu_baseline(wl)
+    torch.cuda.synchronize()
+    B.tir_set_workspace(None, stream=H.stream)
     print(json.dumps(out))
 
 

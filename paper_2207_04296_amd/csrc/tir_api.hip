@@ -105,6 +105,13 @@ static const tir_epilogue kQueryRequant = {nullptr, 0, 1.0f};
 
 static bool aligned(const void* p, uintptr_t a) { return ((uintptr_t)p % a) == 0; }
 
+// Do byte offsets inside one tile of at most 256 rows of `stride` elements (the last one `width` elements wide) fit
+// 31 bits?  (stride * 256 + width) * es < 2^31 - 1, written so that no product can overflow for strides up to 2^63.
+static bool fits_tile_offsets(int64_t stride, int64_t width, int64_t es) {
+    const int64_t room = kMaxExtent / es - width;
+    return room > 0 && stride < (room + 255) / 256 && (stride * 256 + width) * es < kMaxExtent;
+}
+
 // ------------------------------------------------------------------------------- measured choices
 // Records of tir_tune_*: for a problem signature, the variant that ran fastest on this device.
 // kind 0 = (batched) GEMM, 1 = convolution; geom packs the convolution geometry that the GEMM view
@@ -358,11 +365,11 @@ static tir_status plan_gemm(bool need_ptrs, const void* A, const void* B, void* 
     // (rows must not overlap: the copy stage relies on "row r+1 starts after row r ends" to turn
     // rows past the edge into out-of-range reads; byte offsets inside one tile must fit 31 bits)
     if (a_cs == 1 && k_vec && a_rs % vec == 0 && a_bs % vec == 0 && aligned(A, 16) && (a_rs >= K || M == 1) &&
-        (a_rs * 256 + K) * es < kMaxExtent) amode = A_KMAJOR;
+        fits_tile_offsets(a_rs, K, es)) amode = A_KMAJOR;
     if (b_rs == 1 && k_vec && b_cs % vec == 0 && b_bs % vec == 0 && aligned(B, 16) && (b_cs >= K || N == 1) &&
-        (b_cs * 256 + K) * es < kMaxExtent) bmode = B_KMAJOR;
+        fits_tile_offsets(b_cs, K, es)) bmode = B_KMAJOR;
     else if (b_cs == 1 && N % vec == 0 && b_rs % vec == 0 && b_bs % vec == 0 && aligned(B, 16) && b_rs >= N &&
-             (b_rs * 256 + N) * es < kMaxExtent) bmode = B_NMAJOR;
+             fits_tile_offsets(b_rs, N, es)) bmode = B_NMAJOR;
     if (amode == A_GENERIC || bmode == B_GENERIC) { amode = A_GENERIC; bmode = B_GENERIC; }
 
     plan->key = TuneKey{0, in, out, amode, bmode, batch, M, N, K, 0};
@@ -381,7 +388,7 @@ static tir_status plan_gemm(bool need_ptrs, const void* A, const void* B, void* 
     if ((int64_t)p.tiles_m * p.tiles_n > kMaxExtent) return fail(TIR_ERR_UNSUPPORTED, "too many output tiles");
     p.a_bs = a_bs; p.b_bs = b_bs; p.c_bs = c_bs;
     p.a_rs = a_rs; p.a_cs = a_cs; p.b_rs = b_rs; p.b_cs = b_cs; p.c_rs = c_rs; p.c_cs = c_cs;
-    p.c_fast = (c_cs == 1 && (c_rs >= N || M == 1) && (c_rs * 256 + N) * elem_size(out) < kMaxExtent) ? 1 : 0;
+    p.c_fast = (c_cs == 1 && (c_rs >= N || M == 1) && fits_tile_offsets(c_rs, N, elem_size(out))) ? 1 : 0;
     if (ep) { p.bias = ep->bias; p.bias_bs = 0; p.relu = ep->relu != 0; p.scale = ep->scale; p.store_nt = ep->streaming; }
     set_divisors(p);
     plan->v = v;
@@ -643,6 +650,45 @@ static tir_status tune_problem(MakePlan make_plan, int reps, hipStream_t stream,
     TrialGuard guard;
     Choice best = kNoChoice;
     float best_ms = 0.f;
+    // n launches of plan pl captured into one HIP graph and replayed (launched one by one, kernels of a few
+    // microseconds would be timed at the host's launch rate, not the device's); ms per launch in *ms_out
+    auto timed_plan = [&](const Plan& pl, int n, float* ms_out) -> tir_status {
+        hipGraph_t graph = nullptr;
+        hipGraphExec_t exec = nullptr;
+        float ms = 0.f;
+        hipError_t e = hipStreamBeginCapture(stream, hipStreamCaptureModeThreadLocal);
+        if (e != hipSuccess) return fail(TIR_ERR_LAUNCH, "tuning: stream capture failed: %s", hipGetErrorString(e));
+        tir_status s2 = TIR_OK;
+        for (int r = 0; r < n && s2 == TIR_OK; ++r) s2 = run(pl, stream);
+        e = hipStreamEndCapture(stream, &graph);
+        if (s2 == TIR_OK && e == hipSuccess) e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+        if (s2 == TIR_OK && e == hipSuccess) e = hipGraphLaunch(exec, stream);            // upload + first run, untimed
+        if (s2 == TIR_OK && e == hipSuccess) e = hipEventRecord(e0, stream);
+        if (s2 == TIR_OK && e == hipSuccess) e = hipGraphLaunch(exec, stream);
+        if (s2 == TIR_OK && e == hipSuccess) e = hipEventRecord(e1, stream);
+        if (s2 == TIR_OK && e == hipSuccess) e = hipEventSynchronize(e1);
+        if (s2 == TIR_OK && e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+        if (exec) (void)hipGraphExecDestroy(exec);
+        if (graph) (void)hipGraphDestroy(graph);
+        if (s2 != TIR_OK) return s2;
+        if (e != hipSuccess) return fail(TIR_ERR_LAUNCH, "tuning run of %s failed: %s", pl.v->name, hipGetErrorString(e));
+        *ms_out = ms / (float)n;
+        return TIR_OK;
+    };
+    if (base.v->amode == A_DEPTHWISE) {
+        // The direct depth-wise kernel is not a tile variant and the planner prefers it whatever a record says:
+        // there is nothing to choose, so it is timed (best_us is the time of the kernel that will run) and no
+        // record is written.
+        st = timed_plan(base, reps, &best_ms);
+        (void)hipEventDestroy(e0);
+        (void)hipEventDestroy(e1);
+        if (own) (void)hipStreamDestroy(own);
+        if (st == TIR_OK) {
+            if (best_us) *best_us = (double)best_ms * 1e3;
+            if (best_name) *best_name = base.v->name;
+        }
+        return st;
+    }
     // reduction splits tried per variant (where the variant, the workspace and the reduction's length allow
     // them and the workgroups still fit two rounds of the CUs)
     static const int kSplits[] = {1, 2, 3, 4, 6, 8};
@@ -662,33 +708,10 @@ static tir_status tune_problem(MakePlan make_plan, int reps, hipStream_t stream,
             const int64_t stages = ((int64_t)pl.p.K * elem_size(v->dt) + v->rowb - 1) / v->rowb;
             if (wgs > 2 * (int64_t)kCUs || stages / ks < 2) continue;
         }
-        // two launches first (a variant several times slower than the best so far is not worth `reps`
+        // one launch first (a variant several times slower than the best so far is not worth `reps`
         // more), then the measured batch; every HIP call is checked, the first failure ends the tuning
         float ms = 0.f;
-        // The n launches are captured into one HIP graph and replayed: launched one by one, kernels of
-        // a few microseconds would be timed at the host's launch rate, not the device's.
-        auto timed = [&](int n) -> tir_status {
-            hipGraph_t graph = nullptr;
-            hipGraphExec_t exec = nullptr;
-            hipError_t e = hipStreamBeginCapture(stream, hipStreamCaptureModeThreadLocal);
-            if (e != hipSuccess) return fail(TIR_ERR_LAUNCH, "tuning: stream capture failed: %s", hipGetErrorString(e));
-            tir_status s2 = TIR_OK;
-            for (int r = 0; r < n && s2 == TIR_OK; ++r) s2 = run(pl, stream);
-            e = hipStreamEndCapture(stream, &graph);
-            if (s2 == TIR_OK && e == hipSuccess) e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
-            if (s2 == TIR_OK && e == hipSuccess) e = hipGraphLaunch(exec, stream);            // upload + first run, untimed
-            if (s2 == TIR_OK && e == hipSuccess) e = hipEventRecord(e0, stream);
-            if (s2 == TIR_OK && e == hipSuccess) e = hipGraphLaunch(exec, stream);
-            if (s2 == TIR_OK && e == hipSuccess) e = hipEventRecord(e1, stream);
-            if (s2 == TIR_OK && e == hipSuccess) e = hipEventSynchronize(e1);
-            if (s2 == TIR_OK && e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
-            if (exec) (void)hipGraphExecDestroy(exec);
-            if (graph) (void)hipGraphDestroy(graph);
-            if (s2 != TIR_OK) return s2;
-            if (e != hipSuccess) return fail(TIR_ERR_LAUNCH, "tuning run of %s failed: %s", v->name, hipGetErrorString(e));
-            ms /= (float)n;
-            return TIR_OK;
-        };
+        auto timed = [&](int n) -> tir_status { return timed_plan(pl, n, &ms); };
         st = timed(1);
         if (st != TIR_OK) break;
         if (best.v && ms > 4.f * best_ms + 0.05f) continue;
