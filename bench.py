@@ -197,7 +197,7 @@ def roofline_record(B, wl, event_s_per_launch, cache_note):
 def mfma_ceiling(torch, B):
     """Sustained rate of a register-only fp16 MFMA loop (TFLOP/s): the practical ceiling of the matrix
     pipes under the power management, for constant and for random operands."""
-    sink = torch.zeros(4, device="cuda:0")
+    sink = torch.zeros(8, dtype=torch.int32, device="cuda:0")
     out = {}
     for label, rnd in (("const_operands", False), ("random_operands", True)):
         B.tir_probe_mfma_rate(sink, 200, rnd)
@@ -212,6 +212,11 @@ def mfma_ceiling(torch, B):
             torch.cuda.synchronize()
             best = max(best, flop / (e0.elapsed_time(e1) * 1e-3) / 1e12)
         out[label] = round(best, 1)
+        w = [int(v) & 0xffffffff for v in sink.tolist()]      # one wave's view of the last run: counters before and after its loop
+        cycles, ns = (w[3] - w[1]) & 0xffffffff, ((w[4] - w[2]) & 0xffffffff) * 10.0
+        if ns > 0 and cycles > 0:
+            out[label + "_shader_ghz"] = round(cycles / ns, 3)
+            out[label + "_mfma_busy_share"] = round(2000 * 16 * 32 / cycles, 3)      # 16 MFMAs of 32 cycles per iteration
     return out
 
 

@@ -327,7 +327,11 @@ unsigned tir_debug_fastdiv(unsigned d, unsigned m);
  * per wave on 1024 workgroups and report its FLOP count in *flop (may be NULL).  Timed by the
  * caller, it gives the rate the matrix pipes sustain at the clock the power management allows:
  * operands are constants (random_operands = 0) or pseudo-random values in (-1, 1).  `sink` is a
- * device pointer to at least 4 bytes that is practically never written.
+ * device pointer to at least 32 bytes, 4-byte aligned: word 0 is practically never written; one wave in the middle
+ * of the grid stores the low words of the shader-clock counter and of the 100 MHz constant counter before its loop
+ * (words 1, 2) and after it (words 3, 4).  (word 3 - word 1) / ((word 4 - word 2) * 10 ns) is the shader clock the
+ * power management held, and iters * 16 * 32 / (word 3 - word 1) the share of those cycles that SIMD's matrix pipe
+ * was busy (an MFMA of this shape occupies it for 32 cycles).
  */
 tir_status tir_probe_mfma_rate(void* sink, int iters, int random_operands, double* flop, tir_stream stream);
 

@@ -37,6 +37,15 @@ __global__ void __launch_bounds__(256) mfma_probe_kernel(float* sink, int iters,
         x *= 3266489917u; x ^= x >> 16;
         b[e] = (_Float16)(random_operands ? ((x & 0xffff) / 32768.0f - 1.0f) : 0.5f);
     }
+    // Shader-clock counter and 100 MHz wall counter before and after the loop, as one wave in the middle of the grid sees
+    // them (raw low words, stored right away so that nothing stays live across the loop): cycles / time is the clock the
+    // power management held during the loop.
+    const bool reporter = blockIdx.x == gridDim.x / 2 && threadIdx.x == 0;
+    unsigned* const stamps = (unsigned*)sink;
+    if (reporter) {
+        stamps[1] = (unsigned)__builtin_amdgcn_s_memtime();
+        stamps[2] = (unsigned)__builtin_amdgcn_s_memrealtime();
+    }
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, acc[i], 0, 0, 0);
@@ -45,6 +54,10 @@ __global__ void __launch_bounds__(256) mfma_probe_kernel(float* sink, int iters,
     for (int i = 0; i < 16; ++i)
         for (int r = 0; r < 16; ++r) s += acc[i][r];
     if (s == 123.456f) sink[0] = s;      // keeps the loop alive, practically never stores
+    if (reporter) {
+        stamps[3] = (unsigned)__builtin_amdgcn_s_memtime();
+        stamps[4] = (unsigned)__builtin_amdgcn_s_memrealtime();
+    }
 }
 
 // ------------------------------------------------------------------------------- variant table
