@@ -219,7 +219,7 @@ static void set_divisors(Params& p) {
     put((unsigned)(kGroupM * p.tiles_n), &p.div_gw_magic, &p.div_gw_shift);
     put((unsigned)p.tiles_n, &p.div_tn_magic, &p.div_tn_shift);
     put((unsigned)p.tiles_m, &p.div_tm_magic, &p.div_tm_shift);
-    put((unsigned)p.PW, &p.div_pw_magic, &p.div_pw_shift);
+    put((unsigned)(p.PW / 8), &p.div_pw_magic, &p.div_pw_shift);      // copy units (8 pixels) per patch row
     put((unsigned)p.Q, &p.div_q_magic, &p.div_q_shift);
     put((unsigned)(p.P * p.Q), &p.div_pq_magic, &p.div_pq_shift);
     put((unsigned)(p.OD < 1 ? 1 : p.OD) * (unsigned)(p.P * p.Q), &p.div_opq_magic, &p.div_opq_shift);
@@ -479,11 +479,11 @@ static tir_status plan_conv_geom(bool need_ptrs, const void* x, const void* w, v
                         !(g_force_name[0] && (strstr(g_force_name, "convx") || strstr(g_force_name, "generic")));
     if (phased) amode = A_CONV;
     // LDS-resident input patch: one pixel of one group is exactly one 128-byte LDS row, the input rows
-    // that 256 consecutive output pixels touch (copied in passes of 64 pixels) fit beside the R*S filter slabs
+    // that 256 consecutive output pixels touch (rows padded to 8 pixels, copied in passes of 32) fit beside the R*S filter slabs
     const int64_t span_out = (255 + Q - 1) / Q < P - 1 ? (255 + Q - 1) / Q : P - 1;   // output rows a tile can span, minus one
     const int64_t span_rows = span_out * g.stride_h + (R - 1) * g.dil_h + 1;
-    const int64_t patch_w = (Q - 1) * g.stride_w + (S - 1) * g.dil_w + 1;
-    const bool patch_ok = amode == A_CONV && !phased && Cg * es == 128 && P * Q >= 128 && (span_rows * patch_w + 63) / 64 * 8192 + R * S * 8192 <= 160 * 1024 &&
+    const int64_t patch_w = ((Q - 1) * g.stride_w + (S - 1) * g.dil_w + 1 + 7) / 8 * 8;      // patch rows are copied in units of 8 pixels
+    const bool patch_ok = amode == A_CONV && !phased && Cg * es == 128 && P * Q >= 128 && (span_rows * patch_w + 31) / 32 * 4096 + R * S * 8192 <= 160 * 1024 &&
                           (K * 256 + Kg) * elem_size(out) < kMaxExtent;
     plan->patch_ok = patch_ok;
     // records are kept under the implicit-GEMM signature; a record (or a trial) may name either kernel family

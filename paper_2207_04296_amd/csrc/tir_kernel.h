@@ -1111,31 +1111,37 @@ __global__ void __launch_bounds__(512) conv_patch_kernel(const Params p) {
     const int p_a = (int)fastdiv((unsigned)m_first, p.div_q_magic, p.div_q_shift), p_b = (int)fastdiv((unsigned)(m_first + m_cnt - 1), p.div_q_magic, p.div_q_shift);
     const int ih_base = p_a * p.stride_h - p.pad_h;
     const int nrows = (p_b - p_a) * p.stride_h + (p.R - 1) * p.dil_h + 1;
-    const int PW = p.PW;                        // (Q-1)*s_w + (S-1)*d_w + 1 patch columns, first is iw = -pad_w
-    const int npix = nrows * PW;
+    const int PW = p.PW;                        // patch columns: (Q-1)*s_w + (S-1)*d_w + 1 rounded up to 8, the first is iw = -pad_w
+    const int U = PW >> 3;                      // a copy instruction moves one unit: 8 consecutive pixels of one patch row (1 KiB)
 
-    // Passes [first, last) of the patch copy; a pass is 32 pixels x 128 B, written by the four waves of one role.
-    const int nit = (npix + 31) >> 5;
+    // Passes [first, last) of the patch copy; a pass is four units (32 pixels x 128 B), one per wave of the role.
+    const int nit = (nrows * U + 3) >> 2;
     // The multiplying waves are idle until the patch is in: they copy its second half (measured 3/8 .. 8/8 for
     // the copy waves' share: one half each is fastest, 7.8 vs 8.45 us on the 56x56x64 benchmark convolution).
     const int nsplit = (nit + 1) / 2;
     auto copy_patch = [&](int first, int last) {
+        // Unit u = 4*pass + cw is row u / U, columns 8*(u % U) .. of the patch: row and first column are uniform, so
+        // the address is a scalar base plus a constant of the lane and validity is one comparison per lane (columns;
+        // a row outside the image compares against a width of 0).  Per-lane decoding of each pixel made a copy
+        // instruction cost ~270 cycles to issue; this form costs about what a filter slab's does.
         const i32x4 rx = make_rsrc32((const char*)p.A, (unsigned)((long long)p.batch_imgs * p.H * p.W * p.Cin * ES));      // < 2^31: the host checks
-        const unsigned gofs = (unsigned)(grp * p.Cg * ES);
-        const int pc = tid & 7;
-        int px = first * 32 + (tid >> 3);
-        int pr = (int)fastdiv((unsigned)px, p.div_pw_magic, p.div_pw_shift), pcx = px - pr * PW;
-        const int d_r = (int)fastdiv(32u, p.div_pw_magic, p.div_pw_shift), d_c = 32 - d_r * PW;
+        const int pix_bytes = p.Cin * ES;
+        const int lp = lane >> 3;                                       // pixel of the unit
+        // LDS slot (pixel lp, physical column lane & 7) holds logical column (lane & 7) ^ key(pixel index); the pixel
+        // index is 8*u + lp with u = cw mod 4 throughout, so the key (4*(cw & 1) + lp / 2) mod 8 is a constant of the lane
+        const unsigned lane_off = (unsigned)(lp * pix_bytes + grp * p.Cg * ES + (((lane & 7) ^ ((4 * (cw & 1) + (lp >> 1)) & 7)) << 4));
+        const int u0 = 4 * first + cw;
+        int ur = (int)fastdiv((unsigned)u0, p.div_pw_magic, p.div_pw_shift), uc = u0 - ur * U;      // (the host's constants divide by U)
+        char* dst = s_patch + first * 4096 + cw * 1024;
         for (int it = first; it < last; ++it) {
-            const int lc = pc ^ kmajor_swz<128>(px);
-            const int ih = ih_base + pr, iw = pcx - p.pad_w;
-            const bool ok = px < npix && (unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W;
-            const unsigned voff = ok ? (unsigned)(((img * p.H + ih) * p.W + iw) * p.Cin) * ES + gofs + lc * 16 : kOutOfRange;
-            load_to_lds(rx, s_patch + it * 4096 + cw * 1024, voff);
-            px += 32;
-            pr += d_r;
-            pcx += d_c;
-            if (pcx >= PW) { pcx -= PW; ++pr; }
+            const int ih = ih_base + ur, iw0 = 8 * uc - p.pad_w;
+            const unsigned wlim = (ur < nrows && (unsigned)ih < (unsigned)p.H) ? (unsigned)p.W : 0u;
+            const unsigned base = (unsigned)(((img * p.H + ih) * p.W + iw0) * pix_bytes);      // modulo 2^32; used only for pixels that exist
+            const unsigned voff = (unsigned)(iw0 + lp) < wlim ? base + lane_off : kOutOfRange;
+            load_to_lds(rx, dst, voff);
+            dst += 4096;
+            uc += 4;
+            while (uc >= U) { uc -= U; ++ur; }
         }
     };
 
@@ -1165,7 +1171,10 @@ __global__ void __launch_bounds__(512) conv_patch_kernel(const Params p) {
         constexpr int AHEAD = 3;
         int issued = 0;
         for (int t = 0; t < RS; ++t) {
-            const int want = t + 2 + AHEAD < RS ? t + 2 + AHEAD : RS;
+            // (before barrier 0 only what the first tap and its successor need plus one: every copy requested ahead of it
+            // is queued in front of the patch's last rows at the L2, which every workgroup of the launch asks at once)
+            const int ahead = t == 0 ? 1 : AHEAD;
+            const int want = t + 2 + ahead < RS ? t + 2 + ahead : RS;
             for (; issued < want; ++issued) issue_slab(issued);
             wait_vmcnt_upto(2 * (issued - (t + 2)));
             __builtin_amdgcn_s_barrier();

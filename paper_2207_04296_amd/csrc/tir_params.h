@@ -58,7 +58,7 @@ struct Params {
     void* ws;            // partial sums: [grid.y][tile][slice][BM*BN] accumulator elements (4 bytes each)
     unsigned* ws_count;  // [grid.y][tile] arrival counters, zero between launches (the last slice resets its tile's)
     int batch_imgs;   // convolutions: images in x (for the descriptor)
-    int PW;           // patch kernel: columns of the LDS-resident input patch
+    int PW;           // patch kernel: columns of the LDS-resident input patch (a multiple of 8)
     int store_nt;     // the caller does not read the output again soon: non-temporal epilogue stores (see TIR_STORE_AUX_STREAM)
     int reserved0;
     // ---- convolution geometry (A_CONV*): x is [n][H][W][Cin], one group reads Cg channels
@@ -68,7 +68,7 @@ struct Params {
     int div_pq_shift, div_q_shift;
     unsigned div_cg_magic, div_s_magic, div_rs_magic;      // k / Cg, tap / S, tap / (R*S): per-lane tap decode when a stage spans taps
     int div_cg_shift, div_s_shift, div_rs_shift;
-    unsigned div_tn_magic, div_tm_magic, div_pw_magic;     // patch kernel: id / tiles_n, id / tiles_m, pixel / PW
+    unsigned div_tn_magic, div_tm_magic, div_pw_magic;     // patch kernel: id / tiles_n, id / tiles_m, copy unit / (PW / 8)
     int div_tn_shift, div_tm_shift, div_pw_shift;
     // Transposed convolution by output phase (A_CONV variants; phases_h = 0: off).  The output pixels with
     // (oh mod phases_h, ow mod phases_w) = (ph, pw) form a stride-1 convolution of the input with the filter taps
