@@ -1195,14 +1195,19 @@ __global__ void __launch_bounds__(512) conv_patch_kernel(const Params p) {
         const int op = (int)fastdiv((unsigned)mm, p.div_q_magic, p.div_q_shift), oq = mm - op * p.Q;
         base_px[i] = (op - p_a) * p.stride_h * PW + oq * p.stride_w;
     }
-    const int swn = kmajor_swz<128>(l31);
-    auto read_a = [&](int tap_px, int kk, int i) -> uint4 {
+    // Fragment addresses as byte offsets into smem.  A 128-byte row holds 16-byte column (2*kk + g) of k-step kk at physical
+    // column (2*kk + g) ^ key: the k-step only flips bits 5 and 6 of the address, so a lane keeps the address of k-step 0
+    // per tap (A: patch row of its pixel under that tap; B: its filter row in that tap's slab) and every read costs one
+    // XOR.  With one multiplying wave per SIMD, whatever stands between two MFMAs beyond the 32 cycles the first one
+    // takes leaves the matrix pipe idle: decoding pixel and swizzle in front of each read was a chain of five
+    // dependent vector instructions.
+    const int patch_base = p.R * p.S * SLAB;
+    auto a_off0 = [&](int tap_px, int i) -> unsigned {
         const int px = base_px[i] + tap_px;
-        return *(const uint4*)(s_patch + px * 128 + (((2 * kk + g) ^ kmajor_swz<128>(px)) << 4));
+        return (unsigned)(patch_base + px * 128 + ((g ^ kmajor_swz<128>(px)) << 4));
     };
-    auto read_b = [&](int t, int kk, int j) -> uint4 {
-        return *(const uint4*)(s_filt + t * SLAB + (j * 32 + l31) * 128 + (((2 * kk + g) ^ swn) << 4));
-    };
+    const unsigned b_lane = (unsigned)(l31 * 128 + ((g ^ kmajor_swz<128>(l31)) << 4));        // + tap * SLAB, + 4096 for the second block
+    auto read_at = [&](unsigned off0, int kk, int add) -> uint4 { return *(const uint4*)(smem + ((off0 ^ (unsigned)(kk << 5)) + add)); };
 
     acc_t acc[2][2];
 #pragma unroll
@@ -1228,51 +1233,63 @@ __global__ void __launch_bounds__(512) conv_patch_kernel(const Params p) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");          // this wave's patch copies (and its bias) have landed
     __builtin_amdgcn_s_barrier();                 // barrier 0: patch, slabs 0 and 1 are in LDS
     asm volatile("" ::: "memory");
-    constexpr int LOOK = 2;      // k-steps of lookahead (1, 2 and 3 measure alike: the loop is bound by LDS bandwidth, not latency)
+    constexpr int LOOK = 2;      // k-steps of lookahead (1, 2 and 3 measure alike)
+    unsigned cA[2] = {a_off0(0, 0), a_off0(0, 1)}, cB = b_lane;      // k-step 0 of the current tap
+    unsigned nA[2] = {cA[0], cA[1]}, nB = cB;                        // ... of the next one
 #pragma unroll
     for (int kk = 0; kk < LOOK; ++kk)
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
-            af[kk][i] = read_a(0, kk, i);
-            bf[kk][i] = read_b(0, kk, i);
+            af[kk][i] = read_at(cA[i], kk, 0);
+            bf[kk][i] = read_at(cB, kk, i * 4096);
         }
     TIR_FENCE();
 
-    int fr = 0, fs = 0;                           // filter row / column of the current tap
+    // The tap cursor advances by additions under the tap's first MFMA, and the next tap's addresses (needed two k-steps
+    // later) are worked out under the back-to-back MFMA pairs of the first two k-steps; an iteration ends on such a pair,
+    // which covers the loop branch and the barrier.
+    const int row_step = p.dil_h * PW, col_step = p.dil_w;
+    int tap_px = 0, row_px = 0, fs = 0;           // patch offsets of the current tap and of its filter row's first tap; filter column
     for (int t = 0; t < RS; ++t) {
-        const int tap_px = fr * p.dil_h * PW + fs * p.dil_w;
-        int nfs = fs + 1, nfr = fr;
-        if (nfs == p.S) { nfs = 0; ++nfr; }
-        const bool last = t + 1 == RS;
-        const int next_px = last ? tap_px : nfr * p.dil_h * PW + nfs * p.dil_w;
-        const int next_t = last ? t : t + 1;
         if (t > 0) {
             __builtin_amdgcn_s_barrier();         // barrier t: slab t+1 is in LDS
             asm volatile("" ::: "memory");
         }
+        int next_px = tap_px;                     // (the last tap prefetches itself: those fragments are never used)
         TIR_FENCE();
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
             // two k-steps ahead: same tap for kk < 2, the next tap's first k-steps otherwise
             const int rk = (kk + LOOK) & 3;
-            const int rpx = kk < 4 - LOOK ? tap_px : next_px;
-            const int rt = kk < 4 - LOOK ? t : next_t;
+            const bool ahead = kk >= 4 - LOOK;
             acc[0][0] = InTraits<DT>::mfma(af[kk][0], bf[kk][0], acc[0][0]);
             TIR_FENCE();
-            af[rk][0] = read_a(rpx, rk, 0);
-            bf[rk][0] = read_b(rt, rk, 0);
+            if (kk == 0) {
+                const bool more = t + 1 < RS, wrap = fs + 1 == p.S;
+                const int adv = wrap ? row_px + row_step : tap_px + col_step;
+                next_px = more ? adv : tap_px;
+                row_px = wrap ? row_px + row_step : row_px;
+                fs = wrap ? 0 : fs + 1;
+                nB = more ? cB + SLAB : cB;
+            }
+            af[rk][0] = read_at(ahead ? nA[0] : cA[0], rk, 0);
+            bf[rk][0] = read_at(ahead ? nB : cB, rk, 0);
             TIR_FENCE();
             acc[0][1] = InTraits<DT>::mfma(af[kk][0], bf[kk][1], acc[0][1]);
             TIR_FENCE();
-            af[rk][1] = read_a(rpx, rk, 1);
-            bf[rk][1] = read_b(rt, rk, 1);
+            af[rk][1] = read_at(ahead ? nA[1] : cA[1], rk, 0);
+            bf[rk][1] = read_at(ahead ? nB : cB, rk, 4096);
             TIR_FENCE();
             acc[1][0] = InTraits<DT>::mfma(af[kk][1], bf[kk][0], acc[1][0]);
             acc[1][1] = InTraits<DT>::mfma(af[kk][1], bf[kk][1], acc[1][1]);
             TIR_FENCE();
+            if (kk < 2) {                         // under the pair: 64 cycles of cover for five dependent instructions
+                nA[kk] = a_off0(next_px, kk);
+                TIR_FENCE();
+            }
         }
-        fr = nfr;
-        fs = nfs;
+        tap_px = next_px;
+        cA[0] = nA[0]; cA[1] = nA[1]; cB = nB;
     }
 
     // ------------------------------------------------------------ fused epilogue (NHWC rows are output pixels)
