@@ -611,9 +611,9 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
     }
 
     // ------------------------------------------------------------ copy stage: B
-    const int b_r0 = (C::BMODE == B_NMAJOR) ? tid / C::B_RC : tid / C::RCH;
-    const int b_pc = (C::BMODE == B_NMAJOR) ? tid % C::B_RC : tid % C::RCH;
-    const int b_lc = b_pc ^ kmajor_swz<ROWB>(b_r0);     // K-major only
+    const int b_r0 = tid / C::RCH;                      // K-major only: row, physical and logical column of the thread's chunk
+    const int b_pc = tid % C::RCH;
+    const int b_lc = b_pc ^ kmajor_swz<ROWB>(b_r0);
     unsigned b_off[C::B_IT];
     const char* b_base = Bb;
     long long b_bytes = 0;
@@ -633,8 +633,10 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
         b_step = (long long)BK * p.b_rs * ES;
 #pragma unroll
         for (int i = 0; i < C::B_IT; ++i) {
-            const int k = b_r0 + i * C::N_RSTEP;
-            const int lb = (b_pc * 16) ^ nmajor_xor<C>(k);      // logical byte inside the k-row
+            // the copying threads' i-th pass covers 16-byte chunks i*CT .. of the tile (k-rows of B_RC chunks, any count)
+            const int chunk = i * C::CT + tid;
+            const int k = chunk / C::B_RC, pc = chunk - k * C::B_RC;
+            const int lb = (pc * 16) ^ nmajor_xor<C>(k);        // logical byte inside the k-row
             b_off[i] = (n0 + lb / ES < p.N) ? (unsigned)k * (unsigned)(p.b_rs * ES) + lb : kOutOfRange;
         }
     }

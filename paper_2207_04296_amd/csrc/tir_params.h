@@ -150,6 +150,7 @@ __host__ __device__ inline void tile_of_block(int bid, int tiles_m, int tiles_n,
     *tn = q;
 }
 
+constexpr int const_gcd(int a, int b) { return b == 0 ? a : const_gcd(b, a % b); }
 constexpr int elem_size(int dt) { return dt == DT_I8 ? 1 : (dt == DT_F16 || dt == DT_BF16) ? 2 : 4; }
 
 // Compile-time shape of one kernel variant: BM x BN workgroup tile, WM x WN waves, ROWB bytes of k
@@ -181,16 +182,20 @@ struct Cfg {
     // N-major B tile in LDS: BK k-rows of BN*ES bytes
     static constexpr int BROW = BN * ES;
     static constexpr int B_RC = BROW / 16;          // 16-byte chunks per k-row
-    static constexpr int N_RSTEP = CT / B_RC;       // k-rows covered by one pass of the copying threads
     static constexpr int SEG = (ES == 2) ? 64 : 32; // bytes one half-wave reads per k-row on the transposing read
-    static constexpr int WIN = BROW < 256 ? BROW : 256;
-    static constexpr int NSEG = WIN / SEG > 0 ? WIN / SEG : 1;
-    static constexpr int RPW = 256 / WIN;
+    // A transposing read touches 256 / SEG consecutive k-rows at one SEG-byte segment each; they must fall into
+    // different SEG-byte groups of the 256-byte bank sweep.  Row r starts in group r * (BROW / SEG) mod (256 / SEG):
+    // that visits 256 / SEG / NSEG groups, with period RPW, where NSEG = gcd(BROW / SEG, 256 / SEG); XORing
+    // (r / RPW) mod NSEG into the segment index spreads the rows over the rest.  (BROW a multiple of 256: all rows
+    // start alike and the XOR does everything; BROW / SEG odd, e.g. 96 fp16 columns: the stride alone does.)
+    static constexpr int SEGS_PER_SWEEP = 256 / SEG, SEGS_PER_ROW = BROW / SEG;
+    static constexpr int NSEG = const_gcd(SEGS_PER_ROW, SEGS_PER_SWEEP);
+    static constexpr int RPW = SEGS_PER_SWEEP / NSEG;
     static_assert(ROWB == 256 || ROWB == 128 || ROWB == 64, "");
     static_assert(TM % 32 == 0 && TN % 32 == 0, "wave tile must be a multiple of the 32x32 MFMA block");
     static_assert((BM * RCH) % CT == 0 && (BN * RCH) % CT == 0, "copy must divide evenly");
     static_assert(K_RSTEP % 16 == 0, "the K-major swizzle must repeat with the copy's row step");
-    static_assert(BMODE != B_NMAJOR || (CT % B_RC == 0 && BROW >= SEG), "N-major copy shape");
+    static_assert(BMODE != B_NMAJOR || (BROW % SEG == 0 && BROW % (NSEG * SEG) == 0), "N-major tile: whole segments, XOR closed inside a row");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of one CU");
     static_assert(KW >= 1 && KW <= 2 && THREADS <= 1024 && (CW == 0 || KW == 1), "");
     static_assert((KW - 1) * BM * BN * 4 <= LDS_BYTES, "the partial sums of the other groups must fit the rings");
