@@ -523,6 +523,10 @@ static tir_status plan_conv_geom(bool need_ptrs, const void* x, const void* w, v
     if (amode == A_CONV_PATCH) {
         p.tiles_m = (int)((P * Q + 255) / 256);      // pixel tiles per image
         p.PW = (int)patch_w;
+        for (int t = 0; t < 9; ++t) {
+            const int64_t tt = t < R * S ? t : R * S - 1;
+            p.tap_px[t] = R * S <= 9 ? (int)((tt / S) * g.dil_h * patch_w + (tt % S) * g.dil_w) : 0;
+        }
     }
     p.batch_imgs = (int)N;
     p.a_bs = Cg;            // a group starts Cg channels further

@@ -1077,6 +1077,8 @@ __global__ void __launch_bounds__(512) conv_patch_kernel(const Params p) {
                  "s"(p.pad_w), "s"(p.dil_h), "s"(p.dil_w));
     asm volatile("" ::"s"(p.div_q_magic), "s"(p.div_q_shift), "s"(p.div_tn_magic), "s"(p.div_tn_shift), "s"(p.div_tm_magic), "s"(p.div_tm_shift),
                  "s"(p.div_pw_magic), "s"(p.div_pw_shift));
+    asm volatile("" ::"s"(p.tap_px[0]), "s"(p.tap_px[1]), "s"(p.tap_px[2]), "s"(p.tap_px[3]), "s"(p.tap_px[4]), "s"(p.tap_px[5]), "s"(p.tap_px[6]),
+                 "s"(p.tap_px[7]), "s"(p.tap_px[8]));
     char* const s_filt = smem;                  // R*S slabs, then the patch (the host checked that both fit)
     char* const s_patch = smem + p.R * p.S * SLAB;
 
@@ -1121,35 +1123,39 @@ __global__ void __launch_bounds__(512) conv_patch_kernel(const Params p) {
     // The multiplying waves are idle until the patch is in: they copy its second half (measured 3/8 .. 8/8 for
     // the copy waves' share: one half each is fastest, 7.8 vs 8.45 us on the 56x56x64 benchmark convolution).
     const int nsplit = (nit + 1) / 2;
-    auto copy_patch = [&](int first, int last) {
-        // Unit u = 4*pass + cw is row u / U, columns 8*(u % U) .. of the patch: row and first column are uniform, so
-        // the address is a scalar base plus a constant of the lane and validity is one comparison per lane (columns;
-        // a row outside the image compares against a width of 0).  Per-lane decoding of each pixel made a copy
-        // instruction cost ~270 cycles to issue; this form costs about what a filter slab's does.
-        const i32x4 rx = make_rsrc32((const char*)p.A, (unsigned)((long long)p.batch_imgs * p.H * p.W * p.Cin * ES));      // < 2^31: the host checks
-        const int pix_bytes = p.Cin * ES;
-        const int lp = lane >> 3;                                       // pixel of the unit
-        // LDS slot (pixel lp, physical column lane & 7) holds logical column (lane & 7) ^ key(pixel index); the pixel
-        // index is 8*u + lp with u = cw mod 4 throughout, so the key (4*(cw & 1) + lp / 2) mod 8 is a constant of the lane
-        const unsigned lane_off = (unsigned)(lp * pix_bytes + grp * p.Cg * ES + (((lane & 7) ^ ((4 * (cw & 1) + (lp >> 1)) & 7)) << 4));
-        const int u0 = 4 * first + cw;
-        int ur = (int)fastdiv((unsigned)u0, p.div_pw_magic, p.div_pw_shift), uc = u0 - ur * U;      // (the host's constants divide by U)
-        char* dst = s_patch + first * 4096 + cw * 1024;
-        for (int it = first; it < last; ++it) {
+    // The role's passes [c_it, c_last) of the patch copy, one copy instruction per call.
+    // Unit u = 4*pass + cw is row u / U, columns 8*(u % U) .. of the patch: row and first column are uniform, so
+    // the address is a scalar base plus a constant of the lane and validity is one comparison per lane (columns;
+    // a row outside the image compares against a width of 0).  Per-lane decoding of each pixel made a copy
+    // instruction cost ~270 cycles to issue; this form costs about what a filter slab's does.
+    const i32x4 rx = make_rsrc32((const char*)p.A, (unsigned)((long long)p.batch_imgs * p.H * p.W * p.Cin * ES));      // < 2^31: the host checks
+    const int pix_bytes = p.Cin * ES;
+    const int lp = lane >> 3;                                           // pixel of the unit
+    // LDS slot (pixel lp, physical column lane & 7) holds logical column (lane & 7) ^ key(pixel index); the pixel
+    // index is 8*u + lp with u = cw mod 4 throughout, so the key (4*(cw & 1) + lp / 2) mod 8 is a constant of the lane
+    const unsigned lane_off = (unsigned)(lp * pix_bytes + grp * p.Cg * ES + (((lane & 7) ^ ((4 * (cw & 1) + (lp >> 1)) & 7)) << 4));
+    int c_it = copier ? 0 : nsplit;
+    const int c_last = copier ? nsplit : nit;
+    const int u0 = 4 * c_it + cw;
+    int ur = (int)fastdiv((unsigned)u0, p.div_pw_magic, p.div_pw_shift), uc = u0 - ur * U;          // (the host's constants divide by U)
+    char* c_dst = s_patch + c_it * 4096 + cw * 1024;
+    auto copy_step = [&]() __attribute__((always_inline)) {
+        if (c_it < c_last) {
             const int ih = ih_base + ur, iw0 = 8 * uc - p.pad_w;
             const unsigned wlim = (ur < nrows && (unsigned)ih < (unsigned)p.H) ? (unsigned)p.W : 0u;
-            const unsigned base = (unsigned)(((img * p.H + ih) * p.W + iw0) * pix_bytes);      // modulo 2^32; used only for pixels that exist
+            const unsigned base = (unsigned)(((img * p.H + ih) * p.W + iw0) * pix_bytes);          // modulo 2^32; used only for pixels that exist
             const unsigned voff = (unsigned)(iw0 + lp) < wlim ? base + lane_off : kOutOfRange;
-            load_to_lds(rx, dst, voff);
-            dst += 4096;
+            load_to_lds(rx, c_dst, voff);
+            c_dst += 4096;
             uc += 4;
             while (uc >= U) { uc -= U; ++ur; }
+            ++c_it;
         }
     };
 
     if (copier) {
         // ------------------------------------------------------------ copy: patch, then one filter slab per tap
-        copy_patch(0, nsplit);
+        while (c_it < c_last) copy_step();
         const long long Kd = p.K;                               // R*S*Cg
         const char* wbase = (const char*)p.B + ((long long)grp * p.N + n0) * Kd * ES;
         unsigned w_off[2];
@@ -1184,7 +1190,7 @@ __global__ void __launch_bounds__(512) conv_patch_kernel(const Params p) {
         return;
     }
 
-    copy_patch(nsplit, nit);                      // this role's share of the patch (empty unless the roles split it)
+    while (c_it < c_last) copy_step();            // this role's share of the patch
 
     // ------------------------------------------------------------ fragment addressing
     // lane's output pixel of MFMA block i: m = 64*cw + 32*i + l31 -> patch pixel of tap (0,0)
@@ -1232,6 +1238,87 @@ __global__ void __launch_bounds__(512) conv_patch_kernel(const Params p) {
     // Fragment sets: k-step kk of every tap uses set kk, fetched two k-steps ahead (a k-step is only
     // four MFMAs long here, one k-step of lookahead would not cover the LDS latency).
     uint4 af[4][2], bf[4][2];
+    const int row_step = p.dil_h * PW, col_step = p.dil_w;
+
+    // Up to nine taps (3x3 and smaller filters): the loop over the taps is unrolled and the address of every fragment of
+    // every tap is worked out here, after the wave's copies have been requested and while they land.  A wave issues in
+    // order and this one is alone on its SIMD: in the generic loop below the tap cursor, the next tap's addresses and an
+    // XOR per read stand between the MFMAs (770 cycles per tap against the 512 of its MFMAs and ~570 for the same
+    // MFMAs issued from registers alone; 650 this way).  Measured against this placement: the arithmetic between the
+    // copy instructions (the copies go out later: slower than not unrolling at all), and the last six taps' addresses
+    // behind the MFMAs of taps 0 and 1 (1 % slower).
+    unsigned aT[9][2][4];                         // [tap][pixel block][k-step]; the host lists the taps' patch offsets
+    auto tap_addresses = [&](int t, int i) __attribute__((always_inline)) {
+        const unsigned a0 = a_off0(p.tap_px[t], i);
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            aT[t][i][kk] = a0 ^ (unsigned)(kk << 5);
+            asm volatile("" : "+v"(aT[t][i][kk]));                    // here and now, in a register: not again next to its use
+        }
+    };
+    if (RS <= 9) {
+#pragma unroll
+        for (int t = 0; t < 9; ++t)
+#pragma unroll
+            for (int i = 0; i < 2; ++i) tap_addresses(t, i);
+    }
+
+    if (RS <= 9) {
+        // filter rows: slab t starts t * SLAB bytes on, which the read's offset field holds up to 64 KiB: two bases
+        const char* bK[4][2];
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            unsigned b0 = b_lane ^ (unsigned)(kk << 5), b1 = b0 + 32768;
+            asm volatile("" : "+v"(b0), "+v"(b1));
+            bK[kk][0] = smem + b0;
+            bK[kk][1] = smem + b1;
+        }
+        auto read_b = [&](int t, int kk, int j) __attribute__((always_inline)) -> uint4 {
+            return t < 8 ? *(const uint4*)(bK[kk][0] + t * SLAB + j * 4096) : *(const uint4*)(bK[kk][1] + (t * SLAB - 32768) + j * 4096);
+        };
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // this wave's patch copies (and its bias) have landed
+        __builtin_amdgcn_s_barrier();             // barrier 0: patch, slabs 0 and 1 are in LDS
+        asm volatile("" ::: "memory");
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                af[kk][i] = *(const uint4*)(smem + aT[0][i][kk]);
+                bf[kk][i] = read_b(0, kk, i);
+            }
+        TIR_FENCE();
+#pragma unroll
+        for (int t = 0; t < 9; ++t) {
+            if (t < RS) {
+                if (t > 0) {
+                    __builtin_amdgcn_s_barrier();     // barrier t: slab t+1 is in LDS
+                    asm volatile("" ::: "memory");
+                }
+                TIR_FENCE();
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk) {
+                    // two k-steps ahead: same tap for kk < 2, the next tap's first k-steps otherwise; one read behind each MFMA
+                    const int rk = (kk + 2) & 3, rt = kk < 2 ? t : t + 1;
+                    acc[0][0] = InTraits<DT>::mfma(af[kk][0], bf[kk][0], acc[0][0]);
+                    TIR_FENCE();
+                    if (rt < 9) af[rk][0] = *(const uint4*)(smem + aT[rt][0][rk]);
+                    TIR_FENCE();
+                    acc[0][1] = InTraits<DT>::mfma(af[kk][0], bf[kk][1], acc[0][1]);
+                    TIR_FENCE();
+                    if (rt < 9) bf[rk][0] = read_b(rt, rk, 0);
+                    TIR_FENCE();
+                    acc[1][0] = InTraits<DT>::mfma(af[kk][1], bf[kk][0], acc[1][0]);
+                    TIR_FENCE();
+                    if (rt < 9) af[rk][1] = *(const uint4*)(smem + aT[rt][1][rk]);
+                    TIR_FENCE();
+                    acc[1][1] = InTraits<DT>::mfma(af[kk][1], bf[kk][1], acc[1][1]);
+                    TIR_FENCE();
+                    if (rt < 9) bf[rk][1] = read_b(rt, rk, 1);
+                    TIR_FENCE();
+                }
+            }
+        }
+    } else {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");          // this wave's patch copies (and its bias) have landed
     __builtin_amdgcn_s_barrier();                 // barrier 0: patch, slabs 0 and 1 are in LDS
     asm volatile("" ::: "memory");
@@ -1250,7 +1337,6 @@ __global__ void __launch_bounds__(512) conv_patch_kernel(const Params p) {
     // The tap cursor advances by additions under the tap's first MFMA, and the next tap's addresses (needed two k-steps
     // later) are worked out under the back-to-back MFMA pairs of the first two k-steps; an iteration ends on such a pair,
     // which covers the loop branch and the barrier.
-    const int row_step = p.dil_h * PW, col_step = p.dil_w;
     int tap_px = 0, row_px = 0, fs = 0;           // patch offsets of the current tap and of its filter row's first tap; filter column
     for (int t = 0; t < RS; ++t) {
         if (t > 0) {
@@ -1292,6 +1378,7 @@ __global__ void __launch_bounds__(512) conv_patch_kernel(const Params p) {
         }
         tap_px = next_px;
         cA[0] = nA[0]; cA[1] = nA[1]; cB = nB;
+    }
     }
 
     // ------------------------------------------------------------ fused epilogue (NHWC rows are output pixels)

@@ -70,6 +70,7 @@ struct Params {
     int div_cg_shift, div_s_shift, div_rs_shift;
     unsigned div_tn_magic, div_tm_magic, div_pw_magic;     // patch kernel: id / tiles_n, id / tiles_m, copy unit / (PW / 8)
     int div_tn_shift, div_tm_shift, div_pw_shift;
+    int tap_px[9];    // patch kernel, filters of up to nine taps: patch pixel offset (r*dil_h*PW + s*dil_w) of tap t = r*S + s; taps past the last repeat it
     // Transposed convolution by output phase (A_CONV variants; phases_h = 0: off).  The output pixels with
     // (oh mod phases_h, ow mod phases_w) = (ph, pw) form a stride-1 convolution of the input with the filter taps
     // r = r0 + phases_h*t, r0 = (ph + t_pad_h) mod phases_h (likewise in w): grid.y enumerates (phase, group), the

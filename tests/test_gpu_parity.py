@@ -331,6 +331,9 @@ PATCH_CASES = [
     (3, 12, 12, 1, 32, 1, 1, (1, 1), (0, 0), (1, 1)),       # 1x1: a single tap
     (1, 16, 16, 1, 64, 3, 3, (1, 1), (0, 0), (1, 1)),       # no padding
     (1, 14, 100, 1, 64, 3, 3, (1, 1), (1, 1), (1, 1)),      # wide rows: few rows per tile
+    (1, 20, 23, 1, 64, 2, 5, (1, 1), (1, 2), (1, 1)),       # ten taps: the loop over the taps, not its unrolled form
+    (2, 15, 16, 1, 40, 4, 3, (1, 1), (2, 1), (2, 1)),       # twelve taps, dilated rows
+    (1, 18, 18, 1, 64, 2, 2, (1, 1), (0, 0), (1, 1)),       # four taps
 ]
 
 
