@@ -170,8 +170,10 @@ def main():
             "",
             f"Kernel `{info['Kernel_Name']}`: grid {info['Grid_Size_X']} x {info['Grid_Size_Y']} x {info['Grid_Size_Z']} threads, "
             f"workgroup {info['Workgroup_Size_X']}, LDS {info['LDS_Block_Size']} B, {info['VGPR_Count']} VGPR + {info['Accum_VGPR_Count']} AGPR, scratch {info['Scratch_Size']}.",
-            f"Written by `python -m paper_2207_04296_amd.profile --workloads {' '.join(args.workloads)} --steps {args.steps}` on one MI355X "
-            "(variants from an unprofiled `bench.py --tune-only --records ...` run first); every figure below is per launch.",
+            f"Written by `python -m paper_2207_04296_amd.profile --workloads {' '.join(args.workloads)} --steps {args.steps}"
+            f"{' --no-tune' if args.no_tune else ''} --out {args.out}` on one MI355X "
+            + ("(the variant is the library's built-in choice: no tuning records)" if args.no_tune else
+               "(variants from an unprofiled `bench.py --tune-only --records ...` run first)") + "; every figure below is per launch.",
             "",
             "## Kernel time",
             "",
