@@ -10,6 +10,7 @@
 #include <mutex>
 #include <tuple>
 #include <utility>
+#include <vector>
 
 #include "tir.h"
 #include "tir_launch.h"
@@ -667,6 +668,7 @@ static tir_status tune_problem(MakePlan make_plan, int reps, hipStream_t stream,
     TrialGuard guard;
     Choice best = kNoChoice;
     float best_ms = 0.f;
+    std::vector<std::pair<Choice, float>> tried;      // every variant that was measured, with its time per launch
     // n launches of plan pl captured into one HIP graph and replayed (launched one by one, kernels of a few
     // microseconds would be timed at the host's launch rate, not the device's); ms per launch in *ms_out
     auto timed_plan = [&](const Plan& pl, int n, float* ms_out) -> tir_status {
@@ -734,7 +736,42 @@ static tir_status tune_problem(MakePlan make_plan, int reps, hipStream_t stream,
         if (best.v && ms > 4.f * best_ms + 0.05f) continue;
         st = timed(reps);
         if (st != TIR_OK) break;
+        tried.push_back({Choice{v, ks}, ms});
         if (!best.v || ms < best_ms) { best = Choice{v, ks}; best_ms = ms; }
+    }
+    // Play-off.  One timing per variant is good to a few per cent (clocks move with the power the previous trial
+    // drew), and the variants near the top are often closer than that: those within 10 % of the fastest are timed
+    // again, three rounds in turn, and each keeps its fastest round.
+    if (st == TIR_OK && best.v) {
+        std::vector<std::pair<Choice, float>> top;
+        for (const auto& t : tried)
+            if (t.second <= 1.10f * best_ms) top.push_back(t);
+        for (int round = 0; round < 3 && st == TIR_OK && top.size() > 1; ++round) {
+            for (auto& t : top) {
+                g_trial = t.first;
+                Plan pl;
+                st = make_plan(&pl);
+                if (st == TIR_OK) st = attach_workspace(&pl, caller_stream);
+                float ms = 0.f;
+                if (st == TIR_OK) st = timed_plan(pl, reps, &ms);
+                if (st != TIR_OK) break;
+                if (ms < t.second) t.second = ms;
+            }
+        }
+        if (st == TIR_OK) {
+            for (const auto& t : top)
+                if (t.second < best_ms) { best = t.first; best_ms = t.second; }
+            // The trials run on operands that sit in the caches.  Among variants within 2 % of the fastest the one with the
+            // deepest ring wins: it is the one that loses least when the operands come from memory (4096-cube GEMM: the
+            // two-slot 256x256 tile is 7 % slower cold than hot, the three- and four-slot ones are not).
+            const float fastest = best_ms;
+            for (const auto& t : top)
+                if (t.second <= 1.02f * fastest &&
+                    (t.first.v->nstage > best.v->nstage || (t.first.v->nstage == best.v->nstage && t.second < best_ms))) {
+                    best = t.first;
+                    best_ms = t.second;
+                }
+        }
     }
     (void)hipEventDestroy(e0);
     (void)hipEventDestroy(e1);
