@@ -108,6 +108,46 @@ def test_config_4096_sampled_rows_and_columns(B, oracle, name):
     assert np.all(np.abs(got.sum(axis=0) - colsum_ref) <= bound)
 
 
+@pytest.mark.parametrize("force", ["t256x256w2x4s3r64_ak_bn", "t256x256w2x4s4r64_ak_bn", "t256x256w2x4s2_ak_bn", "t256x128w4x2s3c4_ak_bn"])
+def test_config_4096_in_every_variant_the_tuner_has_chosen(B, oracle, force):
+    """The 4096-cube GEMM is timed in whichever of these variants the measurement prefers on the box at hand:
+    each meets the bar on sampled rows and columns at full size."""
+    wl = I.WORKLOADS["c4a_gemm4096_f16"]
+    a_bits, b_bits = wl.operands()
+    B.tir_debug_force_variant(force)
+    try:
+        name = PT.variant_name(B, wl)
+        _say(f"{wl.name} via {name}")
+        assert force in name, name
+        got = PT.run_gpu(wl, a_bits, b_bits)
+    finally:
+        B.tir_debug_force_variant("")
+    rng = np.random.default_rng(wl.seed + 1)
+    rows = np.sort(rng.choice(wl.M, 96, replace=False))
+    cols = np.sort(rng.choice(wl.N, 96, replace=False))
+    ref, S = oracle.gemm(wl.dtype, np.ascontiguousarray(a_bits[rows]), b_bits, len(rows), wl.N, wl.K, wl.K, 1, wl.N, 1)
+    PT.assert_close(got[rows], ref, S, f"{wl.name} via {name}, rows")
+    bsub = np.ascontiguousarray(b_bits[:, cols])
+    ref, S = oracle.gemm(wl.dtype, a_bits, bsub, wl.M, len(cols), wl.K, wl.K, 1, len(cols), 1)
+    PT.assert_close(got[:, cols], ref, S, f"{wl.name} via {name}, columns")
+
+
+@pytest.mark.parametrize("name", ["c4b_gemm_ffn_f16", "c4b_gemm_ffn_bf16", "c4b_gemm_ffn_f16_bias_relu_out16"])
+@pytest.mark.parametrize("force", ["t256x96w4x1s3c4_ak_bn", "t128x192w2x2s3c4_ak_bn"])
+def test_ffn_gemm_full_size_on_the_three_block_wave_tiles(B, oracle, name, force):
+    """2048 x 3072 x 768 on the 256x96 and 128x192 tiles (64x96 wave tiles, N-major B tiles of 192 and 384 bytes per k-row)."""
+    wl = I.WORKLOADS.get(name) or I.FUSED_WORKLOADS[name]
+    B.tir_debug_force_variant(force)
+    try:
+        used = PT.variant_name(B, wl)
+        _say(f"{name} via {used}")
+        assert force in used, used
+        ratio = PT.check_workload(wl, oracle, f"{name} via {used}")
+        _say(f"{name} max err/tol {ratio:.3g}")
+    finally:
+        B.tir_debug_force_variant("")
+
+
 def I_decode(dtype, bits):
     """numpy-side decode for the size-independent property above (not the oracle's decoder)."""
     if dtype == "f16":
