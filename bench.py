@@ -52,6 +52,7 @@ MEASURED_TRAFFIC_BYTES = {
     ("c2a_conv56x64_f16", "f16_f16_patch256x64_conv"): 7243447 + 6422528,
     ("c4a_gemm4096_f16", "f16_f32_t256x128w4x2s3c4_ak_bn"): 268541908 + 67108864,
     ("c4a_gemm4096_f16", "f16_f32_t256x256w2x4s4r64_ak_bn"): 201499478 + 67108864,
+    ("c4a_gemm4096_f16", "f16_f32_t256x256w2x4s3r64_ak_bn"): 201508049 + 67108864,
 }
 
 
@@ -73,6 +74,9 @@ def parse():
     ap.add_argument("--profile-run", action="store_true",
                     help="only the headline timed region (for rocprofv3): no tuning trials (use --records), hot rerun, "
                          "operator table, probe or oracle; 2 replays")
+    ap.add_argument("--variant", default=None,
+                    help="launch this kernel variant (a name or part of one, as tir_debug_force_variant takes it) instead of the chosen one; "
+                         "for profiles of a variant the measurement does not pick on the box at hand")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="instead of the workload, run 8 device-to-device copies of 64 MiB (a plain copy kernel of "
                          "known size, to scale the FETCH_SIZE / WRITE_SIZE counters)")
@@ -339,9 +343,12 @@ def main():
     have_records = bool(args.records) and os.path.exists(args.records)
     if have_records:
         B.tir_tune_load(args.records)
-    measure = not args.no_tune and not have_records and not args.profile_run     # run tir_tune_* before timing
-    selection = ("kept records (tir_tune_load)" if have_records else
+    measure = not args.no_tune and not have_records and not args.profile_run and not args.variant     # run tir_tune_* before timing
+    selection = ("forced (--variant)" if args.variant else "kept records (tir_tune_load)" if have_records else
                  "measured (tir_tune_*, untimed, before the run)" if measure else "scoring rule")
+    if args.variant:
+        B.tir_debug_force_variant(args.variant)
+        args.no_operators = True          # the other workloads have other variants
 
     if args.tune_only:
         for name, o in all_bench_workloads(I):

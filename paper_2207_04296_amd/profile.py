@@ -101,6 +101,7 @@ def main():
     ap.add_argument("--out", default="gpurun_out/prof")
     ap.add_argument("--steps", type=int, default=40, help="launches per replay in the profiled runs")
     ap.add_argument("--no-tune", action="store_true", help="profile the scoring rule's variants (no records)")
+    ap.add_argument("--variant", default=None, help="profile this variant (bench.py --variant) instead of the measured or built-in choice")
     ap.add_argument("--parse-only", action="store_true", help="start nothing: read the CSVs and logs an earlier run left under --out")
     args = ap.parse_args()
     global PARSE_ONLY
@@ -113,8 +114,8 @@ def main():
     py = "python3"
     bench = str(root / "bench.py")
     records = out / "records.txt"
-    rec_args = []
-    if not args.no_tune:
+    rec_args = ["--variant", args.variant] if args.variant else []
+    if not args.no_tune and not args.variant:
         if records.exists() and not PARSE_ONLY:
             records.unlink()
         for w in args.workloads:
@@ -171,8 +172,9 @@ def main():
             f"Kernel `{info['Kernel_Name']}`: grid {info['Grid_Size_X']} x {info['Grid_Size_Y']} x {info['Grid_Size_Z']} threads, "
             f"workgroup {info['Workgroup_Size_X']}, LDS {info['LDS_Block_Size']} B, {info['VGPR_Count']} VGPR + {info['Accum_VGPR_Count']} AGPR, scratch {info['Scratch_Size']}.",
             f"Written by `python -m paper_2207_04296_amd.profile --workloads {' '.join(args.workloads)} --steps {args.steps}"
-            f"{' --no-tune' if args.no_tune else ''} --out {args.out}` on one MI355X "
-            + ("(the variant is the library's built-in choice: no tuning records)" if args.no_tune else
+            f"{' --no-tune' if args.no_tune else ''}{' --variant ' + args.variant if args.variant else ''} --out {args.out}` on one MI355X "
+            + ("(the variant is the one named on the command line)" if args.variant else
+               "(the variant is the library's built-in choice: no tuning records)" if args.no_tune else
                "(variants from an unprofiled `bench.py --tune-only --records ...` run first)") + "; every figure below is per launch.",
             "",
             "## Kernel time",
