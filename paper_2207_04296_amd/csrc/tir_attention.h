@@ -83,7 +83,7 @@ __global__ void __launch_bounds__(256) attention_kernel(const AttnParams p) {
     // ------------------------------------------------------------ copy stage
     // K-major tile (Q, K): slot q = tid + i*256 is row q / (8*HALVES)... kept as HALVES sub-tiles of
     // [128 rows][128 B] so that the row swizzle of the GEMM kernels applies unchanged.
-    auto copy_kmajor = [&](const char* base, long long valid_bytes, char* dst) {
+    auto copy_kmajor = [&](const char* base, long long valid_bytes, char* dst, bool nt) {
         const i32x4 r = make_rsrc(base, valid_bytes);
 #pragma unroll
         for (int h = 0; h < HALVES; ++h)
@@ -92,28 +92,33 @@ __global__ void __launch_bounds__(256) attention_kernel(const AttnParams p) {
                 const int q = tid + i * 256;              // 1024 chunks of 16 B per sub-tile
                 const int row = q >> 3;
                 const int lc = (q & 7) ^ kmajor_swz<128>(row);
-                load_to_lds(r, dst + h * (128 * 128) + i * 4096 + wave * 1024, (unsigned)(row * ROW + h * 128 + lc * 16));
+                if (nt) load_to_lds_nt(r, dst + h * (128 * 128) + i * 4096 + wave * 1024, (unsigned)(row * ROW + h * 128 + lc * 16));
+                else load_to_lds(r, dst + h * (128 * 128) + i * 4096 + wave * 1024, (unsigned)(row * ROW + h * 128 + lc * 16));
             }
     };
-    auto copy_v = [&](const char* base, long long valid_bytes, char* dst) {
+    auto copy_v = [&](const char* base, long long valid_bytes, char* dst, bool nt) {
         const i32x4 r = make_rsrc(base, valid_bytes);
 #pragma unroll
         for (int i = 0; i < 4 * HALVES; ++i) {
             const int q = tid + i * 256;
             const int key = q / VRC;
             const int lb = ((q % VRC) * 16) ^ (((key / RPW) % NSEG) * 64);
-            load_to_lds(r, dst + i * 4096 + wave * 1024, (unsigned)(key * ROW + lb));
+            if (nt) load_to_lds_nt(r, dst + i * 4096 + wave * 1024, (unsigned)(key * ROW + lb));
+            else load_to_lds(r, dst + i * 4096 + wave * 1024, (unsigned)(key * ROW + lb));
         }
     };
     const char* Qb = (const char*)p.Q + ((b * p.M + m0) * (long long)ROW);
     const char* Kb = (const char*)p.K + b * p.N * (long long)ROW;
     const char* Vb = (const char*)p.V + b * p.N * (long long)ROW;
+    // Non-temporal copies for what one workgroup alone reads - the queries always, keys and values when one tile holds all
+    // queries of a head: 7.05 -> 6.63 us on the benchmark's 192 heads with the operands coming from memory, no change from the caches.
+    const bool kv_once = p.tiles_m == 1;
     auto copy_chunk = [&](int c) {
         const long long left = (long long)(p.N - c * 128) * ROW;      // rows past N lie outside the descriptor: zeros
-        copy_kmajor(Kb + (long long)c * TILE, left, s_k(c & 1));
-        copy_v(Vb + (long long)c * TILE, left, s_v(c & 1));
+        copy_kmajor(Kb + (long long)c * TILE, left, s_k(c & 1), kv_once);
+        copy_v(Vb + (long long)c * TILE, left, s_v(c & 1), kv_once);
     };
-    copy_kmajor(Qb, (long long)rows_q * ROW, s_q);
+    copy_kmajor(Qb, (long long)rows_q * ROW, s_q, true);
     copy_chunk(0);
     // Q and the first keys are enough to start on the scores: the first values (the newest 4*HALVES
     // copies of this wave) may still be in flight, they are waited for before the second product
