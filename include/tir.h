@@ -261,7 +261,7 @@ const char* tir_conv2d_transpose_variant(int64_t N, int64_t H, int64_t W, int64_
  * tir_tune_batch_matmul / tir_tune_conv2d take the arguments of tir_batch_matmul_fused / tir_conv2d_fused
  * (batch = 1 with zero batch strides tunes tir_gemm; ep may be NULL), launch every compiled variant that computes this problem
  * - and, where few tiles face a long reduction and `stream` has a registered workspace, the same variant with the
- * reduction split over 2, 3, 4, 6 or 8 workgroups per tile - `reps` times on `stream`, time those within 10 % of the fastest three more
+ * reduction split over 2, 3, 4, 6 or 8 workgroups per tile - `reps` times on `stream`, time those within 10 % of the fastest five more
  * times in turn (each keeps its fastest round; among the ones that end within 2 % of each other the deepest copy ring wins, the
  * trials' operands being warm in the caches), and record the winner under the problem's signature (dtypes, copy
  * modes implied by strides and alignment, extents, convolution geometry).  Later calls of the

@@ -741,12 +741,12 @@ static tir_status tune_problem(MakePlan make_plan, int reps, hipStream_t stream,
     }
     // Play-off.  One timing per variant is good to a few per cent (clocks move with the power the previous trial
     // drew), and the variants near the top are often closer than that: those within 10 % of the fastest are timed
-    // again, three rounds in turn, and each keeps its fastest round.
+    // again, five rounds in turn, and each keeps its fastest round.
     if (st == TIR_OK && best.v) {
         std::vector<std::pair<Choice, float>> top;
         for (const auto& t : tried)
             if (t.second <= 1.10f * best_ms) top.push_back(t);
-        for (int round = 0; round < 3 && st == TIR_OK && top.size() > 1; ++round) {
+        for (int round = 0; round < 5 && st == TIR_OK && top.size() > 1; ++round) {
             for (auto& t : top) {
                 g_trial = t.first;
                 Plan pl;
