@@ -356,3 +356,19 @@ def test_conv1d_conv3d_and_transposed_conv_validate_on_the_host():
     assert "convx" in q(64, (2, 2), (2, 1)) and "convx" in q(32, (2, 2), (1, 1)) and "convx" in q(64, (1, 1), (1, 1))
     assert B.tir_conv3d_variant(1, 10, 16, 16, 128, 64, 3, 3, 3, (1, 1, 1), (1, 1, 1), (1, 1, 1), 1, "f16", "f16").endswith("_convx/z6")
     assert B.tir_conv3d_variant(1, 0, 16, 16, 128, 64, 3, 3, 3, (1, 1, 1), (1, 1, 1), (1, 1, 1), 1, "f16", "f16") == ""
+
+
+def test_variant_table_is_what_its_generator_writes():
+    """csrc/tir_variants.def is generated (gen_variants.py): the committed table and the tile list must not drift apart,
+    and every name must be unique."""
+    import importlib.util
+    import re
+    from pathlib import Path
+    csrc = Path(__file__).resolve().parent.parent / "paper_2207_04296_amd" / "csrc"
+    spec = importlib.util.spec_from_file_location("gen_variants", csrc / "gen_variants.py")
+    gen = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(gen)
+    text = (csrc / "tir_variants.def").read_text()
+    assert gen.render() == text, "run python paper_2207_04296_amd/csrc/gen_variants.py"
+    names = re.findall(r'^V\d+\("([^"]+)"', text, flags=re.M)
+    assert len(names) == len(set(names)) and len(names) > 600
