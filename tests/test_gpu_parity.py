@@ -401,6 +401,42 @@ def test_conv_patch_kernel(B, oracle, dtype, out):
             B.tir_debug_force_variant("")
 
 
+def test_conv_patch_kernel_seeded_shapes(B, oracle):
+    """Two dozen seeded geometries (filter extents 1..4, strides, paddings, dilations, groups, ragged channel counts) through
+    the LDS-resident-patch kernel where it applies, element by element against the oracle."""
+    rng = np.random.default_rng(20240607)
+    done = 0
+    for case in range(200):
+        if done == 24:
+            break
+        # (bf16 outputs have their own, wider bound - rounding the sum to 8 bits - and their own tests)
+        dtype, out = [("f16", "f16"), ("f16", "f32"), ("bf16", "f32"), ("i8", "i32"), ("i8", "i8")][case % 5]
+        cg = 128 if dtype == "i8" else 64
+        groups = int(rng.integers(1, 3))
+        r, s_ = int(rng.integers(1, 5)), int(rng.integers(1, 5))
+        stride = (int(rng.integers(1, 3)), int(rng.integers(1, 3)))
+        dil = (int(rng.integers(1, 3)), int(rng.integers(1, 3)))
+        pad = (int(rng.integers(0, 3)), int(rng.integers(0, 3)))
+        n, h, w = int(rng.integers(1, 4)), int(rng.integers(9, 30)), int(rng.integers(9, 40))
+        k = groups * int(rng.choice([8, 24, 40, 64, 72]))
+        P = (h + 2 * pad[0] - dil[0] * (r - 1) - 1) // stride[0] + 1
+        Q = (w + 2 * pad[1] - dil[1] * (s_ - 1) - 1) // stride[1] + 1
+        if P < 1 or Q < 1:
+            continue
+        fused = dict(ep_bias=True, ep_relu=bool(case & 1)) if out in ("f16", "bf16") else {}
+        if out == "i8":
+            fused = dict(ep_bias=True, ep_relu=True, ep_scale=0.004)
+        wl = I.Workload(f"patch_seeded_{case}_{dtype}_{out}_r{r}s{s_}", "conv2d", dtype, out, "i" if dtype == "i8" else "n0.1", 8800 + case,
+                        n=n, h=h, w=w, c=cg * groups, k=k, r=r, s=s_, stride=stride, pad=pad, dil=dil, groups=groups, **fused)
+        name = PT.variant_name(B, wl)
+        if "patch" not in name:
+            continue
+        _say(f"{wl.name}: n{n} {h}x{w} g{groups} k{k} stride{stride} pad{pad} dil{dil} -> {name}")
+        PT.check_workload(wl, oracle)
+        done += 1
+    assert done == 24
+
+
 # ------------------------------------------------------------------------------ choice by measurement
 def test_tuning_measures_records_and_keeps_results_correct(B, oracle, tmp_path):
     """tir_tune_* runs every variant that can compute the problem, records the fastest, and the
