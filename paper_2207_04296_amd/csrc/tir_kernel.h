@@ -478,11 +478,11 @@ __device__ __forceinline__ void store_tile_phase(const Params& p, long long bz, 
 // Fast kernel: vector copy modes, global -> LDS without a register hop, NSTAGE-deep copy ring.
 //
 // Stage h of the reduction lives in ring slot h % NSTAGE.  Iteration h of the main loop
-//   (1) multiplies k-steps 0 .. KSTEPS-2 of stage h while it requests the fragments of the next
-//       k-step from LDS and issues the global->LDS copy of stage h+NSTAGE-1 (its slot held stage
+//   (1) multiplies k-steps 0 .. KSTEPS-LA-1 of stage h while it requests the fragments LA k-steps ahead
+//       from LDS and issues the global->LDS copy of stage h+NSTAGE-1 (its slot held stage
 //       h-1, which every wave finished reading before the previous barrier);
 //   (2) waits until this wave's copy of stage h+1 has landed and joins the workgroup barrier;
-//   (3) multiplies the last k-step of stage h while requesting the first fragments of stage h+1.
+//   (3) multiplies the last LA k-steps of stage h while requesting the first fragments of stage h+1.
 // The last NSTAGE-1 iterations have no stage left to copy and skip that part of (1).
 // A wave issues one instruction per ~4 cycles whatever its kind, and at one or two waves per SIMD all of
 // them are exposed: slots and stages advance by counters (no h % NSTAGE), divisions by launch constants
@@ -498,7 +498,6 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
     static_assert(C::AMODE == A_KMAJOR || C::AMODE == A_CONV || C::AMODE == A_CONVX, "");
     static_assert(C::BMODE == B_KMAJOR || C::BMODE == B_NMAJOR, "");
     static_assert((NSTAGE - 2) * L <= 63, "vmcnt range");
-    static_assert(KSTEPS % 2 == 0, "fragment sets alternate per k-step and must line up per stage");
 
     __shared__ __attribute__((aligned(1024))) char smem[C::LDS_BYTES];
     prefetch_args(p, C::AMODE != A_KMAJOR);
@@ -870,12 +869,17 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
     acc_e bias_r[C::NI];
     load_bias<C>(p, bz, n0, wn, lane, bias_r);
 
-    uint4 af[2][C::MI], bf[2][C::NI];
+    // Fragment look-ahead: the fragments of k-step g are requested while k-step g - LA multiplies, into one of
+    // LA + 1 register sets.  A wave with one or two MFMAs per k-step has 32-64 cycles of them in flight, less
+    // than an LDS read's round trip, and stalls every k-step with a look-ahead of one.
+    constexpr int LA = C::LA, NSET = LA + 1;
+    static_assert(KSTEPS % NSET == 0 && LA < KSTEPS, "fragment sets rotate per k-step and must line up per stage");
+    uint4 af[NSET][C::MI], bf[NSET][C::NI];
 
     // One k-step: the MI*NI MFMAs on fragment set `set`, interleaved with `nside` units of side
-    // work: first the fragment reads of (ra_s, rb_s, rk) into the other set, then copy units
+    // work: first the fragment reads of (ra_s, rb_s, rk) into set `into`, then copy units
     // [v0, v0 + nv).
-    auto kstep = [&](int set, const char* ra_s, const char* rb_s, int rk, int v0, int nv) __attribute__((always_inline)) {
+    auto kstep = [&](int set, int into, const char* ra_s, const char* rb_s, int rk, int v0, int nv) __attribute__((always_inline)) {
         constexpr int NM = C::MI * C::NI;
         constexpr int NR = C::MI + C::NI;
         const int nside = NR + nv;
@@ -885,8 +889,8 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
             TIR_FENCE();
 #pragma unroll
             for (int u = t * nside / NM; u < (t + 1) * nside / NM; ++u) {
-                if (u < C::MI) af[set ^ 1][u] = frag.read_a1(ra_s, rk, u);
-                else if (u < NR) bf[set ^ 1][u - C::MI] = frag.read_b1(rb_s, rk, u - C::MI);
+                if (u < C::MI) af[into][u] = frag.read_a1(ra_s, rk, u);
+                else if (u < NR) bf[into][u - C::MI] = frag.read_b1(rb_s, rk, u - C::MI);
                 else copy_unit(v0 + u - NR);
                 TIR_FENCE();
             }
@@ -907,12 +911,21 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
         }
         if (nh >= NSTAGE - 1) copy_barrier<(NSTAGE - 2) * L>();
         else copy_barrier<0>();
-        frag.read_a(ring, 0, af[0]);
-        frag.read_b(ring + C::A_BYTES, 0, bf[0]);
+#pragma unroll
+        for (int kk = 0; kk < LA; ++kk) {
+            frag.read_a(ring, kk, af[kk]);
+            frag.read_b(ring + C::A_BYTES, kk, bf[kk]);
+        }
         TIR_FENCE();
 
-        constexpr int LM = SPEC ? 0 : L;                           // copy units the multiplying waves issue per stage
-        constexpr int VPK = (LM + KSTEPS - 2) / (KSTEPS - 1);     // ... per k-step of part (1)
+        // Copy units the multiplying waves issue per stage, and per k-step.  With a look-ahead of one they all
+        // precede the barrier; with a longer one the barrier comes LA k-steps before the stage's end and (a ring of
+        // three or more) the units are spread over the whole stage, U_PRE of them before the barrier.
+        constexpr int LM = SPEC ? 0 : L;
+        constexpr int KS_COPY = (LA == 1 || NSTAGE < 3) ? KSTEPS - LA : KSTEPS;
+        constexpr int VPK = (LM + KS_COPY - 1) / KS_COPY;
+        constexpr int U_PRE = (KSTEPS - LA) * VPK < LM ? (KSTEPS - LA) * VPK : LM;
+        static_assert(NSTAGE >= 3 || U_PRE == LM, "a ring of two copies the very stage the barrier waits for");
         int r_off = 0;                                             // byte offset of stage h's ring slot (h % NSTAGE, without the division)
         // One iteration of the loop described above; COPY: stage h+NSTAGE-1 exists and is copied meanwhile.  The last
         // NSTAGE-1 iterations have nothing left to copy (a copy instruction costs its wave ~60 cycles even when its
@@ -927,15 +940,18 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
             if constexpr (!SPEC && COPY) copy_begin();
             TIR_FENCE();
 #pragma unroll
-            for (int kk = 0; kk < KSTEPS - 1; ++kk) {
+            for (int kk = 0; kk < KSTEPS; ++kk) {
+                // Before the first read of stage h+1: this wave's copy of it has landed (the copies issued after it
+                // may be in flight: NSTAGE-3 whole stages and this iteration's first U_PRE units); after the barrier
+                // everybody's has, and every wave is done reading stage h-1's slot ... and stage h (its last
+                // fragments are in registers).
+                if (kk == KSTEPS - LA) copy_barrier<COPY ? (NSTAGE - 3) * L + (SPEC ? L : U_PRE) : 0>();
                 const int v0 = kk * VPK;
                 const int nv = v0 + VPK <= LC ? VPK : (LC > v0 ? LC - v0 : 0);
-                kstep(kk & 1, sa, sb, kk + 1, v0, nv);
+                const int rk = kk + LA;
+                if (rk < KSTEPS) kstep(kk % NSET, rk % NSET, sa, sb, rk, v0, nv);
+                else kstep(kk % NSET, rk % NSET, na, na + C::A_BYTES, rk - KSTEPS, v0, nv);
             }
-            // this wave's copy of stage h+1 has landed; after the barrier everybody's has, and
-            // every wave is done reading stage h-1's slot ... and stage h (its last fragments are in registers)
-            copy_barrier<COPY ? (NSTAGE - 2) * L : 0>();
-            kstep((KSTEPS - 1) & 1, na, na + C::A_BYTES, 0, 0, 0);
         };
         int h = 0;
         for (; h + NSTAGE - 1 < nh; ++h) iteration(h, std::true_type());

@@ -173,6 +173,9 @@ struct Cfg {
     static constexpr int RCH = ROWB / 16;      // 16-byte columns per K-major row
     static constexpr int TM = BM / WM, TN = BN / WN;
     static constexpr int MI = TM / 32, NI = TN / 32;
+    // k-steps by which the LDS fragment reads run ahead of the MFMAs that use them: three where a k-step is one or two
+    // MFMAs (shorter than an LDS round trip), else one
+    static constexpr int LA = (MI * NI <= 2 && KSTEPS % 4 == 0) ? 3 : 1;
     static constexpr int A_BYTES = BM * ROWB, B_BYTES = BN * ROWB;
     static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
     static constexpr int RING_BYTES = NSTAGE * STAGE_BYTES;   // one reduction group's ring
