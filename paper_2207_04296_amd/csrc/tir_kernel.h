@@ -919,13 +919,13 @@ __global__ void __launch_bounds__(C::THREADS) contract_direct_kernel(const Param
         TIR_FENCE();
 
         // Copy units the multiplying waves issue per stage, and per k-step.  With a look-ahead of one they all
-        // precede the barrier; with a longer one the barrier comes LA k-steps before the stage's end and (a ring of
-        // three or more) the units are spread over the whole stage, U_PRE of them before the barrier.
+        // precede the barrier; with a longer one (rings of three slots or more) the barrier comes LA k-steps before the
+        // stage's end and the units are spread over the whole stage, U_PRE of them before the barrier.
         constexpr int LM = SPEC ? 0 : L;
-        constexpr int KS_COPY = (LA == 1 || NSTAGE < 3) ? KSTEPS - LA : KSTEPS;
+        constexpr int KS_COPY = LA == 1 ? KSTEPS - 1 : KSTEPS;
         constexpr int VPK = (LM + KS_COPY - 1) / KS_COPY;
         constexpr int U_PRE = (KSTEPS - LA) * VPK < LM ? (KSTEPS - LA) * VPK : LM;
-        static_assert(NSTAGE >= 3 || U_PRE == LM, "a ring of two copies the very stage the barrier waits for");
+        static_assert(NSTAGE >= 3 || LA == 1, "a ring of two copies the very stage the barrier waits for");
         int r_off = 0;                                             // byte offset of stage h's ring slot (h % NSTAGE, without the division)
         // One iteration of the loop described above; COPY: stage h+NSTAGE-1 exists and is copied meanwhile.  The last
         // NSTAGE-1 iterations have nothing left to copy (a copy instruction costs its wave ~60 cycles even when its

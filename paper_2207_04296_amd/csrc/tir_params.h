@@ -174,8 +174,9 @@ struct Cfg {
     static constexpr int TM = BM / WM, TN = BN / WN;
     static constexpr int MI = TM / 32, NI = TN / 32;
     // k-steps by which the LDS fragment reads run ahead of the MFMAs that use them: three where a k-step is one or two
-    // MFMAs (shorter than an LDS round trip), else one
-    static constexpr int LA = (MI * NI <= 2 && KSTEPS % 4 == 0) ? 3 : 1;
+    // MFMAs (shorter than an LDS round trip) and the ring has three slots or more, else one (with two slots the stage the
+    // early barrier waits for is the one whose copy the iteration has just requested)
+    static constexpr int LA = (MI * NI <= 2 && KSTEPS % 4 == 0 && NSTAGE >= 3) ? 3 : 1;
     static constexpr int A_BYTES = BM * ROWB, B_BYTES = BN * ROWB;
     static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
     static constexpr int RING_BYTES = NSTAGE * STAGE_BYTES;   // one reduction group's ring
