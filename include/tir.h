@@ -262,7 +262,7 @@ const char* tir_conv2d_transpose_variant(int64_t N, int64_t H, int64_t W, int64_
  * (batch = 1 with zero batch strides tunes tir_gemm; ep may be NULL), launch every compiled variant that computes this problem
  * - and, where few tiles face a long reduction and `stream` has a registered workspace, the same variant with the
  * reduction split over 2, 3, 4, 6 or 8 workgroups per tile - `reps` times on `stream`, time those within 10 % of the fastest five more
- * times in turn (each keeps its fastest round; among the ones that end within 2 % of each other the deepest copy ring wins, the
+ * times in turn (each keeps its fastest round; a copy ring of three or more slots wins over a two-slot ring that is less than 2 % faster, the
  * trials' operands being warm in the caches), and record the winner under the problem's signature (dtypes, copy
  * modes implied by strides and alignment, extents, convolution geometry).  Later calls of the
  * operator entry points with the same signature use the recorded variant instead of the built-in

@@ -761,16 +761,19 @@ static tir_status tune_problem(MakePlan make_plan, int reps, hipStream_t stream,
         if (st == TIR_OK) {
             for (const auto& t : top)
                 if (t.second < best_ms) { best = t.first; best_ms = t.second; }
-            // The trials run on operands that sit in the caches.  Among variants within 2 % of the fastest the one with the
-            // deepest ring wins: it is the one that loses least when the operands come from memory (4096-cube GEMM: the
-            // two-slot 256x256 tile is 7 % slower cold than hot, the three- and four-slot ones are not).
-            const float fastest = best_ms;
-            for (const auto& t : top)
-                if (t.second <= 1.02f * fastest &&
-                    (t.first.v->nstage > best.v->nstage || (t.first.v->nstage == best.v->nstage && t.second < best_ms))) {
-                    best = t.first;
-                    best_ms = t.second;
-                }
+            // The trials run on operands that sit in the caches.  If a two-slot ring is the fastest, a ring of three or more
+            // slots within 2 % of it wins instead: two slots lose most when the operands come from memory (4096-cube GEMM: the
+            // two-slot 256x256 tile is 7 % slower cold than hot, the three- and four-slot ones are not).  Rings deeper than three
+            // earn no such bonus: their longer prologue delays the first stage of a cold launch (2048-cube int8 GEMM on 128x128
+            // tiles, four slots against three: the same 11.2 us hot, 17.1 - 18.8 against 16.0 - 16.3 us cold).
+            if (best.v->nstage < 3) {
+                const float fastest = best_ms;
+                for (const auto& t : top)
+                    if (t.second <= 1.02f * fastest && t.first.v->nstage >= 3 && (best.v->nstage < 3 || t.second < best_ms)) {
+                        best = t.first;
+                        best_ms = t.second;
+                    }
+            }
         }
     }
     (void)hipEventDestroy(e0);
