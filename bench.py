@@ -13,7 +13,7 @@ memory before the timed region.
 
 Timing protocol.  The K steps are captured in one HIP graph (the kernels are microseconds long, a
 Python launch loop would measure the host).  The timed region is one replay of that graph, bracketed
-by device synchronisations; it is repeated R times (default 31) and the MEDIAN replay is reported
+by device synchronisations and holding nothing else; it is repeated R times (default 31) and the MEDIAN replay is reported
 (minimum and maximum beside it), so the line does not hang on one sample of a fraction of a
 millisecond.  Cold mode (default): the K steps walk over enough distinct operand / output sets to
 exceed the 256 MB memory-side cache plus the L2s - the number of sets does not depend on K - and
@@ -24,8 +24,9 @@ run with streaming output stores is reported beside it.
 
 Prints ONE JSON line.  `value` = algorithmic TFLOP/s of the median replay by the host clock
 (2*M*N*K of the fused GEMM view per step).  `roofline` prices the headline kernel against the roof
-that binds it (min of the MFMA peak and arithmetic intensity x 8 TB/s) with HIP-event times of the
-same replays; `roofline_gemm` is the same record for the 4096^3 fp16 GEMM; `cpu_baseline` times
+that binds it (min of the MFMA peak and arithmetic intensity x 8 TB/s) with HIP-event times of
+replays taken in turn with the host-clock ones (an event record is device work of its own and stays out of the
+host-clock region); `roofline_gemm` is the same record for the 4096^3 fp16 GEMM; `cpu_baseline` times
 the CPU oracle on the same workload on this machine's host cores; `operators` lists every other
 benchmark configuration, plain and with a fused consumer, hot cache, and cold as well where the
 roofline that binds them is HBM.
@@ -73,7 +74,7 @@ def parse():
     ap.add_argument("--tune-only", action="store_true", help="measure the variants of every bench workload, write --records, exit")
     ap.add_argument("--profile-run", action="store_true",
                     help="only the headline timed region (for rocprofv3): no tuning trials (use --records), hot rerun, "
-                         "operator table, probe or oracle; 2 replays")
+                         "operator table, probe or oracle; 2 replays (one by the host clock, one between events)")
     ap.add_argument("--variant", default=None,
                     help="launch this kernel variant (a name or part of one, as tir_debug_force_variant takes it) instead of the chosen one; "
                          "for profiles of a variant the measurement does not pick on the box at hand")
@@ -102,7 +103,7 @@ class Harness:
 
     def timed(self, launch, steps, warmup, replays, cold):
         """launch(i, stream) enqueues step i.  Returns (wall seconds per replay, HIP-event seconds per replay), lists
-        of `replays` samples; one replay = `steps` launches from one HIP graph."""
+        of `replays` samples each, taken in turn; one replay = `steps` launches from one HIP graph."""
         torch = self.torch
         with torch.cuda.stream(self.stream):
             for i in range(warmup):
@@ -116,18 +117,25 @@ class Harness:
             torch.cuda.synchronize()
             walls, events = [], []
             for _ in range(replays):
+                # one replay under the host clock with nothing else in the timed region ...
+                if cold:
+                    self.flush()
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                graph.replay()
+                torch.cuda.synchronize()
+                t1 = time.perf_counter()
+                walls.append(t1 - t0)
+                # ... and one between HIP events on the launch stream (their records are device work of their own)
                 if cold:
                     self.flush()
                 e0 = torch.cuda.Event(enable_timing=True)
                 e1 = torch.cuda.Event(enable_timing=True)
                 torch.cuda.synchronize()
-                t0 = time.perf_counter()
                 e0.record(self.stream)
                 graph.replay()
                 e1.record(self.stream)
                 torch.cuda.synchronize()
-                t1 = time.perf_counter()
-                walls.append(t1 - t0)
                 events.append(e0.elapsed_time(e1) * 1e-3)
             del graph
         return walls, events
@@ -366,7 +374,7 @@ def main():
 
     wl = I.WORKLOADS[args.workload or "c2a_conv56x64_f16"]
     steps, warmup = max(1, args.steps), max(0, args.warmup)
-    replays = 2 if args.profile_run else max(1, args.replays)
+    replays = 1 if args.profile_run else max(1, args.replays)      # (each is two replays of the graph: one by the host clock, one between events)
     cold = not args.hot
     nsets = cold_set_count(wl) if cold else 1
     sets = make_sets(B, wl, nsets)
@@ -445,7 +453,7 @@ def main():
                    "out_dtype": wl.out, "variant": variant_of(B, wl), "launch": "hip_graph",
                    "selection": selection, "cache": cache_note,
                    "output_stores": "cached (library default)"},
-        "timing": {"replays": replays, "reported": "median replay; ms_per_step x steps = one replay",
+        "timing": {"replays": replays, "reported": "median replay by the host clock; ms_per_step x steps = one replay; event-timed replays alternate with the host-clock ones",
                    "wall_ms_per_replay": stats(walls, 1e3), "event_ms_per_replay": stats(events, 1e3)},
         "frac_mfma_peak": round(value / peak, 4),
         "value_device_clock": round(wl.flops() * steps / statistics.median(events) / 1e12, 3),
