@@ -361,6 +361,34 @@ def test_every_variant_on_ragged_problems(B, oracle, dtype, out):
         B.tir_debug_force_variant("")
 
 
+@pytest.mark.parametrize("dtype,out", [("f16", "f32"), ("bf16", "bf16"), ("i8", "i32")])
+def test_every_variant_on_short_reductions(B, oracle, dtype, out):
+    """Reductions of fewer stages than the copy ring has slots (one vector, one stage, one stage and a tail, two and
+    three stages and a tail) through every tile shape / ring depth of both GEMM copy modes: prologue, the iterations
+    without a copy, the early barrier of the tiles that read their fragments three k-steps ahead."""
+    names = B.tir_debug_variant_names()
+    tag = f"{dtype}_{out}_"
+    dist = "i" if dtype == "i8" else "u"
+    vec = 16 if dtype == "i8" else 8
+    try:
+        for kv in (1, 8, 9, 17, 25):
+            for suffix, trans_b in (("_ak_bn", False), ("_ak_bk", True)):
+                wl = I.Workload(f"v_short_k{kv}{suffix}", "gemm", dtype, out, dist, 8500 + kv, M=70, N=5 * vec, K=kv * vec, trans_b=trans_b)
+                a_bits, b_bits = wl.operands()
+                ref, S = PT.run_oracle(wl, a_bits, b_bits, oracle)
+                if out == "bf16":
+                    S = S + 2.0 ** -8 * np.abs(ref) / 2e-3
+                todo = [n for n in names if n.startswith(tag) and n.endswith(suffix)]
+                assert todo
+                for name in todo:
+                    _say(f"{wl.name} {name}")
+                    B.tir_debug_force_variant(name)
+                    got = PT.run_gpu(wl, a_bits, b_bits)
+                    PT.assert_close(got, ref, S, f"{wl.name} via {name}")
+    finally:
+        B.tir_debug_force_variant("")
+
+
 # ------------------------------------------------------------------------------ LDS-resident-patch convolution
 PATCH_CASES = [
     # n, h, w, c_per_group_bytes=128 -> c, k, r, s, stride, pad, dil, groups
