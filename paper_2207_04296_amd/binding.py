@@ -439,6 +439,35 @@ def run_workload(wl, a_dev, b_dev, c_dev, bias_dev=None, stream=None, streaming=
                                wl.dtype, wl.out, ep, stream)
 
 
+def prepare_workload(wl, a_dev, b_dev, c_dev, bias_dev=None, stream=None, streaming=False):
+    """run_workload with the argument marshalling done once: returns a function of no arguments that launches
+    the workload on these operands and this stream (for launch loops where the host's time per call matters)."""
+    ep = _wl_epilogue(wl, bias_dev, streaming)            # kept alive by the closure below
+    L, st = lib(), _stream(stream)
+    a, b, c, ep_ref = _ptr(a_dev), _ptr(b_dev), _ptr(c_dev), _ep_arg(ep)
+    dt, od = _code(wl.dtype), _code(wl.out)
+    if wl.kind == "conv2d":
+        fn = L.tir_conv2d_fused
+        args = (a, b, c, wl.n, wl.h, wl.w, wl.c, wl.k, wl.r, wl.s, wl.stride[0], wl.stride[1], wl.pad[0], wl.pad[1],
+                wl.dil[0], wl.dil[1], wl.groups, dt, od, ep_ref, st)
+    else:
+        M, N, K = wl.M, wl.N, wl.K
+        b_rs, b_cs = (1, K) if wl.trans_b else (N, 1)
+        if wl.kind == "gemm":
+            fn = L.tir_gemm_fused
+            args = (a, b, c, M, N, K, K, 1, b_rs, b_cs, N, 1, dt, od, ep_ref, st)
+        else:
+            fn = L.tir_batch_matmul_fused
+            args = (a, b, c, wl.batch, M, N, K, M * K, K, 1, K * N, b_rs, b_cs, M * N, N, 1, dt, od, ep_ref, st)
+
+    def launch(_keep=(a_dev, b_dev, c_dev, bias_dev, ep)) -> None:
+        status = fn(*args)
+        if status != TIR_OK:
+            _check(status)
+
+    return launch
+
+
 def tune_workload(wl, a_dev, b_dev, c_dev, bias_dev=None, reps=5, stream=None) -> float:
     """tir_tune_* for one paper_2207_04296_amd.inputs.Workload; returns the winner's microseconds per launch."""
     ep = _wl_epilogue(wl, bias_dev)
