@@ -51,7 +51,7 @@ FLUSH_BYTES = 320 << 20           # source and destination of the flush copy, ea
 # to paste here and writes the summary under profiles/.  Keyed by (workload, variant): a figure measured on another
 # variant than the one timed is not reported.
 MEASURED_TRAFFIC_BYTES = {
-    ("c2a_conv56x64_f16", "f16_f16_patch256x64_conv"): 7243461 + 6422528,
+    ("c2a_conv56x64_f16", "f16_f16_patch256x64_conv"): 7251628 + 6422528,
     ("c4a_gemm4096_f16", "f16_f32_t256x128w4x2s3c4_ak_bn"): 268541908 + 67108864,
     ("c4a_gemm4096_f16", "f16_f32_t256x256w2x4s4r64_ak_bn"): 201499478 + 67108864,
     ("c4a_gemm4096_f16", "f16_f32_t256x256w2x4s3r64_ak_bn"): 201508049 + 67108864,

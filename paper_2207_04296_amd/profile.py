@@ -10,7 +10,8 @@ the program directly behind `--`,
     rocprofv3 --pmc WRITE_SIZE        ... -- python3 bench.py --profile-run ...
     rocprofv3 --pmc SQ_VALU_MFMA_BUSY_CYCLES SQ_BUSY_CYCLES SQ_LDS_BANK_CONFLICT SQ_WAVE_CYCLES SQ_WAIT_INST_ANY GRBM_GUI_ACTIVE ...
 
-(counters in runs of their own, never together with a trace), plus the two counter runs of
+(counters in runs of their own, never together with a trace), the same bench.py command once without the profiler
+(what a step takes when nothing traces it), plus the two counter runs of
 `bench.py --copy-calibration` (a device copy of known size that scales FETCH_SIZE / WRITE_SIZE), after one
 unprofiled `bench.py --tune-only --records R` so that the profiled runs launch the MEASURED variants without
 the tuning trials in the trace.  It then reads the CSVs and prints, per workload, and writes as
@@ -150,6 +151,13 @@ def main():
         for line in open(out / f"kt_{w}.log"):
             if line.startswith('{"metric"'):
                 bench_line = json.loads(line)
+        # the same command without the profiler: what the tracer itself adds per launch
+        run([py, bench] + bargs, out / f"plain_{w}.log", env)
+        plain_line = {}
+        if not PARSE_ONLY or (out / f"plain_{w}.log").exists():
+            for line in open(out / f"plain_{w}.log"):
+                if line.startswith('{"metric"'):
+                    plain_line = json.loads(line)
         d, cmd_f = rocprof(f"fetch_{w}", ["--pmc", "FETCH_SIZE"], bargs)
         fetch = counters(d, is_lib_kernel)[0]["FETCH_SIZE"]
         d, cmd_w = rocprof(f"write_{w}", ["--pmc", "WRITE_SIZE"], bargs)
@@ -186,6 +194,8 @@ def main():
             f"median {statistics.median(dur_timed):.0f}; all launches: average {mean(dur_all):.0f} ns.",
             f"The same run's bench line (HIP events around each replay, inside bench.py): avg_launch_us = {rl.get('avg_launch_us')}, "
             f"bound = {rl.get('bound')}, frac = {rl.get('frac')}, frac_mfma = {rl.get('frac_mfma')}, frac_hbm = {rl.get('frac_hbm')} ({rl.get('cache')}).",
+            f"The same command without rocprofv3 in front: avg_launch_us = {plain_line.get('roofline', {}).get('avg_launch_us')} per step, gaps between the launches included "
+            "(the kernels run in stream order, so this bounds a launch's own duration from above: what the trace adds to every dispatch is the difference).",
             "",
             "## MFMA utilisation and shader clock",
             "",
