@@ -389,6 +389,31 @@ def test_every_variant_on_short_reductions(B, oracle, dtype, out):
         B.tir_debug_force_variant("")
 
 
+def test_prepared_calls_launch_what_run_workload_launches(B, oracle):
+    """binding.prepare_workload marshals once and launches per call: a GEMM, a batched matmul and a fused convolution,
+    each launched twice from its prepared call (the second time over a poisoned output), against the oracle."""
+    import torch
+    cases = [
+        I.Workload("prep_gemm", "gemm", "f16", "f32", "u", 8601, M=150, N=72, K=200),
+        I.Workload("prep_bmm", "bmm", "bf16", "f32", "u", 8602, batch=3, M=70, N=40, K=96, trans_b=True),
+        I.Workload("prep_conv", "conv2d", "i8", "i8", "i", 8603, n=2, h=9, w=11, c=32, k=24, r=3, s=3, stride=(1, 2), pad=(1, 1),
+                   dil=(1, 1), groups=2, ep_bias=True, ep_relu=True, ep_scale=0.01),
+    ]
+    stream = torch.cuda.Stream()
+    for wl in cases:
+        a_bits, b_bits = wl.operands()
+        ref, S = PT.run_oracle(wl, a_bits, b_bits, oracle)
+        a, b = B.to_device(a_bits, wl.dtype), B.to_device(b_bits, wl.dtype)
+        c = B.empty_out(B.out_shape(wl), wl.out)
+        call = B.prepare_workload(wl, a, b, c, B.bias_to_device(wl), stream=stream)
+        for _ in range(2):
+            c.fill_(float("nan") if c.dtype.is_floating_point else -77)
+            torch.cuda.synchronize()
+            call()
+            torch.cuda.synchronize()
+            PT.assert_close(PT.gpu_to_f64(c), ref, S, wl.name)
+
+
 # ------------------------------------------------------------------------------ LDS-resident-patch convolution
 PATCH_CASES = [
     # n, h, w, c_per_group_bytes=128 -> c, k, r, s, stride, pad, dil, groups
