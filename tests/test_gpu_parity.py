@@ -712,6 +712,28 @@ def test_seeded_random_problems(B, oracle, seed):
         PT.assert_close(got, ref, S, wl.name)
 
 
+@pytest.mark.parametrize("seed", [4, 5, 6, 7])
+def test_seeded_random_problems_through_forced_variants(B, oracle, seed):
+    """The same generator, each problem through one more variant of its dtype pair and copy mode drawn at random:
+    tile shapes, ring depths and copy-wave variants the scoring rule would never pick for such extents."""
+    names = B.tir_debug_variant_names()
+    rng = np.random.default_rng(900 + seed)
+    try:
+        for wl in _random_workloads(seed, 40):
+            default = PT.variant_name(B, wl).split("/")[0]
+            if any(t in default for t in ("generic", "depthwise", "patch")):
+                continue
+            parts = default.split("_")
+            cands = [n for n in names if n.startswith("_".join(parts[:2]) + "_") and n.endswith("_" + "_".join(parts[3:]))]
+            assert cands, default
+            force = str(rng.choice(cands))
+            _say(f"{wl.name}: {default} -> {force}")
+            B.tir_debug_force_variant(force)
+            PT.check_workload(wl, oracle, f"{wl.name} via {force}")
+    finally:
+        B.tir_debug_force_variant("")
+
+
 # ------------------------------------------------------------------------------ conv1d / conv3d / transposed conv2d
 def _gpu_out(B, shape, out):
     o = B.empty_out(shape, out)
